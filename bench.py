@@ -1,0 +1,213 @@
+"""Benchmark of the compressed-shard hot path on one MI355X.
+
+A step is one pass of a Llama-7B-shaped shard over one prefill batch: the incoming hidden state
+is decoded from its blockwise 8-bit form, the 16 linears of 4 decoder layers (QKV 4096->12288,
+O 4096->4096, gate/up 4096->22016, down 11008->4096; 2048 tokens) run through the mixed int8
+decomposition (scan, pack, int8 GEMM with fused epilogue), and the outgoing hidden state is
+encoded again.  Weights are pre-quantized before the timed region (they are static).  Inputs are
+seeded synthetic tensors resident in HBM.  Prints one JSON line.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=4)
+    ap.add_argument("--codec-block", type=int, default=1024)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """hipEvent_t handles made through the HIP runtime, so that the library can record them."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+        return ev.value
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
+
+def cpu_baseline(wl, layers_sample=1):
+    """The CPU oracle on a bounded sample of the same workload: one decoder layer's four linears
+    at full size plus the codec round trip of one hidden state."""
+    import numpy as np
+    from oracle import blockwise_codec as bc
+    from oracle import mixed_linear as ml
+    ops = 0
+    M = 2048
+    prepared = []
+    for i, shp in enumerate(wl.LLAMA_7B_LINEARS):
+        X, _ = wl.prefill_activation(2, 10 + shp.K % 5, M, shp.K)
+        W = wl.prefill_weight(2, 20 + i, shp, 0.02)
+        Wq, c = ml.prequantize_weight(W)             # offline step, untimed like on the GPU
+        prepared.append((X, Wq, c))
+        ops += 2 * M * shp.K * shp.N
+    hidden = prepared[0][0]
+    t0 = time.perf_counter()
+    codes, a = bc.quantize_blockwise(hidden, 1024)
+    bc.dequantize_blockwise(codes, a, 1024)
+    for X, Wq, c in prepared:
+        ml.mixed_int8_linear(X, Wq, c, wl.TAU)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
+            "sample": "1 of 4 decoder layers (4 linears, 2048 tokens, full size) + codec round trip of one "
+                      "[2048,4096] hidden state; %.1f s" % dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2407_19775_amd import binding, workloads as wl
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    M = 2048
+    shapes = wl.LLAMA_7B_LINEARS
+    block = args.codec_block
+
+    # ---- static state: pre-quantized weights (distinct per layer), inputs, outputs, workspaces
+    weights, Xs, Ys = [], {}, {}
+    for layer in range(args.layers):
+        row = []
+        for i, shp in enumerate(shapes):
+            W = torch.from_numpy(wl.prefill_weight(2, 20 + 10 * layer + i, shp, 0.02)).to(dev)
+            row.append(binding.prequantize_weight(W))
+            del W
+        weights.append(row)
+    for K in sorted({s.K for s in shapes}):
+        X, _ = wl.prefill_activation(2, 10 + K % 5, M, K)
+        Xs[K] = torch.from_numpy(X).to(dev)
+    for shp in shapes:
+        Ys[shp.name] = torch.empty((M, shp.N), dtype=torch.float16, device=dev)
+    ws_bytes = max(binding.lib().mmd8_linear_workspace_bytes(M, s.K, s.N) for s in shapes)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    # incoming hidden state arrives encoded
+    codes_in, absmax_in = binding.quantize_blockwise(Xs[4096], block)
+    hidden_in = torch.empty((M, 4096), dtype=torch.float16, device=dev)
+    codes_out = torch.empty(M * 4096, dtype=torch.uint8, device=dev)
+    absmax_out = torch.empty((M * 4096 + block - 1) // block, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        binding.dequantize_blockwise(codes_in, absmax_in, block, out=hidden_in.view(-1))
+        n = 0
+        for layer in range(args.layers):
+            for i, shp in enumerate(shapes):
+                X = hidden_in if (layer == 0 and i == 0) else Xs[shp.K]
+                binding.mixed_int8_linear(X, weights[layer][i], wl.TAU, out=Ys[shp.name], workspace=workspace,
+                                          events=events[n] if events else None)
+                n += 1
+        binding.quantize_blockwise(Ys["down"], block, codes=codes_out, absmax=absmax_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    ops_per_step = args.layers * wl.linear_ops(M, shapes)
+    tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- second pass with events around every GEMM kernel (roofline of the dominant kernel) and
+    # around the codec kernels
+    he = HipEvents()
+    n_lin = args.layers * len(shapes)
+    evs = [[he.create() for _ in range(3)] for _ in range(n_lin)]
+    gemm_ms, prep_ms = [0.0] * n_lin, [0.0] * n_lin
+    reps = max(3, min(10, args.steps))
+    for _ in range(reps):
+        step(evs)
+        torch.cuda.synchronize()
+        for i, (e0, e1, e2) in enumerate(evs):
+            prep_ms[i] += he.elapsed_ms(e0, e1) / reps
+            gemm_ms[i] += he.elapsed_ms(e1, e2) / reps
+    gemm_ops = [2.0 * M * s.K * s.N for _ in range(args.layers) for s in shapes]
+    gemm_tops = sum(gemm_ops) / (sum(gemm_ms) * 1e-3) / 1e12
+    per_shape = {}
+    for j, shp in enumerate(shapes):
+        ms = np.mean([gemm_ms[l * len(shapes) + j] for l in range(args.layers)])
+        pm = np.mean([prep_ms[l * len(shapes) + j] for l in range(args.layers)])
+        per_shape[shp.name] = {"gemm_us": round(ms * 1e3, 1), "gemm_tops": round(2.0 * M * shp.K * shp.N / ms / 1e9, 1),
+                               "scan_pack_us": round(pm * 1e3, 1),
+                               "scan_pack_gbs": round(3.0 * M * shp.K / pm / 1e6, 1)}
+
+    def timed(fn, n=20):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    nel = M * 4096
+    codec_bytes = 3.0 * nel + 4.0 * nel / block
+    q_ms = timed(lambda: binding.quantize_blockwise(Ys["down"], block, codes=codes_out, absmax=absmax_out))
+    d_ms = timed(lambda: binding.dequantize_blockwise(codes_in, absmax_in, block, out=hidden_in.view(-1)))
+
+    out = {
+        "metric": "mixed int8 linear TOPS (+% int8 MFMA peak); blockwise codec GB/s (+% HBM)",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "Llama-7B-shaped shard prefill: %d decoder layers x (QKV 4096->12288, O 4096->4096, "
+                               "gate/up 4096->22016, down 11008->4096), 2048 tokens, tau 6.0, 0.1%% outlier dims; "
+                               "hidden state [2048,4096] decoded on entry and encoded on exit, block %d"
+                               % (args.layers, block),
+                   "tokens": M, "layers": args.layers, "codec_block": block},
+        "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_mixed (int8 MFMA GEMM + fused epilogue)",
+                     "achieved": round(gemm_tops, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None},
+        "per_linear": per_shape,
+        "codec": {"quantize_gbs": round(codec_bytes / q_ms / 1e6, 1), "dequantize_gbs": round(codec_bytes / d_ms / 1e6, 1),
+                  "quantize_pct_hbm": round(100 * codec_bytes / q_ms / 1e6 / HBM_PEAK_GBS, 1),
+                  "dequantize_pct_hbm": round(100 * codec_bytes / d_ms / 1e6 / HBM_PEAK_GBS, 1),
+                  "elements": nel, "note": "33.6 MB tensor: resident in the last-level cache between calls"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/* mmd8 -- mixed-matrix-decomposition int8 linear layer and dynamic blockwise 8-bit codec
+ * for AMD Instinct MI355X (gfx950).  C ABI.
+ *
+ * The two operations are the compression techniques of the paper's section "Compression
+ * techniques": item 1 (dynamic blockwise quantization of the hidden states sent from one shard
+ * to the next) and item 2 (mixed matrix decomposition: 8-bit weights and activations with a
+ * small 16-bit part for the critical feature dimensions).
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are device memory owned by the caller; the library never
+ *     allocates, frees or copies to the host.  HOST pointers returned by the library point at
+ *     static read-only data.
+ *   - fp16 data are IEEE binary16 bit patterns (mmd8_half).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     the call returns without synchronising.  Calls on one stream are ordered.
+ *   - Return value: MMD8_OK, or a negative status; on error nothing has been enqueued.
+ *   - Zero-sized problems (M == 0, n == 0) are valid and enqueue nothing.
+ *   - Inputs are assumed finite; NaN/Inf give unspecified values but never a fault.
+ */
+#ifndef MMD8_H
+#define MMD8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t mmd8_half;
+
+enum {
+  MMD8_OK          = 0,
+  MMD8_E_ARG       = -1,  /* null pointer, negative size, leading dimension too small, misaligned, NaN tau */
+  MMD8_E_SHAPE     = -2,  /* unsupported shape: K % 16, N % 8, K above MMD8_MAX_K, bad block size          */
+  MMD8_E_WORKSPACE = -3,  /* workspace smaller than mmd8_linear_workspace_bytes()                           */
+  MMD8_E_HIP       = -4   /* a HIP call or kernel launch failed                                             */
+};
+
+/* Largest supported K.  K * 127^2 must stay below 2^31 so that the int32 accumulators of the
+ * integer product cannot overflow (that alone allows 133144); column indices are also held in
+ * 16 bits inside the kernels. */
+#define MMD8_MAX_K 65536
+
+/* Human-readable text for a status code (HOST, static). */
+const char* mmd8_status_string(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * Dynamic blockwise 8-bit codec ("Compression techniques", item 1).
+ *
+ * The tensor is treated as a flat contiguous array of n fp16 values cut into blocks of `block`
+ * consecutive elements (the last block may be short).  Per block b:
+ *     absmax[b] = max |x_i|                                  (fp32, exact)
+ *     v_i       = f32(x_i) * (1.0f / absmax[b])              (0 if absmax[b] == 0)
+ *     codes[i]  = number of midpoints Mid[j] (j = 0..254) with v_i > Mid[j]
+ * and decoding is  out[i] = f16( T[codes[i]] * absmax[b] )  (fp32 product, round to nearest even).
+ * T is the 256-entry signed dynamic code: magnitudes 10^-e (0.1 + 0.9 (j + 1/2) / 2^(6-e)),
+ * e = 0..6, j = 0..2^(6-e)-1, both signs, plus 0 and +1.0; Mid[j] = f32((T[j] + T[j+1]) / 2).
+ * `block` must be a multiple of 64 with 64 <= block <= 4096, else MMD8_E_SHAPE.
+ * x, out: 16-byte aligned; codes: 8-byte aligned; absmax: 4-byte aligned; else MMD8_E_ARG.
+ * ------------------------------------------------------------------------------------------ */
+int mmd8_quantize_blockwise(const mmd8_half* x /*DEVICE [n]*/, size_t n, int block,
+                            uint8_t* codes /*DEVICE [n]*/, float* absmax /*DEVICE [ceil(n/block)]*/,
+                            void* stream);
+int mmd8_dequantize_blockwise(const uint8_t* codes /*DEVICE [n]*/, const float* absmax /*DEVICE*/,
+                              size_t n, int block, mmd8_half* out /*DEVICE [n]*/, void* stream);
+/* HOST pointers to the 256 code values (ascending) and the 255 midpoints. */
+const float* mmd8_code_table(void);
+const float* mmd8_code_midpoints(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Mixed int8 linear layer ("Compression techniques", item 2).   Y[M,N] = X[M,K] W[K,N]
+ *
+ * Weight pre-quantization (once per weight matrix):
+ *     col_absmax[n] = max_k |W[k,n]|
+ *     Wq[k,n]       = clamp(rint(f32(W[k,n]) * (127.0f / col_absmax[n])), -127, 127)   (0 if absmax 0)
+ * W is read as W[k*ldw + n] (ldw >= N).  Wq is written in an opaque layout of
+ * mmd8_packed_weight_bytes(K, N) bytes; mmd8_unpack_weight recovers the plain row-major
+ * int8 [K,N] matrix (for checking).  mmd8_packed_weight_layout() identifies the layout; a blob
+ * written under a different value must be regenerated.
+ * Requirements: K % 16 == 0, 16 <= K <= MMD8_MAX_K, N % 8 == 0, N >= 8 (else MMD8_E_SHAPE);
+ * W 16-byte aligned and ldw % 8 == 0, Wq_packed 256-byte aligned (else MMD8_E_ARG).
+ * ------------------------------------------------------------------------------------------ */
+uint32_t mmd8_packed_weight_layout(void);
+size_t   mmd8_packed_weight_bytes(int K, int N);
+int mmd8_prequantize_weight(const mmd8_half* W /*DEVICE*/, int K, int N, int ldw,
+                            int8_t* Wq_packed /*DEVICE*/, float* col_absmax /*DEVICE [N]*/, void* stream);
+int mmd8_unpack_weight(const int8_t* Wq_packed /*DEVICE*/, int K, int N,
+                       int8_t* Wq_rowmajor /*DEVICE [K,N]*/, void* stream);
+
+/* Optional taps that expose the intermediates of one mmd8_mixed_int8_linear call (for parity
+ * checks).  Any member may be NULL.  All are DEVICE pointers. */
+typedef struct {
+  uint8_t* outlier_mask;  /* [K]    1 = critical feature dimension                         */
+  float*   row_absmax;    /* [M]    r[m]                                                   */
+  int8_t*  xq;            /* [M,K]  row-major activation codes                             */
+  int32_t* acc;           /* [M,N]  row-major int32 accumulators of the integer product    */
+  int32_t* n_outliers;    /* [1]                                                           */
+  int32_t* outlier_idx;   /* [K]    ascending indices of the critical dimensions; entries
+                                    past n_outliers are unspecified                         */
+  /* Optional hipEvent_t handles (HOST, created by the caller) recorded on `stream`: when the
+     call starts, just before the GEMM kernel and just after it.  For per-stage timing.      */
+  void* event_begin;
+  void* event_gemm_begin;
+  void* event_gemm_end;
+} mmd8_debug_taps;
+
+/* The layer, per call (tau: threshold; X read as X[m*ldx + k]; Y written as Y[m*ldy + n]):
+ *     flag[k]  = any_m |X[m,k]| >= tau
+ *     r[m]     = max over k of |X[m,k]| restricted to |X[m,k]| < tau        (0 if none)
+ *     Xq[m,k]  = flag[k] ? 0 : clamp(rint(f32(X[m,k]) * (127.0f / r[m])), -127, 127)
+ *     acc[m,n] = sum_k Xq[m,k] * Wq[k,n]                                     (int32, exact)
+ *     Y[m,n]   = f16( acc[m,n] r[m] c[n] / 127^2
+ *                     + sum_{k: flag[k]} X[m,k] * f16(Wq[k,n] * (c[n] / 127.0f))   (fp32 accumulation)
+ *                     + bias[n] )
+ * tau may be 0 (every dimension critical: a pure fp16 product) or +INFINITY (pure int8).
+ * Requirements: shapes as for mmd8_prequantize_weight; X, Y 16-byte aligned, ldx % 8 == 0,
+ * ldx >= K, ldy % 8 == 0, ldy >= N; Y must not alias X; workspace 256-byte aligned and at
+ * least mmd8_linear_workspace_bytes(M, K, N) bytes; its contents on entry are irrelevant and
+ * it may be reused by the next call on the same stream. */
+size_t mmd8_linear_workspace_bytes(int M, int K, int N);
+int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                           const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                           const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                           mmd8_half* Y /*DEVICE*/, int ldy,
+                           void* workspace /*DEVICE*/, size_t workspace_bytes,
+                           const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
+/* HOST helper: the bit pattern of the smallest non-negative fp16 value that is >= tau (0 for
+ * tau <= 0, 0x7c00 = +inf when no finite fp16 value reaches tau).  The outlier scan compares fp16
+ * magnitudes against this pattern, which is equivalent to |x| >= tau for every fp16 x. */
+uint32_t mmd8_threshold_fp16_pattern(float tau);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMD8_H */

@@ -101,13 +101,19 @@ def int_gemm(Xq: np.ndarray, Wq: np.ndarray) -> np.ndarray:
 
 
 # ---------------------------------------------------------------- whole layer
-def mixed_int8_linear(X, Wq, c, tau, bias=None):
+def mixed_int8_linear(X, Wq, c, tau, bias=None, rows=None):
     """Returns a dict with every intermediate: flag, outlier_idx, r, Xq, acc, Y (fp16) and the
-    float64 value Y64 before the final rounding."""
+    float64 value Y64 before the final rounding.
+
+    rows: optional index array.  The critical-dimension mask is always taken over every row of
+    X (step A1); with ``rows`` given, the per-row quantities (r, Xq, acc, Y) are produced for
+    those rows only, which is how full-size problems are spot-checked."""
     assert X.dtype == np.float16 and Wq.dtype == np.int8 and c.dtype == np.float32
+    flag = outlier_mask(X, tau)
+    if rows is not None:
+        X = np.ascontiguousarray(X[np.asarray(rows)])
     M, K = X.shape
     N = Wq.shape[1]
-    flag = outlier_mask(X, tau)
     r = row_absmax(X, tau)
     Xq = quantize_activations(X, flag, r)
     acc = int_gemm(Xq, Wq)
@@ -127,9 +133,9 @@ def mixed_int8_linear(X, Wq, c, tau, bias=None):
     return dict(flag=flag, outlier_idx=idx.astype(np.int32), r=r, Xq=Xq, acc=acc, Y=Y, Y64=Y64)
 
 
-def linear_from_fp16_weight(X, W, tau, bias=None):
+def linear_from_fp16_weight(X, W, tau, bias=None, rows=None):
     """Convenience: pre-quantize W (W1, W2) then run the layer."""
     Wq, c = prequantize_weight(W)
-    out = mixed_int8_linear(X, Wq, c, tau, bias)
+    out = mixed_int8_linear(X, Wq, c, tau, bias, rows)
     out["Wq"], out["c"] = Wq, c
     return out

@@ -1,0 +1,180 @@
+"""ctypes binding of libmmd8.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their addresses,
+shapes and strides through the C ABI (include/mmd8.h) on torch's current HIP stream, and
+raises on a non-zero status.  There is no CPU fallback: if the library has not been built the
+first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmmd8.so")
+_lib = None
+
+EXPORTS = (
+    "mmd8_status_string", "mmd8_quantize_blockwise", "mmd8_dequantize_blockwise", "mmd8_code_table",
+    "mmd8_code_midpoints", "mmd8_packed_weight_layout", "mmd8_packed_weight_bytes", "mmd8_prequantize_weight",
+    "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_mixed_int8_linear",
+    "mmd8_threshold_fp16_pattern",
+)
+
+
+class DebugTaps(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in
+                ("outlier_mask", "row_absmax", "xq", "acc", "n_outliers", "outlier_idx",
+                 "event_begin", "event_gemm_begin", "event_gemm_end")]
+
+
+class Mmd8Error(RuntimeError):
+    pass
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise Mmd8Error("libmmd8.so is not built: run `python -m paper_2407_19775_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+        L.mmd8_status_string.restype = ctypes.c_char_p
+        L.mmd8_status_string.argtypes = [i32]
+        L.mmd8_quantize_blockwise.argtypes = [vp, sz, i32, vp, vp, vp]
+        L.mmd8_dequantize_blockwise.argtypes = [vp, vp, sz, i32, vp, vp]
+        L.mmd8_code_table.restype = ctypes.POINTER(ctypes.c_float)
+        L.mmd8_code_midpoints.restype = ctypes.POINTER(ctypes.c_float)
+        L.mmd8_packed_weight_layout.restype = ctypes.c_uint32
+        L.mmd8_packed_weight_bytes.restype = sz
+        L.mmd8_packed_weight_bytes.argtypes = [i32, i32]
+        L.mmd8_prequantize_weight.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        L.mmd8_unpack_weight.argtypes = [vp, i32, i32, vp, vp]
+        L.mmd8_linear_workspace_bytes.restype = sz
+        L.mmd8_linear_workspace_bytes.argtypes = [i32, i32, i32]
+        L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, sz,
+                                             ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
+        L.mmd8_threshold_fp16_pattern.argtypes = [f32]
+        L.mmd8_set_gemm_variant.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise Mmd8Error("mmd8 status %d: %s" % (status, lib().mmd8_status_string(status).decode()))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype):
+        raise Mmd8Error("%s must be a GPU tensor of dtype %s" % (name, dtype))
+    return t
+
+
+def code_table() -> torch.Tensor:
+    return torch.tensor([lib().mmd8_code_table()[i] for i in range(256)], dtype=torch.float32)
+
+
+def code_midpoints() -> torch.Tensor:
+    return torch.tensor([lib().mmd8_code_midpoints()[i] for i in range(255)], dtype=torch.float32)
+
+
+# ------------------------------------------------------------------ blockwise codec
+def quantize_blockwise(x: torch.Tensor, block: int, codes: torch.Tensor = None, absmax: torch.Tensor = None):
+    """x: fp16 GPU tensor (contiguous, any shape) -> (codes uint8 [n], absmax float32 [ceil(n/block)])."""
+    _dev(x, torch.float16, "x")
+    if not x.is_contiguous():
+        raise Mmd8Error("x must be contiguous")
+    n = x.numel()
+    nblk = (n + block - 1) // block if block > 0 else 0
+    if codes is None:
+        codes = torch.empty(n, dtype=torch.uint8, device=x.device)
+    if absmax is None:
+        absmax = torch.empty(nblk, dtype=torch.float32, device=x.device)
+    _check(lib().mmd8_quantize_blockwise(x.data_ptr(), n, block, codes.data_ptr(), absmax.data_ptr(), _stream()))
+    return codes, absmax
+
+
+def dequantize_blockwise(codes: torch.Tensor, absmax: torch.Tensor, block: int, out: torch.Tensor = None):
+    _dev(codes, torch.uint8, "codes")
+    _dev(absmax, torch.float32, "absmax")
+    n = codes.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.float16, device=codes.device)
+    _check(lib().mmd8_dequantize_blockwise(codes.data_ptr(), absmax.data_ptr(), n, block, out.data_ptr(), _stream()))
+    return out
+
+
+# ------------------------------------------------------------------ mixed int8 linear
+class PackedWeight:
+    """Pre-quantized weight: opaque int8 blob + per-column absmax."""
+
+    def __init__(self, blob, col_absmax, K, N):
+        self.blob, self.col_absmax, self.K, self.N = blob, col_absmax, K, N
+        self.layout = lib().mmd8_packed_weight_layout()
+
+
+def prequantize_weight(W: torch.Tensor) -> PackedWeight:
+    """W: fp16 GPU tensor [K, N] (row stride may exceed N)."""
+    _dev(W, torch.float16, "W")
+    K, N = W.shape
+    if W.stride(1) != 1:
+        raise Mmd8Error("W must have unit stride along N")
+    nbytes = lib().mmd8_packed_weight_bytes(K, N)
+    if nbytes == 0:
+        _check(-2)
+    blob = torch.empty(nbytes, dtype=torch.int8, device=W.device)
+    c = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(lib().mmd8_prequantize_weight(W.data_ptr(), K, N, W.stride(0), blob.data_ptr(), c.data_ptr(), _stream()))
+    return PackedWeight(blob, c, K, N)
+
+
+def unpack_weight(pw: PackedWeight) -> torch.Tensor:
+    out = torch.empty((pw.K, pw.N), dtype=torch.int8, device=pw.blob.device)
+    _check(lib().mmd8_unpack_weight(pw.blob.data_ptr(), pw.K, pw.N, out.data_ptr(), _stream()))
+    return out
+
+
+def linear_workspace(M: int, K: int, N: int, device) -> torch.Tensor:
+    nbytes = lib().mmd8_linear_workspace_bytes(M, K, N)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
+                      out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
+                      events=None):
+    """Y = X W through the mixed decomposition.  With taps=True also returns a dict of the
+    intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx)."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    if K != pw.K or X.stride(1) != 1:
+        raise Mmd8Error("X must be [M, %d] with unit stride along K" % pw.K)
+    N = pw.N
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = linear_workspace(M, K, N, X.device)
+    tp, tensors = None, None
+    if events is not None:                      # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
+        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
+    if taps:
+        dev = X.device
+        tensors = dict(
+            outlier_mask=torch.zeros(K, dtype=torch.uint8, device=dev),
+            row_absmax=torch.zeros(M, dtype=torch.float32, device=dev),
+            xq=torch.zeros((M, K), dtype=torch.int8, device=dev),
+            acc=torch.zeros((M, N), dtype=torch.int32, device=dev),
+            n_outliers=torch.zeros(1, dtype=torch.int32, device=dev),
+            outlier_idx=torch.zeros(K, dtype=torch.int32, device=dev),
+        )
+        tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
+    _check(lib().mmd8_mixed_int8_linear(
+        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+        bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(), out.stride(0) if M > 0 else N,
+        workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
+    return (out, tensors) if taps else out

@@ -1,0 +1,236 @@
+// C ABI of the mmd8 library: argument checks, workspace carving, kernel sequencing.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "common.h"
+#include "gemm.h"
+#include "weight_layout.h"
+
+namespace mmd8 {
+
+// launchers defined next to their kernels
+const float* code_table_host();
+const float* code_midpoints_host();
+hipError_t launch_quantize_blockwise(const uint16_t*, size_t, int, uint8_t*, float*, hipStream_t);
+hipError_t launch_dequantize_blockwise(const uint8_t*, const float*, size_t, int, uint16_t*, hipStream_t);
+hipError_t launch_fill_u32(uint32_t*, uint32_t, int, hipStream_t);
+hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, uint8_t*, float*, hipStream_t);
+hipError_t launch_compact(const uint8_t*, int, int32_t*, int32_t*, uint8_t*, int32_t*, int32_t*, hipStream_t);
+hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*,
+                       hipStream_t);
+hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
+hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
+hipError_t launch_weight_unpack(const int8_t*, int, int, int8_t*, hipStream_t);
+
+int device_cu_count() {
+  static std::mutex mu;
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cached[dev] = cus;
+  }
+  return cached[dev];
+}
+
+// smallest fp16 bit pattern (non-negative) whose value is >= tau; 0x7c00 (+inf) if none is finite
+static uint32_t threshold_pattern(float tau) {
+  if (!(tau > 0.0f)) return 0;
+  if (tau > 65504.0f) return 0x7c00u;
+  // walk the exponent/mantissa of tau into an fp16 pattern rounded towards +inf
+  uint32_t fb;
+  memcpy(&fb, &tau, 4);
+  const int exp = (int)((fb >> 23) & 0xff) - 127;
+  const uint32_t man = fb & 0x7fffffu;
+  if (exp < -24) return 1u;                                        // below the smallest subnormal
+  if (exp < -14) {                                                 // subnormal range: value = m * 2^-24
+    const uint64_t sig = (uint64_t)(0x800000u | man);              // tau = sig * 2^(exp - 23)
+    const int drop = -exp - 1;                                     // tau / 2^-24 = sig >> drop, drop = 14..23
+    uint32_t m = (uint32_t)(sig >> drop);
+    if (sig & ((1ull << drop) - 1)) m += 1;                        // round up
+    return m;                                                      // may reach 0x400 = smallest normal: still correct
+  }
+  uint32_t h = ((uint32_t)(exp + 15) << 10) | (man >> 13);
+  if (man & 0x1fffu) h += 1;                                       // round up; a carry moves into the exponent correctly
+  return h;
+}
+
+static inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+static int check_linear_shape(int K, int N) {
+  if (K < 16 || K > MMD8_MAX_K || (K % 16) != 0 || N < 8 || (N % 8) != 0) return MMD8_E_SHAPE;
+  return MMD8_OK;
+}
+
+struct Workspace {
+  uint8_t* flag;       // [Kpad]
+  int32_t* n_out;      // [1] (64 bytes reserved)
+  int32_t* idx;        // [Kpad]
+  float* r;            // [Mpad]
+  int8_t* xq;          // [Mpad][Kpad]
+  size_t bytes;
+};
+static Workspace carve(void* base, int M, int K) {
+  const size_t Kpad = packed_k(K), Mpad = packed_n(M);
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    uint8_t* p = base ? static_cast<uint8_t*>(base) + off : nullptr;
+    off += round_up_sz(n, 256);
+    return p;
+  };
+  w.flag = take(Kpad);
+  w.n_out = reinterpret_cast<int32_t*>(take(64));
+  w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
+  w.r = reinterpret_cast<float*>(take(Mpad * 4));
+  w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
+  w.bytes = off;
+  return w;
+}
+
+static int g_gemm_variant = -1;
+
+}  // namespace mmd8
+
+using namespace mmd8;
+
+extern "C" {
+
+const char* mmd8_status_string(int status) {
+  switch (status) {
+    case MMD8_OK: return "ok";
+    case MMD8_E_ARG: return "invalid argument (null, negative, misaligned, leading dimension, NaN threshold)";
+    case MMD8_E_SHAPE: return "unsupported shape or block size";
+    case MMD8_E_WORKSPACE: return "workspace too small";
+    case MMD8_E_HIP: return "HIP runtime or launch error";
+    default: return "unknown status";
+  }
+}
+
+const float* mmd8_code_table(void) { return code_table_host(); }
+const float* mmd8_code_midpoints(void) { return code_midpoints_host(); }
+
+static int check_block(int block) { return (block >= 64 && block <= 4096 && block % 64 == 0) ? MMD8_OK : MMD8_E_SHAPE; }
+
+int mmd8_quantize_blockwise(const mmd8_half* x, size_t n, int block, uint8_t* codes, float* absmax, void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  if (n == 0) return MMD8_OK;
+  if (!x || !codes || !absmax || !aligned(x, 16) || !aligned(codes, 8) || !aligned(absmax, 4)) return MMD8_E_ARG;
+  return launch_quantize_blockwise(x, n, block, codes, absmax, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
+int mmd8_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block, mmd8_half* out,
+                              void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  if (n == 0) return MMD8_OK;
+  if (!codes || !absmax || !out || !aligned(out, 16) || !aligned(codes, 16) || !aligned(absmax, 4)) return MMD8_E_ARG;
+  return launch_dequantize_blockwise(codes, absmax, n, block, out, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
+uint32_t mmd8_packed_weight_layout(void) { return kPackedLayoutTag; }
+
+size_t mmd8_packed_weight_bytes(int K, int N) {
+  if (check_linear_shape(K, N) != MMD8_OK) return 0;
+  return (size_t)packed_k(K) * (size_t)packed_n(N);
+}
+
+int mmd8_prequantize_weight(const mmd8_half* W, int K, int N, int ldw, int8_t* Wq_packed, float* col_absmax,
+                            void* stream) {
+  if (int s = check_linear_shape(K, N)) return s;
+  if (!W || !Wq_packed || !col_absmax || ldw < N || (ldw % 8) != 0 || !aligned(W, 16) || !aligned(Wq_packed, 256) ||
+      !aligned(col_absmax, 4))
+    return MMD8_E_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_fill_u32(reinterpret_cast<uint32_t*>(col_absmax), 0u, N, st) != hipSuccess) return MMD8_E_HIP;
+  if (launch_col_absmax(W, K, N, ldw, col_absmax, st) != hipSuccess) return MMD8_E_HIP;
+  if (launch_weight_quant_pack(W, K, N, ldw, col_absmax, Wq_packed, st) != hipSuccess) return MMD8_E_HIP;
+  return MMD8_OK;
+}
+
+int mmd8_unpack_weight(const int8_t* Wq_packed, int K, int N, int8_t* Wq_rowmajor, void* stream) {
+  if (int s = check_linear_shape(K, N)) return s;
+  if (!Wq_packed || !Wq_rowmajor) return MMD8_E_ARG;
+  return launch_weight_unpack(Wq_packed, K, N, Wq_rowmajor, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
+size_t mmd8_linear_workspace_bytes(int M, int K, int N) {
+  if (M < 0 || check_linear_shape(K, N) != MMD8_OK) return 0;
+  return carve(nullptr, M, K).bytes;
+}
+
+int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                           const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                           void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  if (M < 0) return MMD8_E_ARG;
+  if (int s = check_linear_shape(K, N)) return s;
+  if (isnan(tau)) return MMD8_E_ARG;
+  if (M == 0) return MMD8_OK;
+  if (!X || !Wq_packed || !col_absmax || !Y || !workspace) return MMD8_E_ARG;
+  if (ldx < K || ldy < N || (ldx % 8) != 0 || (ldy % 8) != 0) return MMD8_E_ARG;
+  if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(Wq_packed, 256) || !aligned(workspace, 256) ||
+      !aligned(col_absmax, 4) || (bias && !aligned(bias, 2)))
+    return MMD8_E_ARG;
+  if (static_cast<const void*>(X) == static_cast<const void*>(Y)) return MMD8_E_ARG;
+  const Workspace ws = carve(workspace, M, K);
+  if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int Kpad = packed_k(K);
+  const mmd8_debug_taps none = {};
+  const mmd8_debug_taps& t = taps ? *taps : none;
+
+  auto record = [&](void* ev) {
+    return !ev || hipEventRecord(static_cast<hipEvent_t>(ev), st) == hipSuccess;
+  };
+  if (!record(t.event_begin)) return MMD8_E_HIP;
+  // flags and the count share the head of the workspace: one fill clears both
+  const int head_words = (int)((reinterpret_cast<uint8_t*>(ws.n_out) + 64 - ws.flag) / 4);
+  if (launch_fill_u32(reinterpret_cast<uint32_t*>(ws.flag), 0u, head_words, st) != hipSuccess) return MMD8_E_HIP;
+  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
+  if (launch_compact(ws.flag, K, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers, st) != hipSuccess)
+    return MMD8_E_HIP;
+  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, st) != hipSuccess) return MMD8_E_HIP;
+  if (t.row_absmax &&
+      hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return MMD8_E_HIP;
+
+  GemmArgs g;
+  g.Xq = ws.xq;
+  g.Wt = Wq_packed;
+  g.M = M;
+  g.N = N;
+  g.Kpad = Kpad;
+  g.r = ws.r;
+  g.c = col_absmax;
+  g.bias = bias;
+  g.X = X;
+  g.ldx = ldx;
+  g.idx = ws.idx;
+  g.n_out = ws.n_out;
+  g.Y = Y;
+  g.ldy = ldy;
+  g.tap_acc = t.acc;
+  g.tiles_m = g.tiles_n = 0;
+  if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
+  if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
+  if (!record(t.event_gemm_end)) return MMD8_E_HIP;
+  return MMD8_OK;
+}
+
+uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau); }
+
+// Tuning hook (not part of the documented interface): force a GEMM tile configuration; -1 = automatic.
+void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
+
+}  // extern "C"

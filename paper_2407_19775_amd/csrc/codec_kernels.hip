@@ -1,0 +1,214 @@
+// Dynamic blockwise 8-bit codec kernels ("Compression techniques", item 1).
+//
+// Both directions are streaming kernels bound by HBM traffic (3 + 4/B bytes per element).
+// A workgroup of 256 threads works on a span of whole quantization blocks of at most 4096
+// elements, 16 bytes of fp16 per thread per load; workgroups stride over the spans so the
+// lookup tables are staged into LDS once per workgroup, not once per span.
+#include "common.h"
+#include "dynamic_code.h"
+
+namespace mmd8 {
+
+static constexpr DynamicCode kCodeHost = make_dynamic_code();
+static_assert(kCodeHost.one_midpoint_per_cell, "a lookup cell holds more than one midpoint");
+static_assert(sizeof(CodeCell) == 8, "cell is read with one 64-bit LDS load");
+__device__ const DynamicCode kCodeDev = make_dynamic_code();
+
+const float* code_table_host() { return kCodeHost.T; }
+const float* code_midpoints_host() { return kCodeHost.Mid; }
+
+constexpr int kThreads = 256;
+constexpr int kChunk = 8;                         // fp16 elements per 16-byte load
+constexpr int kSpanMax = 4096;                    // elements per span: 2 chunks per thread
+constexpr int kChunksPerThread = kSpanMax / (kThreads * kChunk);
+constexpr int kSpanChunks = kSpanMax / kChunk;    // 512
+
+// count of midpoints strictly below v, from the cell table in LDS
+__device__ inline uint32_t encode_one(float v, const CodeCell* __restrict__ cells) {
+  const uint32_t bits = __float_as_uint(v);
+  const uint32_t sign = (uint32_t)((int32_t)bits >> 31);          // 0 or 0xffffffff
+  const uint32_t u = (bits & 0x7fffffffu) - sign;                  // |v| bits, +1 for negatives (>= becomes >)
+  uint32_t c = u >> kCellShift;
+  c = min(max(c, (uint32_t)DynamicCode::kCellLo), (uint32_t)DynamicCode::kCellHi) - DynamicCode::kCellLo;
+  const CodeCell cell = cells[c];
+  uint32_t cnt = cell.base + (u > cell.threshold ? 1u : 0u);
+  cnt = min(cnt, 128u + sign);                                     // negatives count P[0..126] only
+  return 127u + ((cnt ^ sign) - sign);
+}
+
+// kLogBlock >= 0: block == 1 << kLogBlock.  kLogBlock < 0: any multiple of 64 (runtime division).
+template <int kLogBlock>
+__global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
+    const uint16_t* __restrict__ x, size_t n, int block, uint8_t* __restrict__ codes,
+    float* __restrict__ absmax, int blocks_per_span, size_t n_spans) {
+  __shared__ CodeCell s_cells[DynamicCode::kCells];
+  __shared__ uint32_t s_chunk_max[kSpanChunks];    // |x| bit pattern maxima, one per 8-element chunk
+  __shared__ uint32_t s_block_max[kSpanMax / 64];
+
+  for (int i = threadIdx.x; i < DynamicCode::kCells; i += kThreads) s_cells[i] = kCodeDev.cell[i];
+
+  const int chunks_per_block = (kLogBlock >= 0) ? (1 << (kLogBlock - 3)) : (block >> 3);
+  const int span_elems = blocks_per_span * block;
+  const int span_chunks = span_elems >> 3;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+
+  for (size_t span = blockIdx.x; span < n_spans; span += gridDim.x) {
+    const size_t span_base = span * (size_t)span_elems;
+    v4u raw[kChunksPerThread];
+    bool live[kChunksPerThread];
+    int valid[kChunksPerThread];                   // elements of the chunk inside the tensor (0..8)
+#pragma unroll
+    for (int j = 0; j < kChunksPerThread; ++j) {
+      const int ch = j * kThreads + threadIdx.x;
+      const size_t e0 = span_base + (size_t)ch * kChunk;
+      live[j] = ch < span_chunks && e0 < n;
+      valid[j] = live[j] ? (int)min((size_t)kChunk, n - e0) : 0;
+      raw[j] = v4u{0, 0, 0, 0};
+      if (valid[j] == kChunk) {
+        raw[j] = *reinterpret_cast<const v4u*>(x + e0);
+      } else if (valid[j] > 0) {                   // ragged end of the tensor: element loads
+        uint32_t tmp[4] = {0, 0, 0, 0};
+        for (int t = 0; t < valid[j]; ++t) tmp[t >> 1] |= (uint32_t)x[e0 + t] << (16 * (t & 1));
+        raw[j] = v4u{tmp[0], tmp[1], tmp[2], tmp[3]};
+      }
+    }
+    // chunk maxima of |x| (fp16 magnitudes order like their 15-bit patterns)
+#pragma unroll
+    for (int j = 0; j < kChunksPerThread; ++j) {
+      uint32_t m = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t a = raw[j][w] & 0x7fff7fffu;
+        m = max(m, max(a & 0xffffu, a >> 16));
+      }
+      const int ch = j * kThreads + threadIdx.x;
+      if (ch < span_chunks) s_chunk_max[ch] = m;
+    }
+    __syncthreads();
+    // block maxima: one wave per block, lanes stride over the block's chunks
+    for (int b = wave; b < blocks_per_span; b += kThreads / kWave) {
+      uint32_t m = 0;
+      for (int c = lane; c < chunks_per_block; c += kWave) m = max(m, s_chunk_max[b * chunks_per_block + c]);
+      m = wave_max_u32(m);
+      if (lane == 0) {
+        s_block_max[b] = m;
+        const size_t gb = span * (size_t)blocks_per_span + b;
+        if (gb * (size_t)block < n) absmax[gb] = half_lo_to_float(m);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kChunksPerThread; ++j) {
+      if (!live[j]) continue;
+      const int ch = j * kThreads + threadIdx.x;
+      const int b = (kLogBlock >= 0) ? (ch >> (kLogBlock - 3)) : (ch / chunks_per_block);
+      const float a = half_lo_to_float(s_block_max[b]);
+      const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;            // IEEE division, once per chunk
+      uint32_t out[2];
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const uint32_t w0 = raw[j][2 * w], w1 = raw[j][2 * w + 1];
+        const uint32_t c0 = encode_one(half_lo_to_float(w0) * inv, s_cells);
+        const uint32_t c1 = encode_one(half_hi_to_float(w0) * inv, s_cells);
+        const uint32_t c2 = encode_one(half_lo_to_float(w1) * inv, s_cells);
+        const uint32_t c3 = encode_one(half_hi_to_float(w1) * inv, s_cells);
+        out[w] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+      }
+      const size_t e0 = span_base + (size_t)ch * kChunk;
+      if (valid[j] == kChunk) {
+        *reinterpret_cast<v2u*>(codes + e0) = v2u{out[0], out[1]};
+      } else {
+        for (int t = 0; t < valid[j]; ++t) codes[e0 + t] = (uint8_t)(out[t >> 2] >> (8 * (t & 3)));
+      }
+    }
+    __syncthreads();                                // s_chunk_max / s_block_max are reused by the next span
+  }
+}
+
+// 16 codes (16 bytes) per thread per load; the block index of a 16-element group is unique
+// because every block size is a multiple of 64.
+constexpr int kDeqGroup = 16;
+__global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
+    const uint8_t* __restrict__ codes, const float* __restrict__ absmax, size_t n, int block,
+    int log_block /* -1 if block is not a power of two */, uint16_t* __restrict__ out, size_t n_groups) {
+  __shared__ float s_T[256];
+  s_T[threadIdx.x] = kCodeDev.T[threadIdx.x];
+  __syncthreads();
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < n_groups; g += stride) {
+    const size_t e0 = g * kDeqGroup;
+    const size_t b = (log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block);
+    const float a = absmax[b];
+    const int valid = (int)min((size_t)kDeqGroup, n - e0);
+    v4u c = v4u{0, 0, 0, 0};
+    if (valid == kDeqGroup) {
+      c = *reinterpret_cast<const v4u*>(codes + e0);
+    } else {
+      uint32_t tmp[4] = {0, 0, 0, 0};
+      for (int t = 0; t < valid; ++t) tmp[t >> 2] |= (uint32_t)codes[e0 + t] << (8 * (t & 3));
+      c = v4u{tmp[0], tmp[1], tmp[2], tmp[3]};
+    }
+    uint32_t o[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t cw = c[w];
+      const float f0 = s_T[cw & 0xffu] * a;
+      const float f1 = s_T[(cw >> 8) & 0xffu] * a;
+      const float f2 = s_T[(cw >> 16) & 0xffu] * a;
+      const float f3 = s_T[cw >> 24] * a;
+      o[2 * w] = float_to_half_bits(f0) | (float_to_half_bits(f1) << 16);
+      o[2 * w + 1] = float_to_half_bits(f2) | (float_to_half_bits(f3) << 16);
+    }
+    if (valid == kDeqGroup) {
+      *reinterpret_cast<v4u*>(out + e0) = v4u{o[0], o[1], o[2], o[3]};
+      *reinterpret_cast<v4u*>(out + e0 + 8) = v4u{o[4], o[5], o[6], o[7]};
+    } else {
+      for (int t = 0; t < valid; ++t) out[e0 + t] = (uint16_t)(o[t >> 1] >> (16 * (t & 1)));
+    }
+  }
+}
+
+// ------------------------------------------------------------------ launchers
+static int log2_exact(int v) {
+  for (int l = 0; l < 31; ++l)
+    if ((1 << l) == v) return l;
+  return -1;
+}
+
+hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
+                                     hipStream_t stream) {
+  const int blocks_per_span = kSpanMax / block;                  // >= 1
+  const size_t span_elems = (size_t)blocks_per_span * block;
+  const size_t n_spans = (n + span_elems - 1) / span_elems;
+  const size_t max_grid = (size_t)device_cu_count() * 8;
+  const dim3 grid((unsigned)(n_spans < max_grid ? n_spans : max_grid));
+#define MMD8_Q(L) \
+  hipLaunchKernelGGL((k_quantize_blockwise<L>), grid, dim3(kThreads), 0, stream, x, n, block, codes, absmax, \
+                     blocks_per_span, n_spans)
+  switch (log2_exact(block)) {
+    case 6: MMD8_Q(6); break;
+    case 7: MMD8_Q(7); break;
+    case 8: MMD8_Q(8); break;
+    case 9: MMD8_Q(9); break;
+    case 10: MMD8_Q(10); break;
+    case 11: MMD8_Q(11); break;
+    case 12: MMD8_Q(12); break;
+    default: MMD8_Q(-1); break;
+  }
+#undef MMD8_Q
+  return hipGetLastError();
+}
+
+hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block,
+                                       uint16_t* out, hipStream_t stream) {
+  const size_t n_groups = (n + kDeqGroup - 1) / kDeqGroup;
+  const size_t wgs = (n_groups + kThreads - 1) / kThreads;
+  const size_t max_grid = (size_t)device_cu_count() * 8;
+  const dim3 grid((unsigned)(wgs < max_grid ? wgs : max_grid));
+  hipLaunchKernelGGL(k_dequantize_blockwise, grid, dim3(kThreads), 0, stream, codes, absmax, n, block,
+                     log2_exact(block), out, n_groups);
+  return hipGetLastError();
+}
+
+}  // namespace mmd8

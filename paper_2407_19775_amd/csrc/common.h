@@ -1,0 +1,58 @@
+// Shared host/device helpers for the mmd8 library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/mmd8.h"
+
+namespace mmd8 {
+
+constexpr int kWave = 64;
+
+typedef int      v4i  __attribute__((ext_vector_type(4)));
+typedef int      v2i  __attribute__((ext_vector_type(2)));
+typedef int      v16i __attribute__((ext_vector_type(16)));
+typedef float    v16f __attribute__((ext_vector_type(16)));
+typedef float    v4f  __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h  __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h  __attribute__((ext_vector_type(2)));
+typedef uint32_t v4u  __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u  __attribute__((ext_vector_type(2)));
+
+__host__ __device__ constexpr inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+__host__ __device__ constexpr inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+__host__ __device__ constexpr inline size_t round_up_sz(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// fp16 bit pattern -> fp32 (exact).  The low/high halves of a packed dword.
+__device__ inline float half_lo_to_float(uint32_t w) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+}
+__device__ inline float half_hi_to_float(uint32_t w) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+}
+// fp32 -> fp16 bit pattern, round to nearest even.
+__device__ inline uint32_t float_to_half_bits(float f) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// ---- wave-wide max of a u32 held by every lane (DPP row shifts + row broadcasts); result valid in lane 63
+template <int kCtrl>
+__device__ inline uint32_t dpp_mov(uint32_t v) {
+  // lanes without a source keep their own value (old = v, bound_ctrl off)
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, kCtrl, 0xf, 0xf, false);
+}
+__device__ inline uint32_t wave_max_u32_to_lane63(uint32_t v) {
+  v = max(v, dpp_mov<0x111>(v));   // row_shr:1
+  v = max(v, dpp_mov<0x112>(v));   // row_shr:2
+  v = max(v, dpp_mov<0x114>(v));   // row_shr:4
+  v = max(v, dpp_mov<0x118>(v));   // row_shr:8   -> lane 15 of each row of 16 holds the row max
+  v = max(v, dpp_mov<0x142>(v));   // row_bcast:15 -> lanes 31 and 63 hold the max of their 32
+  v = max(v, dpp_mov<0x143>(v));   // row_bcast:31 -> lane 63 holds the wave max
+  return v;
+}
+__device__ inline uint32_t wave_max_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_max_u32_to_lane63(v), 63);
+}
+
+int device_cu_count();   // compute units of the current device (cached per device)
+
+}  // namespace mmd8

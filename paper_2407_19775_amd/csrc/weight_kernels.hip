@@ -1,0 +1,108 @@
+// Weight pre-quantization ("Compression techniques", item 2): per-column absmax, int8 codes,
+// and the packed layout the GEMM streams.
+//
+// Packed layout: the transposed code matrix Wt[n][k] (k contiguous), N padded to a multiple of
+// kPackN rows and K to a multiple of kPackK bytes, padding filled with zeros.  Both GEMM
+// operands are then K-contiguous, which is what the int8 MFMA fragments want (16 consecutive k
+// per lane).
+#include "common.h"
+#include "weight_layout.h"
+
+namespace mmd8 {
+
+// c[n] = max_k |W[k,n]| via atomicMax on the bit pattern of the non-negative float; c must be
+// zero on entry.  Thread = 8 columns (16 bytes), workgroup = 32 column groups x 8 row lanes.
+__global__ __launch_bounds__(256) void k_col_absmax(const uint16_t* __restrict__ W, int K, int N, int ldw,
+                                                    uint32_t* __restrict__ c_bits) {
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int n0 = (blockIdx.x * 32 + cg) * 8;
+  if (n0 >= N) return;
+  uint32_t m[4] = {0, 0, 0, 0};
+  for (int k = blockIdx.y * 8 + rl; k < K; k += gridDim.y * 8) {
+    const v4u raw = *reinterpret_cast<const v4u*>(W + (size_t)k * ldw + n0);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+      const us2 a = __builtin_bit_cast(us2, raw[w] & 0x7fff7fffu);
+      m[w] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, m[w]), a));
+    }
+  }
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    atomicMax(c_bits + n0 + 2 * w, __float_as_uint(half_lo_to_float(m[w])));
+    atomicMax(c_bits + n0 + 2 * w + 1, __float_as_uint(half_hi_to_float(m[w])));
+  }
+}
+
+// One workgroup converts a tile of 128 k x 64 n and writes it transposed through LDS.
+constexpr int kTileK = 128, kTileN = 64;
+__device__ inline uint32_t weight_code(float w, float scale) {
+  float q = __builtin_rintf(w * scale);
+  q = fminf(fmaxf(q, -127.0f), 127.0f);
+  return (uint32_t)((int)q) & 0xffu;
+}
+__global__ __launch_bounds__(256) void k_weight_quant_pack(const uint16_t* __restrict__ W, int K, int N, int ldw,
+                                                           const float* __restrict__ c,
+                                                           int8_t* __restrict__ Wt, int Kpad) {
+  __shared__ uint8_t s_tile[kTileN][kTileK + 16];
+  const int kt0 = blockIdx.x * kTileK, nt0 = blockIdx.y * kTileN;
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;          // 8 column groups x 32 row lanes
+  const int n0 = nt0 + cg * 8;
+  float scale[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float cn = (n0 + t < N) ? c[n0 + t] : 0.0f;
+    scale[t] = (cn == 0.0f) ? 0.0f : 127.0f / cn;                  // IEEE division
+  }
+#pragma unroll
+  for (int pass = 0; pass < kTileK / 32; ++pass) {
+    const int kl = pass * 32 + rl, k = kt0 + kl;
+    v4u raw = v4u{0, 0, 0, 0};
+    if (k < K && n0 < N) raw = *reinterpret_cast<const v4u*>(W + (size_t)k * ldw + n0);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      s_tile[cg * 8 + 2 * w][kl] = (uint8_t)weight_code(half_lo_to_float(raw[w]), scale[2 * w]);
+      s_tile[cg * 8 + 2 * w + 1][kl] = (uint8_t)weight_code(half_hi_to_float(raw[w]), scale[2 * w + 1]);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < (kTileN * kTileK / 16) / 256; ++pass) {
+    const int ch = pass * 256 + threadIdx.x;                       // 16-byte chunk of the tile
+    const int nl = ch / (kTileK / 16), kc = ch % (kTileK / 16);
+    const v4u v = *reinterpret_cast<const v4u*>(&s_tile[nl][kc * 16]);
+    *reinterpret_cast<v4u*>(Wt + (size_t)(nt0 + nl) * Kpad + kt0 + kc * 16) = v;
+  }
+}
+
+__global__ void k_weight_unpack(const int8_t* __restrict__ Wt, int K, int N, int Kpad,
+                                int8_t* __restrict__ Wq) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)K * N) return;
+  const int k = (int)(i / N), n = (int)(i % N);
+  Wq[i] = Wt[(size_t)n * Kpad + k];
+}
+
+hipError_t launch_col_absmax(const uint16_t* W, int K, int N, int ldw, float* c, hipStream_t stream) {
+  const int ysplit = max(1, min(ceil_div(K, 8), 4096 / max(1, ceil_div(N, 256))));
+  hipLaunchKernelGGL(k_col_absmax, dim3(ceil_div(N, 256), ysplit), dim3(256), 0, stream, W, K, N, ldw,
+                     reinterpret_cast<uint32_t*>(c));
+  return hipGetLastError();
+}
+
+hipError_t launch_weight_quant_pack(const uint16_t* W, int K, int N, int ldw, const float* c, int8_t* Wt,
+                                    hipStream_t stream) {
+  const int Kpad = packed_k(K), Npad = packed_n(N);
+  hipLaunchKernelGGL(k_weight_quant_pack, dim3(Kpad / kTileK, Npad / kTileN), dim3(256), 0, stream, W, K, N, ldw,
+                     c, Wt, Kpad);
+  return hipGetLastError();
+}
+
+hipError_t launch_weight_unpack(const int8_t* Wt, int K, int N, int8_t* Wq, hipStream_t stream) {
+  const size_t total = (size_t)K * N;
+  hipLaunchKernelGGL(k_weight_unpack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, Wt, K, N,
+                     packed_k(K), Wq);
+  return hipGetLastError();
+}
+
+}  // namespace mmd8

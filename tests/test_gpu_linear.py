@@ -1,0 +1,139 @@
+"""GPU parity of the mixed int8 linear layer against the CPU oracle.
+
+Bit-exact: outlier mask and index list, row absmax, activation codes, weight codes and scales,
+int32 accumulators.  Tolerance (fp16 output): 1e-2 relative, see gpu_util.assert_y_close.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixed_linear as ml
+from paper_2407_19775_amd import binding, workloads as wl
+from gpu_util import assert_y_close, to_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def check_weight(W: np.ndarray):
+    pw = binding.prequantize_weight(to_gpu(W))
+    Wq_o, c_o = ml.prequantize_weight(W)
+    assert np.array_equal(to_np(pw.col_absmax).view(np.uint32), c_o.view(np.uint32)), "column absmax"
+    Wq_g = to_np(binding.unpack_weight(pw))
+    bad = np.argwhere(Wq_g != Wq_o)
+    assert bad.shape[0] == 0, ("weight codes", bad[:5])
+    return pw, Wq_o, c_o
+
+
+def check_linear(X, W, tau, bias=None, rows=None, pw_pack=None):
+    """Runs the layer on the GPU with all taps and compares with the oracle (on `rows` only for
+    the per-row outputs when given)."""
+    pw, Wq_o, c_o = pw_pack if pw_pack is not None else check_weight(W)
+    Xg = to_gpu(X)
+    bg = to_gpu(bias) if bias is not None else None
+    Y, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)
+    Y2 = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                 # the untapped path
+    torch.cuda.synchronize()
+    o = ml.mixed_int8_linear(X, Wq_o, c_o, tau, bias, rows=rows)
+    sel = slice(None) if rows is None else np.asarray(rows)
+    assert np.array_equal(to_np(taps["outlier_mask"]).astype(bool), o["flag"]), "outlier mask"
+    n_o = int(to_np(taps["n_outliers"])[0])
+    assert n_o == o["outlier_idx"].size
+    assert np.array_equal(to_np(taps["outlier_idx"])[:n_o], o["outlier_idx"]), "outlier index list"
+    assert np.array_equal(to_np(taps["row_absmax"])[sel].view(np.uint32), o["r"].view(np.uint32)), "row absmax"
+    assert np.array_equal(to_np(taps["xq"])[sel], o["Xq"]), "activation codes"
+    acc_g = to_np(taps["acc"])[sel]
+    bad = np.argwhere(acc_g != o["acc"])
+    assert bad.shape[0] == 0, ("int32 accumulators", bad[:5])
+    Yg = to_np(Y)
+    assert np.array_equal(Yg.view(np.uint16), to_np(Y2).view(np.uint16)), "tapped and untapped outputs differ"
+    return assert_y_close(Yg[sel], o["Y"])
+
+
+def test_config1_tiny():
+    cfg = wl.config1()
+    check_linear(cfg["X"], cfg["W"], cfg["tau"])
+    mask = ml.outlier_mask(cfg["X"], cfg["tau"])
+    assert np.array_equal(np.flatnonzero(mask), cfg["planted"])
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 16, 8), (5, 144, 40), (77, 272, 264), (130, 1040, 520), (300, 512, 1000)])
+@pytest.mark.parametrize("tau", [6.0, float("inf"), 0.0, 2.5])
+def test_ragged_shapes_and_thresholds(M, K, N, tau):
+    rng = np.random.default_rng([M, K, N])
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.integers(0, K, max(1, K // 100))] *= 15.0
+    W = wl.gaussian_weight(K, N, 0.02, rng)
+    bias = wl.gaussian_bias(N, 0.1, rng) if N % 16 == 8 else None
+    check_linear(wl.to_fp16(x), W, tau, bias=bias)
+
+
+def test_zero_row_zero_column_and_all_zero_input():
+    rng = np.random.default_rng(1)
+    X = wl.to_fp16(rng.standard_normal((40, 256)).astype(np.float32))
+    W = wl.gaussian_weight(256, 72, 0.02, rng)
+    X[3, :] = 0
+    W[:, 5] = 0
+    check_linear(X, W, 6.0)
+    check_linear(np.zeros((9, 64), np.float16), wl.gaussian_weight(64, 16, 0.02, rng), 6.0)
+
+
+def test_row_stride_larger_than_k():
+    rng = np.random.default_rng(2)
+    big = wl.to_fp16(rng.standard_normal((33, 512)).astype(np.float32) * 3)
+    W = wl.gaussian_weight(256, 64, 0.02, rng)
+    pw = binding.prequantize_weight(to_gpu(W))
+    Xg = to_gpu(big)[:, :256]
+    assert Xg.stride(0) == 512
+    Y = to_np(binding.mixed_int8_linear(Xg, pw, 6.0))
+    Wq_o, c_o = ml.prequantize_weight(W)
+    o = ml.mixed_int8_linear(np.ascontiguousarray(big[:, :256]), Wq_o, c_o, 6.0)
+    assert_y_close(Y, o["Y"])
+
+
+def test_empty_batch():
+    pw = binding.prequantize_weight(to_gpu(wl.gaussian_weight(64, 16, 0.02, np.random.default_rng(0))))
+    Y = binding.mixed_int8_linear(torch.empty((0, 64), dtype=torch.float16, device="cuda"), pw, 6.0)
+    assert Y.shape == (0, 16)
+
+
+def test_repeated_calls_are_deterministic():
+    cfg = wl.config1()
+    pw = binding.prequantize_weight(to_gpu(cfg["W"]))
+    Xg = to_gpu(cfg["X"])
+    ws = binding.linear_workspace(16, 1024, 1024, "cuda")
+    ref = None
+    for _ in range(3):
+        Y, taps = binding.mixed_int8_linear(Xg, pw, 6.0, workspace=ws, taps=True)
+        h = (to_np(Y).tobytes(), to_np(taps["acc"]).tobytes(), to_np(taps["xq"]).tobytes())
+        ref = ref or h
+        assert h == ref
+
+
+@pytest.mark.parametrize("M", [1, 8, 32, 64])
+@pytest.mark.parametrize("shape", [wl.LLAMA_7B_LINEARS[1], wl.LLAMA_7B_LINEARS[3]], ids=lambda s: s.name)
+def test_config3_decode_shapes(M, shape):
+    """Student-t decode activations: up to ~45 % of the feature dimensions are critical."""
+    X = wl.decode_activation(10 * M + shape.K % 7, M, shape.K)
+    W = wl.prefill_weight(3, 100 + shape.K % 7, shape, 0.02)
+    check_linear(X, W, wl.TAU)
+
+
+@pytest.mark.parametrize("shape", wl.LLAMA_7B_LINEARS, ids=lambda s: s.name)
+def test_config2_prefill_full_size(shape):
+    """The launches the benchmark times (2048 tokens), compared in full."""
+    X, dims = wl.prefill_activation(2, 10 + shape.K % 5, 2048, shape.K)
+    W = wl.prefill_weight(2, 20 + wl.LLAMA_7B_LINEARS.index(shape), shape, 0.02)
+    fro, worst = check_linear(X, W, wl.TAU)
+    flag = ml.outlier_mask(X, wl.TAU)
+    assert set(dims.tolist()) <= set(np.flatnonzero(flag).tolist())
+
+
+@pytest.mark.parametrize("shape", wl.LLAMA_70B_LINEARS, ids=lambda s: s.name)
+def test_config5_prefill_full_size_sampled_rows(shape):
+    """70B-shaped linears at full size (4096 tokens).  Weight codes, mask and index list are
+    compared in full; the per-row outputs on 48 sampled rows (every value of those rows)."""
+    X, _ = wl.prefill_activation(5, 10 + shape.K % 5, 4096, shape.K)
+    W = wl.prefill_weight(5, 20 + wl.LLAMA_70B_LINEARS.index(shape), shape, 0.015)
+    rows = np.sort(np.random.default_rng(shape.N).choice(4096, 48, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    check_linear(X, W, wl.TAU, rows=rows)

@@ -1,0 +1,109 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, its host
+tables equal the oracle's, and its argument checks reject bad calls before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import dynamic_code as dc
+from paper_2407_19775_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(binding.LIB_PATH),
+                                reason="libmmd8.so not built (python -m paper_2407_19775_amd.build)")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mmd8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mmd8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert len(names) >= 12
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for name in names:
+        assert hasattr(L, name), name
+    for name in binding.EXPORTS:
+        assert name in names
+
+
+def test_host_tables_equal_the_oracle_bit_for_bit():
+    T = binding.code_table().numpy()
+    Mid = binding.code_midpoints().numpy()
+    assert T.tobytes() == dc.code_table().tobytes()
+    assert Mid.tobytes() == dc.midpoints().tobytes()
+
+
+def test_threshold_pattern_is_the_fp16_ceiling():
+    L = binding.lib()
+    finite = np.arange(0, 0x7c00, dtype=np.uint16)
+    vals = finite.view(np.float16).astype(np.float64)
+    rng = np.random.default_rng(0)
+    taus = np.concatenate([
+        vals[rng.integers(0, vals.size, 300)],                           # exactly representable
+        vals[rng.integers(1, vals.size, 300)] * (1 - 1e-4),              # just below a value
+        vals[rng.integers(0, vals.size - 1, 300)] * (1 + 1e-4) + 1e-12,  # just above a value
+        [6.0, 0.0, -1.0, 1e-9, 5.96e-8, 6.0e-8, 65504.0, 65505.0, 1e9, np.inf, 6.1e-5, 6.2e-5],
+    ]).astype(np.float32)
+    for tau in taus:
+        got = L.mmd8_threshold_fp16_pattern(float(tau))
+        if tau <= 0:
+            want = 0
+        else:
+            above = np.flatnonzero(vals >= np.float64(tau))
+            want = int(above[0]) if above.size else 0x7c00
+        assert got == want, (tau, got, want)
+
+
+def test_sizes_and_layout_tag():
+    L = binding.lib()
+    assert L.mmd8_packed_weight_layout() != 0
+    assert L.mmd8_packed_weight_bytes(4096, 12288) >= 4096 * 12288
+    assert L.mmd8_packed_weight_bytes(4096, 12288) % 256 == 0
+    assert L.mmd8_packed_weight_bytes(4095, 12288) == 0        # K % 16
+    assert L.mmd8_packed_weight_bytes(4096, 12) == 0           # N % 8
+    assert L.mmd8_packed_weight_bytes(1 << 20, 64) == 0        # K too large
+    assert L.mmd8_linear_workspace_bytes(2048, 4096, 4096) >= 2048 * 4096
+    assert L.mmd8_linear_workspace_bytes(0, 4096, 4096) > 0
+    assert L.mmd8_linear_workspace_bytes(-1, 4096, 4096) == 0
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)         # aligned, never dereferenced: every call below must fail first
+    odd = ctypes.c_void_p(0x1002)
+    assert L.mmd8_quantize_blockwise(fake, 1024, 100, fake, fake, None) == -2      # block % 64
+    assert L.mmd8_quantize_blockwise(fake, 1024, 8192, fake, fake, None) == -2     # block > 4096
+    assert L.mmd8_quantize_blockwise(None, 1024, 256, fake, fake, None) == -1
+    assert L.mmd8_quantize_blockwise(odd, 1024, 256, fake, fake, None) == -1
+    assert L.mmd8_quantize_blockwise(None, 0, 256, None, None, None) == 0          # empty is fine
+    assert L.mmd8_dequantize_blockwise(fake, None, 1024, 256, fake, None) == -1
+    assert L.mmd8_dequantize_blockwise(None, None, 0, 64, None, None) == 0
+    assert L.mmd8_prequantize_weight(fake, 100, 64, 64, fake, fake, None) == -2    # K % 16
+    assert L.mmd8_prequantize_weight(fake, 128, 64, 32, fake, fake, None) == -1    # ldw < N
+    assert L.mmd8_prequantize_weight(fake, 128, 64, 64, None, fake, None) == -1
+    ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
+    args = dict(X=fake, M=8, K=128, ldx=128, W=fake, c=fake, N=64, bias=None, tau=6.0, Y=ctypes.c_void_p(0x2000),
+                ldy=64, ws=fake, wsb=ws)
+
+    def call(**kw):
+        a = dict(args, **kw)
+        return L.mmd8_mixed_int8_linear(a["X"], a["M"], a["K"], a["ldx"], a["W"], a["c"], a["N"], a["bias"],
+                                        a["tau"], a["Y"], a["ldy"], a["ws"], a["wsb"], None, None)
+
+    assert call(K=100) == -2
+    assert call(N=60) == -2
+    assert call(tau=float("nan")) == -1
+    assert call(ldx=64) == -1
+    assert call(ldy=60) == -1
+    assert call(Y=fake) == -1                                                      # aliasing X
+    assert call(wsb=ws - 1) == -3
+    assert call(X=None) == -1
+    assert call(M=-1) == -1
+    assert call(M=0, X=None, Y=None, ws=None, wsb=0) == 0                          # empty is fine
+    assert b"workspace" in L.mmd8_status_string(-3)

@@ -194,3 +194,13 @@ def test_threshold_comparison_is_inclusive():
     X = np.array([[6.0, 5.9960938]], np.float16)
     assert np.array_equal(ml.outlier_mask(X, 6.0), [True, False])
     assert ml.row_absmax(X, 6.0)[0] == np.float32(5.9960938)
+
+
+def test_row_sampling_matches_full_run():
+    X, W = rand_case(9, 10, 48, 7, outlier_cols=(3,))
+    full = ml.linear_from_fp16_weight(X, W, 6.0)
+    rows = np.array([7, 0, 4])
+    part = ml.linear_from_fp16_weight(X, W, 6.0, rows=rows)
+    assert np.array_equal(part["flag"], full["flag"])
+    for key in ("r", "Xq", "acc", "Y"):
+        assert np.array_equal(part[key], full[key][rows])
