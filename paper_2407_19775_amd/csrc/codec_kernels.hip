@@ -157,8 +157,8 @@ __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
       const float f1 = s_T[(cw >> 8) & 0xffu] * a;
       const float f2 = s_T[(cw >> 16) & 0xffu] * a;
       const float f3 = s_T[cw >> 24] * a;
-      o[2 * w] = float_to_half_bits(f0) | (float_to_half_bits(f1) << 16);
-      o[2 * w + 1] = float_to_half_bits(f2) | (float_to_half_bits(f3) << 16);
+      o[2 * w] = rounded_float_to_half_bits(f0) | (rounded_float_to_half_bits(f1) << 16);
+      o[2 * w + 1] = rounded_float_to_half_bits(f2) | (rounded_float_to_half_bits(f3) << 16);
     }
     if (valid == kDeqGroup) {
       *reinterpret_cast<v4u*>(out + e0) = v4u{o[0], o[1], o[2], o[3]};

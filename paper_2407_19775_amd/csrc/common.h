@@ -33,6 +33,13 @@ __device__ inline float half_hi_to_float(uint32_t w) {
 __device__ inline uint32_t float_to_half_bits(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
 }
+// Same, for a value that must first exist as a rounded fp32 number.  Without the empty asm the
+// compiler folds "multiply, then convert" into v_fma_mixlo_f16, which rounds the exact product
+// once; the definition of the codec and of the fp16 weights rounds twice (fp32, then fp16).
+__device__ inline uint32_t rounded_float_to_half_bits(float f) {
+  asm("" : "+v"(f));
+  return float_to_half_bits(f);
+}
 
 // ---- wave-wide max of a u32 held by every lane (DPP row shifts + row broadcasts); result valid in lane 63
 template <int kCtrl>

@@ -137,3 +137,21 @@ def test_config5_prefill_full_size_sampled_rows(shape):
     rows = np.sort(np.random.default_rng(shape.N).choice(4096, 48, replace=False))
     rows[0], rows[-1] = 0, 4095
     check_linear(X, W, wl.TAU, rows=rows)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_every_gemm_tile_configuration(variant):
+    """All tile configurations of the GEMM kernel give the same integers (and pass the output bar)."""
+    L = binding.lib()
+    L.mmd8_set_gemm_variant(variant)
+    try:
+        rng = np.random.default_rng(variant)
+        x = rng.standard_normal((300, 1040)).astype(np.float32)
+        x[:, [3, 777]] *= 25.0
+        check_linear(wl.to_fp16(x), wl.gaussian_weight(1040, 520, 0.02, rng), 6.0)
+        cfg = wl.config1()
+        check_linear(cfg["X"], cfg["W"], cfg["tau"])
+        X, _ = wl.prefill_activation(2, 99, 512, 4096)       # full tiles: the unchecked store path
+        check_linear(X, wl.gaussian_weight(4096, 512, 0.02, rng), 6.0)
+    finally:
+        L.mmd8_set_gemm_variant(-1)
