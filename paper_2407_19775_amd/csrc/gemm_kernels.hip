@@ -56,6 +56,7 @@ struct GemmCfg {
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be whole MFMA tiles");
   static_assert(NKS % 2 == 0, "fragment double buffering assumes an even number of k-steps");
   static_assert(kStages >= 3, "the slab ring needs one slab in use, one landed and one in flight");
+  static constexpr int kAhead = kStages - 1;                       // slabs requested ahead of the MFMAs
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   // epilogue staging of the critical columns: [rows][16 k] fp16 for both operands
   static constexpr int EPI_BYTES = (BM + BN) * 32;
@@ -238,13 +239,18 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
     const int r = (j * Cfg::kWaves + wave) * Cfg::ROWS_PER_DMA + lane / CPR;
     srcB[j] = a.Wt + (size_t)(n0 + r) * a.Kpad + ((lane % CPR) ^ swizzle<BK>(r)) * 16;
   }
-  auto issue_slab = [&](int slab, int stage) {
+  // request d (0 .. DMA_PER_SLAB-1) of a slab: the A rows first, then the B rows
+  auto issue_dma = [&](int slab, int stage, int d) {
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
+    if (d < Cfg::A_DMA)
+      dma16(srcA[d] + (size_t)slab * BK, base + d * Cfg::kWaves * (kWave * 16));
+    else
+      dma16(srcB[d - Cfg::A_DMA] + (size_t)slab * BK,
+            base + Cfg::A_BYTES + (d - Cfg::A_DMA) * Cfg::kWaves * (kWave * 16));
+  };
+  auto issue_slab = [&](int slab, int stage) {
 #pragma unroll
-    for (int j = 0; j < Cfg::A_DMA; ++j) dma16(srcA[j] + (size_t)slab * BK, base + j * Cfg::kWaves * (kWave * 16));
-#pragma unroll
-    for (int j = 0; j < Cfg::B_DMA; ++j)
-      dma16(srcB[j] + (size_t)slab * BK, base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
+    for (int d = 0; d < Cfg::DMA_PER_SLAB; ++d) issue_dma(slab, stage, d);
   };
 
   // ---- per-lane LDS read offsets: row (lane % 32) of an MFMA tile, chunk (2 ks + lane / 32)
@@ -273,38 +279,51 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-  // ---- software pipeline over the slab ring.  In iteration s: slab s is being multiplied, slab
-  // s+1 was requested one iteration ago, slab s+2 is requested now into the buffer that held
-  // slab s-1 (every wave finished reading it before the barrier of iteration s-1).
-  // kIssue: slab s+2 exists and is requested in this iteration; kNext: slab s+1 exists.
+  // ---- software pipeline over the slab ring.  In iteration s slab s is being multiplied and
+  // slab s + kAhead is requested into the buffer that held slab s - 1 (every wave finished
+  // reading it before the barrier that ended iteration s - 1).  At the end of iteration s the
+  // wave waits until only the requests younger than slab s + 1 are outstanding.
+  // A wave issues in order, and a request that finds the memory queue full blocks the MFMAs
+  // behind it, so the requests of a slab are spread evenly between the MFMAs of the iteration.
+  // kIssue: slab s + kAhead exists and is requested in this iteration; kNext: slab s + 1 exists.
+  constexpr int AHEAD = Cfg::kAhead;
+  constexpr int MFMAS = TI * TJ;                                   // per k-step
+  constexpr int DMA_PER_KS = Cfg::DMA_PER_SLAB / NKS;
+  static_assert(Cfg::DMA_PER_SLAB % NKS == 0 && DMA_PER_KS >= 1 && DMA_PER_KS <= MFMAS, "request spreading");
   int stage = 0;
   auto iteration = [&](int s, auto issue_tag, auto next_tag) {
     constexpr bool kIssue = decltype(issue_tag)::value, kNext = decltype(next_tag)::value;
     const int stage1 = (stage + 1 == STAGES) ? 0 : stage + 1;
-    const int stage2 = (stage1 + 1 == STAGES) ? 0 : stage1 + 1;
+    const int stage_req = (stage == 0) ? STAGES - 1 : stage - 1;   // (s + kAhead) mod kStages
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
-      // the first MFMA of the k-step goes out before any new memory operation is issued, so the
-      // wait for its fragments (read during the previous k-step) is already satisfied and the
-      // requests below run under it
-      acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][0], fb[cur][0], acc[0][0], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (ks == 0 && kIssue) issue_slab(s + 2, stage2);
-      if (ks + 1 < NKS) {
-        read_frags(stage, ks + 1, nxt);
-      } else {
-        // last k-step of the slab: make slab s+1 visible, then prefetch its first fragments
-        wait_slab_and_sync<kIssue ? Cfg::DMA_PER_SLAB : 0>();
-        if (kNext) read_frags(stage1, 0, nxt);
+#pragma unroll
+      for (int t = 0; t < MFMAS; ++t) {
+        const int i = t / TJ, j = t % TJ;
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        if (t == 0) {
+          // the first MFMA of the k-step goes out before any new LDS read, so the wait for its
+          // fragments (read during the previous k-step) is already satisfied
+          __builtin_amdgcn_sched_barrier(0);
+          if (ks + 1 < NKS) {
+            read_frags(stage, ks + 1, nxt);
+          } else {
+            // last k-step of the slab: make slab s+1 visible, then prefetch its first fragments
+            // still allowed in flight: slabs s+2 .. s+kAhead-1 in full and the part of slab
+            // s+kAhead requested during the earlier k-steps of this iteration
+            wait_slab_and_sync<kIssue ? (AHEAD - 2) * Cfg::DMA_PER_SLAB + DMA_PER_KS * (NKS - 1) : 0>();
+            if (kNext) read_frags(stage1, 0, nxt);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // requests number (t DMA_PER_KS) / MFMAS .. ((t + 1) DMA_PER_KS) / MFMAS - 1 of this k-step
+        if (kIssue && (t * DMA_PER_KS) / MFMAS != ((t + 1) * DMA_PER_KS) / MFMAS) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_dma(s + AHEAD, stage_req, ks * DMA_PER_KS + (t * DMA_PER_KS) / MFMAS);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          if (i + j > 0)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
     stage = stage1;
@@ -312,20 +331,19 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   using yes = std::true_type;
   using no = std::false_type;
 
-  issue_slab(0, 0);
-  if (n_slabs > 1) {
-    issue_slab(1, 1);
-    wait_slab_and_sync<Cfg::DMA_PER_SLAB>();
-  } else {
+  static_assert(AHEAD >= 2 && AHEAD <= 3, "prologue written for two or three slabs ahead");
+  int issued = 0;
+  for (; issued < AHEAD && issued < n_slabs; ++issued) issue_slab(issued, issued);
+  if (issued == 1)
     wait_slab_and_sync<0>();
-  }
+  else if (issued == 2)
+    wait_slab_and_sync<Cfg::DMA_PER_SLAB>();
+  else
+    wait_slab_and_sync<2 * Cfg::DMA_PER_SLAB>();
   read_frags(0, 0, 0);
   int s = 0;
-  for (; s + 2 < n_slabs; ++s) iteration(s, yes{}, yes{});
-  if (s + 1 < n_slabs) {
-    iteration(s, no{}, yes{});
-    ++s;
-  }
+  for (; s + AHEAD < n_slabs; ++s) iteration(s, yes{}, yes{});
+  for (; s + 1 < n_slabs; ++s) iteration(s, no{}, yes{});
   iteration(s, no{}, no{});
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
   // free for the epilogue, which starts with a barrier of its own before writing them
@@ -358,10 +376,24 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
 }
 
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
+  if (variant < 0) {
+    // automatic: the large tile whenever it fills the chip reasonably, else smaller tiles
+    const long tiles_256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
+    const long tiles_128x256 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
+    if (a.M > 128 && tiles_256 >= 192)
+      variant = 3;
+    else if (a.M > 64 && tiles_128x256 >= 64)
+      variant = 2;
+    else
+      variant = 0;
+  }
   switch (variant) {
     case 1: return launch_cfg<GemmCfg<256, 128, 64, 2, 2, 3, 2>>(a, stream);
     case 2: return launch_cfg<GemmCfg<128, 256, 64, 2, 2, 3, 2>>(a, stream);
     case 3: return launch_cfg<GemmCfg<256, 256, 64, 2, 4, 3, 2>>(a, stream);
+    case 4: return launch_cfg<GemmCfg<128, 256, 64, 2, 2, 4, 2>>(a, stream);
+    case 5: return launch_cfg<GemmCfg<256, 256, 64, 4, 2, 4, 2>>(a, stream);
+    case 6: return launch_cfg<GemmCfg<256, 256, 64, 2, 4, 4, 2>>(a, stream);
     default: return launch_cfg<GemmCfg<128, 128, 64, 2, 2, 3, 2>>(a, stream);
   }
 }
