@@ -6,10 +6,22 @@
 // and  t = a - th  (mod 2^16) has its top bit set exactly for the sub-threshold entries while
 // keeping their order; a single unsigned max of t therefore yields the row scale.
 #include "common.h"
+#include "gemm.h"
+#include "weight_layout.h"
 
 namespace mmd8 {
 
 constexpr int kThreads = 256;
+
+struct PackOutliers {   // operands of the critical-column slab, written alongside the int8 codes
+  const int32_t* idx;
+  const int32_t* n_out;
+  const int8_t* Wt;
+  const float* c;
+  int N;
+  uint16_t* Xo;
+  uint16_t* Wo;
+};
 
 __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -134,10 +146,40 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
   q = fminf(fmaxf(q, -127.0f), 127.0f);
   return (uint32_t)((int)q) & 0xffu;
 }
+// Rows of the critical-column slab, 8 columns (16 bytes) per thread: Xo[m][j] = X[m, O_j] for
+// the first kOutlierSlab critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
+// j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).
+__device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int Kpad,
+                                           const PackOutliers& o, int item) {
+  const int row = item / (kOutlierSlab / 8), j0 = (item % (kOutlierSlab / 8)) * 8;
+  if (row >= M + o.N) return;
+  const int n_out = min(*o.n_out, kOutlierSlab);
+  uint32_t out[4] = {0, 0, 0, 0};
+  if (row < M) {
+    for (int t = 0; t < 8 && j0 + t < n_out; ++t)
+      out[t >> 1] |= (uint32_t)X[(size_t)row * ldx + o.idx[j0 + t]] << (16 * (t & 1));
+    *reinterpret_cast<v4u*>(o.Xo + (size_t)row * kOutlierSlab + j0) = v4u{out[0], out[1], out[2], out[3]};
+  } else {
+    const int n = row - M;
+    const float step = o.c[n] / 127.0f;
+    for (int t = 0; t < 8 && j0 + t < n_out; ++t) {
+      const float w = (float)o.Wt[(size_t)n * Kpad + o.idx[j0 + t]] * step;
+      out[t >> 1] |= rounded_float_to_half_bits(w) << (16 * (t & 1));
+    }
+    *reinterpret_cast<v4u*>(o.Wo + (size_t)n * kOutlierSlab + j0) = v4u{out[0], out[1], out[2], out[3]};
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ X, int M, int K, int ldx,
                                                    const uint8_t* __restrict__ flag,
                                                    const float* __restrict__ r, int8_t* __restrict__ Xq,
-                                                   int Kpad, int8_t* __restrict__ tap_xq) {
+                                                   int Kpad, int8_t* __restrict__ tap_xq, int pack_blocks_y,
+                                                   const PackOutliers o) {
+  if ((int)blockIdx.y >= pack_blocks_y) {                         // the extra blocks prepare the slab
+    const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
+    gather_outlier_slab(X, M, ldx, Kpad, o, b * kThreads + threadIdx.x);
+    return;
+  }
   const int k0 = (blockIdx.x * kThreads + threadIdx.x) * 16;
   if (k0 >= Kpad) return;
   const int m0 = blockIdx.y * kPackRows;
@@ -201,9 +243,12 @@ hipError_t launch_compact(const uint8_t* flag, int K, int32_t* idx, int32_t* n_o
 }
 
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
-                       int Kpad, int8_t* tap_xq, hipStream_t stream) {
-  const dim3 grid(ceil_div(Kpad / 16, kThreads), ceil_div(M, kPackRows));
-  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, Kpad, tap_xq);
+                       int Kpad, int8_t* tap_xq, const PackOutliers& o, hipStream_t stream) {
+  const int gx = ceil_div(Kpad / 16, kThreads), pack_y = ceil_div(M, kPackRows);
+  const int slab_items = (M + o.N) * (kOutlierSlab / 8);
+  const int slab_y = ceil_div(ceil_div(slab_items, kThreads), gx);
+  const dim3 grid(gx, pack_y + slab_y);
+  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, Kpad, tap_xq, pack_y, o);
   return hipGetLastError();
 }
 

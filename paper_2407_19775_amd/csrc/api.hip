@@ -18,8 +18,17 @@ hipError_t launch_dequantize_blockwise(const uint8_t*, const float*, size_t, int
 hipError_t launch_fill_u32(uint32_t*, uint32_t, int, hipStream_t);
 hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, uint8_t*, float*, hipStream_t);
 hipError_t launch_compact(const uint8_t*, int, int32_t*, int32_t*, uint8_t*, int32_t*, int32_t*, hipStream_t);
+struct PackOutliers {   // operands of the critical-column slab, written alongside the int8 codes
+  const int32_t* idx;
+  const int32_t* n_out;
+  const int8_t* Wt;
+  const float* c;
+  int N;
+  uint16_t* Xo;
+  uint16_t* Wo;
+};
 hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*,
-                       hipStream_t);
+                       const PackOutliers&, hipStream_t);
 hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
 hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
 hipError_t launch_weight_unpack(const int8_t*, int, int, int8_t*, hipStream_t);
@@ -71,12 +80,14 @@ struct Workspace {
   uint8_t* flag;       // [Kpad]
   int32_t* n_out;      // [1] (64 bytes reserved)
   int32_t* idx;        // [Kpad]
-  float* r;            // [Mpad]
+  float* r;            // [Mpad + 256]
+  uint16_t* xo;        // [Mpad][kOutlierSlab]
+  uint16_t* wo;        // [Npad][kOutlierSlab]
   int8_t* xq;          // [Mpad][Kpad]
   size_t bytes;
 };
-static Workspace carve(void* base, int M, int K) {
-  const size_t Kpad = packed_k(K), Mpad = packed_n(M);
+static Workspace carve(void* base, int M, int K, int N) {
+  const size_t Kpad = packed_k(K), Mpad = packed_n(M), Npad = packed_n(N);
   Workspace w;
   size_t off = 0;
   auto take = [&](size_t n) {
@@ -87,7 +98,9 @@ static Workspace carve(void* base, int M, int K) {
   w.flag = take(Kpad);
   w.n_out = reinterpret_cast<int32_t*>(take(64));
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
-  w.r = reinterpret_cast<float*>(take(Mpad * 4));
+  w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
+  w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2));
+  w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2));
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
   w.bytes = off;
   return w;
@@ -166,7 +179,7 @@ int mmd8_unpack_weight(const int8_t* Wq_packed, int K, int N, int8_t* Wq_rowmajo
 
 size_t mmd8_linear_workspace_bytes(int M, int K, int N) {
   if (M < 0 || check_linear_shape(K, N) != MMD8_OK) return 0;
-  return carve(nullptr, M, K).bytes;
+  return carve(nullptr, M, K, N).bytes;
 }
 
 int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
@@ -182,7 +195,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
       !aligned(col_absmax, 4) || (bias && !aligned(bias, 2)))
     return MMD8_E_ARG;
   if (static_cast<const void*>(X) == static_cast<const void*>(Y)) return MMD8_E_ARG;
-  const Workspace ws = carve(workspace, M, K);
+  const Workspace ws = carve(workspace, M, K, N);
   if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -200,7 +213,8 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   if (launch_scan(X, M, K, ldx, threshold_pattern(tau), ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
   if (launch_compact(ws.flag, K, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers, st) != hipSuccess)
     return MMD8_E_HIP;
-  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, st) != hipSuccess) return MMD8_E_HIP;
+  const PackOutliers po = {ws.idx, ws.n_out, Wq_packed, col_absmax, N, ws.xo, ws.wo};
+  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, po, st) != hipSuccess) return MMD8_E_HIP;
   if (t.row_absmax &&
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MMD8_E_HIP;
@@ -218,6 +232,8 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   g.ldx = ldx;
   g.idx = ws.idx;
   g.n_out = ws.n_out;
+  g.Xo = ws.xo;
+  g.Wo = ws.wo;
   g.Y = Y;
   g.ldy = ldy;
   g.tap_acc = t.acc;

@@ -4,25 +4,30 @@
 
 namespace mmd8 {
 
+// Critical columns handled on the fast path: they travel as one extra 64-byte K-slab of fp16
+// operands (32 columns).  Columns beyond that go through the gather loop of the epilogue.
+constexpr int kOutlierSlab = 32;
+
 struct GemmArgs {
   const int8_t* Xq;      // [Mpad][Kpad]
   const int8_t* Wt;      // [Npad][Kpad]
   int M, N, Kpad;
-  const float* r;        // [M]
+  const float* r;        // [Mpad + 256]
   const float* c;        // [N]
   const uint16_t* bias;  // [N] or null
-  const uint16_t* X;     // [M][ldx] fp16 (critical columns are read from here)
+  const uint16_t* X;     // [M][ldx] fp16 (critical columns beyond the slab are read from here)
   int ldx;
   const int32_t* idx;    // ascending critical columns
   const int32_t* n_out;  // their count
+  const uint16_t* Xo;    // [Mpad][kOutlierSlab] fp16: X[m, O_j], zero for j >= n_out
+  const uint16_t* Wo;    // [Npad][kOutlierSlab] fp16: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   uint16_t* Y;
   int ldy;
   int32_t* tap_acc;      // [M][N] or null
   int tiles_m, tiles_n;
 };
 
-
-// variant selects a tile configuration; every variant computes the same result.
+// variant selects a tile configuration (< 0: automatic); every variant computes the same result.
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream);
 
 }  // namespace mmd8

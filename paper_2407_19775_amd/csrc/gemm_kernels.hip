@@ -7,14 +7,18 @@
 //
 // Both operands are K-contiguous byte matrices padded to whole tiles (rows to kPackN, K to
 // kPackK), so the main loop has no bounds checks.  A workgroup owns one BM x BN tile of Y.
-// K is walked in slabs of BK bytes.  A slab of both operands goes from global memory straight
-// into LDS (global_load_lds_dwordx4: no register staging) through a ring of LDS buffers, two
-// slabs ahead of the MFMAs.  LDS rows are BK bytes; the 16-byte chunks of a row are XOR-swizzled
-// with a function of the row so that the rows read by neighbouring lanes of a ds_read_b128 fall
-// in distinct banks.  A lane's 16 bytes feed one operand row of the 32x32x32 MFMA; the k order
-// inside the instruction is irrelevant as long as both operands use the same chunk for the same
-// lane group, which they do.  Operand fragments are double-buffered in registers, so the LDS
-// reads of one k-step run under the MFMAs of the previous one.
+// K is walked in slabs of 64 bytes.  A slab of both operands goes from global memory straight
+// into LDS (global_load_lds_dwordx4: no register staging) through a ring of LDS buffers, two or
+// three slabs ahead of the MFMAs.  LDS rows are 64 bytes; the four 16-byte chunks of a row are
+// XOR-swizzled with a function of the row so that the rows read by neighbouring lanes of a
+// ds_read_b128 fall in distinct banks.  A lane's 16 bytes feed one operand row of the 32x32x32
+// MFMA; the k order inside the instruction is irrelevant as long as both operands use the same
+// chunk for the same lane group, which they do.
+//
+// Two kernels share these pieces:
+//   k_gemm_mixed     4 waves, small tiles, fragments double-buffered in registers (small problems)
+//   k_gemm_pingpong  8 waves, 256 x 256 tile: the two waves of a SIMD alternate between a memory
+//                    phase and an MFMA phase, so the matrix pipe always has a wave feeding it
 #include <type_traits>
 
 #include "common.h"
@@ -23,105 +27,117 @@
 
 namespace mmd8 {
 
-template <int kBK>
-__device__ inline int swizzle(int r) {
-  if constexpr (kBK == 64) {
-    // 4 chunks per row: distinct for rows {r, r+2, r+4, r+6} and for rows {r, r+4, r+8, r+12}
-    return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1);
-  } else {
-    // 8 chunks per row: a bijection of rows r..r+7 and, for fixed parity, of r, r+2, .., r+14
-    return ((r >> 1) & 3) | ((((r) ^ (r >> 3)) & 1) << 2);
-  }
-}
+constexpr int BK = 64;                  // bytes of K per slab
+constexpr int CPR = BK / 16;            // 16-byte chunks per LDS row
+constexpr int ROWS_PER_DMA = kWave / CPR;
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int WAVES_PER_SIMD_>
+// chunk swizzle: distinct for rows {r, r+2, r+4, r+6} and for rows {r, r+4, r+8, r+12}
+__device__ inline int swizzle(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_, int WAVES_PER_SIMD_>
 struct GemmCfg {
   static constexpr int kWavesPerSimd = WAVES_PER_SIMD_;           // register budget: 512 / this
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int kWaves = WAVES_M * WAVES_N;
   static constexpr int kThreads = kWaves * kWave;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int TI = WM / 32, TJ = WN / 32;                 // MFMA tiles per wave
   static constexpr int NKS = BK / 32;                              // MFMA k-steps per slab
-  static constexpr int CPR = BK / 16;                              // 16-byte chunks per LDS row
-  static constexpr int ROWS_PER_DMA = kWave / CPR;                 // rows covered by one wave-wide DMA
   static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int kStages = STAGES_;
-  static constexpr int LDS_BYTES = STAGE_BYTES * kStages;
+  static constexpr int RING_BYTES = STAGE_BYTES * kStages;
+  static constexpr int R_BYTES = 1024;                             // 256 row scales, one DMA instruction
+  static constexpr int LDS_BYTES = RING_BYTES + R_BYTES;
   static constexpr int A_DMA = BM / ROWS_PER_DMA / kWaves;         // DMA instructions per wave per slab
   static constexpr int B_DMA = BN / ROWS_PER_DMA / kWaves;
   static constexpr int DMA_PER_SLAB = A_DMA + B_DMA;
+  static constexpr int kAhead = kStages - 1;                       // slabs requested ahead of the MFMAs
   static_assert(BM % (ROWS_PER_DMA * kWaves) == 0 && BN % (ROWS_PER_DMA * kWaves) == 0, "tile/wave mismatch");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be whole MFMA tiles");
-  static_assert(NKS % 2 == 0, "fragment double buffering assumes an even number of k-steps");
-  static_assert(kStages >= 3, "the slab ring needs one slab in use, one landed and one in flight");
-  static constexpr int kAhead = kStages - 1;                       // slabs requested ahead of the MFMAs
+  static_assert(NKS == 2, "fragment buffering below is written for two k-steps per slab");
+  static_assert(kStages >= 3 && kStages <= 4, "ring of three or four slabs");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-  // epilogue staging of the critical columns: [rows][16 k] fp16 for both operands
-  static constexpr int EPI_BYTES = (BM + BN) * 32;
-  static_assert(EPI_BYTES <= LDS_BYTES, "epilogue staging must fit in the slab buffers");
+  static_assert(BM <= 256, "row scales are staged with one 1 KB request");
+  // gather staging of critical columns beyond the slab: [rows][16 k] fp16 for both operands
+  static_assert((BM + BN) * 32 <= RING_BYTES, "epilogue staging must fit in the slab buffers");
 };
 
 // One 16-byte-per-lane global -> LDS copy (no registers in between).  Lane i's 16 bytes land at
 // lds_addr + 16 i.  Issued through asm so that the compiler does not serialise later LDS reads
-// behind it: completion is tracked by hand with vmcnt (see the main loop).
-__device__ inline void dma16(const int8_t* src, uint32_t lds_addr) {
+// behind it: completion is tracked by hand with vmcnt.
+__device__ inline void dma16(const void* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(src), "s"(lds_addr)
                : "memory");
 }
 
+// own requests older than the newest kVm have landed, own LDS reads have returned; after the
+// barrier that holds for every wave of the workgroup
 template <int kVm>
 __device__ inline void wait_slab_and_sync() {
-  // own DMA older than the newest kVm instructions has landed, own LDS reads have returned;
-  // after the barrier that holds for every wave of the workgroup
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kVm) : "memory");
 }
+__device__ inline void wait_lds_and_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); }
+__device__ inline void sync_only() { asm volatile("s_barrier" : : : "memory"); }
 
-// Epilogue of one workgroup tile.  C layout of the 32x32 MFMA: a lane holds column (lane % 32);
-// register e holds row 8 (e / 4) + 4 (lane / 32) + (e % 4).
-// kFull: the tile lies wholly inside Y, so no store needs a bounds check.
-// kTap: also write the raw int32 accumulators (parity checks).
-// The accumulators stay where the MFMAs left them: they are dequantized in place (the registers
-// then hold fp32 bits), the fp16 MFMAs of the critical columns accumulate onto them in place,
-// and each 32x32 tile is converted and stored on its own, so the working set stays small.
-template <class Cfg, bool kFull, bool kTap>
-__device__ inline void epilogue(const GemmArgs& a, v16i (&acc)[Cfg::TI][Cfg::TJ], int8_t* smem, int m0, int n0,
-                                int wm, int wn, int lane) {
-  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, TILE_M = Cfg::BM, TILE_N = Cfg::BN;
-  const int lr = lane & 31, lg = lane >> 5;
-  const int mw = m0 + wm * Cfg::WM, nw = n0 + wn * Cfg::WN;       // first row / column of the wave tile
+// tile assignment: consecutive workgroup ids land on different XCDs (8 of them), so each XCD gets
+// a contiguous run of tiles that walk M fastest: the run shares a few Wt row panels in its L2
+__device__ inline bool tile_of_block(const GemmArgs& a, int bid, int& tm, int& tn) {
+  const int n_tiles = a.tiles_m * a.tiles_n;
+  const int per_xcd = ceil_div(n_tiles, 8);
+  const int logical = (bid % 8) * per_xcd + bid / 8;
+  if (logical >= n_tiles) return false;
+  tm = logical % a.tiles_m;
+  tn = logical / a.tiles_m;
+  return true;
+}
 
-  if constexpr (kTap) {
+// ------------------------------------------------------------------------------------------------
+// Epilogue pieces.  C layout of the 32x32 MFMA: a lane holds column (lane % 32); register e holds
+// row 8 (e / 4) + 4 (lane / 32) + (e % 4).  The accumulators stay where the MFMAs left them: they
+// are dequantized in place (the registers then hold fp32 bits), the fp16 MFMAs of the critical
+// columns accumulate onto them in place, and each 32x32 tile is converted and stored on its own.
+// ------------------------------------------------------------------------------------------------
+template <class Cfg>
+struct WavePos {
+  int m0, n0, wm, wn, lane, lr, lg, mw, nw;
+  __device__ WavePos(int m0_, int n0_, int wave, int lane_)
+      : m0(m0_), n0(n0_), wm(wave / Cfg::WAVES_N), wn(wave % Cfg::WAVES_N), lane(lane_), lr(lane_ & 31),
+        lg(lane_ >> 5), mw(m0_ + (wave / Cfg::WAVES_N) * Cfg::WM), nw(n0_ + (wave % Cfg::WAVES_N) * Cfg::WN) {}
+};
+
+template <class Cfg>
+__device__ inline void tap_accumulators(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ]) {
 #pragma unroll
-    for (int i = 0; i < TI; ++i)
+  for (int i = 0; i < Cfg::TI; ++i)
 #pragma unroll
-      for (int j = 0; j < TJ; ++j) {
+    for (int j = 0; j < Cfg::TJ; ++j) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e / 4) + 4 * lg + (e % 4), n = nw + j * 32 + lr;
-          if (m < a.M && n < a.N) a.tap_acc[(size_t)m * a.N + n] = acc[i][j][e];
-        }
-        __builtin_amdgcn_sched_barrier(0);
+      for (int e = 0; e < 16; ++e) {
+        const int m = p.mw + i * 32 + 8 * (e / 4) + 4 * p.lg + (e % 4), n = p.nw + j * 32 + p.lr;
+        if (m < a.M && n < a.N) a.tap_acc[(size_t)m * a.N + n] = acc[i][j][e];
       }
-  }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
 
-  // outer-product dequantization in place: acc * r[m] * (c[n] / 127^2)
-  float cs[TJ];
+// acc := bits( acc * r[m] * (c[n] / 127^2) ).  r_tile points at the 256 (or fewer) row scales of
+// this workgroup tile, in LDS or in global memory.
+template <class Cfg, class RPtr>
+__device__ inline void dequantize_in_place(const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ], RPtr r_tile,
+                                           const float (&cs)[Cfg::TJ]) {
 #pragma unroll
-  for (int j = 0; j < TJ; ++j) cs[j] = a.c[min(nw + j * 32 + lr, a.N - 1)] / 16129.0f;
-#pragma unroll
-  for (int i = 0; i < TI; ++i) {
+  for (int i = 0; i < Cfg::TI; ++i) {
     float rm[16];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {                                  // r is padded to whole tiles: always in bounds
-      const v4f v = *reinterpret_cast<const v4f*>(a.r + mw + i * 32 + 8 * q + 4 * lg);
+    for (int q = 0; q < 4; ++q) {
+      const v4f v = *reinterpret_cast<const v4f*>(r_tile + p.wm * Cfg::WM + i * 32 + 8 * q + 4 * p.lg);
       rm[4 * q] = v[0], rm[4 * q + 1] = v[1], rm[4 * q + 2] = v[2], rm[4 * q + 3] = v[3];
     }
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) {
+    for (int j = 0; j < Cfg::TJ; ++j) {
       v16f y;
 #pragma unroll
       for (int e = 0; e < 16; ++e) y[e] = (float)acc[i][j][e] * (rm[e] * cs[j]);
@@ -129,71 +145,76 @@ __device__ inline void epilogue(const GemmArgs& a, v16i (&acc)[Cfg::TI][Cfg::TJ]
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+}
 
-  const int n_out = *a.n_out;
-  if (n_out > 0) {
-    // Critical columns, 16 at a time: stage X[m, O_j] (fp16) and f16(Wt[n, O_j] c[n] / 127) for the
-    // whole tile in LDS as [row][16] fp16, then one 32x32x16 fp16 MFMA per output tile.
-    uint16_t* sXo = reinterpret_cast<uint16_t*>(smem);             // [TILE_M][16], then [TILE_N][16]
-    uint16_t* sWo = sXo + TILE_M * 16;
-    __syncthreads();                                               // every wave is done with the slab ring
-    for (int j0 = 0; j0 < n_out; j0 += 16) {
-      for (int t = threadIdx.x; t < (TILE_M + TILE_N) * 16; t += Cfg::kThreads) {
-        const int row = t >> 4, kk = t & 15;
-        const int k = (j0 + kk < n_out) ? a.idx[j0 + kk] : -1;
-        uint16_t v = 0;
-        if (row < TILE_M) {
-          const int m = m0 + row;
-          if (k >= 0 && m < a.M) v = a.X[(size_t)m * a.ldx + k];
-        } else {
-          const int n = n0 + row - TILE_M;
-          if (k >= 0 && n < a.N) {
-            const float step = a.c[n] / 127.0f;
-            v = (uint16_t)rounded_float_to_half_bits((float)a.Wt[(size_t)n * a.Kpad + k] * step);
-          }
+// Critical columns j_begin .. n_out-1, 16 at a time: every thread helps to stage X[m, O_j] (fp16)
+// and f16(Wt[n, O_j] c[n] / 127) for the whole tile in LDS as [row][16] fp16, then one 32x32x16
+// fp16 MFMA per output tile.  Slow (gathers) and general; the slab buffers must be free.
+template <class Cfg>
+__device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+                                              int8_t* smem, int j_begin, int n_out) {
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, TILE_M = Cfg::BM, TILE_N = Cfg::BN;
+  uint16_t* sXo = reinterpret_cast<uint16_t*>(smem);             // [TILE_M][16], then [TILE_N][16]
+  uint16_t* sWo = sXo + TILE_M * 16;
+  __syncthreads();                                               // every wave is done with the slab ring
+  for (int j0 = j_begin; j0 < n_out; j0 += 16) {
+    for (int t = threadIdx.x; t < (TILE_M + TILE_N) * 16; t += Cfg::kThreads) {
+      const int row = t >> 4, kk = t & 15;
+      const int k = (j0 + kk < n_out) ? a.idx[j0 + kk] : -1;
+      uint16_t v = 0;
+      if (row < TILE_M) {
+        const int m = p.m0 + row;
+        if (k >= 0 && m < a.M) v = a.X[(size_t)m * a.ldx + k];
+      } else {
+        const int n = p.n0 + row - TILE_M;
+        if (k >= 0 && n < a.N) {
+          const float step = a.c[n] / 127.0f;
+          v = (uint16_t)rounded_float_to_half_bits((float)a.Wt[(size_t)n * a.Kpad + k] * step);
         }
-        sXo[t] = v;
       }
-      __syncthreads();
-      v8h fxa[TI], fxb[TJ];
+      sXo[t] = v;
+    }
+    __syncthreads();
+    v8h fxa[TI], fxb[TJ];
 #pragma unroll
-      for (int i = 0; i < TI; ++i)
-        fxa[i] = *reinterpret_cast<const v8h*>(sXo + (wm * Cfg::WM + i * 32 + lr) * 16 + lg * 8);
+    for (int i = 0; i < TI; ++i)
+      fxa[i] = *reinterpret_cast<const v8h*>(sXo + (p.wm * Cfg::WM + i * 32 + p.lr) * 16 + p.lg * 8);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+      fxb[j] = *reinterpret_cast<const v8h*>(sWo + (p.wn * Cfg::WN + j * 32 + p.lr) * 16 + p.lg * 8);
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
       for (int j = 0; j < TJ; ++j)
-        fxb[j] = *reinterpret_cast<const v8h*>(sWo + (wn * Cfg::WN + j * 32 + lr) * 16 + lg * 8);
-#pragma unroll
-      for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          acc[i][j] = __builtin_bit_cast(
-              v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(fxa[i], fxb[j], __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
-      __syncthreads();
-    }
+        acc[i][j] = __builtin_bit_cast(
+            v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(fxa[i], fxb[j], __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
+    __syncthreads();
   }
+}
 
-  // bias, rounding to fp16, and stores.  Neighbouring lanes hold neighbouring columns of the same
-  // rows; an even/odd lane pair swaps halves so that each lane stores two adjacent columns (4
-  // bytes): the even lane of row e, the odd lane of row e + 1.
-  const int odd = lane & 1;
-  // lane part of the store offset (elements); the row/column part is wave-uniform
-  const int lane_off = (4 * lg + odd) * a.ldy + (lr & ~1);
+// bias, rounding to fp16, and stores.  Neighbouring lanes hold neighbouring columns of the same
+// rows; an even/odd lane pair swaps halves so that each lane stores two adjacent columns (4
+// bytes): the even lane of row e, the odd lane of row e + 1.
+template <class Cfg, bool kFull>
+__device__ inline void store_tile(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+                                  const float (&bn)[Cfg::TJ]) {
+  const int odd = p.lane & 1;
+  const int lane_off = (4 * p.lg + odd) * a.ldy + (p.lr & ~1);   // lane part of the offset (elements)
 #pragma unroll
-  for (int j = 0; j < TJ; ++j) {
-    const int n = nw + j * 32 + lr;
-    const float bn = a.bias ? half_lo_to_float(a.bias[min(n, a.N - 1)]) : 0.0f;
+  for (int j = 0; j < Cfg::TJ; ++j) {
+    const int n = p.nw + j * 32 + p.lr;
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
+    for (int i = 0; i < Cfg::TI; ++i) {
       const v16f y = __builtin_bit_cast(v16f, acc[i][j]);
-      uint16_t* tile = a.Y + (size_t)(mw + i * 32) * a.ldy + nw + j * 32;   // wave-uniform
+      uint16_t* tile = a.Y + (size_t)(p.mw + i * 32) * a.ldy + p.nw + j * 32;   // wave-uniform
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const uint32_t h = float_to_half_bits(y[e] + bn) | (float_to_half_bits(y[e + 1] + bn) << 16);
-        const uint32_t p = (uint32_t)__builtin_amdgcn_mov_dpp((int)h, 0xb1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
-        const uint32_t out = odd ? ((p >> 16) | (h & 0xffff0000u)) : ((h & 0xffffu) | (p << 16));
+        const uint32_t h = float_to_half_bits(y[e] + bn[j]) | (float_to_half_bits(y[e + 1] + bn[j]) << 16);
+        const uint32_t q = (uint32_t)__builtin_amdgcn_mov_dpp((int)h, 0xb1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+        const uint32_t out = odd ? ((q >> 16) | (h & 0xffff0000u)) : ((h & 0xffffu) | (q << 16));
         const int row = 8 * (e / 4) + (e % 4);                                 // + 4 lg + odd via lane_off
         bool ok = true;
-        if constexpr (!kFull) ok = (mw + i * 32 + row + 4 * lg + odd < a.M) && ((n & ~1) < a.N);
+        if constexpr (!kFull) ok = (p.mw + i * 32 + row + 4 * p.lg + odd < a.M) && ((n & ~1) < a.N);
         if (ok) *reinterpret_cast<uint32_t*>(tile + (size_t)row * a.ldy + lane_off) = out;
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -201,26 +222,32 @@ __device__ inline void epilogue(const GemmArgs& a, v16i (&acc)[Cfg::TI][Cfg::TJ]
   }
 }
 
+template <class Cfg>
+__device__ inline void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& p, float (&cs)[Cfg::TJ],
+                                         float (&bn)[Cfg::TJ]) {
+#pragma unroll
+  for (int j = 0; j < Cfg::TJ; ++j) {
+    const int n = min(p.nw + j * 32 + p.lr, a.N - 1);
+    cs[j] = a.c[n] / 16129.0f;
+    bn[j] = a.bias ? half_lo_to_float(a.bias[n]) : 0.0f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Generic kernel: 4 waves, one wave per SIMD or two workgroups per CU, small tiles.
 // kFull: M and N are multiples of the tile, so no output store needs a bounds check.
+// kTap: also write the raw int32 accumulators (parity checks).
+// ------------------------------------------------------------------------------------------------
 template <class Cfg, bool kTap, bool kFull>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, CPR = Cfg::CPR, BK = Cfg::BK, NKS = Cfg::NKS;
-  constexpr int TILE_M = Cfg::BM, TILE_N = Cfg::BN, WAVES_N = Cfg::WAVES_N, STAGES = Cfg::kStages;
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages;
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-  // ---- tile assignment: consecutive workgroup ids land on different XCDs (8 of them), so give
-  // each XCD a contiguous run of tiles that walk M fastest: the run shares a few Wt row panels
-  // through that XCD's L2.
-  const int n_tiles = a.tiles_m * a.tiles_n;
-  const int per_xcd = ceil_div(n_tiles, 8);
-  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (logical >= n_tiles) return;
-  const int tm = logical % a.tiles_m, tn = logical / a.tiles_m;
-  const int m0 = tm * TILE_M, n0 = tn * TILE_N;
+  int tm, tn;
+  if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
+  const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
   const int n_slabs = a.Kpad / BK;
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
@@ -231,13 +258,13 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   const int8_t* srcB[Cfg::B_DMA];
 #pragma unroll
   for (int j = 0; j < Cfg::A_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * Cfg::ROWS_PER_DMA + lane / CPR;
-    srcA[j] = a.Xq + (size_t)(m0 + r) * a.Kpad + ((lane % CPR) ^ swizzle<BK>(r)) * 16;
+    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
+    srcA[j] = a.Xq + (size_t)(p.m0 + r) * a.Kpad + ((lane % CPR) ^ swizzle(r)) * 16;
   }
 #pragma unroll
   for (int j = 0; j < Cfg::B_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * Cfg::ROWS_PER_DMA + lane / CPR;
-    srcB[j] = a.Wt + (size_t)(n0 + r) * a.Kpad + ((lane % CPR) ^ swizzle<BK>(r)) * 16;
+    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
+    srcB[j] = a.Wt + (size_t)(p.n0 + r) * a.Kpad + ((lane % CPR) ^ swizzle(r)) * 16;
   }
   // request d (0 .. DMA_PER_SLAB-1) of a slab: the A rows first, then the B rows
   auto issue_dma = [&](int slab, int stage, int d) {
@@ -254,13 +281,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   };
 
   // ---- per-lane LDS read offsets: row (lane % 32) of an MFMA tile, chunk (2 ks + lane / 32)
-  const int lr = lane & 31, lg = lane >> 5;
   int a_off[NKS], b_off[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    const int ra = wm * Cfg::WM + lr, rb = wn * Cfg::WN + lr;
-    a_off[ks] = (ra * CPR + ((2 * ks + lg) ^ swizzle<BK>(ra))) * 16;
-    b_off[ks] = Cfg::A_BYTES + (rb * CPR + ((2 * ks + lg) ^ swizzle<BK>(rb))) * 16;
+    const int ra = p.wm * Cfg::WM + p.lr, rb = p.wn * Cfg::WN + p.lr;
+    a_off[ks] = (ra * CPR + ((2 * ks + p.lg) ^ swizzle(ra))) * 16;
+    b_off[ks] = Cfg::A_BYTES + (rb * CPR + ((2 * ks + p.lg) ^ swizzle(rb))) * 16;
   }
   v4i fa[2][TI], fb[2][TJ];
   auto read_frags = [&](int stage, int ks, int buf) {
@@ -309,8 +335,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
           if (ks + 1 < NKS) {
             read_frags(stage, ks + 1, nxt);
           } else {
-            // last k-step of the slab: make slab s+1 visible, then prefetch its first fragments
-            // still allowed in flight: slabs s+2 .. s+kAhead-1 in full and the part of slab
+            // last k-step of the slab: make slab s+1 visible, then prefetch its first fragments.
+            // Still allowed in flight: slabs s+2 .. s+kAhead-1 in full and the part of slab
             // s+kAhead requested during the earlier k-steps of this iteration
             wait_slab_and_sync<kIssue ? (AHEAD - 2) * Cfg::DMA_PER_SLAB + DMA_PER_KS * (NKS - 1) : 0>();
             if (kNext) read_frags(stage1, 0, nxt);
@@ -331,7 +357,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   using yes = std::true_type;
   using no = std::false_type;
 
-  static_assert(AHEAD >= 2 && AHEAD <= 3, "prologue written for two or three slabs ahead");
   int issued = 0;
   for (; issued < AHEAD && issued < n_slabs; ++issued) issue_slab(issued, issued);
   if (issued == 1)
@@ -346,33 +371,224 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   for (; s + 1 < n_slabs; ++s) iteration(s, no{}, yes{});
   iteration(s, no{}, no{});
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
-  // free for the epilogue, which starts with a barrier of its own before writing them
+  // free for the gather staging, which starts with a barrier of its own before writing them
 
-  // ------------------------------------------------------------------ epilogue
-  epilogue<Cfg, kFull, kTap>(a, acc, smem, m0, n0, wm, wn, lane);
+  if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
+  float cs[TJ], bn[TJ];
+  load_column_terms<Cfg>(a, p, cs, bn);
+  dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
+  const int n_out = *a.n_out;
+  if (n_out > 0) gather_outlier_columns<Cfg>(a, p, acc, smem, 0, n_out);
+  store_tile<Cfg, kFull>(a, p, acc, bn);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Ping-pong kernel: 8 waves, two per SIMD (waves w and w + 4 share SIMD w % 4).  The time between
+// two workgroup barriers is one phase.  In a memory phase a wave reads all fragments of a slab
+// from LDS into registers and requests a slab from global memory; in an MFMA phase it issues the
+// 16 MFMAs of that slab at raised priority.  The second group of four waves runs one phase behind
+// the first, so on every SIMD one wave is always in its MFMA phase while the other fetches.
+//
+//   phase T:          2s            2s+1           2s+2
+//   waves 0-3:      MEM(s)       MFMA(s)        MEM(s+1)
+//   waves 4-7:      MFMA(s-1)    MEM(s)         MFMA(s)
+//
+// Slab s must be visible in LDS before phase 2s: every wave waits for its share of slab s+1 at
+// the end of phase 2s+1 (group 0: end of MFMA(s); group 1: end of MEM(s)) and the barrier makes
+// it visible.  Slab s + kAhead is requested during MEM(s) into the buffer of slab s - 1, whose
+// last reader (group 1, phase 2s-1) finished before the barrier that ended that phase.
+//
+// The first kOutlierSlab critical columns ride along as one more slab of fp16 operands
+// (X[m, O_j] and f16(Wt[n, O_j] c[n]/127), prepared by the pack kernel): same LDS layout, same
+// fragment reads, fp16 MFMAs onto the already dequantized accumulators.  The row scales of the
+// tile are brought into LDS by one extra request at the very start.
+// ------------------------------------------------------------------------------------------------
 template <class Cfg, bool kTap, bool kFull>
+__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_pingpong(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages, AHEAD = Cfg::kAhead;
+  constexpr int DPS = Cfg::DMA_PER_SLAB;
+  static_assert(Cfg::kWaves == 8, "two groups of four waves");
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int grp = wave >> 2;
+  int tm, tn;
+  if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
+  const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
+  const int n_slabs = a.Kpad / BK;
+  const int n_out = *a.n_out;
+  const bool has_slab_o = n_out > 0;
+  const int total_slabs = n_slabs + (has_slab_o ? 1 : 0);
+
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  float* s_r = reinterpret_cast<float*>(smem + Cfg::RING_BYTES);
+  // the row scales first: the oldest request of wave 0, so every later wait covers it
+  if (wave == 0) dma16(a.r + p.m0 + lane * 4, lds0 + Cfg::RING_BYTES);
+
+  float cs[TJ], bn[TJ];
+  load_column_terms<Cfg>(a, p, cs, bn);
+
+  const int8_t* srcA[Cfg::A_DMA];
+  const int8_t* srcB[Cfg::B_DMA];
+  const int8_t* srcXo[Cfg::A_DMA];
+  const int8_t* srcWo[Cfg::B_DMA];
+#pragma unroll
+  for (int j = 0; j < Cfg::A_DMA; ++j) {
+    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
+    const int chunk = ((lane % CPR) ^ swizzle(r)) * 16;
+    srcA[j] = a.Xq + (size_t)(p.m0 + r) * a.Kpad + chunk;
+    srcXo[j] = reinterpret_cast<const int8_t*>(a.Xo) + (size_t)(p.m0 + r) * BK + chunk;
+  }
+#pragma unroll
+  for (int j = 0; j < Cfg::B_DMA; ++j) {
+    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
+    const int chunk = ((lane % CPR) ^ swizzle(r)) * 16;
+    srcB[j] = a.Wt + (size_t)(p.n0 + r) * a.Kpad + chunk;
+    srcWo[j] = reinterpret_cast<const int8_t*>(a.Wo) + (size_t)(p.n0 + r) * BK + chunk;
+  }
+  auto issue_slab = [&](int slab, int stage) {
+    const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
+    const bool o = slab >= n_slabs;                                // the fp16 slab of critical columns
+#pragma unroll
+    for (int j = 0; j < Cfg::A_DMA; ++j)
+      dma16(o ? srcXo[j] : srcA[j] + (size_t)slab * BK, base + j * Cfg::kWaves * (kWave * 16));
+#pragma unroll
+    for (int j = 0; j < Cfg::B_DMA; ++j)
+      dma16(o ? srcWo[j] : srcB[j] + (size_t)slab * BK, base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
+  };
+
+  int a_off[NKS], b_off[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    const int ra = p.wm * Cfg::WM + p.lr, rb = p.wn * Cfg::WN + p.lr;
+    a_off[ks] = (ra * CPR + ((2 * ks + p.lg) ^ swizzle(ra))) * 16;
+    b_off[ks] = Cfg::A_BYTES + (rb * CPR + ((2 * ks + p.lg) ^ swizzle(rb))) * 16;
+  }
+  v4i fa[NKS][TI], fb[NKS][TJ];
+  auto read_slab = [&](int stage) {
+    const int8_t* base = smem + stage * Cfg::STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TI; ++i) fa[ks][i] = *reinterpret_cast<const v4i*>(base + a_off[ks] + i * 32 * BK);
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) fb[ks][j] = *reinterpret_cast<const v4i*>(base + b_off[ks] + j * 32 * BK);
+    }
+  };
+
+  v16i acc[TI][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+  // kIssue: slab s + kAhead exists and is requested in this iteration.  kFp16: slab s is the slab
+  // of critical columns.
+  int stage = 0;
+  auto iteration = [&](int s, auto issue_tag, auto fp16_tag) {
+    constexpr bool kIssue = decltype(issue_tag)::value, kFp16 = decltype(fp16_tag)::value;
+    constexpr int kVm = kIssue ? (AHEAD - 1) * DPS : 0;            // younger than slab s+1: slabs s+2 .. s+kAhead
+    const int stage_req = (stage == 0) ? STAGES - 1 : stage - 1;   // (s + kAhead) mod kStages
+    // ---- memory phase (the accumulators are dequantized before the fp16 fragments occupy registers)
+    if constexpr (kFp16) dequantize_in_place<Cfg>(p, acc, s_r, cs);
+    read_slab(stage);
+    if (kIssue) issue_slab(s + AHEAD, stage_req);
+    if (grp == 1)
+      wait_slab_and_sync<kVm>();
+    else
+      wait_lds_and_sync();
+    // ---- MFMA phase
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (kFp16) {
+      __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j)
+            acc[i][j] = __builtin_bit_cast(
+                v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fa[ks][i]),
+                                                             __builtin_bit_cast(v8h, fb[ks][j]),
+                                                             __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
+    } else {
+      __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 0)
+      wait_slab_and_sync<kVm>();
+    else
+      sync_only();
+    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+  };
+  using yes = std::true_type;
+  using no = std::false_type;
+
+  static_assert(AHEAD == 3, "prologue written for three slabs ahead");
+  int issued = 0;
+  for (; issued < AHEAD && issued < total_slabs; ++issued) issue_slab(issued, issued);
+  if (issued == 1)
+    wait_slab_and_sync<0>();
+  else if (issued == 2)
+    wait_slab_and_sync<DPS>();
+  else
+    wait_slab_and_sync<2 * DPS>();
+  if (grp == 1) sync_only();                                       // group 1 runs one phase behind
+  int s = 0;
+  for (; s + AHEAD < total_slabs && s < n_slabs; ++s) iteration(s, yes{}, no{});
+  for (; s < n_slabs; ++s) iteration(s, no{}, no{});
+  if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
+  if (has_slab_o) {
+    iteration(s, no{}, yes{});
+  } else {
+    dequantize_in_place<Cfg>(p, acc, s_r, cs);
+  }
+  if (grp == 0) sync_only();                                       // as many barriers as group 1
+
+  if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
+  store_tile<Cfg, kFull>(a, p, acc, bn);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <class Cfg, bool kTap, bool kFull, bool kPingPong>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
   static bool attr_set = false;
+  const void* fn;
+  if constexpr (kPingPong)
+    fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull>);
+  else
+    fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull>);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int grid = ceil_div(a.tiles_m * a.tiles_n, 8) * 8;
-  hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
+  if constexpr (kPingPong)
+    hipLaunchKernelGGL((k_gemm_pingpong<Cfg, kTap, kFull>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
+  else
+    hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
-template <class Cfg>
+template <class Cfg, bool kPingPong>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   a.tiles_m = ceil_div(a.M, Cfg::BM);
   a.tiles_n = ceil_div(a.N, Cfg::BN);
-  if (a.tap_acc) return launch_one<Cfg, true, false>(a, stream);
+  if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong>(a, stream);
   const bool full = (a.M % Cfg::BM == 0) && (a.N % Cfg::BN == 0);
-  return full ? launch_one<Cfg, false, true>(a, stream) : launch_one<Cfg, false, false>(a, stream);
+  return full ? launch_one<Cfg, false, true, kPingPong>(a, stream) : launch_one<Cfg, false, false, kPingPong>(a, stream);
 }
 
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
@@ -388,13 +604,11 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
       variant = 0;
   }
   switch (variant) {
-    case 1: return launch_cfg<GemmCfg<256, 128, 64, 2, 2, 3, 2>>(a, stream);
-    case 2: return launch_cfg<GemmCfg<128, 256, 64, 2, 2, 3, 2>>(a, stream);
-    case 3: return launch_cfg<GemmCfg<256, 256, 64, 2, 4, 3, 2>>(a, stream);
-    case 4: return launch_cfg<GemmCfg<128, 256, 64, 2, 2, 4, 2>>(a, stream);
-    case 5: return launch_cfg<GemmCfg<256, 256, 64, 4, 2, 4, 2>>(a, stream);
-    case 6: return launch_cfg<GemmCfg<256, 256, 64, 2, 4, 4, 2>>(a, stream);
-    default: return launch_cfg<GemmCfg<128, 128, 64, 2, 2, 3, 2>>(a, stream);
+    case 1: return launch_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>(a, stream);
+    case 2: return launch_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>(a, stream);
+    case 3: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, true>(a, stream);
+    case 4: return launch_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>(a, stream);
+    default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 2>, false>(a, stream);
   }
 }
 

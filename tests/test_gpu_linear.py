@@ -139,7 +139,7 @@ def test_config5_prefill_full_size_sampled_rows(shape):
     check_linear(X, W, wl.TAU, rows=rows)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
 def test_every_gemm_tile_configuration(variant):
     """All tile configurations of the GEMM kernel give the same integers (and pass the output bar)."""
     L = binding.lib()
