@@ -36,8 +36,7 @@ __device__ inline uint32_t encode_one(float v, const CodeCell* __restrict__ cell
   return 127u + ((cnt ^ sign) - sign);
 }
 
-// kLogBlock >= 0: block == 1 << kLogBlock.  kLogBlock < 0: any multiple of 64 (runtime division).
-template <int kLogBlock>
+// Generic kernel: any block size that is a multiple of 64, any n (ragged end included).
 __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
     const uint16_t* __restrict__ x, size_t n, int block, uint8_t* __restrict__ codes,
     float* __restrict__ absmax, int blocks_per_span, size_t n_spans) {
@@ -47,7 +46,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
 
   for (int i = threadIdx.x; i < DynamicCode::kCells; i += kThreads) s_cells[i] = kCodeDev.cell[i];
 
-  const int chunks_per_block = (kLogBlock >= 0) ? (1 << (kLogBlock - 3)) : (block >> 3);
+  const int chunks_per_block = block >> 3;
   const int span_elems = blocks_per_span * block;
   const int span_chunks = span_elems >> 3;
   const int lane = threadIdx.x & (kWave - 1);
@@ -102,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
     for (int j = 0; j < kChunksPerThread; ++j) {
       if (!live[j]) continue;
       const int ch = j * kThreads + threadIdx.x;
-      const int b = (kLogBlock >= 0) ? (ch >> (kLogBlock - 3)) : (ch / chunks_per_block);
+      const int b = ch / chunks_per_block;
       const float a = half_lo_to_float(s_block_max[b]);
       const float inv = (a == 0.0f) ? 0.0f : 1.0f / a;            // IEEE division, once per chunk
       uint32_t out[2];
@@ -123,6 +122,138 @@ __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
       }
     }
     __syncthreads();                                // s_chunk_max / s_block_max are reused by the next span
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fast path: block sizes that are powers of two.  A workgroup walks spans of 4096 elements; each
+// of its four waves owns a 1024-element quarter (two 16-byte loads per lane, 1 KB per wave
+// instruction).  Blocks of up to 1024 elements live inside one wave, so their absmax is a
+// cross-lane reduction (DPP / swizzle, no LDS memory, no barrier); 2048 and 4096 exchange four
+// wave maxima through LDS with one barrier per span.
+//
+// Encoding, per element: r = rotate_left(bits(v), 1) = 2 |v|bits + (v < 0), so that
+// "|v| > P" for v >= 0 and "|v| >= P" for v < 0 are both  r > 2 bits(P);  cell = r >> 18;
+// count = base[cell] + (r > threshold2[cell]).  The sign is applied afterwards on two counts at a
+// time with packed 16-bit operations, taking the sign bits from the fp16 inputs.
+// ------------------------------------------------------------------------------------------------
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef short ss2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const v2u* lds_cell_ptr;
+
+template <int kCtrl>
+__device__ inline uint32_t dpp_max(uint32_t v) {
+  return max(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, kCtrl, 0xf, 0xf, false));
+}
+// max over aligned groups of kLanes lanes, result in every lane of the group
+template <int kLanes>
+__device__ inline uint32_t group_max(uint32_t v) {
+  if constexpr (kLanes >= 2) v = dpp_max<0xB1>(v);      // quad_perm [1,0,3,2]
+  if constexpr (kLanes >= 4) v = dpp_max<0x4E>(v);      // quad_perm [2,3,0,1]
+  if constexpr (kLanes >= 8) v = dpp_max<0x141>(v);     // row_half_mirror
+  if constexpr (kLanes >= 16) v = dpp_max<0x140>(v);    // row_mirror
+  if constexpr (kLanes >= 32) v = max(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401f));   // lane ^ 16
+  if constexpr (kLanes >= 64)
+    v = max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 32));
+  return v;
+}
+
+__device__ inline uint32_t chunk_absmax_pattern(const v4u& raw) {
+  us2 m = __builtin_bit_cast(us2, raw[0] & 0x7fff7fffu);
+#pragma unroll
+  for (int w = 1; w < 4; ++w) m = __builtin_elementwise_max(m, __builtin_bit_cast(us2, raw[w] & 0x7fff7fffu));
+  const uint32_t both = __builtin_bit_cast(uint32_t, m);
+  return max(both & 0xffffu, both >> 16);
+}
+
+__device__ inline uint32_t midpoints_below(float v, uint32_t cells_biased) {
+  const uint32_t r = __builtin_amdgcn_alignbit(__float_as_uint(v), __float_as_uint(v), 31);
+  const uint32_t c = min(max(r >> (kCellShift + 1), (uint32_t)DynamicCode::kCellLo), (uint32_t)DynamicCode::kCellHi);
+  const v2u cell = *(lds_cell_ptr)(cells_biased + (c << 3));
+  return cell[1] + (r > cell[0] ? 1u : 0u);
+}
+
+// eight fp16 values (one 16-byte chunk) -> eight codes (8 bytes)
+__device__ inline v2u encode_chunk(const v4u& raw, float inv, uint32_t cells_biased) {
+  uint32_t pair[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t word = raw[w];
+    const uint32_t n0 = midpoints_below(half_lo_to_float(word) * inv, cells_biased);
+    const uint32_t n1 = midpoints_below(half_hi_to_float(word) * inv, cells_biased);
+    const us2 cnt = __builtin_bit_cast(us2, n0 | (n1 << 16));
+    // 0xffff in the halves where x < 0 (sign bit of each fp16 times 0xffff; no carries)
+    const us2 neg = __builtin_bit_cast(us2, ((word >> 15) & 0x00010001u) * 0xffffu);
+    const us2 cap = neg + (unsigned short)128;                    // 128, or 127 for negatives
+    const us2 off = (unsigned short)255 - cap;                    // 127, or 128 for negatives
+    // x >= 0: 127 + n ;  x < 0: 127 - min(n, 127) = (min(n, 127) ^ 0xffff) + 128  (mod 2^16)
+    pair[w] = __builtin_bit_cast(uint32_t, (us2)((__builtin_elementwise_min(cnt, cap) ^ neg) + off));
+  }
+  // pair[w] holds two codes in its 16-bit halves: gather the low bytes
+  return v2u{__builtin_amdgcn_perm(pair[1], pair[0], 0x06040200u), __builtin_amdgcn_perm(pair[3], pair[2], 0x06040200u)};
+}
+
+template <int kLogBlock>
+__global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __restrict__ x, size_t n_spans,
+                                                            uint8_t* __restrict__ codes,
+                                                            float* __restrict__ absmax) {
+  static_assert(kLogBlock >= 6 && kLogBlock <= 12, "64 .. 4096");
+  __shared__ v2u s_cells[DynamicCode::kCells];
+  __shared__ uint32_t s_wave_max[2][kThreads / kWave];
+  for (int i = threadIdx.x; i < DynamicCode::kCells; i += kThreads) {
+    const CodeCell c = kCodeDev.cell[i];
+    s_cells[i] = v2u{c.threshold == kNoThreshold ? kNoThreshold : c.threshold * 2u, c.base};
+  }
+  __syncthreads();
+  const uint32_t cells_biased = (uint32_t)(uintptr_t)s_cells - (uint32_t)DynamicCode::kCellLo * 8u;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  constexpr int kBlock = 1 << kLogBlock;
+  constexpr int kLanesPerBlock = kBlock / kChunk;                  // lanes of one load that share a block
+
+  v4u raw[2], nxt[2];
+  auto load_span = [&](size_t span, v4u (&dst)[2]) {
+    const uint16_t* base = x + span * kSpanMax + wave * 1024 + lane * kChunk;
+    dst[0] = *reinterpret_cast<const v4u*>(base);
+    dst[1] = *reinterpret_cast<const v4u*>(base + 512);
+  };
+  size_t span = blockIdx.x;
+  if (span < n_spans) load_span(span, raw);
+  for (int it = 0; span < n_spans; span += gridDim.x, ++it) {
+    const size_t next = span + gridDim.x;
+    if (next < n_spans) load_span(next, nxt);                      // in flight while this span is encoded
+    uint32_t m0 = chunk_absmax_pattern(raw[0]), m1 = chunk_absmax_pattern(raw[1]);
+    const size_t e_wave = span * kSpanMax + wave * 1024;           // first element of this wave's quarter
+    if constexpr (kLogBlock <= 9) {
+      m0 = group_max<kLanesPerBlock>(m0);
+      m1 = group_max<kLanesPerBlock>(m1);
+      if ((lane & (kLanesPerBlock - 1)) == 0) {
+        absmax[(e_wave + lane * kChunk) >> kLogBlock] = half_lo_to_float(m0);
+        absmax[(e_wave + 512 + lane * kChunk) >> kLogBlock] = half_lo_to_float(m1);
+      }
+    } else {
+      m0 = group_max<kWave>(max(m0, m1));
+      if constexpr (kLogBlock >= 11) {
+        // blocks of 2 or 4 waves: exchange through LDS (slot alternates, so one barrier per span)
+        if (lane == 0) s_wave_max[it & 1][wave] = m0;
+        __syncthreads();
+        if constexpr (kLogBlock == 11)
+          m0 = max(s_wave_max[it & 1][wave & ~1], s_wave_max[it & 1][wave | 1]);
+        else
+          m0 = max(max(s_wave_max[it & 1][0], s_wave_max[it & 1][1]), max(s_wave_max[it & 1][2], s_wave_max[it & 1][3]));
+      }
+      m1 = m0;
+      const bool writer = (kLogBlock == 10) ? lane == 0 : (kLogBlock == 11) ? (lane == 0 && (wave & 1) == 0)
+                                                                            : threadIdx.x == 0;
+      if (writer) absmax[e_wave >> kLogBlock] = half_lo_to_float(m0);
+    }
+    const float a0 = half_lo_to_float(m0), a1 = half_lo_to_float(m1);
+    const float inv0 = (a0 == 0.0f) ? 0.0f : 1.0f / a0;            // IEEE division
+    const float inv1 = (kLogBlock >= 10) ? inv0 : ((a1 == 0.0f) ? 0.0f : 1.0f / a1);
+    uint8_t* out = codes + e_wave + lane * kChunk;
+    *reinterpret_cast<v2u*>(out) = encode_chunk(raw[0], inv0, cells_biased);
+    *reinterpret_cast<v2u*>(out + 512) = encode_chunk(raw[1], inv1, cells_biased);
+    raw[0] = nxt[0];
+    raw[1] = nxt[1];
   }
 }
 
@@ -176,28 +307,46 @@ static int log2_exact(int v) {
   return -1;
 }
 
-hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
-                                     hipStream_t stream) {
+static hipError_t launch_quantize_generic(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
+                                          hipStream_t stream) {
   const int blocks_per_span = kSpanMax / block;                  // >= 1
   const size_t span_elems = (size_t)blocks_per_span * block;
   const size_t n_spans = (n + span_elems - 1) / span_elems;
   const size_t max_grid = (size_t)device_cu_count() * 8;
   const dim3 grid((unsigned)(n_spans < max_grid ? n_spans : max_grid));
-#define MMD8_Q(L) \
-  hipLaunchKernelGGL((k_quantize_blockwise<L>), grid, dim3(kThreads), 0, stream, x, n, block, codes, absmax, \
-                     blocks_per_span, n_spans)
-  switch (log2_exact(block)) {
-    case 6: MMD8_Q(6); break;
-    case 7: MMD8_Q(7); break;
-    case 8: MMD8_Q(8); break;
-    case 9: MMD8_Q(9); break;
-    case 10: MMD8_Q(10); break;
-    case 11: MMD8_Q(11); break;
-    case 12: MMD8_Q(12); break;
-    default: MMD8_Q(-1); break;
-  }
-#undef MMD8_Q
+  hipLaunchKernelGGL(k_quantize_blockwise, grid, dim3(kThreads), 0, stream, x, n, block, codes, absmax,
+                     blocks_per_span, n_spans);
   return hipGetLastError();
+}
+
+hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
+                                     hipStream_t stream) {
+  const int log_block = log2_exact(block);
+  if (log_block < 0) return launch_quantize_generic(x, n, block, codes, absmax, stream);
+  // whole 4096-element spans on the fast path, the ragged end (whole blocks plus a short one)
+  // through the generic kernel
+  const size_t n_spans = n / kSpanMax;
+  if (n_spans > 0) {
+    const size_t max_grid = (size_t)device_cu_count() * 8;
+    const dim3 grid((unsigned)(n_spans < max_grid ? n_spans : max_grid));
+#define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L>), grid, dim3(kThreads), 0, stream, x, n_spans, codes, absmax)
+    switch (log_block) {
+      case 6: MMD8_Q(6); break;
+      case 7: MMD8_Q(7); break;
+      case 8: MMD8_Q(8); break;
+      case 9: MMD8_Q(9); break;
+      case 10: MMD8_Q(10); break;
+      case 11: MMD8_Q(11); break;
+      default: MMD8_Q(12); break;
+    }
+#undef MMD8_Q
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const size_t done = n_spans * kSpanMax;
+  if (done < n)
+    return launch_quantize_generic(x + done, n - done, block, codes + done, absmax + done / block, stream);
+  return hipSuccess;
 }
 
 hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block,
