@@ -213,8 +213,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
   v4u raw[2], nxt[2];
   auto load_span = [&](size_t span, v4u (&dst)[2]) {
     const uint16_t* base = x + span * kSpanMax + wave * 1024 + lane * kChunk;
-    dst[0] = *reinterpret_cast<const v4u*>(base);
-    dst[1] = *reinterpret_cast<const v4u*>(base + 512);
+    dst[0] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base));
+    dst[1] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base + 512));
   };
   size_t span = blockIdx.x;
   if (span < n_spans) load_span(span, raw);
@@ -250,8 +250,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
     const float inv0 = (a0 == 0.0f) ? 0.0f : 1.0f / a0;            // IEEE division
     const float inv1 = (kLogBlock >= 10) ? inv0 : ((a1 == 0.0f) ? 0.0f : 1.0f / a1);
     uint8_t* out = codes + e_wave + lane * kChunk;
-    *reinterpret_cast<v2u*>(out) = encode_chunk(raw[0], inv0, cells_biased);
-    *reinterpret_cast<v2u*>(out + 512) = encode_chunk(raw[1], inv1, cells_biased);
+    __builtin_nontemporal_store(encode_chunk(raw[0], inv0, cells_biased), reinterpret_cast<v2u*>(out));
+    __builtin_nontemporal_store(encode_chunk(raw[1], inv1, cells_biased), reinterpret_cast<v2u*>(out + 512));
     raw[0] = nxt[0];
     raw[1] = nxt[1];
   }
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
     const int valid = (int)min((size_t)kDeqGroup, n - e0);
     v4u c = v4u{0, 0, 0, 0};
     if (valid == kDeqGroup) {
-      c = *reinterpret_cast<const v4u*>(codes + e0);
+      c = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(codes + e0));
     } else {
       uint32_t tmp[4] = {0, 0, 0, 0};
       for (int t = 0; t < valid; ++t) tmp[t >> 2] |= (uint32_t)codes[e0 + t] << (8 * (t & 3));
