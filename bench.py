@@ -114,8 +114,8 @@ def main():
         Xs[K] = torch.from_numpy(X).to(dev)
     for shp in shapes:
         Ys[shp.name] = torch.empty((M, shp.N), dtype=torch.float16, device=dev)
-    ws_bytes = max(binding.lib().mmd8_linear_workspace_bytes(M, s.K, s.N) for s in shapes)
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    biggest = max(shapes, key=lambda s: binding.lib().mmd8_linear_workspace_bytes(M, s.K, s.N))
+    workspace = binding.linear_workspace(M, biggest.K, biggest.N, dev)
     # incoming hidden state arrives encoded
     codes_in, absmax_in = binding.quantize_blockwise(Xs[4096], block)
     hidden_in = torch.empty((M, 4096), dtype=torch.float16, device=dev)

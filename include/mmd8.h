@@ -116,9 +116,15 @@ typedef struct {
  * tau may be 0 (every dimension critical: a pure fp16 product) or +INFINITY (pure int8).
  * Requirements: shapes as for mmd8_prequantize_weight; X, Y 16-byte aligned, ldx % 8 == 0,
  * ldx >= K, ldy % 8 == 0, ldy >= N; Y must not alias X; workspace 256-byte aligned and at
- * least mmd8_linear_workspace_bytes(M, K, N) bytes; its contents on entry are irrelevant and
- * it may be reused by the next call on the same stream. */
+ * least mmd8_linear_workspace_bytes(M, K, N) bytes.
+ *
+ * Workspace protocol: a workspace is set up once with mmd8_linear_workspace_init (it zeroes a
+ * small head of counters and column flags; everything else may hold anything).  Every call
+ * leaves the head zeroed again, so the same workspace serves any number of calls of any shape
+ * that fits, one after the other on one stream.  Two calls must not use one workspace at the
+ * same time.  After a call that returned MMD8_E_HIP, set the workspace up again. */
 size_t mmd8_linear_workspace_bytes(int M, int K, int N);
+int mmd8_linear_workspace_init(void* workspace /*DEVICE*/, size_t workspace_bytes, void* stream);
 int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
                            const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
                            const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,

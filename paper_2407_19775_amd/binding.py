@@ -17,7 +17,7 @@ _lib = None
 EXPORTS = (
     "mmd8_status_string", "mmd8_quantize_blockwise", "mmd8_dequantize_blockwise", "mmd8_code_table",
     "mmd8_code_midpoints", "mmd8_packed_weight_layout", "mmd8_packed_weight_bytes", "mmd8_prequantize_weight",
-    "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_mixed_int8_linear",
+    "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
     "mmd8_threshold_fp16_pattern",
 )
 
@@ -52,6 +52,7 @@ def lib():
         L.mmd8_unpack_weight.argtypes = [vp, i32, i32, vp, vp]
         L.mmd8_linear_workspace_bytes.restype = sz
         L.mmd8_linear_workspace_bytes.argtypes = [i32, i32, i32]
+        L.mmd8_linear_workspace_init.argtypes = [vp, sz, vp]
         L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, sz,
                                              ctypes.POINTER(DebugTaps), vp]
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
@@ -141,8 +142,13 @@ def unpack_weight(pw: PackedWeight) -> torch.Tensor:
 
 
 def linear_workspace(M: int, K: int, N: int, device) -> torch.Tensor:
+    """Allocates and sets up a workspace large enough for one [M,K] x [K,N] call."""
     nbytes = lib().mmd8_linear_workspace_bytes(M, K, N)
-    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    if nbytes == 0:
+        _check(-2)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(lib().mmd8_linear_workspace_init(ws.data_ptr(), ws.numel(), _stream()))
+    return ws
 
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,

@@ -28,34 +28,59 @@ __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
   if (i < n) p[i] = v;
 }
 
-// ------------------------------------------------------------------ scan
-// One workgroup owns kRows consecutive rows over all K columns: row scales need no atomics.
-// A column is flagged by a plain store of 1 (every writer stores the same value); the flag
-// array must be zero on entry.
+// ------------------------------------------------------------------ scan + compaction
+// One workgroup owns kScanRows consecutive rows over all K columns: row scales need no atomics.
+// A column is flagged by a device-scope atomic OR into a byte-per-column flag array that is zero
+// when the kernel starts.  The workgroup that finishes last (a ticket counter,
+// also zero at the start) turns the flags into the ascending list of critical columns, their
+// count and a byte mask for the pack kernel, and then puts flags and ticket back to zero: the
+// two are part of the workspace's standing state, zeroed once when the workspace is set up.
 constexpr int kScanRows = 4;
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 __device__ inline us2 as_us2(uint32_t v) { return __builtin_bit_cast(us2, v); }
 __device__ inline uint32_t as_u32(us2 v) { return __builtin_bit_cast(uint32_t, v); }
 
+struct ScanOut {
+  uint8_t* flag;         // [Kpad] standing state, zero between calls
+  uint32_t* ticket;      // [1]    standing state, zero between calls
+  float* r;              // [M]
+  uint8_t* mask;         // [Kpad] 1 = critical column (padding 0)
+  int32_t* idx;          // ascending critical columns
+  int32_t* n_out;        // [1]
+  uint8_t* tap_mask;     // [K] or null
+  int32_t* tap_idx;      // or null
+  int32_t* tap_n;        // or null
+};
+
 __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ X, int M, int K, int ldx,
-                                                   uint32_t th, uint8_t* __restrict__ flag,
-                                                   float* __restrict__ r) {
+                                                   uint32_t th, int Kpad, const ScanOut o) {
   __shared__ uint32_t s_part[kScanRows][kThreads / kWave];
+  __shared__ int s_wave_total[kThreads / kWave];
+  __shared__ int s_last;
   const int m0 = blockIdx.x * kScanRows;
   const us2 th2 = as_us2(th | (th << 16));
   us2 rowt[kScanRows];
 #pragma unroll
   for (int i = 0; i < kScanRows; ++i) rowt[i] = as_us2(0u);
 
-  for (int k0 = threadIdx.x * 8; k0 < K; k0 += kThreads * 8) {
-    v4u raw[kScanRows];
+  // two column groups per pass: eight 16-byte loads in flight per thread
+  for (int kk = threadIdx.x * 8; kk < K; kk += 2 * kThreads * 8) {
+    v4u raw2[2][kScanRows];
 #pragma unroll
-    for (int i = 0; i < kScanRows; ++i) {
-      // rows past M read as zeros: sub-threshold for tau > 0, and for tau <= 0 every column is
-      // flagged by the real rows anyway
-      raw[i] = v4u{0, 0, 0, 0};
-      if (m0 + i < M) raw[i] = *reinterpret_cast<const v4u*>(X + (size_t)(m0 + i) * ldx + k0);
-    }
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int i = 0; i < kScanRows; ++i) {
+        // rows past M (and a missing second group) read as zeros: sub-threshold for tau > 0, and
+        // for tau <= 0 every column is flagged by the real rows anyway
+        raw2[g][i] = v4u{0, 0, 0, 0};
+        const int kc = kk + g * kThreads * 8;
+        if (m0 + i < M && kc < K) raw2[g][i] = *reinterpret_cast<const v4u*>(X + (size_t)(m0 + i) * ldx + kc);
+      }
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+    const int k0 = kk + g * kThreads * 8;
+    if (k0 >= K) break;
+    const v4u (&raw)[kScanRows] = raw2[g];
     uint32_t col_and[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
 #pragma unroll
     for (int i = 0; i < kScanRows; ++i) {
@@ -68,11 +93,18 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
     }
     const uint32_t all_and = col_and[0] & col_and[1] & col_and[2] & col_and[3];
     if ((~all_and) & 0x80008000u) {                   // rare: some entry of this thread is >= th
+      // the thread's 8 columns are 8 flag bytes = 2 words; device-scope OR (performed at the
+      // coherent level of the memory system, so no cache write-back is needed to publish it)
+      uint32_t f[2] = {0, 0};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        if (!(col_and[w] & 0x8000u)) flag[k0 + 2 * w] = 1;
-        if (!(col_and[w] & 0x80000000u)) flag[k0 + 2 * w + 1] = 1;
+        if (!(col_and[w] & 0x8000u)) f[w >> 1] |= 1u << (16 * (w & 1));
+        if (!(col_and[w] & 0x80000000u)) f[w >> 1] |= 1u << (16 * (w & 1) + 8);
       }
+      uint32_t* fw = reinterpret_cast<uint32_t*>(o.flag + k0);
+      if (f[0]) __hip_atomic_fetch_or(fw, f[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (f[1]) __hip_atomic_fetch_or(fw + 1, f[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     }
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -82,37 +114,43 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
     const uint32_t m = wave_max_u32_to_lane63(max(both & 0xffffu, both >> 16));
     if (lane == kWave - 1) s_part[i][wave] = m;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this thread's flag updates have been performed
   __syncthreads();
   if (threadIdx.x < kScanRows && m0 + threadIdx.x < M) {
     uint32_t m = 0;
 #pragma unroll
     for (int w = 0; w < kThreads / kWave; ++w) m = max(m, s_part[threadIdx.x][w]);
     // top bit set: a sub-threshold entry exists and its pattern is m + th (mod 2^16)
-    r[m0 + threadIdx.x] = (m & 0x8000u) ? half_lo_to_float((m + th) & 0xffffu) : 0.0f;
+    o.r[m0 + threadIdx.x] = (m & 0x8000u) ? half_lo_to_float((m + th) & 0xffffu) : 0.0f;
   }
-}
+  if (threadIdx.x == 0)
+    s_last = (__hip_atomic_fetch_add(o.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1) ? 1 : 0;
+  __syncthreads();
+  if (!s_last) return;
 
-// ------------------------------------------------------------------ compaction
-// Single workgroup: ascending list of flagged columns, their count, and a copy of the mask.
-constexpr int kCompactThreads = 1024;
-__global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __restrict__ flag, int K,
-                                                             int32_t* __restrict__ idx,
-                                                             int32_t* __restrict__ n_out,
-                                                             uint8_t* __restrict__ tap_mask,
-                                                             int32_t* __restrict__ tap_idx,
-                                                             int32_t* __restrict__ tap_n) {
-  __shared__ int s_wave_total[kCompactThreads / kWave];
-  const int per = ceil_div(K, kCompactThreads);
-  const int k_begin = threadIdx.x * per;
-  const int k_end = min(K, k_begin + per);
+  // ---- last workgroup: every other workgroup drew its ticket after its flag updates had been
+  // performed at device scope; drop whatever stale copies this CU / XCD may cache, then read the
+  // flags with ordinary wide loads.  Each thread owns a contiguous run of 16-byte units.
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  constexpr int kMaxUnits = MMD8_MAX_K / 16 / kThreads;            // 16
+  const int units = Kpad / 16;
+  const int per = ceil_div(units, kThreads);
+  const int u_begin = min(units, (int)threadIdx.x * per);
+  const v4u* flag16 = reinterpret_cast<const v4u*>(o.flag);
+  v4u f[kMaxUnits];
   int cnt = 0;
-  for (int k = k_begin; k < k_end; ++k) {
-    const uint8_t f = flag[k];
-    cnt += f ? 1 : 0;
-    if (tap_mask) tap_mask[k] = f ? 1 : 0;
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i) {
+    f[i] = v4u{0, 0, 0, 0};
+    if (i < per && u_begin + i < units) f[i] = flag16[u_begin + i];
   }
-  // inclusive scan inside the wave
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      f[i][w] &= 0x01010101u;
+      cnt += __builtin_popcount(f[i][w]);
+    }
   int incl = cnt;
   for (int d = 1; d < kWave; d <<= 1) {
     const int up = __shfl_up(incl, d, kWave);
@@ -123,16 +161,30 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
   int before = 0;
   for (int w = 0; w < wave; ++w) before += s_wave_total[w];
   int pos = before + incl - cnt;
-  for (int k = k_begin; k < k_end; ++k) {
-    if (flag[k]) {
-      idx[pos] = k;
-      if (tap_idx) tap_idx[pos] = k;
-      ++pos;
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i) {
+    if (i < per && u_begin + i < units) {
+      const int u = u_begin + i;
+      reinterpret_cast<v4u*>(o.mask)[u] = f[i];
+      reinterpret_cast<v4u*>(o.flag)[u] = v4u{0, 0, 0, 0};        // standing state restored
+      if ((f[i][0] | f[i][1] | f[i][2] | f[i][3]) || o.tap_mask) {
+        for (int t = 0; t < 16; ++t) {
+          const int k = 16 * u + t;
+          const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
+          if (o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
+          if (set) {
+            o.idx[pos] = k;
+            if (o.tap_idx) o.tap_idx[pos] = k;
+            ++pos;
+          }
+        }
+      }
     }
   }
-  if (threadIdx.x == kCompactThreads - 1) {
-    *n_out = before + incl;
-    if (tap_n) *tap_n = before + incl;
+  if (threadIdx.x == kThreads - 1) {
+    *o.n_out = before + incl;
+    if (o.tap_n) *o.tap_n = before + incl;
+    *o.ticket = 0;
   }
 }
 
@@ -140,7 +192,7 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
 // Xq[m, k] for k < Kpad (row stride Kpad): codes of the non-critical columns, zeros in the
 // critical columns and in the padding.  One thread converts 16 columns (two 16-byte loads, one
 // 16-byte store) of kPackRows rows; the thread's 16 column flags are turned into byte masks once.
-constexpr int kPackRows = 8;
+constexpr int kPackRows = 4;
 __device__ inline uint32_t to_code_byte(float x, float scale) {
   float q = __builtin_rintf(x * scale);
   q = fminf(fmaxf(q, -127.0f), 127.0f);
@@ -229,16 +281,9 @@ hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, uint8_t* flag, float* r,
+hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, const ScanOut& o,
                        hipStream_t stream) {
-  hipLaunchKernelGGL(k_scan, dim3(ceil_div(M, kScanRows)), dim3(kThreads), 0, stream, X, M, K, ldx, th, flag, r);
-  return hipGetLastError();
-}
-
-hipError_t launch_compact(const uint8_t* flag, int K, int32_t* idx, int32_t* n_out, uint8_t* tap_mask,
-                          int32_t* tap_idx, int32_t* tap_n, hipStream_t stream) {
-  hipLaunchKernelGGL(k_compact, dim3(1), dim3(kCompactThreads), 0, stream, flag, K, idx, n_out, tap_mask, tap_idx,
-                     tap_n);
+  hipLaunchKernelGGL(k_scan, dim3(ceil_div(M, kScanRows)), dim3(kThreads), 0, stream, X, M, K, ldx, th, Kpad, o);
   return hipGetLastError();
 }
 

@@ -16,8 +16,18 @@ const float* code_midpoints_host();
 hipError_t launch_quantize_blockwise(const uint16_t*, size_t, int, uint8_t*, float*, hipStream_t);
 hipError_t launch_dequantize_blockwise(const uint8_t*, const float*, size_t, int, uint16_t*, hipStream_t);
 hipError_t launch_fill_u32(uint32_t*, uint32_t, int, hipStream_t);
-hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, uint8_t*, float*, hipStream_t);
-hipError_t launch_compact(const uint8_t*, int, int32_t*, int32_t*, uint8_t*, int32_t*, int32_t*, hipStream_t);
+struct ScanOut {
+  uint8_t* flag;
+  uint32_t* ticket;
+  float* r;
+  uint8_t* mask;
+  int32_t* idx;
+  int32_t* n_out;
+  uint8_t* tap_mask;
+  int32_t* tap_idx;
+  int32_t* tap_n;
+};
+hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, int, const ScanOut&, hipStream_t);
 struct PackOutliers {   // operands of the critical-column slab, written alongside the int8 codes
   const int32_t* idx;
   const int32_t* n_out;
@@ -76,9 +86,15 @@ static int check_linear_shape(int K, int N) {
   return MMD8_OK;
 }
 
+// Workspace layout.  The head (counters and the column flags, sized for the largest K so that
+// its place does not depend on the shape) is standing state: zero between calls.
+constexpr size_t kHeadCounters = 256;
+constexpr size_t kHeadBytes = kHeadCounters + MMD8_MAX_K;
 struct Workspace {
-  uint8_t* flag;       // [Kpad]
-  int32_t* n_out;      // [1] (64 bytes reserved)
+  int32_t* n_out;      // [1]
+  uint32_t* ticket;    // [1]   standing state
+  uint8_t* flag;       // [MMD8_MAX_K] standing state
+  uint8_t* mask;       // [Kpad]
   int32_t* idx;        // [Kpad]
   float* r;            // [Mpad + 256]
   uint16_t* xo;        // [Mpad][kOutlierSlab]
@@ -95,8 +111,11 @@ static Workspace carve(void* base, int M, int K, int N) {
     off += round_up_sz(n, 256);
     return p;
   };
-  w.flag = take(Kpad);
-  w.n_out = reinterpret_cast<int32_t*>(take(64));
+  uint8_t* counters = take(kHeadCounters);
+  w.n_out = reinterpret_cast<int32_t*>(counters);
+  w.ticket = reinterpret_cast<uint32_t*>(counters ? counters + 64 : nullptr);
+  w.flag = take(MMD8_MAX_K);
+  w.mask = take(Kpad);
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
   w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
   w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2));
@@ -182,6 +201,15 @@ size_t mmd8_linear_workspace_bytes(int M, int K, int N) {
   return carve(nullptr, M, K, N).bytes;
 }
 
+int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || !aligned(workspace, 256)) return MMD8_E_ARG;
+  if (workspace_bytes < kHeadBytes) return MMD8_E_WORKSPACE;
+  return launch_fill_u32(static_cast<uint32_t*>(workspace), 0u, (int)(kHeadBytes / 4),
+                         static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
 int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
                            const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
                            void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
@@ -207,14 +235,10 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     return !ev || hipEventRecord(static_cast<hipEvent_t>(ev), st) == hipSuccess;
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
-  // flags and the count share the head of the workspace: one fill clears both
-  const int head_words = (int)((reinterpret_cast<uint8_t*>(ws.n_out) + 64 - ws.flag) / 4);
-  if (launch_fill_u32(reinterpret_cast<uint32_t*>(ws.flag), 0u, head_words, st) != hipSuccess) return MMD8_E_HIP;
-  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
-  if (launch_compact(ws.flag, K, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers, st) != hipSuccess)
-    return MMD8_E_HIP;
+  const ScanOut so = {ws.flag, ws.ticket, ws.r, ws.mask, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers};
+  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, so, st) != hipSuccess) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, Wq_packed, col_absmax, N, ws.xo, ws.wo};
-  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, po, st) != hipSuccess) return MMD8_E_HIP;
+  if (launch_pack(X, M, K, ldx, ws.mask, ws.r, ws.xq, Kpad, t.xq, po, st) != hipSuccess) return MMD8_E_HIP;
   if (t.row_absmax &&
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MMD8_E_HIP;

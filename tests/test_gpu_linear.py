@@ -155,3 +155,25 @@ def test_every_gemm_tile_configuration(variant):
         check_linear(X, wl.gaussian_weight(4096, 512, 0.02, rng), 6.0)
     finally:
         L.mmd8_set_gemm_variant(-1)
+
+
+def test_one_workspace_serves_calls_of_different_shapes():
+    """The head of the workspace (column flags, ticket) is standing state: every call must leave it
+    ready for the next one, whatever the shapes and however many columns were flagged."""
+    rng = np.random.default_rng(42)
+    shapes = [(70, 2064, 72), (5, 144, 40), (300, 512, 264), (33, 2064, 72), (1, 16, 8)]
+    ws = binding.linear_workspace(300, 2064, 264, "cuda")
+    for rep in range(2):
+        for (M, K, N) in shapes:
+            x = rng.standard_normal((M, K)).astype(np.float32)
+            x[:, rng.integers(0, K, max(1, K // 50))] *= 15.0
+            X = wl.to_fp16(x)
+            W = wl.gaussian_weight(K, N, 0.02, rng)
+            tau = [6.0, 0.0, 2.0][(rep + M) % 3]
+            pw = binding.prequantize_weight(to_gpu(W))
+            Y, taps = binding.mixed_int8_linear(to_gpu(X), pw, tau, workspace=ws, taps=True)
+            Wq_o, c_o = ml.prequantize_weight(W)
+            o = ml.mixed_int8_linear(X, Wq_o, c_o, tau)
+            assert np.array_equal(to_np(taps["outlier_mask"]).astype(bool), o["flag"]), (rep, M, K, N)
+            assert np.array_equal(to_np(taps["acc"]), o["acc"]), (rep, M, K, N)
+            assert_y_close(to_np(Y), o["Y"])
