@@ -7,7 +7,7 @@
 // keeping their order; a single unsigned max of t therefore yields the row scale.
 #include "common.h"
 #include "gemm.h"
-#include "weight_layout.h"
+#include "operand_layout.h"
 
 namespace mmd8 {
 
@@ -189,10 +189,14 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
 }
 
 // ------------------------------------------------------------------ pack
-// Xq[m, k] for k < Kpad (row stride Kpad): codes of the non-critical columns, zeros in the
-// critical columns and in the padding.  One thread converts 16 columns (two 16-byte loads, one
-// 16-byte store) of kPackRows rows; the thread's 16 column flags are turned into byte masks once.
-constexpr int kPackRows = 4;
+// Xq in the blocked operand layout (operand_layout.h): codes of the non-critical columns, zeros
+// in the critical columns and in the K padding.  A wave writes 16 rows x one 64-byte slab = 1 KB
+// of contiguous output per step: lane = (row, 16-byte chunk); its input is 32 bytes of one row of
+// X, so four neighbouring lanes read one full 128-byte line.  The lane's 16 column flags are
+// turned into byte masks once and reused for kPackRowSteps groups of 16 rows.
+constexpr int kPackRowSteps = 4;
+constexpr int kPackRows = 16 * kPackRowSteps;          // rows per workgroup
+constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (one per wave)
 __device__ inline uint32_t to_code_byte(float x, float scale) {
   float q = __builtin_rintf(x * scale);
   q = fminf(fmaxf(q, -127.0f), 127.0f);
@@ -200,77 +204,89 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
 }
 // Rows of the critical-column slab, 8 columns (16 bytes) per thread: Xo[m][j] = X[m, O_j] for
 // the first kOutlierSlab critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
-// j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).
-__device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int Kpad,
+// j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Both
+// are stored like one slab of a packed operand (64 bytes per row, chunks swizzled).
+__device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                            const PackOutliers& o, int item) {
-  const int row = item / (kOutlierSlab / 8), j0 = (item % (kOutlierSlab / 8)) * 8;
+  const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8), j0 = ch * 8;
   if (row >= M + o.N) return;
   const int n_out = min(*o.n_out, kOutlierSlab);
   uint32_t out[4] = {0, 0, 0, 0};
   if (row < M) {
     for (int t = 0; t < 8 && j0 + t < n_out; ++t)
       out[t >> 1] |= (uint32_t)X[(size_t)row * ldx + o.idx[j0 + t]] << (16 * (t & 1));
-    *reinterpret_cast<v4u*>(o.Xo + (size_t)row * kOutlierSlab + j0) = v4u{out[0], out[1], out[2], out[3]};
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, 1)) =
+        v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
     const float step = o.c[n] / 127.0f;
     for (int t = 0; t < 8 && j0 + t < n_out; ++t) {
-      const float w = (float)o.Wt[(size_t)n * Kpad + o.idx[j0 + t]] * step;
+      const float w = (float)o.Wt[packed_offset(n, o.idx[j0 + t], n_slabs)] * step;
       out[t >> 1] |= rounded_float_to_half_bits(w) << (16 * (t & 1));
     }
-    *reinterpret_cast<v4u*>(o.Wo + (size_t)n * kOutlierSlab + j0) = v4u{out[0], out[1], out[2], out[3]};
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, 1)) =
+        v4u{out[0], out[1], out[2], out[3]};
   }
 }
 
 __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ X, int M, int K, int ldx,
                                                    const uint8_t* __restrict__ flag,
                                                    const float* __restrict__ r, int8_t* __restrict__ Xq,
-                                                   int Kpad, int8_t* __restrict__ tap_xq, int pack_blocks_y,
+                                                   int n_slabs, int8_t* __restrict__ tap_xq, int pack_blocks_y,
                                                    const PackOutliers o) {
   if ((int)blockIdx.y >= pack_blocks_y) {                         // the extra blocks prepare the slab
     const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
-    gather_outlier_slab(X, M, ldx, Kpad, o, b * kThreads + threadIdx.x);
+    gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x);
     return;
   }
-  const int k0 = (blockIdx.x * kThreads + threadIdx.x) * 16;
-  if (k0 >= Kpad) return;
-  const int m0 = blockIdx.y * kPackRows;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int slab = blockIdx.x * kPackSlabs + wave;
+  if (slab >= n_slabs) return;
+  const int rl = lane >> 2, ch = lane & 3;
+  const int k0 = slab * kSlabBytes + ch * 16;
+  const bool in_k = k0 < K;                           // K % 16 == 0: a chunk is all inside or all padding
   uint32_t keep[4] = {0, 0, 0, 0};                    // 0xff per kept byte
-  if (k0 < K) {                                       // K % 16 == 0: a group is all inside or all padding
+  if (in_k) {
     const v4u f = *reinterpret_cast<const v4u*>(flag + k0);
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      // bytes are 0 or 1: (1 - f) * 0xff per byte, no carries between bytes
-      keep[w] = (0x01010101u - f[w]) * 0xffu;
+    for (int w = 0; w < 4; ++w) keep[w] = (0x01010101u - f[w]) * 0xffu;   // bytes are 0 or 1: no carries
+  }
+  const int m0 = blockIdx.y * kPackRows + rl;
+  v4u a[kPackRowSteps], b[kPackRowSteps];
+  float rm[kPackRowSteps];
+#pragma unroll
+  for (int i = 0; i < kPackRowSteps; ++i) {
+    const int m = m0 + i * 16;
+    a[i] = b[i] = v4u{0, 0, 0, 0};
+    rm[i] = 0.0f;
+    if (m < M && in_k) {
+      a[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0);
+      b[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0 + 8);
+      rm[i] = r[m];
     }
   }
 #pragma unroll
-  for (int i = 0; i < kPackRows; ++i) {
-    const int m = m0 + i;
+  for (int i = 0; i < kPackRowSteps; ++i) {
+    const int m = m0 + i * 16;
     if (m >= M) break;
-    uint32_t out[4] = {0, 0, 0, 0};
-    if (k0 < K) {
-      const float rm = r[m];
-      const float scale = (rm == 0.0f) ? 0.0f : 127.0f / rm;       // IEEE division
-      const v4u a = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0);
-      const v4u b = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0 + 8);
+    const float scale = (rm[i] == 0.0f) ? 0.0f : 127.0f / rm[i];   // IEEE division
+    uint32_t out[4];
 #pragma unroll
-      for (int w = 0; w < 2; ++w) {
-        out[w] = to_code_byte(half_lo_to_float(a[2 * w]), scale) |
-                 (to_code_byte(half_hi_to_float(a[2 * w]), scale) << 8) |
-                 (to_code_byte(half_lo_to_float(a[2 * w + 1]), scale) << 16) |
-                 (to_code_byte(half_hi_to_float(a[2 * w + 1]), scale) << 24);
-        out[2 + w] = to_code_byte(half_lo_to_float(b[2 * w]), scale) |
-                     (to_code_byte(half_hi_to_float(b[2 * w]), scale) << 8) |
-                     (to_code_byte(half_lo_to_float(b[2 * w + 1]), scale) << 16) |
-                     (to_code_byte(half_hi_to_float(b[2 * w + 1]), scale) << 24);
-      }
-#pragma unroll
-      for (int w = 0; w < 4; ++w) out[w] &= keep[w];
+    for (int w = 0; w < 2; ++w) {
+      out[w] = to_code_byte(half_lo_to_float(a[i][2 * w]), scale) |
+               (to_code_byte(half_hi_to_float(a[i][2 * w]), scale) << 8) |
+               (to_code_byte(half_lo_to_float(a[i][2 * w + 1]), scale) << 16) |
+               (to_code_byte(half_hi_to_float(a[i][2 * w + 1]), scale) << 24);
+      out[2 + w] = to_code_byte(half_lo_to_float(b[i][2 * w]), scale) |
+                   (to_code_byte(half_hi_to_float(b[i][2 * w]), scale) << 8) |
+                   (to_code_byte(half_lo_to_float(b[i][2 * w + 1]), scale) << 16) |
+                   (to_code_byte(half_hi_to_float(b[i][2 * w + 1]), scale) << 24);
     }
-    const v4u o = v4u{out[0], out[1], out[2], out[3]};
-    *reinterpret_cast<v4u*>(Xq + (size_t)m * Kpad + k0) = o;
-    if (tap_xq && k0 < K) *reinterpret_cast<v4u*>(tap_xq + (size_t)m * K + k0) = o;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) out[w] &= keep[w];
+    const v4u v = v4u{out[0], out[1], out[2], out[3]};
+    *reinterpret_cast<v4u*>(Xq + packed_chunk_offset(m, slab, ch, n_slabs)) = v;
+    if (tap_xq && in_k) *reinterpret_cast<v4u*>(tap_xq + (size_t)m * K + k0) = v;
   }
 }
 
@@ -289,11 +305,12 @@ hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, in
 
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
                        int Kpad, int8_t* tap_xq, const PackOutliers& o, hipStream_t stream) {
-  const int gx = ceil_div(Kpad / 16, kThreads), pack_y = ceil_div(M, kPackRows);
+  const int n_slabs = Kpad / kSlabBytes;
+  const int gx = ceil_div(n_slabs, kPackSlabs), pack_y = ceil_div(M, kPackRows);
   const int slab_items = (M + o.N) * (kOutlierSlab / 8);
   const int slab_y = ceil_div(ceil_div(slab_items, kThreads), gx);
   const dim3 grid(gx, pack_y + slab_y);
-  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, Kpad, tap_xq, pack_y, o);
+  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, o);
   return hipGetLastError();
 }
 

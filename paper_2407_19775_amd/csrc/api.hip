@@ -6,7 +6,7 @@
 
 #include "common.h"
 #include "gemm.h"
-#include "weight_layout.h"
+#include "operand_layout.h"
 
 namespace mmd8 {
 

@@ -9,8 +9,8 @@ namespace mmd8 {
 constexpr int kOutlierSlab = 32;
 
 struct GemmArgs {
-  const int8_t* Xq;      // [Mpad][Kpad]
-  const int8_t* Wt;      // [Npad][Kpad]
+  const int8_t* Xq;      // activation codes, blocked layout (operand_layout.h), Mpad x Kpad
+  const int8_t* Wt;      // weight codes, blocked layout, Npad x Kpad
   int M, N, Kpad;
   const float* r;        // [Mpad + 256]
   const float* c;        // [N]
@@ -19,8 +19,8 @@ struct GemmArgs {
   int ldx;
   const int32_t* idx;    // ascending critical columns
   const int32_t* n_out;  // their count
-  const uint16_t* Xo;    // [Mpad][kOutlierSlab] fp16: X[m, O_j], zero for j >= n_out
-  const uint16_t* Wo;    // [Npad][kOutlierSlab] fp16: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
+  const uint16_t* Xo;    // one slab of fp16 per row, blocked like the codes: X[m, O_j], zero for j >= n_out
+  const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   uint16_t* Y;
   int ldy;
   int32_t* tap_acc;      // [M][N] or null

@@ -5,15 +5,16 @@
 //                   + sum_j X[m,O_j] f16(Wt[n,O_j] c[n]/127)   v_mfma_f32_32x32x16_f16 on the critical columns
 //                   + bias[n] )
 //
-// Both operands are K-contiguous byte matrices padded to whole tiles (rows to kPackN, K to
-// kPackK), so the main loop has no bounds checks.  A workgroup owns one BM x BN tile of Y.
+// Both operands are K-contiguous int8 codes in the blocked layout of operand_layout.h, padded to
+// whole tiles, so the main loop has no bounds checks.  A workgroup owns one BM x BN tile of Y.
 // K is walked in slabs of 64 bytes.  A slab of both operands goes from global memory straight
-// into LDS (global_load_lds_dwordx4: no register staging) through a ring of LDS buffers, two or
-// three slabs ahead of the MFMAs.  LDS rows are 64 bytes; the four 16-byte chunks of a row are
-// XOR-swizzled with a function of the row so that the rows read by neighbouring lanes of a
-// ds_read_b128 fall in distinct banks.  A lane's 16 bytes feed one operand row of the 32x32x32
-// MFMA; the k order inside the instruction is irrelevant as long as both operands use the same
-// chunk for the same lane group, which they do.
+// into LDS (global_load_lds_dwordx4: no register staging, every wave instruction copies 1 KB that
+// is contiguous in HBM) through a ring of LDS buffers, two or three slabs ahead of the MFMAs.  LDS
+// rows are 64 bytes; the four 16-byte chunks of a row are XOR-swizzled (already so in HBM) with a
+// function of the row so that the rows read by neighbouring lanes of a ds_read_b128 fall in
+// distinct banks.  A lane's 16 bytes feed one operand row of the 32x32x32 MFMA; the k order
+// inside the instruction is irrelevant as long as both operands use the same chunk for the same
+// lane group, which they do.
 //
 // Two kernels share these pieces:
 //   k_gemm_mixed     4 waves, small tiles, fragments double-buffered in registers (small problems)
@@ -23,7 +24,7 @@
 
 #include "common.h"
 #include "gemm.h"
-#include "weight_layout.h"
+#include "operand_layout.h"
 
 namespace mmd8 {
 
@@ -31,8 +32,16 @@ constexpr int BK = 64;                  // bytes of K per slab
 constexpr int CPR = BK / 16;            // 16-byte chunks per LDS row
 constexpr int ROWS_PER_DMA = kWave / CPR;
 
-// chunk swizzle: distinct for rows {r, r+2, r+4, r+6} and for rows {r, r+4, r+8, r+12}
-__device__ inline int swizzle(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
+static_assert(BK == kSlabBytes, "one LDS slab is one slab of the packed operands");
+__device__ inline int swizzle(int r) { return chunk_swizzle(r); }
+
+// Address of the first byte that DMA instruction j of `wave` copies for slab 0 of an operand tile
+// whose first row is row0 (a multiple of 16 inside one panel): 16 rows x 64 bytes, contiguous.
+__device__ inline const int8_t* dma_source(const int8_t* base, int row0, int n_slabs, int j, int waves, int wave,
+                                           int lane) {
+  return base + (size_t)(row0 >> 8) * n_slabs * kBlockBytes +
+         (size_t)((row0 & 255) + (j * waves + wave) * ROWS_PER_DMA) * kSlabBytes + lane * 16;
+}
 
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_, int WAVES_PER_SIMD_>
 struct GemmCfg {
@@ -169,7 +178,7 @@ __device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<C
         const int n = p.n0 + row - TILE_M;
         if (k >= 0 && n < a.N) {
           const float step = a.c[n] / 127.0f;
-          v = (uint16_t)rounded_float_to_half_bits((float)a.Wt[(size_t)n * a.Kpad + k] * step);
+          v = (uint16_t)rounded_float_to_half_bits((float)a.Wt[packed_offset(n, k, a.Kpad / BK)] * step);
         }
       }
       sXo[t] = v;
@@ -249,30 +258,36 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
   const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
   const int n_slabs = a.Kpad / BK;
+  const int n_out = *a.n_out;
+  const bool has_slab_o = n_out > 0;                                // the critical columns ride as one more slab
+  const int total_slabs = n_slabs + (has_slab_o ? 1 : 0);
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
-  // [(j kWaves + wave) ROWS_PER_DMA, +ROWS_PER_DMA) of the operand tile; the lane brings the
-  // 16-byte chunk that belongs in slot (lane % CPR) of row (lane / CPR) of that group.
+  // [(j kWaves + wave) ROWS_PER_DMA, +ROWS_PER_DMA) of the operand tile: 1 KB, contiguous in
+  // HBM and in LDS.
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   const int8_t* srcA[Cfg::A_DMA];
   const int8_t* srcB[Cfg::B_DMA];
+  const int8_t* srcXo[Cfg::A_DMA];
+  const int8_t* srcWo[Cfg::B_DMA];
 #pragma unroll
   for (int j = 0; j < Cfg::A_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
-    srcA[j] = a.Xq + (size_t)(p.m0 + r) * a.Kpad + ((lane % CPR) ^ swizzle(r)) * 16;
+    srcA[j] = dma_source(a.Xq, p.m0, n_slabs, j, Cfg::kWaves, wave, lane);
+    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, 1, j, Cfg::kWaves, wave, lane);
   }
 #pragma unroll
   for (int j = 0; j < Cfg::B_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
-    srcB[j] = a.Wt + (size_t)(p.n0 + r) * a.Kpad + ((lane % CPR) ^ swizzle(r)) * 16;
+    srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
+    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, 1, j, Cfg::kWaves, wave, lane);
   }
   // request d (0 .. DMA_PER_SLAB-1) of a slab: the A rows first, then the B rows
   auto issue_dma = [&](int slab, int stage, int d) {
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
+    const bool o = slab >= n_slabs;                                 // the fp16 slab of critical columns
     if (d < Cfg::A_DMA)
-      dma16(srcA[d] + (size_t)slab * BK, base + d * Cfg::kWaves * (kWave * 16));
+      dma16(o ? srcXo[d] : srcA[d] + (size_t)slab * kBlockBytes, base + d * Cfg::kWaves * (kWave * 16));
     else
-      dma16(srcB[d - Cfg::A_DMA] + (size_t)slab * BK,
+      dma16(o ? srcWo[d - Cfg::A_DMA] : srcB[d - Cfg::A_DMA] + (size_t)slab * kBlockBytes,
             base + Cfg::A_BYTES + (d - Cfg::A_DMA) * Cfg::kWaves * (kWave * 16));
   };
   auto issue_slab = [&](int slab, int stage) {
@@ -316,18 +331,30 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   constexpr int MFMAS = TI * TJ;                                   // per k-step
   constexpr int DMA_PER_KS = Cfg::DMA_PER_SLAB / NKS;
   static_assert(Cfg::DMA_PER_SLAB % NKS == 0 && DMA_PER_KS >= 1 && DMA_PER_KS <= MFMAS, "request spreading");
+  float cs[TJ], bn[TJ];
+  load_column_terms<Cfg>(a, p, cs, bn);
   int stage = 0;
-  auto iteration = [&](int s, auto issue_tag, auto next_tag) {
+  // kFp16: slab s is the slab of critical columns (fp16 operands, fp32 accumulation onto the
+  // accumulators, which are dequantized first)
+  auto iteration = [&](int s, auto issue_tag, auto next_tag, auto fp16_tag) {
     constexpr bool kIssue = decltype(issue_tag)::value, kNext = decltype(next_tag)::value;
+    constexpr bool kFp16 = decltype(fp16_tag)::value;
     const int stage1 = (stage + 1 == STAGES) ? 0 : stage + 1;
     const int stage_req = (stage == 0) ? STAGES - 1 : stage - 1;   // (s + kAhead) mod kStages
+    if constexpr (kFp16) dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
 #pragma unroll
       for (int t = 0; t < MFMAS; ++t) {
         const int i = t / TJ, j = t % TJ;
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        if constexpr (kFp16)
+          acc[i][j] = __builtin_bit_cast(
+              v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fa[cur][i]),
+                                                           __builtin_bit_cast(v8h, fb[cur][j]),
+                                                           __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
         if (t == 0) {
           // the first MFMA of the k-step goes out before any new LDS read, so the wait for its
           // fragments (read during the previous k-step) is already satisfied
@@ -358,7 +385,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   using no = std::false_type;
 
   int issued = 0;
-  for (; issued < AHEAD && issued < n_slabs; ++issued) issue_slab(issued, issued);
+  for (; issued < AHEAD && issued < total_slabs; ++issued) issue_slab(issued, issued);
   if (issued == 1)
     wait_slab_and_sync<0>();
   else if (issued == 2)
@@ -367,18 +394,17 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
     wait_slab_and_sync<2 * Cfg::DMA_PER_SLAB>();
   read_frags(0, 0, 0);
   int s = 0;
-  for (; s + AHEAD < n_slabs; ++s) iteration(s, yes{}, yes{});
-  for (; s + 1 < n_slabs; ++s) iteration(s, no{}, yes{});
-  iteration(s, no{}, no{});
+  for (; s + AHEAD < total_slabs && s < n_slabs; ++s) iteration(s, yes{}, yes{}, no{});
+  for (; s + 1 < total_slabs && s < n_slabs; ++s) iteration(s, no{}, yes{}, no{});
+  if (s < n_slabs) iteration(s, no{}, no{}, no{});                  // the last slab when nothing follows it
+  if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
+  if (has_slab_o)
+    iteration(n_slabs, no{}, no{}, yes{});
+  else
+    dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
   // free for the gather staging, which starts with a barrier of its own before writing them
-
-  if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
-  float cs[TJ], bn[TJ];
-  load_column_terms<Cfg>(a, p, cs, bn);
-  dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
-  const int n_out = *a.n_out;
-  if (n_out > 0) gather_outlier_columns<Cfg>(a, p, acc, smem, 0, n_out);
+  if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
   store_tile<Cfg, kFull>(a, p, acc, bn);
 }
 
@@ -435,27 +461,23 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
   const int8_t* srcWo[Cfg::B_DMA];
 #pragma unroll
   for (int j = 0; j < Cfg::A_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
-    const int chunk = ((lane % CPR) ^ swizzle(r)) * 16;
-    srcA[j] = a.Xq + (size_t)(p.m0 + r) * a.Kpad + chunk;
-    srcXo[j] = reinterpret_cast<const int8_t*>(a.Xo) + (size_t)(p.m0 + r) * BK + chunk;
+    srcA[j] = dma_source(a.Xq, p.m0, n_slabs, j, Cfg::kWaves, wave, lane);
+    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, 1, j, Cfg::kWaves, wave, lane);
   }
 #pragma unroll
   for (int j = 0; j < Cfg::B_DMA; ++j) {
-    const int r = (j * Cfg::kWaves + wave) * ROWS_PER_DMA + lane / CPR;
-    const int chunk = ((lane % CPR) ^ swizzle(r)) * 16;
-    srcB[j] = a.Wt + (size_t)(p.n0 + r) * a.Kpad + chunk;
-    srcWo[j] = reinterpret_cast<const int8_t*>(a.Wo) + (size_t)(p.n0 + r) * BK + chunk;
+    srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
+    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, 1, j, Cfg::kWaves, wave, lane);
   }
   auto issue_slab = [&](int slab, int stage) {
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
     const bool o = slab >= n_slabs;                                // the fp16 slab of critical columns
 #pragma unroll
     for (int j = 0; j < Cfg::A_DMA; ++j)
-      dma16(o ? srcXo[j] : srcA[j] + (size_t)slab * BK, base + j * Cfg::kWaves * (kWave * 16));
+      dma16(o ? srcXo[j] : srcA[j] + (size_t)slab * kBlockBytes, base + j * Cfg::kWaves * (kWave * 16));
 #pragma unroll
     for (int j = 0; j < Cfg::B_DMA; ++j)
-      dma16(o ? srcWo[j] : srcB[j] + (size_t)slab * BK, base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
+      dma16(o ? srcWo[j] : srcB[j] + (size_t)slab * kBlockBytes, base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
   };
 
   int a_off[NKS], b_off[NKS];
@@ -593,11 +615,15 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
 
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
   if (variant < 0) {
-    // automatic: the large tile whenever it fills the chip reasonably, else smaller tiles
+    // automatic.  The 256 x 256 tile (one workgroup per CU) is the most efficient per CU but runs
+    // in rounds of one tile per CU; when there are few rounds and the last one would leave half
+    // of the chip or more idle, 128 x 256 tiles (two workgroups per CU) balance better.
     const long tiles_256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
     const long tiles_128x256 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
-    if (a.M > 128 && tiles_256 >= 192)
-      variant = 3;
+    const long cus = device_cu_count();
+    const long full_rounds = tiles_256 / cus, rest = tiles_256 % cus;
+    if (a.M > 128 && tiles_256 >= cus / 2 && !(full_rounds < 2 && rest > 0 && 2 * rest <= cus))
+      variant = 6;
     else if (a.M > 64 && tiles_128x256 >= 64)
       variant = 2;
     else
@@ -608,6 +634,8 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     case 2: return launch_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>(a, stream);
     case 3: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, true>(a, stream);
     case 4: return launch_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>(a, stream);
+    case 5: return launch_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>(a, stream);
+    case 6: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>(a, stream);
     default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 2>, false>(a, stream);
   }
 }

@@ -1,12 +1,11 @@
 // Weight pre-quantization ("Compression techniques", item 2): per-column absmax, int8 codes,
 // and the packed layout the GEMM streams.
 //
-// Packed layout: the transposed code matrix Wt[n][k] (k contiguous), N padded to a multiple of
-// kPackN rows and K to a multiple of kPackK bytes, padding filled with zeros.  Both GEMM
-// operands are then K-contiguous, which is what the int8 MFMA fragments want (16 consecutive k
-// per lane).
+// The codes are written transposed (Wt[n][k]: both GEMM operands are then K-contiguous, which is
+// what the int8 MFMA fragments want, 16 consecutive k per lane) in the blocked order described in
+// operand_layout.h; padding is zero.
 #include "common.h"
-#include "weight_layout.h"
+#include "operand_layout.h"
 
 namespace mmd8 {
 
@@ -43,7 +42,7 @@ __device__ inline uint32_t weight_code(float w, float scale) {
 }
 __global__ __launch_bounds__(256) void k_weight_quant_pack(const uint16_t* __restrict__ W, int K, int N, int ldw,
                                                            const float* __restrict__ c,
-                                                           int8_t* __restrict__ Wt, int Kpad) {
+                                                           int8_t* __restrict__ Wt, int n_slabs) {
   __shared__ uint8_t s_tile[kTileN][kTileK + 16];
   const int kt0 = blockIdx.x * kTileK, nt0 = blockIdx.y * kTileN;
   const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;          // 8 column groups x 32 row lanes
@@ -66,21 +65,22 @@ __global__ __launch_bounds__(256) void k_weight_quant_pack(const uint16_t* __res
     }
   }
   __syncthreads();
+  // one 64-byte slab of the 64 rows per pass: 4 KB contiguous in the packed layout
+  static_assert(kTileK / kSlabBytes == 2 && kTileN * (kSlabBytes / 16) == 256, "write-out mapping");
 #pragma unroll
-  for (int pass = 0; pass < (kTileN * kTileK / 16) / 256; ++pass) {
-    const int ch = pass * 256 + threadIdx.x;                       // 16-byte chunk of the tile
-    const int nl = ch / (kTileK / 16), kc = ch % (kTileK / 16);
-    const v4u v = *reinterpret_cast<const v4u*>(&s_tile[nl][kc * 16]);
-    *reinterpret_cast<v4u*>(Wt + (size_t)(nt0 + nl) * Kpad + kt0 + kc * 16) = v;
+  for (int pass = 0; pass < kTileK / kSlabBytes; ++pass) {
+    const int nl = threadIdx.x >> 2, ch = threadIdx.x & 3;
+    const v4u v = *reinterpret_cast<const v4u*>(&s_tile[nl][pass * kSlabBytes + ch * 16]);
+    *reinterpret_cast<v4u*>(Wt + packed_chunk_offset(nt0 + nl, kt0 / kSlabBytes + pass, ch, n_slabs)) = v;
   }
 }
 
-__global__ void k_weight_unpack(const int8_t* __restrict__ Wt, int K, int N, int Kpad,
+__global__ void k_weight_unpack(const int8_t* __restrict__ Wt, int K, int N, int n_slabs,
                                 int8_t* __restrict__ Wq) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)K * N) return;
   const int k = (int)(i / N), n = (int)(i % N);
-  Wq[i] = Wt[(size_t)n * Kpad + k];
+  Wq[i] = Wt[packed_offset(n, k, n_slabs)];
 }
 
 hipError_t launch_col_absmax(const uint16_t* W, int K, int N, int ldw, float* c, hipStream_t stream) {
@@ -94,14 +94,14 @@ hipError_t launch_weight_quant_pack(const uint16_t* W, int K, int N, int ldw, co
                                     hipStream_t stream) {
   const int Kpad = packed_k(K), Npad = packed_n(N);
   hipLaunchKernelGGL(k_weight_quant_pack, dim3(Kpad / kTileK, Npad / kTileN), dim3(256), 0, stream, W, K, N, ldw,
-                     c, Wt, Kpad);
+                     c, Wt, Kpad / kSlabBytes);
   return hipGetLastError();
 }
 
 hipError_t launch_weight_unpack(const int8_t* Wt, int K, int N, int8_t* Wq, hipStream_t stream) {
   const size_t total = (size_t)K * N;
   hipLaunchKernelGGL(k_weight_unpack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, Wt, K, N,
-                     packed_k(K), Wq);
+                     packed_k(K) / kSlabBytes, Wq);
   return hipGetLastError();
 }
 
