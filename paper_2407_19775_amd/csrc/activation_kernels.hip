@@ -190,12 +190,13 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
 
 // ------------------------------------------------------------------ pack
 // Xq in the blocked operand layout (operand_layout.h): codes of the non-critical columns, zeros
-// in the critical columns and in the K padding.  A wave writes 16 rows x one 64-byte slab = 1 KB
-// of contiguous output per step: lane = (row, 16-byte chunk); its input is 32 bytes of one row of
-// X, so four neighbouring lanes read one full 128-byte line.  The lane's 16 column flags are
-// turned into byte masks once and reused for kPackRowSteps groups of 16 rows.
-constexpr int kPackRowSteps = 4;
-constexpr int kPackRows = 16 * kPackRowSteps;          // rows per workgroup
+// in the critical columns and in the K padding.  A wave converts 32 rows x one 64-byte slab per
+// step and writes it as two runs of 1 KB (the two half slabs, fragment-major): lane = (row, 16-byte
+// piece of the half slab).  Its input per half slab is 32 bytes of one row of X; the two lanes of a
+// row read 64 contiguous bytes, and the two half slabs make up one 128-byte line.  The lane's
+// column flags are turned into byte masks once and reused for kPackRowSteps groups of 32 rows.
+constexpr int kPackRowSteps = 2;
+constexpr int kPackRows = 32 * kPackRowSteps;          // rows per workgroup
 constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (one per wave)
 __device__ inline uint32_t to_code_byte(float x, float scale) {
   float q = __builtin_rintf(x * scale);
@@ -205,7 +206,7 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
 // Rows of the critical-column slab, 8 columns (16 bytes) per thread: Xo[m][j] = X[m, O_j] for
 // the first kOutlierSlab critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
 // j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Both
-// are stored like one slab of a packed operand (64 bytes per row, chunks swizzled).
+// are stored like one slab of a packed operand.
 __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                            const PackOutliers& o, int item) {
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8), j0 = ch * 8;
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
                                                    const uint8_t* __restrict__ flag,
                                                    const float* __restrict__ r, int8_t* __restrict__ Xq,
                                                    int n_slabs, int8_t* __restrict__ tap_xq, int pack_blocks_y,
-                                                   const PackOutliers o) {
+                                                   uint16_t* __restrict__ Xf, const PackOutliers o) {
   if ((int)blockIdx.y >= pack_blocks_y) {                         // the extra blocks prepare the slab
     const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
     gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x);
@@ -242,51 +243,71 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int slab = blockIdx.x * kPackSlabs + wave;
   if (slab >= n_slabs) return;
-  const int rl = lane >> 2, ch = lane & 3;
-  const int k0 = slab * kSlabBytes + ch * 16;
-  const bool in_k = k0 < K;                           // K % 16 == 0: a chunk is all inside or all padding
-  uint32_t keep[4] = {0, 0, 0, 0};                    // 0xff per kept byte
-  if (in_k) {
-    const v4u f = *reinterpret_cast<const v4u*>(flag + k0);
+  const int rl = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) keep[w] = (0x01010101u - f[w]) * 0xffu;   // bytes are 0 or 1: no carries
-  }
-  const int m0 = blockIdx.y * kPackRows + rl;
-  v4u a[kPackRowSteps], b[kPackRowSteps];
-  float rm[kPackRowSteps];
+  for (int ks = 0; ks < 2; ++ks) {
+    const int ch = 2 * ks + g;
+    const int k0 = slab * kSlabBytes + ch * 16;
+    const bool in_k = k0 < K;                         // K % 16 == 0: a piece is all inside or all padding
+    uint32_t keep[4] = {0, 0, 0, 0};                  // 0xff per kept byte
+    if (in_k) {
+      const v4u f = *reinterpret_cast<const v4u*>(flag + k0);
 #pragma unroll
-  for (int i = 0; i < kPackRowSteps; ++i) {
-    const int m = m0 + i * 16;
-    a[i] = b[i] = v4u{0, 0, 0, 0};
-    rm[i] = 0.0f;
-    if (m < M && in_k) {
-      a[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0);
-      b[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0 + 8);
-      rm[i] = r[m];
+      for (int w = 0; w < 4; ++w) keep[w] = (0x01010101u - f[w]) * 0xffu;   // bytes are 0 or 1: no carries
     }
-  }
+    const int m0 = blockIdx.y * kPackRows + rl;
+    v4u a[kPackRowSteps], b[kPackRowSteps];
+    float rm[kPackRowSteps];
 #pragma unroll
-  for (int i = 0; i < kPackRowSteps; ++i) {
-    const int m = m0 + i * 16;
-    if (m >= M) break;
-    const float scale = (rm[i] == 0.0f) ? 0.0f : 127.0f / rm[i];   // IEEE division
-    uint32_t out[4];
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-      out[w] = to_code_byte(half_lo_to_float(a[i][2 * w]), scale) |
-               (to_code_byte(half_hi_to_float(a[i][2 * w]), scale) << 8) |
-               (to_code_byte(half_lo_to_float(a[i][2 * w + 1]), scale) << 16) |
-               (to_code_byte(half_hi_to_float(a[i][2 * w + 1]), scale) << 24);
-      out[2 + w] = to_code_byte(half_lo_to_float(b[i][2 * w]), scale) |
-                   (to_code_byte(half_hi_to_float(b[i][2 * w]), scale) << 8) |
-                   (to_code_byte(half_lo_to_float(b[i][2 * w + 1]), scale) << 16) |
-                   (to_code_byte(half_hi_to_float(b[i][2 * w + 1]), scale) << 24);
+    for (int i = 0; i < kPackRowSteps; ++i) {
+      const int m = m0 + i * 32;
+      a[i] = b[i] = v4u{0, 0, 0, 0};
+      rm[i] = 0.0f;
+      if (m < M && in_k) {
+        a[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0);
+        b[i] = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0 + 8);
+        rm[i] = r[m];
+      }
     }
 #pragma unroll
-    for (int w = 0; w < 4; ++w) out[w] &= keep[w];
-    const v4u v = v4u{out[0], out[1], out[2], out[3]};
-    *reinterpret_cast<v4u*>(Xq + packed_chunk_offset(m, slab, ch, n_slabs)) = v;
-    if (tap_xq && in_k) *reinterpret_cast<v4u*>(tap_xq + (size_t)m * K + k0) = v;
+    for (int i = 0; i < kPackRowSteps; ++i) {
+      const int m = m0 + i * 32;
+      if (m >= M) break;
+      const float scale = (rm[i] == 0.0f) ? 0.0f : 127.0f / rm[i];   // IEEE division
+      uint32_t out[4];
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        out[w] = to_code_byte(half_lo_to_float(a[i][2 * w]), scale) |
+                 (to_code_byte(half_hi_to_float(a[i][2 * w]), scale) << 8) |
+                 (to_code_byte(half_lo_to_float(a[i][2 * w + 1]), scale) << 16) |
+                 (to_code_byte(half_hi_to_float(a[i][2 * w + 1]), scale) << 24);
+        out[2 + w] = to_code_byte(half_lo_to_float(b[i][2 * w]), scale) |
+                     (to_code_byte(half_hi_to_float(b[i][2 * w]), scale) << 8) |
+                     (to_code_byte(half_lo_to_float(b[i][2 * w + 1]), scale) << 16) |
+                     (to_code_byte(half_hi_to_float(b[i][2 * w + 1]), scale) << 24);
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) out[w] &= keep[w];
+      const v4u v = v4u{out[0], out[1], out[2], out[3]};
+      *reinterpret_cast<v4u*>(Xq + packed_chunk_offset(m, slab, ch, n_slabs)) = v;
+      if (tap_xq && in_k) *reinterpret_cast<v4u*>(tap_xq + (size_t)m * K + k0) = v;
+      if (Xf) {
+        // decode path: the critical columns of X as fp16, everything else (K padding included) zero
+        uint32_t fa[4], fb[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // ~keep[] has 0xff per critical column byte; the fp16 pair w of a[] covers columns 2w, 2w+1
+          const uint32_t ca = (~keep[w >> 1]) >> (16 * (w & 1)), cb = (~keep[2 + (w >> 1)]) >> (16 * (w & 1));
+          const uint32_t ma = ((ca & 0xffu) * 0x0101u) | (((ca >> 8) & 0xffu) * 0x01010000u);
+          const uint32_t mb = ((cb & 0xffu) * 0x0101u) | (((cb >> 8) & 0xffu) * 0x01010000u);
+          fa[w] = in_k ? (a[i][w] & ma) : 0u;
+          fb[w] = in_k ? (b[i][w] & mb) : 0u;
+        }
+        uint16_t* dst = Xf + (size_t)m * (n_slabs * kSlabBytes) + k0;
+        *reinterpret_cast<v4u*>(dst) = v4u{fa[0], fa[1], fa[2], fa[3]};
+        *reinterpret_cast<v4u*>(dst + 8) = v4u{fb[0], fb[1], fb[2], fb[3]};
+      }
+    }
   }
 }
 
@@ -304,13 +325,14 @@ hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, in
 }
 
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
-                       int Kpad, int8_t* tap_xq, const PackOutliers& o, hipStream_t stream) {
+                       int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes;
   const int gx = ceil_div(n_slabs, kPackSlabs), pack_y = ceil_div(M, kPackRows);
-  const int slab_items = (M + o.N) * (kOutlierSlab / 8);
+  // the slab of critical columns is for the tiled GEMM kernels; the decode kernel reads Xf instead
+  const int slab_items = Xf ? 0 : (M + o.N) * (kOutlierSlab / 8);
   const int slab_y = ceil_div(ceil_div(slab_items, kThreads), gx);
   const dim3 grid(gx, pack_y + slab_y);
-  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, o);
+  hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, Xf, o);
   return hipGetLastError();
 }
 

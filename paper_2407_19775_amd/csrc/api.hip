@@ -7,6 +7,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "operand_layout.h"
+#include "skinny.h"
 
 namespace mmd8 {
 
@@ -37,7 +38,7 @@ struct PackOutliers {   // operands of the critical-column slab, written alongsi
   uint16_t* Xo;
   uint16_t* Wo;
 };
-hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*,
+hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*, uint16_t*,
                        const PackOutliers&, hipStream_t);
 hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
 hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
@@ -99,7 +100,9 @@ struct Workspace {
   float* r;            // [Mpad + 256]
   uint16_t* xo;        // [Mpad][kOutlierSlab]
   uint16_t* wo;        // [Npad][kOutlierSlab]
-  int8_t* xq;          // [Mpad][Kpad]
+  int8_t* xq;          // Mpad x Kpad codes, blocked layout
+  uint16_t* xf;        // decode path only: [64][Kpad] fp16
+  float* partial;      // decode path only: split-K partial outputs
   size_t bytes;
 };
 static Workspace carve(void* base, int M, int K, int N) {
@@ -121,6 +124,13 @@ static Workspace carve(void* base, int M, int K, int N) {
   w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2));
   w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2));
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
+  w.xf = nullptr;
+  w.partial = nullptr;
+  if (M > 0 && M <= kSkinnyMaxM) {
+    w.xf = reinterpret_cast<uint16_t*>(take((size_t)kSkinnyMaxM * Kpad * 2));
+    const size_t pb = plan_skinny(M, K, N).partial_bytes;
+    if (pb) w.partial = reinterpret_cast<float*>(take(pb));
+  }
   w.bytes = off;
   return w;
 }
@@ -238,32 +248,53 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   const ScanOut so = {ws.flag, ws.ticket, ws.r, ws.mask, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers};
   if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, so, st) != hipSuccess) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, Wq_packed, col_absmax, N, ws.xo, ws.wo};
-  if (launch_pack(X, M, K, ldx, ws.mask, ws.r, ws.xq, Kpad, t.xq, po, st) != hipSuccess) return MMD8_E_HIP;
+  const bool skinny = M <= kSkinnyMaxM;
+  if (launch_pack(X, M, K, ldx, ws.mask, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
+    return MMD8_E_HIP;
   if (t.row_absmax &&
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MMD8_E_HIP;
 
-  GemmArgs g;
-  g.Xq = ws.xq;
-  g.Wt = Wq_packed;
-  g.M = M;
-  g.N = N;
-  g.Kpad = Kpad;
-  g.r = ws.r;
-  g.c = col_absmax;
-  g.bias = bias;
-  g.X = X;
-  g.ldx = ldx;
-  g.idx = ws.idx;
-  g.n_out = ws.n_out;
-  g.Xo = ws.xo;
-  g.Wo = ws.wo;
-  g.Y = Y;
-  g.ldy = ldy;
-  g.tap_acc = t.acc;
-  g.tiles_m = g.tiles_n = 0;
   if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
-  if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
+  if (skinny) {
+    SkinnyArgs g = {};
+    g.Xq = ws.xq;
+    g.Wt = Wq_packed;
+    g.Xf = ws.xf;
+    g.mask = ws.mask;
+    g.M = M;
+    g.N = N;
+    g.Kpad = Kpad;
+    g.r = ws.r;
+    g.c = col_absmax;
+    g.bias = bias;
+    g.Y = Y;
+    g.ldy = ldy;
+    g.partial = ws.partial;
+    g.tap_acc = t.acc;
+    if (launch_gemm_skinny(g, plan_skinny(M, K, N), st) != hipSuccess) return MMD8_E_HIP;
+  } else {
+    GemmArgs g;
+    g.Xq = ws.xq;
+    g.Wt = Wq_packed;
+    g.M = M;
+    g.N = N;
+    g.Kpad = Kpad;
+    g.r = ws.r;
+    g.c = col_absmax;
+    g.bias = bias;
+    g.X = X;
+    g.ldx = ldx;
+    g.idx = ws.idx;
+    g.n_out = ws.n_out;
+    g.Xo = ws.xo;
+    g.Wo = ws.wo;
+    g.Y = Y;
+    g.ldy = ldy;
+    g.tap_acc = t.acc;
+    g.tiles_m = g.tiles_n = 0;
+    if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
+  }
   if (!record(t.event_gemm_end)) return MMD8_E_HIP;
   return MMD8_OK;
 }

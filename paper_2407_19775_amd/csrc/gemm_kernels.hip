@@ -9,11 +9,10 @@
 // whole tiles, so the main loop has no bounds checks.  A workgroup owns one BM x BN tile of Y.
 // K is walked in slabs of 64 bytes.  A slab of both operands goes from global memory straight
 // into LDS (global_load_lds_dwordx4: no register staging, every wave instruction copies 1 KB that
-// is contiguous in HBM) through a ring of LDS buffers, two or three slabs ahead of the MFMAs.  LDS
-// rows are 64 bytes; the four 16-byte chunks of a row are XOR-swizzled (already so in HBM) with a
-// function of the row so that the rows read by neighbouring lanes of a ds_read_b128 fall in
-// distinct banks.  A lane's 16 bytes feed one operand row of the 32x32x32 MFMA; the k order
-// inside the instruction is irrelevant as long as both operands use the same chunk for the same
+// is contiguous in HBM) through a ring of LDS buffers, two or three slabs ahead of the MFMAs.  The
+// blocks are fragment-major already in HBM: the 64 lanes of an MFMA operand read 64 consecutive
+// 16-byte pieces.  A lane's 16 bytes feed one operand row of the 32x32x32 MFMA; the k order
+// inside the instruction is irrelevant as long as both operands use the same piece for the same
 // lane group, which they do.
 //
 // Two kernels share these pieces:
@@ -33,7 +32,6 @@ constexpr int CPR = BK / 16;            // 16-byte chunks per LDS row
 constexpr int ROWS_PER_DMA = kWave / CPR;
 
 static_assert(BK == kSlabBytes, "one LDS slab is one slab of the packed operands");
-__device__ inline int swizzle(int r) { return chunk_swizzle(r); }
 
 // Address of the first byte that DMA instruction j of `wave` copies for slab 0 of an operand tile
 // whose first row is row0 (a multiple of 16 inside one panel): 16 rows x 64 bytes, contiguous.
@@ -295,13 +293,13 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
     for (int d = 0; d < Cfg::DMA_PER_SLAB; ++d) issue_dma(slab, stage, d);
   };
 
-  // ---- per-lane LDS read offsets: row (lane % 32) of an MFMA tile, chunk (2 ks + lane / 32)
+  // ---- per-lane LDS read offsets: row (lane % 32) of an MFMA tile, piece (2 ks + lane / 32)
   int a_off[NKS], b_off[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    const int ra = p.wm * Cfg::WM + p.lr, rb = p.wn * Cfg::WN + p.lr;
-    a_off[ks] = (ra * CPR + ((2 * ks + p.lg) ^ swizzle(ra))) * 16;
-    b_off[ks] = Cfg::A_BYTES + (rb * CPR + ((2 * ks + p.lg) ^ swizzle(rb))) * 16;
+    // group of 32 rows: 2 KB = [k-step][lane] 16-byte pieces
+    a_off[ks] = (p.wm * Cfg::WM / 32) * 2048 + ks * 1024 + p.lane * 16;
+    b_off[ks] = Cfg::A_BYTES + (p.wn * Cfg::WN / 32) * 2048 + ks * 1024 + p.lane * 16;
   }
   v4i fa[2][TI], fb[2][TJ];
   auto read_frags = [&](int stage, int ks, int buf) {
@@ -483,9 +481,9 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
   int a_off[NKS], b_off[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    const int ra = p.wm * Cfg::WM + p.lr, rb = p.wn * Cfg::WN + p.lr;
-    a_off[ks] = (ra * CPR + ((2 * ks + p.lg) ^ swizzle(ra))) * 16;
-    b_off[ks] = Cfg::A_BYTES + (rb * CPR + ((2 * ks + p.lg) ^ swizzle(rb))) * 16;
+    // group of 32 rows: 2 KB = [k-step][lane] 16-byte pieces
+    a_off[ks] = (p.wm * Cfg::WM / 32) * 2048 + ks * 1024 + p.lane * 16;
+    b_off[ks] = Cfg::A_BYTES + (p.wn * Cfg::WN / 32) * 2048 + ks * 1024 + p.lane * 16;
   }
   v4i fa[NKS][TI], fb[NKS][TJ];
   auto read_slab = [&](int stage) {
