@@ -30,6 +30,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--codec-block", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-variant", type=int, default=-1, help="tuning: force a GEMM tile configuration (-1 = automatic)")
     return ap.parse_args()
 
 
@@ -96,6 +97,7 @@ def main():
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    binding.lib().mmd8_set_gemm_variant(args.gemm_variant)
     M = 2048
     shapes = wl.LLAMA_7B_LINEARS
     block = args.codec_block

@@ -13,9 +13,13 @@ namespace mmd8 {
 
 constexpr int kThreads = 256;
 
-struct PackOutliers {   // operands of the critical-column slab, written alongside the int8 codes
-  const int32_t* idx;
-  const int32_t* n_out;
+struct PackOutliers {   // the critical columns: compaction outputs and the operands of their fp16 slab
+  int32_t* idx;          // ascending critical columns
+  int32_t* n_out;        // [1]
+  uint8_t* mask;         // [Kpad] 1 = critical column (padding 0)
+  uint8_t* tap_mask;     // [K] or null
+  int32_t* tap_idx;      // or null
+  int32_t* tap_n;        // or null
   const int8_t* Wt;
   const float* c;
   int N;
@@ -28,35 +32,24 @@ __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
   if (i < n) p[i] = v;
 }
 
-// ------------------------------------------------------------------ scan + compaction
-// One workgroup owns kScanRows consecutive rows over all K columns: row scales need no atomics.
+// ------------------------------------------------------------------ scan
+// One workgroup owns kRows consecutive rows over all K columns: row scales need no atomics.
+// kRows is 4 for tall inputs and smaller for short ones, so that there are always enough
+// workgroups to keep the memory system busy.
 // A column is flagged by a device-scope atomic OR into a byte-per-column flag array that is zero
-// when the kernel starts.  The workgroup that finishes last (a ticket counter,
-// also zero at the start) turns the flags into the ascending list of critical columns, their
-// count and a byte mask for the pack kernel, and then puts flags and ticket back to zero: the
-// two are part of the workspace's standing state, zeroed once when the workspace is set up.
-constexpr int kScanRows = 4;
+// when the kernel starts.  Every row tends to exceed the threshold in the same few columns, and
+// atomics on one address are served one after the other, so the workgroups spread over
+// kFlagReplicas copies of the array; the readers OR the copies.  The flags are part of the
+// workspace's standing state: zeroed once when the workspace is set up, read by the pack kernel,
+// and zeroed again by the GEMM kernel that ends the call.
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 __device__ inline us2 as_us2(uint32_t v) { return __builtin_bit_cast(us2, v); }
 __device__ inline uint32_t as_u32(us2 v) { return __builtin_bit_cast(uint32_t, v); }
 
-struct ScanOut {
-  uint8_t* flag;         // [Kpad] standing state, zero between calls
-  uint32_t* ticket;      // [1]    standing state, zero between calls
-  float* r;              // [M]
-  uint8_t* mask;         // [Kpad] 1 = critical column (padding 0)
-  int32_t* idx;          // ascending critical columns
-  int32_t* n_out;        // [1]
-  uint8_t* tap_mask;     // [K] or null
-  int32_t* tap_idx;      // or null
-  int32_t* tap_n;        // or null
-};
-
+template <int kScanRows>
 __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ X, int M, int K, int ldx,
-                                                   uint32_t th, int Kpad, const ScanOut o) {
+                                                   uint32_t th, int Kpad, uint8_t* __restrict__ flag, float* __restrict__ r_out) {
   __shared__ uint32_t s_part[kScanRows][kThreads / kWave];
-  __shared__ int s_wave_total[kThreads / kWave];
-  __shared__ int s_last;
   const int m0 = blockIdx.x * kScanRows;
   const us2 th2 = as_us2(th | (th << 16));
   us2 rowt[kScanRows];
@@ -101,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
         if (!(col_and[w] & 0x8000u)) f[w >> 1] |= 1u << (16 * (w & 1));
         if (!(col_and[w] & 0x80000000u)) f[w >> 1] |= 1u << (16 * (w & 1) + 8);
       }
-      uint32_t* fw = reinterpret_cast<uint32_t*>(o.flag + k0);
+      uint32_t* fw = reinterpret_cast<uint32_t*>(flag + (size_t)(blockIdx.x % kFlagReplicas) * Kpad + k0);
       if (f[0]) __hip_atomic_fetch_or(fw, f[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (f[1]) __hip_atomic_fetch_or(fw + 1, f[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -114,77 +107,13 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
     const uint32_t m = wave_max_u32_to_lane63(max(both & 0xffffu, both >> 16));
     if (lane == kWave - 1) s_part[i][wave] = m;
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this thread's flag updates have been performed
   __syncthreads();
   if (threadIdx.x < kScanRows && m0 + threadIdx.x < M) {
     uint32_t m = 0;
 #pragma unroll
     for (int w = 0; w < kThreads / kWave; ++w) m = max(m, s_part[threadIdx.x][w]);
     // top bit set: a sub-threshold entry exists and its pattern is m + th (mod 2^16)
-    o.r[m0 + threadIdx.x] = (m & 0x8000u) ? half_lo_to_float((m + th) & 0xffffu) : 0.0f;
-  }
-  if (threadIdx.x == 0)
-    s_last = (__hip_atomic_fetch_add(o.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1) ? 1 : 0;
-  __syncthreads();
-  if (!s_last) return;
-
-  // ---- last workgroup: every other workgroup drew its ticket after its flag updates had been
-  // performed at device scope; drop whatever stale copies this CU / XCD may cache, then read the
-  // flags with ordinary wide loads.  Each thread owns a contiguous run of 16-byte units.
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  constexpr int kMaxUnits = MMD8_MAX_K / 16 / kThreads;            // 16
-  const int units = Kpad / 16;
-  const int per = ceil_div(units, kThreads);
-  const int u_begin = min(units, (int)threadIdx.x * per);
-  const v4u* flag16 = reinterpret_cast<const v4u*>(o.flag);
-  v4u f[kMaxUnits];
-  int cnt = 0;
-#pragma unroll
-  for (int i = 0; i < kMaxUnits; ++i) {
-    f[i] = v4u{0, 0, 0, 0};
-    if (i < per && u_begin + i < units) f[i] = flag16[u_begin + i];
-  }
-#pragma unroll
-  for (int i = 0; i < kMaxUnits; ++i)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      f[i][w] &= 0x01010101u;
-      cnt += __builtin_popcount(f[i][w]);
-    }
-  int incl = cnt;
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int up = __shfl_up(incl, d, kWave);
-    if (lane >= d) incl += up;
-  }
-  if (lane == kWave - 1) s_wave_total[wave] = incl;
-  __syncthreads();
-  int before = 0;
-  for (int w = 0; w < wave; ++w) before += s_wave_total[w];
-  int pos = before + incl - cnt;
-#pragma unroll
-  for (int i = 0; i < kMaxUnits; ++i) {
-    if (i < per && u_begin + i < units) {
-      const int u = u_begin + i;
-      reinterpret_cast<v4u*>(o.mask)[u] = f[i];
-      reinterpret_cast<v4u*>(o.flag)[u] = v4u{0, 0, 0, 0};        // standing state restored
-      if ((f[i][0] | f[i][1] | f[i][2] | f[i][3]) || o.tap_mask) {
-        for (int t = 0; t < 16; ++t) {
-          const int k = 16 * u + t;
-          const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
-          if (o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
-          if (set) {
-            o.idx[pos] = k;
-            if (o.tap_idx) o.tap_idx[pos] = k;
-            ++pos;
-          }
-        }
-      }
-    }
-  }
-  if (threadIdx.x == kThreads - 1) {
-    *o.n_out = before + incl;
-    if (o.tap_n) *o.tap_n = before + incl;
-    *o.ticket = 0;
+    r_out[m0 + threadIdx.x] = (m & 0x8000u) ? half_lo_to_float((m + th) & 0xffffu) : 0.0f;
   }
 }
 
@@ -203,26 +132,98 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
   q = fminf(fmaxf(q, -127.0f), 127.0f);
   return (uint32_t)((int)q) & 0xffu;
 }
+// 16 column flags (bytes 0 / 1) starting at column k0: the OR of the replicas
+__device__ inline v4u merged_flags16(const uint8_t* __restrict__ flag, int Kpad, int k0) {
+  v4u f = v4u{0, 0, 0, 0};
+#pragma unroll
+  for (int rep = 0; rep < kFlagReplicas; ++rep) f |= *reinterpret_cast<const v4u*>(flag + (size_t)rep * Kpad + k0);
+  return f & 0x01010101u;
+}
+
+// The ascending list of critical columns and their count, computed by one whole workgroup from
+// the flags (every workgroup that needs the list recomputes it: a few KB of flags from L2 are
+// cheaper than a serial step between two kernels).  The first kOutlierSlab indices and the count
+// land in LDS; the workgroup with `publish` also writes the list, the count, the byte mask and
+// the taps to global memory.  Each thread owns a contiguous run of 16-column units.
+__device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag, int K, int Kpad, const PackOutliers& o,
+                                                bool publish, int* s_idx /*[kOutlierSlab]*/, int* s_n_out,
+                                                int* s_wave_total /*[kThreads / kWave]*/) {
+  constexpr int kMaxUnits = MMD8_MAX_K / 16 / kThreads;            // 16
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int units = Kpad / 16;
+  const int per = ceil_div(units, kThreads);
+  const int u_begin = min(units, (int)threadIdx.x * per);
+  v4u f[kMaxUnits];
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i) {
+    f[i] = v4u{0, 0, 0, 0};
+    if (i < per && u_begin + i < units) f[i] = merged_flags16(flag, Kpad, 16 * (u_begin + i));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) cnt += __builtin_popcount(f[i][w]);
+  }
+  int incl = cnt;
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int up = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += up;
+  }
+  if (lane == kWave - 1) s_wave_total[wave] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += s_wave_total[w];
+  int pos = before + incl - cnt;
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i) {
+    if (i < per && u_begin + i < units) {
+      const int u = u_begin + i;
+      if (publish) reinterpret_cast<v4u*>(o.mask)[u] = f[i];
+      if ((f[i][0] | f[i][1] | f[i][2] | f[i][3]) || (publish && o.tap_mask)) {
+        for (int t = 0; t < 16; ++t) {
+          const int k = 16 * u + t;
+          const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
+          if (publish && o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
+          if (set) {
+            if (pos < kOutlierSlab) s_idx[pos] = k;
+            if (publish) {
+              o.idx[pos] = k;
+              if (o.tap_idx) o.tap_idx[pos] = k;
+            }
+            ++pos;
+          }
+        }
+      }
+    }
+  }
+  if (threadIdx.x == kThreads - 1) {
+    *s_n_out = before + incl;
+    if (publish) {
+      *o.n_out = before + incl;
+      if (o.tap_n) *o.tap_n = before + incl;
+    }
+  }
+  __syncthreads();
+}
+
 // Rows of the critical-column slab, 8 columns (16 bytes) per thread: Xo[m][j] = X[m, O_j] for
 // the first kOutlierSlab critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
 // j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Both
 // are stored like one slab of a packed operand.
 __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
-                                           const PackOutliers& o, int item) {
+                                           const PackOutliers& o, int item, const int* s_idx, int n_out_all) {
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8), j0 = ch * 8;
   if (row >= M + o.N) return;
-  const int n_out = min(*o.n_out, kOutlierSlab);
+  const int n_out = min(n_out_all, kOutlierSlab);
   uint32_t out[4] = {0, 0, 0, 0};
   if (row < M) {
     for (int t = 0; t < 8 && j0 + t < n_out; ++t)
-      out[t >> 1] |= (uint32_t)X[(size_t)row * ldx + o.idx[j0 + t]] << (16 * (t & 1));
+      out[t >> 1] |= (uint32_t)X[(size_t)row * ldx + s_idx[j0 + t]] << (16 * (t & 1));
     *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, 1)) =
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
     const float step = o.c[n] / 127.0f;
     for (int t = 0; t < 8 && j0 + t < n_out; ++t) {
-      const float w = (float)o.Wt[packed_offset(n, o.idx[j0 + t], n_slabs)] * step;
+      const float w = (float)o.Wt[packed_offset(n, s_idx[j0 + t], n_slabs)] * step;
       out[t >> 1] |= rounded_float_to_half_bits(w) << (16 * (t & 1));
     }
     *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, 1)) =
@@ -235,9 +236,14 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
                                                    const float* __restrict__ r, int8_t* __restrict__ Xq,
                                                    int n_slabs, int8_t* __restrict__ tap_xq, int pack_blocks_y,
                                                    uint16_t* __restrict__ Xf, const PackOutliers o) {
-  if ((int)blockIdx.y >= pack_blocks_y) {                         // the extra blocks prepare the slab
+  if ((int)blockIdx.y >= pack_blocks_y) {
+    // the extra blocks list the critical columns and prepare their slab; the first one publishes
+    __shared__ int s_idx[kOutlierSlab];
+    __shared__ int s_n_out;
+    __shared__ int s_wave_total[kThreads / kWave];
     const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
-    gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x);
+    compact_critical_columns(flag, K, n_slabs * kSlabBytes, o, b == 0, s_idx, &s_n_out, s_wave_total);
+    if (!Xf) gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x, s_idx, s_n_out);
     return;
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -251,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
     const bool in_k = k0 < K;                         // K % 16 == 0: a piece is all inside or all padding
     uint32_t keep[4] = {0, 0, 0, 0};                  // 0xff per kept byte
     if (in_k) {
-      const v4u f = *reinterpret_cast<const v4u*>(flag + k0);
+      const v4u f = merged_flags16(flag, n_slabs * kSlabBytes, k0);
 #pragma unroll
       for (int w = 0; w < 4; ++w) keep[w] = (0x01010101u - f[w]) * 0xffu;   // bytes are 0 or 1: no carries
     }
@@ -318,9 +324,15 @@ hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, const ScanOut& o,
+hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
                        hipStream_t stream) {
-  hipLaunchKernelGGL(k_scan, dim3(ceil_div(M, kScanRows)), dim3(kThreads), 0, stream, X, M, K, ldx, th, Kpad, o);
+  const int want = 2 * device_cu_count();                // workgroups
+  if (M >= 4 * want)
+    hipLaunchKernelGGL(k_scan<4>, dim3(ceil_div(M, 4)), dim3(kThreads), 0, stream, X, M, K, ldx, th, Kpad, flag, r);
+  else if (M >= 2 * want)
+    hipLaunchKernelGGL(k_scan<2>, dim3(ceil_div(M, 2)), dim3(kThreads), 0, stream, X, M, K, ldx, th, Kpad, flag, r);
+  else
+    hipLaunchKernelGGL(k_scan<1>, dim3(M), dim3(kThreads), 0, stream, X, M, K, ldx, th, Kpad, flag, r);
   return hipGetLastError();
 }
 
@@ -329,8 +341,9 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
   const int n_slabs = Kpad / kSlabBytes;
   const int gx = ceil_div(n_slabs, kPackSlabs), pack_y = ceil_div(M, kPackRows);
   // the slab of critical columns is for the tiled GEMM kernels; the decode kernel reads Xf instead
+  // (one extra block still lists the critical columns)
   const int slab_items = Xf ? 0 : (M + o.N) * (kOutlierSlab / 8);
-  const int slab_y = ceil_div(ceil_div(slab_items, kThreads), gx);
+  const int slab_y = max(1, ceil_div(ceil_div(slab_items, kThreads), gx));
   const dim3 grid(gx, pack_y + slab_y);
   hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, Xf, o);
   return hipGetLastError();

@@ -17,21 +17,14 @@ const float* code_midpoints_host();
 hipError_t launch_quantize_blockwise(const uint16_t*, size_t, int, uint8_t*, float*, hipStream_t);
 hipError_t launch_dequantize_blockwise(const uint8_t*, const float*, size_t, int, uint16_t*, hipStream_t);
 hipError_t launch_fill_u32(uint32_t*, uint32_t, int, hipStream_t);
-struct ScanOut {
-  uint8_t* flag;
-  uint32_t* ticket;
-  float* r;
-  uint8_t* mask;
+hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, hipStream_t);
+struct PackOutliers {   // the critical columns: compaction outputs and the operands of their fp16 slab
   int32_t* idx;
   int32_t* n_out;
+  uint8_t* mask;
   uint8_t* tap_mask;
   int32_t* tap_idx;
   int32_t* tap_n;
-};
-hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, int, const ScanOut&, hipStream_t);
-struct PackOutliers {   // operands of the critical-column slab, written alongside the int8 codes
-  const int32_t* idx;
-  const int32_t* n_out;
   const int8_t* Wt;
   const float* c;
   int N;
@@ -90,11 +83,11 @@ static int check_linear_shape(int K, int N) {
 // Workspace layout.  The head (counters and the column flags, sized for the largest K so that
 // its place does not depend on the shape) is standing state: zero between calls.
 constexpr size_t kHeadCounters = 256;
-constexpr size_t kHeadBytes = kHeadCounters + MMD8_MAX_K;
+constexpr size_t kFlagCopies = kFlagReplicas;
+constexpr size_t kHeadBytes = kHeadCounters + kFlagCopies * MMD8_MAX_K;
 struct Workspace {
   int32_t* n_out;      // [1]
-  uint32_t* ticket;    // [1]   standing state
-  uint8_t* flag;       // [MMD8_MAX_K] standing state
+  uint8_t* flag;       // [kFlagReplicas][Kpad] inside a region sized for the largest K: standing state
   uint8_t* mask;       // [Kpad]
   int32_t* idx;        // [Kpad]
   float* r;            // [Mpad + 256]
@@ -116,8 +109,7 @@ static Workspace carve(void* base, int M, int K, int N) {
   };
   uint8_t* counters = take(kHeadCounters);
   w.n_out = reinterpret_cast<int32_t*>(counters);
-  w.ticket = reinterpret_cast<uint32_t*>(counters ? counters + 64 : nullptr);
-  w.flag = take(MMD8_MAX_K);
+  w.flag = take(kFlagCopies * MMD8_MAX_K);
   w.mask = take(Kpad);
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
   w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
@@ -245,11 +237,11 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     return !ev || hipEventRecord(static_cast<hipEvent_t>(ev), st) == hipSuccess;
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
-  const ScanOut so = {ws.flag, ws.ticket, ws.r, ws.mask, ws.idx, ws.n_out, t.outlier_mask, t.outlier_idx, t.n_outliers};
-  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, so, st) != hipSuccess) return MMD8_E_HIP;
-  const PackOutliers po = {ws.idx, ws.n_out, Wq_packed, col_absmax, N, ws.xo, ws.wo};
+  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
+  const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
+                           Wq_packed, col_absmax, N, ws.xo, ws.wo};
   const bool skinny = M <= kSkinnyMaxM;
-  if (launch_pack(X, M, K, ldx, ws.mask, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
+  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
     return MMD8_E_HIP;
   if (t.row_absmax &&
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
@@ -272,6 +264,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     g.ldy = ldy;
     g.partial = ws.partial;
     g.tap_acc = t.acc;
+    g.flag_reset = ws.flag;
     if (launch_gemm_skinny(g, plan_skinny(M, K, N), st) != hipSuccess) return MMD8_E_HIP;
   } else {
     GemmArgs g;
@@ -293,6 +286,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     g.ldy = ldy;
     g.tap_acc = t.acc;
     g.tiles_m = g.tiles_n = 0;
+    g.flag_reset = ws.flag;
     if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
   }
   if (!record(t.event_gemm_end)) return MMD8_E_HIP;

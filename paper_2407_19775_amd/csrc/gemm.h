@@ -7,6 +7,8 @@ namespace mmd8 {
 // Critical columns handled on the fast path: they travel as one extra 64-byte K-slab of fp16
 // operands (32 columns).  Columns beyond that go through the gather loop of the epilogue.
 constexpr int kOutlierSlab = 32;
+// Copies of the per-column flag array that the scan kernel's atomic updates spread over.
+constexpr int kFlagReplicas = 4;
 
 struct GemmArgs {
   const int8_t* Xq;      // activation codes, blocked layout (operand_layout.h), Mpad x Kpad
@@ -25,7 +27,17 @@ struct GemmArgs {
   int ldy;
   int32_t* tap_acc;      // [M][N] or null
   int tiles_m, tiles_n;
+  uint8_t* flag_reset;   // [kFlagReplicas][Kpad] column flags of the scan: zeroed again by workgroup 0
 };
+
+// Workgroup 0 of the kernel that ends a call puts the scan's column flags back to zero (the next
+// call's scan is ordered after it on the stream).
+__device__ inline void reset_column_flags(uint8_t* flags, int Kpad) {
+  if (blockIdx.x != 0 || flags == nullptr) return;
+  v4u* p = reinterpret_cast<v4u*>(flags);
+  const int n = kFlagReplicas * Kpad / 16;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = v4u{0, 0, 0, 0};
+}
 
 // variant selects a tile configuration (< 0: automatic); every variant computes the same result.
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream);

@@ -252,6 +252,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  reset_column_flags(a.flag_reset, a.Kpad);
   int tm, tn;
   if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
   const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
@@ -437,6 +438,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int grp = wave >> 2;
+  reset_column_flags(a.flag_reset, a.Kpad);
   int tm, tn;
   if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
   const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
@@ -613,14 +615,13 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
 
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
   if (variant < 0) {
-    // automatic.  The 256 x 256 tile (one workgroup per CU) is the most efficient per CU but runs
-    // in rounds of one tile per CU; when there are few rounds and the last one would leave half
-    // of the chip or more idle, 128 x 256 tiles (two workgroups per CU) balance better.
+    // automatic.  The 256 x 256 tile with the four-slab ring wins whenever there are enough tiles
+    // to occupy a good part of the chip: with weights coming cold from HBM (every layer has its
+    // own) the deeper prefetch matters more than the better balance of smaller tiles.
     const long tiles_256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
     const long tiles_128x256 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
     const long cus = device_cu_count();
-    const long full_rounds = tiles_256 / cus, rest = tiles_256 % cus;
-    if (a.M > 128 && tiles_256 >= cus / 2 && !(full_rounds < 2 && rest > 0 && 2 * rest <= cus))
+    if (a.M > 128 && 4 * tiles_256 >= cus)
       variant = 6;
     else if (a.M > 64 && tiles_128x256 >= 64)
       variant = 2;

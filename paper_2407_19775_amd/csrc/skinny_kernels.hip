@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(const SkinnyArgs
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int lr = lane & 31, lg = lane >> 5;
+  reset_column_flags(a.flag_reset, a.Kpad);
   const int tile = blockIdx.x % a.tiles_n, split = blockIdx.x / a.tiles_n;
   const int n = tile * 32 + lr;                                    // < Npad
   const int s_begin = split * a.slabs_per_split;
@@ -271,6 +272,7 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void k_gemm_skinny16(const Skinn
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int l16 = lane & 15, grp = lane >> 4;
+  reset_column_flags(a.flag_reset, a.Kpad);
   const int tile = blockIdx.x % a.tiles_n, split = blockIdx.x / a.tiles_n;
   const int n_base = tile * 32;
   const int s_begin = split * a.slabs_per_split;
