@@ -328,8 +328,11 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   // kIssue: slab s + kAhead exists and is requested in this iteration; kNext: slab s + 1 exists.
   constexpr int AHEAD = Cfg::kAhead;
   constexpr int MFMAS = TI * TJ;                                   // per k-step
-  constexpr int DMA_PER_KS = Cfg::DMA_PER_SLAB / NKS;
-  static_assert(Cfg::DMA_PER_SLAB % NKS == 0 && DMA_PER_KS >= 1 && DMA_PER_KS <= MFMAS, "request spreading");
+  // request d of a slab goes out after MFMA number d SLOTS / DMA_PER_SLAB of the iteration
+  constexpr int SLOTS = NKS * MFMAS, DPS_ = Cfg::DMA_PER_SLAB;
+  static_assert(DPS_ >= 1 && DPS_ <= SLOTS, "request spreading");
+  // requests of the iteration that are out before the wait in the last k-step (slot (NKS-1) MFMAS)
+  constexpr int kBeforeWait = ((NKS - 1) * MFMAS * DPS_ + SLOTS - 1) / SLOTS;
   float cs[TJ], bn[TJ];
   load_column_terms<Cfg>(a, p, cs, bn);
   int stage = 0;
@@ -364,16 +367,21 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
             // last k-step of the slab: make slab s+1 visible, then prefetch its first fragments.
             // Still allowed in flight: slabs s+2 .. s+kAhead-1 in full and the part of slab
             // s+kAhead requested during the earlier k-steps of this iteration
-            wait_slab_and_sync<kIssue ? (AHEAD - 2) * Cfg::DMA_PER_SLAB + DMA_PER_KS * (NKS - 1) : 0>();
+            wait_slab_and_sync<kIssue ? (AHEAD - 2) * Cfg::DMA_PER_SLAB + kBeforeWait : 0>();
             if (kNext) read_frags(stage1, 0, nxt);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        // requests number (t DMA_PER_KS) / MFMAS .. ((t + 1) DMA_PER_KS) / MFMAS - 1 of this k-step
-        if (kIssue && (t * DMA_PER_KS) / MFMAS != ((t + 1) * DMA_PER_KS) / MFMAS) {
-          __builtin_amdgcn_sched_barrier(0);
-          issue_dma(s + AHEAD, stage_req, ks * DMA_PER_KS + (t * DMA_PER_KS) / MFMAS);
-          __builtin_amdgcn_sched_barrier(0);
+        // request d with ceil(d SLOTS / DPS) == slot, if there is one (at most one: DPS <= SLOTS)
+        {
+          const int slot = ks * MFMAS + t;
+          const int d = slot * DPS_ / SLOTS;                             // the only candidate: d SLOTS / DPS in (slot - 1, slot]
+          const bool here = d < DPS_ && (d * SLOTS + DPS_ - 1) / DPS_ == slot;
+          if (kIssue && here) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue_dma(s + AHEAD, stage_req, d);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -621,8 +629,10 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     const long tiles_256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
     const long tiles_128x256 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
     const long cus = device_cu_count();
-    if (a.M > 128 && 4 * tiles_256 >= cus)
+    if (a.M > 128 && tiles_256 >= cus)
       variant = 6;
+    else if (a.M > 64 && 2 * tiles_128x256 >= cus)
+      variant = 7;                                   // less than one round of 256 x 256 tiles: halve them
     else if (a.M > 64 && tiles_128x256 >= 64)
       variant = 2;
     else
@@ -635,6 +645,7 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     case 4: return launch_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>(a, stream);
     case 5: return launch_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>(a, stream);
     case 6: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>(a, stream);
+    case 7: return launch_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>(a, stream);
     default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 2>, false>(a, stream);
   }
 }

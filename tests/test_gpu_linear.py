@@ -139,7 +139,7 @@ def test_config5_prefill_full_size_sampled_rows(shape):
     check_linear(X, W, wl.TAU, rows=rows)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
 def test_every_gemm_tile_configuration(variant):
     """All tile configurations of the GEMM kernel give the same integers (and pass the output bar)."""
     L = binding.lib()
@@ -158,7 +158,7 @@ def test_every_gemm_tile_configuration(variant):
 
 
 def test_one_workspace_serves_calls_of_different_shapes():
-    """The head of the workspace (column flags, ticket) is standing state: every call must leave it
+    """The head of the workspace (column flags) is standing state: every call must leave it
     ready for the next one, whatever the shapes and however many columns were flagged."""
     rng = np.random.default_rng(42)
     shapes = [(70, 2064, 72), (5, 144, 40), (300, 512, 264), (33, 2064, 72), (1, 16, 8)]
