@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--codec-block", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-variant", type=int, default=-1, help="tuning: force a GEMM tile configuration (-1 = automatic)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a kernel of known HBM traffic, to scale rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -206,6 +209,12 @@ def main():
                   "dequantize_pct_hbm": round(100 * codec_bytes / d_ms / 1e6 / HBM_PEAK_GBS, 1),
                   "elements": nel, "note": "33.6 MB tensor: resident in the last-level cache between calls"},
     }
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)            # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
