@@ -285,6 +285,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     g.Y = Y;
     g.ldy = ldy;
     g.tap_acc = t.acc;
+    g.tap_ld = N;
     g.tiles_m = g.tiles_n = 0;
     g.flag_reset = ws.flag;
     if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;

@@ -25,7 +25,8 @@ struct GemmArgs {
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   uint16_t* Y;
   int ldy;
-  int32_t* tap_acc;      // [M][N] or null
+  int32_t* tap_acc;      // [M][tap_ld] or null
+  int tap_ld;
   int tiles_m, tiles_n;
   uint8_t* flag_reset;   // [kFlagReplicas][Kpad] column flags of the scan: zeroed again by workgroup 0
 };

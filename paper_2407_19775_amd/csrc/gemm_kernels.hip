@@ -124,7 +124,7 @@ __device__ inline void tap_accumulators(const GemmArgs& a, const WavePos<Cfg>& p
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int m = p.mw + i * 32 + 8 * (e / 4) + 4 * p.lg + (e % 4), n = p.nw + j * 32 + p.lr;
-        if (m < a.M && n < a.N) a.tap_acc[(size_t)m * a.N + n] = acc[i][j][e];
+        if (m < a.M && n < a.N) a.tap_acc[(size_t)m * a.tap_ld + n] = acc[i][j][e];
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -621,23 +621,7 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   return full ? launch_one<Cfg, false, true, kPingPong>(a, stream) : launch_one<Cfg, false, false, kPingPong>(a, stream);
 }
 
-hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
-  if (variant < 0) {
-    // automatic.  The 256 x 256 tile with the four-slab ring wins whenever there are enough tiles
-    // to occupy a good part of the chip: with weights coming cold from HBM (every layer has its
-    // own) the deeper prefetch matters more than the better balance of smaller tiles.
-    const long tiles_256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
-    const long tiles_128x256 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
-    const long cus = device_cu_count();
-    if (a.M > 128 && tiles_256 >= cus)
-      variant = 6;
-    else if (a.M > 64 && 2 * tiles_128x256 >= cus)
-      variant = 7;                                   // less than one round of 256 x 256 tiles: halve them
-    else if (a.M > 64 && tiles_128x256 >= 64)
-      variant = 2;
-    else
-      variant = 0;
-  }
+static hipError_t launch_variant(const GemmArgs& a, int variant, hipStream_t stream) {
   switch (variant) {
     case 1: return launch_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>(a, stream);
     case 2: return launch_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>(a, stream);
@@ -648,6 +632,47 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     case 7: return launch_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>(a, stream);
     default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 2>, false>(a, stream);
   }
+}
+
+// the same problem restricted to output columns [n0, n0 + n): n0 a multiple of 256
+static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
+  GemmArgs b = a;
+  const size_t panels = (size_t)n0 / kPanelRows;
+  b.Wt = a.Wt + panels * (size_t)(a.Kpad / BK) * kBlockBytes;
+  b.Wo = a.Wo + panels * (kBlockBytes / 2);
+  b.c = a.c + n0;
+  b.bias = a.bias ? a.bias + n0 : nullptr;
+  b.Y = a.Y + n0;
+  b.tap_acc = a.tap_acc ? a.tap_acc + n0 : nullptr;
+  b.N = n;
+  return b;
+}
+
+hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
+  if (variant >= 0) return launch_variant(a, variant, stream);
+  // Automatic.  The 256 x 256 tile with the four-slab ring is the most efficient per CU, but it runs
+  // in rounds of one tile per CU.  Whole rounds go to it; a remainder that would leave a good part of
+  // the chip idle is launched separately with 128 x 256 tiles (same ring depth, twice as many
+  // workgroups).  With weights coming cold from HBM (every layer has its own) the deep prefetch
+  // matters more than the better balance of small tiles, so small tiles are for small problems only.
+  const int tiles_m = ceil_div(a.M, 256), tiles_n = ceil_div(a.N, 256);
+  const long tiles_256 = (long)tiles_m * tiles_n;
+  const long tiles_128x256 = (long)ceil_div(a.M, 128) * tiles_n;
+  const long cus = device_cu_count();
+  if (a.M > 128 && tiles_256 >= cus) {
+    const long rest = tiles_256 % cus;
+    const int n_tiles_main = (int)((tiles_256 - rest) / tiles_m);      // whole columns of tiles in the whole rounds
+    const int n_tiles_rest = tiles_n - n_tiles_main;
+    if (rest > 0 && 2 * rest <= cus && n_tiles_main > 0 && n_tiles_rest > 0) {
+      hipError_t e = launch_variant(column_range(a, 0, n_tiles_main * 256), 6, stream);
+      if (e != hipSuccess) return e;
+      return launch_variant(column_range(a, n_tiles_main * 256, a.N - n_tiles_main * 256), 7, stream);
+    }
+    return launch_variant(a, 6, stream);
+  }
+  if (a.M > 64 && 2 * tiles_128x256 >= cus) return launch_variant(a, 7, stream);   // less than one round of large tiles
+  if (a.M > 64 && tiles_128x256 >= 64) return launch_variant(a, 2, stream);
+  return launch_variant(a, 0, stream);
 }
 
 }  // namespace mmd8
