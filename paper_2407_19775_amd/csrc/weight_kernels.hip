@@ -15,21 +15,42 @@ __global__ __launch_bounds__(256) void k_col_absmax(const uint16_t* __restrict__
                                                     uint32_t* __restrict__ c_bits) {
   const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
   const int n0 = (blockIdx.x * 32 + cg) * 8;
-  if (n0 >= N) return;
+  const bool live = n0 < N;
   uint32_t m[4] = {0, 0, 0, 0};
-  for (int k = blockIdx.y * 8 + rl; k < K; k += gridDim.y * 8) {
-    const v4u raw = *reinterpret_cast<const v4u*>(W + (size_t)k * ldw + n0);
+  typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+  // four rows in flight per thread (rows past K read as zeros)
+  const int stride = gridDim.y * 8;
+  for (int k = blockIdx.y * 8 + rl; k < K; k += 4 * stride) {
+    v4u raw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      raw[u] = v4u{0, 0, 0, 0};
+      if (live && k + u * stride < K) raw[u] = *reinterpret_cast<const v4u*>(W + (size_t)(k + u * stride) * ldw + n0);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const us2 a = __builtin_bit_cast(us2, raw[u][w] & 0x7fff7fffu);
+        m[w] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, m[w]), a));
+      }
+  }
+  // the 8 row lanes of a column group meet in LDS: one atomic per column and workgroup
+  __shared__ uint32_t s_m[8][32][4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) s_m[rl][cg][w] = m[w];
+  __syncthreads();
+  if (rl == 0 && live) {
+#pragma unroll
+    for (int r = 1; r < 8; ++r)
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        m[w] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, m[w]), __builtin_bit_cast(us2, s_m[r][cg][w])));
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-      const us2 a = __builtin_bit_cast(us2, raw[w] & 0x7fff7fffu);
-      m[w] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, m[w]), a));
+      atomicMax(c_bits + n0 + 2 * w, __float_as_uint(half_lo_to_float(m[w])));
+      atomicMax(c_bits + n0 + 2 * w + 1, __float_as_uint(half_hi_to_float(m[w])));
     }
-  }
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    atomicMax(c_bits + n0 + 2 * w, __float_as_uint(half_lo_to_float(m[w])));
-    atomicMax(c_bits + n0 + 2 * w + 1, __float_as_uint(half_hi_to_float(m[w])));
   }
 }
 
@@ -84,7 +105,7 @@ __global__ void k_weight_unpack(const int8_t* __restrict__ Wt, int K, int N, int
 }
 
 hipError_t launch_col_absmax(const uint16_t* W, int K, int N, int ldw, float* c, hipStream_t stream) {
-  const int ysplit = max(1, min(ceil_div(K, 8), 4096 / max(1, ceil_div(N, 256))));
+  const int ysplit = max(1, min(ceil_div(K, 32), 2048 / max(1, ceil_div(N, 256))));
   hipLaunchKernelGGL(k_col_absmax, dim3(ceil_div(N, 256), ysplit), dim3(256), 0, stream, W, K, N, ldw,
                      reinterpret_cast<uint32_t*>(c));
   return hipGetLastError();
