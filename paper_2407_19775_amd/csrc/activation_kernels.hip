@@ -36,12 +36,11 @@ __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
 // One workgroup owns kRows consecutive rows over all K columns: row scales need no atomics.
 // kRows is 4 for tall inputs and smaller for short ones, so that there are always enough
 // workgroups to keep the memory system busy.
-// A column is flagged by a device-scope atomic OR into a byte-per-column flag array that is zero
-// when the kernel starts.  Every row tends to exceed the threshold in the same few columns, and
-// atomics on one address are served one after the other, so the workgroups spread over
-// kFlagReplicas copies of the array; the readers OR the copies.  The flags are part of the
-// workspace's standing state: zeroed once when the workspace is set up, read by the pack kernel,
-// and zeroed again by the GEMM kernel that ends the call.
+// A column is flagged by a plain byte store of 1 into a byte-per-column flag array that is zero
+// when the kernel starts: every writer stores the same value and the readers are later kernels,
+// so no atomics and no waiting are needed.  The flags are part of the workspace's standing state:
+// zeroed once when the workspace is set up, read by the kernels that follow the scan, and zeroed
+// again by the GEMM kernel that ends the call.
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 __device__ inline us2 as_us2(uint32_t v) { return __builtin_bit_cast(us2, v); }
 __device__ inline uint32_t as_u32(us2 v) { return __builtin_bit_cast(uint32_t, v); }
@@ -86,17 +85,11 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
     }
     const uint32_t all_and = col_and[0] & col_and[1] & col_and[2] & col_and[3];
     if ((~all_and) & 0x80008000u) {                   // rare: some entry of this thread is >= th
-      // the thread's 8 columns are 8 flag bytes = 2 words; device-scope OR (performed at the
-      // coherent level of the memory system, so no cache write-back is needed to publish it)
-      uint32_t f[2] = {0, 0};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        if (!(col_and[w] & 0x8000u)) f[w >> 1] |= 1u << (16 * (w & 1));
-        if (!(col_and[w] & 0x80000000u)) f[w >> 1] |= 1u << (16 * (w & 1) + 8);
+        if (!(col_and[w] & 0x8000u)) flag[k0 + 2 * w] = 1;
+        if (!(col_and[w] & 0x80000000u)) flag[k0 + 2 * w + 1] = 1;
       }
-      uint32_t* fw = reinterpret_cast<uint32_t*>(flag + (size_t)(blockIdx.x % kFlagReplicas) * Kpad + k0);
-      if (f[0]) __hip_atomic_fetch_or(fw, f[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (f[1]) __hip_atomic_fetch_or(fw + 1, f[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     }
   }
@@ -132,12 +125,9 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
   q = fminf(fmaxf(q, -127.0f), 127.0f);
   return (uint32_t)((int)q) & 0xffu;
 }
-// 16 column flags (bytes 0 / 1) starting at column k0: the OR of the replicas
-__device__ inline v4u merged_flags16(const uint8_t* __restrict__ flag, int Kpad, int k0) {
-  v4u f = v4u{0, 0, 0, 0};
-#pragma unroll
-  for (int rep = 0; rep < kFlagReplicas; ++rep) f |= *reinterpret_cast<const v4u*>(flag + (size_t)rep * Kpad + k0);
-  return f & 0x01010101u;
+// 16 column flags (bytes 0 / 1) starting at column k0
+__device__ inline v4u flags16(const uint8_t* __restrict__ flag, int k0) {
+  return *reinterpret_cast<const v4u*>(flag + k0) & 0x01010101u;
 }
 
 // The ascending list of critical columns and their count, computed by one whole workgroup from
@@ -157,8 +147,12 @@ __device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag
   int cnt = 0;
 #pragma unroll
   for (int i = 0; i < kMaxUnits; ++i) {
-    f[i] = v4u{0, 0, 0, 0};
-    if (i < per && u_begin + i < units) f[i] = merged_flags16(flag, Kpad, 16 * (u_begin + i));
+    // unconditional loads (a unit past the thread's run re-reads unit 0 and is masked): all in flight together
+    const bool mine = i < per && u_begin + i < units;
+    f[i] = flags16(flag, mine ? 16 * (u_begin + i) : 0) & (mine ? 0xffffffffu : 0u);
+  }
+#pragma unroll
+  for (int i = 0; i < kMaxUnits; ++i) {
 #pragma unroll
     for (int w = 0; w < 4; ++w) cnt += __builtin_popcount(f[i][w]);
   }
@@ -213,18 +207,29 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8), j0 = ch * 8;
   if (row >= M + o.N) return;
   const int n_out = min(n_out_all, kOutlierSlab);
+  // all eight loads of a thread are issued together: a missing column re-reads column 0 and is masked
+  int kcol[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) kcol[t] = (j0 + t < n_out) ? s_idx[j0 + t] : -1;
   uint32_t out[4] = {0, 0, 0, 0};
   if (row < M) {
-    for (int t = 0; t < 8 && j0 + t < n_out; ++t)
-      out[t >> 1] |= (uint32_t)X[(size_t)row * ldx + s_idx[j0 + t]] << (16 * (t & 1));
+    uint16_t v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + max(kcol[t], 0)];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) out[t >> 1] |= (kcol[t] >= 0 ? (uint32_t)v[t] : 0u) << (16 * (t & 1));
     *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, 1)) =
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
     const float step = o.c[n] / 127.0f;
-    for (int t = 0; t < 8 && j0 + t < n_out; ++t) {
-      const float w = (float)o.Wt[packed_offset(n, s_idx[j0 + t], n_slabs)] * step;
-      out[t >> 1] |= rounded_float_to_half_bits(w) << (16 * (t & 1));
+    int8_t q[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) q[t] = o.Wt[packed_offset(n, max(kcol[t], 0), n_slabs)];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t h = rounded_float_to_half_bits((float)q[t] * step);
+      out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
     }
     *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, 1)) =
         v4u{out[0], out[1], out[2], out[3]};
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
     const bool in_k = k0 < K;                         // K % 16 == 0: a piece is all inside or all padding
     uint32_t keep[4] = {0, 0, 0, 0};                  // 0xff per kept byte
     if (in_k) {
-      const v4u f = merged_flags16(flag, n_slabs * kSlabBytes, k0);
+      const v4u f = flags16(flag, k0);
 #pragma unroll
       for (int w = 0; w < 4; ++w) keep[w] = (0x01010101u - f[w]) * 0xffu;   // bytes are 0 or 1: no carries
     }
@@ -317,6 +322,183 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
   }
 }
 
+// ------------------------------------------------------------------ one-pass preparation (tall inputs)
+// Scan and quantization in a single pass over X: a workgroup holds four whole rows in registers,
+// finds their scales and the columns that reach the threshold, and writes the codes of every
+// column straight away.  Which columns are critical is only known once every row has been seen,
+// so the codes of critical columns are cleared afterwards by k_outlier_columns (a few bytes per
+// row); X is read once and the codes written once: 3 bytes per element instead of 5.
+//
+// Lane l of a wave owns row (l % 4) of the workgroup's four rows and, in pass q, the 16-column
+// piece 16 (q kWaves + wave) + l / 4 of that row: a load instruction reads 512 contiguous bytes of
+// each of four rows, and a store instruction writes 64-byte runs (the four rows of a piece are
+// neighbours in the blocked layout).
+template <int kWaves, int kPasses>
+__global__ __launch_bounds__(kWaves * kWave) void k_prep(const uint16_t* __restrict__ X, int M, int K, int ldx, uint32_t th,
+                                                         int n_slabs, uint8_t* __restrict__ flag,
+                                                         float* __restrict__ r_out, int8_t* __restrict__ Xq,
+                                                         int8_t* __restrict__ tap_xq) {
+  __shared__ uint32_t s_part[kWaves][4];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int j = lane & 3, i = lane >> 2;
+  const int m = blockIdx.x * 4 + j;
+  const bool row_ok = m < M;
+  const int Kpad = n_slabs * kSlabBytes;
+  const int n_pieces = Kpad / 16, k_pieces = K / 16;
+  const us2 th2 = as_us2(th | (th << 16));
+
+  // every load is unconditional (a lane without data re-reads the first piece of row 0, and what
+  // it derives from that is discarded), so that all of them are in flight together
+  v4u a[kPasses], b[kPasses];
+#pragma unroll
+  for (int q = 0; q < kPasses; ++q) {
+    const int piece = (q * kWaves + wave) * 16 + i;
+    const bool ok = row_ok && piece < k_pieces;
+    const uint16_t* src = X + (ok ? (size_t)m * ldx + piece * 16 : (size_t)0);
+    a[q] = *reinterpret_cast<const v4u*>(src);
+    b[q] = *reinterpret_cast<const v4u*>(src + 8);
+  }
+
+  // ---- row scale and column flags (packed 16-bit compares, see the top of the file)
+  us2 rowt = as_us2(0u);
+#pragma unroll
+  for (int q = 0; q < kPasses; ++q) {
+    const int piece = (q * kWaves + wave) * 16 + i;
+    uint32_t t_and = 0xffffffffu;
+    us2 t_max = as_us2(0u);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const us2 t0 = as_us2(a[q][w] & 0x7fff7fffu) - th2, t1 = as_us2(b[q][w] & 0x7fff7fffu) - th2;
+      t_max = __builtin_elementwise_max(t_max, __builtin_elementwise_max(t0, t1));
+      t_and &= as_u32(t0) & as_u32(t1);
+    }
+    if (row_ok && piece < k_pieces) rowt = __builtin_elementwise_max(rowt, t_max);
+    {
+      // evaluate now: left alone, the compiler keeps all differences of every piece until after the loop
+      uint32_t pin = as_u32(rowt);
+      asm volatile("" : "+v"(pin));
+      rowt = as_us2(pin);
+    }
+    const bool hit = row_ok && piece < k_pieces && ((~t_and) & 0x80008000u);
+    if (__builtin_amdgcn_ballot_w64(hit)) {                 // rare for prefill-like inputs
+      // one bit per column of the piece that reaches the threshold in this row, then over the
+      // four rows of the quad; the quad's first lane publishes what is not yet known
+      uint32_t bits = 0;
+      if (hit) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // plain magnitude compares here: sharing the packed differences of the common path with
+          // this rare one would keep them in registers for every piece
+          bits |= (uint32_t)((a[q][w] & 0x7fffu) >= th) << (2 * w) | (uint32_t)(((a[q][w] >> 16) & 0x7fffu) >= th) << (2 * w + 1);
+          bits |= (uint32_t)((b[q][w] & 0x7fffu) >= th) << (8 + 2 * w) | (uint32_t)(((b[q][w] >> 16) & 0x7fffu) >= th) << (9 + 2 * w);
+        }
+      }
+      bits |= (uint32_t)__builtin_amdgcn_mov_dpp((int)bits, 0xb1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+      bits |= (uint32_t)__builtin_amdgcn_mov_dpp((int)bits, 0x4e, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+      if (j == 0) {
+        // plain byte stores of 1: every writer stores the same value, nobody reads before the
+        // kernel ends, and nothing is waited for
+        uint8_t* fb = flag + piece * 16;
+        while (bits) {
+          fb[__builtin_ctz(bits)] = 1;
+          bits &= bits - 1;
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);                    // one piece at a time: bounded registers
+  }
+  uint32_t mx = max(as_u32(rowt) & 0xffffu, as_u32(rowt) >> 16);
+#pragma unroll
+  for (int d = 4; d < kWave; d <<= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, d, kWave));
+  if (lane < 4) s_part[wave][lane] = mx;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) mx = max(mx, s_part[w][j]);
+  // top bit set: a sub-threshold entry exists and its pattern is mx + th (mod 2^16)
+  const float r = (mx & 0x8000u) ? half_lo_to_float((mx + th) & 0xffffu) : 0.0f;
+  if (threadIdx.x < 4 && row_ok) r_out[m] = r;
+  const float scale = (r == 0.0f) ? 0.0f : 127.0f / r;            // IEEE division
+
+  // ---- codes of every column (critical ones are cleared later); K padding gets zeros
+  if (!row_ok) return;
+#pragma unroll
+  for (int q = 0; q < kPasses; ++q) {
+    int piece = (q * kWaves + wave) * 16 + i;
+    // keeps the address arithmetic and the fp16 -> fp32 conversions of this piece here (hoisted above
+    // the barrier they would double the registers)
+    asm volatile("" : "+v"(piece), "+v"(a[q]), "+v"(b[q]));
+    if (piece >= n_pieces) break;
+    uint32_t out[4];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      out[w] = to_code_byte(half_lo_to_float(a[q][2 * w]), scale) | (to_code_byte(half_hi_to_float(a[q][2 * w]), scale) << 8) |
+               (to_code_byte(half_lo_to_float(a[q][2 * w + 1]), scale) << 16) |
+               (to_code_byte(half_hi_to_float(a[q][2 * w + 1]), scale) << 24);
+      out[2 + w] = to_code_byte(half_lo_to_float(b[q][2 * w]), scale) | (to_code_byte(half_hi_to_float(b[q][2 * w]), scale) << 8) |
+                   (to_code_byte(half_lo_to_float(b[q][2 * w + 1]), scale) << 16) |
+                   (to_code_byte(half_hi_to_float(b[q][2 * w + 1]), scale) << 24);
+    }
+    const uint32_t in_k = piece < k_pieces ? 0xffffffffu : 0u;     // the K padding holds zeros
+    const v4u v = v4u{out[0] & in_k, out[1] & in_k, out[2] & in_k, out[3] & in_k};
+    *reinterpret_cast<v4u*>(Xq + packed_chunk_offset(m, piece >> 2, piece & 3, n_slabs)) = v;
+    if (tap_xq && piece < k_pieces) *reinterpret_cast<v4u*>(tap_xq + (size_t)m * K + piece * 16) = v;
+    __builtin_amdgcn_sched_barrier(0);                    // one piece at a time: bounded registers
+  }
+}
+
+// After k_prep: the first `slab_blocks` workgroups list the critical columns (the first one
+// publishes the list, the count and the byte mask) and build the fp16 slab of the first
+// kOutlierSlab of them; in the remaining workgroups every wave owns 64 rows (lane = row) and
+// clears the codes of the critical columns in those rows with byte stores of zero.  Driven by the
+// flags themselves, so any number of critical columns is handled the same way.
+__global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __restrict__ X, int M, int K, int ldx,
+                                                              const uint8_t* __restrict__ flag, int8_t* __restrict__ Xq,
+                                                              int n_slabs, int8_t* __restrict__ tap_xq, int slab_blocks,
+                                                              const PackOutliers o) {
+  const int Kpad = n_slabs * kSlabBytes;
+  if ((int)blockIdx.x < slab_blocks) {
+    __shared__ int s_idx[kOutlierSlab];
+    __shared__ int s_n_out;
+    __shared__ int s_wave_total[kThreads / kWave];
+    compact_critical_columns(flag, K, Kpad, o, blockIdx.x == 0, s_idx, &s_n_out, s_wave_total);
+    gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
+    return;
+  }
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int m = (((int)blockIdx.x - slab_blocks) * (kThreads / kWave) + wave) * kWave + lane;
+  const int units = Kpad / 16;
+  // lane l looks at unit u0 + l; the flags of the next 64 units are fetched while these are handled
+  v4u f = lane < units ? flags16(flag, 16 * lane) : v4u{0, 0, 0, 0};
+  for (int u0 = 0; u0 < units; u0 += kWave) {
+    const int u_next = u0 + kWave + lane;
+    const v4u f_next = u_next < units ? flags16(flag, 16 * u_next) : v4u{0, 0, 0, 0};
+    uint64_t todo = __builtin_amdgcn_ballot_w64((f[0] | f[1] | f[2] | f[3]) != 0);
+    while (todo) {
+      const int t = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int unit = u0 + t;
+      // the flagged columns of this unit, one bit each (the same for every lane)
+      uint32_t cols = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t fw = (uint32_t)__builtin_amdgcn_readlane((int)f[w], t);
+        cols |= ((fw & 1u) | ((fw >> 7) & 2u) | ((fw >> 14) & 4u) | ((fw >> 21) & 8u)) << (4 * w);
+      }
+      if (m < M) {
+        int8_t* p = Xq + packed_chunk_offset(m, unit >> 2, unit & 3, n_slabs);
+        int8_t* tp = tap_xq ? tap_xq + (size_t)m * K + unit * 16 : nullptr;
+        while (cols) {
+          const int c = __builtin_ctz(cols);
+          cols &= cols - 1;
+          p[c] = 0;
+          if (tp) tp[c] = 0;
+        }
+      }
+    }
+    f = f_next;
+  }
+}
+
 // ------------------------------------------------------------------ launchers
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
@@ -346,6 +528,32 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
   const int slab_y = max(1, ceil_div(ceil_div(slab_items, kThreads), gx));
   const dim3 grid(gx, pack_y + slab_y);
   hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, Xf, o);
+  return hipGetLastError();
+}
+
+// One-pass preparation for inputs taller than the decode kernels take; false when K is too large for
+// a row to be held in the registers of one workgroup (the caller then uses scan + pack).
+bool prep_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 8; }
+
+hipError_t launch_prep(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
+                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, hipStream_t stream) {
+  const int n_slabs = Kpad / kSlabBytes, n_pieces = Kpad / 16;
+  const dim3 grid(ceil_div(M, 4));
+#define MMD8_PREP(W_, P_)                                                                                      \
+  hipLaunchKernelGGL((k_prep<W_, P_>), grid, dim3(W_ * kWave), 0, stream, X, M, K, ldx, th, n_slabs, flag, r, Xq, tap_xq)
+  if (n_pieces <= 64) MMD8_PREP(4, 1);
+  else if (n_pieces <= 128) MMD8_PREP(4, 2);
+  else if (n_pieces <= 256) MMD8_PREP(4, 4);
+  else if (n_pieces <= 512) MMD8_PREP(8, 4);
+  else if (n_pieces <= 1024) MMD8_PREP(16, 4);
+  else MMD8_PREP(16, 8);
+#undef MMD8_PREP
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int slab_blocks = max(1, ceil_div((M + o.N) * (kOutlierSlab / 8), kThreads));
+  const int clear_blocks = ceil_div(M, kThreads);
+  hipLaunchKernelGGL(k_outlier_columns, dim3(slab_blocks + clear_blocks), dim3(kThreads), 0, stream, X, M, K, ldx, flag, Xq,
+                     n_slabs, tap_xq, slab_blocks, o);
   return hipGetLastError();
 }
 

@@ -33,6 +33,9 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
 };
 hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*, uint16_t*,
                        const PackOutliers&, hipStream_t);
+bool prep_fits(int K);
+hipError_t launch_prep(const uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, int8_t*, int8_t*, const PackOutliers&,
+                       hipStream_t);
 hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
 hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
 hipError_t launch_weight_unpack(const int8_t*, int, int, int8_t*, hipStream_t);
@@ -83,11 +86,10 @@ static int check_linear_shape(int K, int N) {
 // Workspace layout.  The head (counters and the column flags, sized for the largest K so that
 // its place does not depend on the shape) is standing state: zero between calls.
 constexpr size_t kHeadCounters = 256;
-constexpr size_t kFlagCopies = kFlagReplicas;
-constexpr size_t kHeadBytes = kHeadCounters + kFlagCopies * MMD8_MAX_K;
+constexpr size_t kHeadBytes = kHeadCounters + MMD8_MAX_K;
 struct Workspace {
   int32_t* n_out;      // [1]
-  uint8_t* flag;       // [kFlagReplicas][Kpad] inside a region sized for the largest K: standing state
+  uint8_t* flag;       // [Kpad] inside a region sized for the largest K: standing state
   uint8_t* mask;       // [Kpad]
   int32_t* idx;        // [Kpad]
   float* r;            // [Mpad + 256]
@@ -109,7 +111,7 @@ static Workspace carve(void* base, int M, int K, int N) {
   };
   uint8_t* counters = take(kHeadCounters);
   w.n_out = reinterpret_cast<int32_t*>(counters);
-  w.flag = take(kFlagCopies * MMD8_MAX_K);
+  w.flag = take(MMD8_MAX_K);
   w.mask = take(Kpad);
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
   w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
@@ -237,12 +239,18 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
     return !ev || hipEventRecord(static_cast<hipEvent_t>(ev), st) == hipSuccess;
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
-  if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
                            Wq_packed, col_absmax, N, ws.xo, ws.wo};
   const bool skinny = M <= kSkinnyMaxM;
-  if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
-    return MMD8_E_HIP;
+  if (!skinny && prep_fits(K)) {
+    // one pass over X: scales, flags and codes together, then the critical columns are cleared
+    if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, st) != hipSuccess)
+      return MMD8_E_HIP;
+  } else {
+    if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
+    if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
+      return MMD8_E_HIP;
+  }
   if (t.row_absmax &&
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MMD8_E_HIP;

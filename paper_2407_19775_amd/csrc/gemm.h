@@ -7,8 +7,6 @@ namespace mmd8 {
 // Critical columns handled on the fast path: they travel as one extra 64-byte K-slab of fp16
 // operands (32 columns).  Columns beyond that go through the gather loop of the epilogue.
 constexpr int kOutlierSlab = 32;
-// Copies of the per-column flag array that the scan kernel's atomic updates spread over.
-constexpr int kFlagReplicas = 4;
 
 struct GemmArgs {
   const int8_t* Xq;      // activation codes, blocked layout (operand_layout.h), Mpad x Kpad
@@ -28,7 +26,7 @@ struct GemmArgs {
   int32_t* tap_acc;      // [M][tap_ld] or null
   int tap_ld;
   int tiles_m, tiles_n;
-  uint8_t* flag_reset;   // [kFlagReplicas][Kpad] column flags of the scan: zeroed again by workgroup 0
+  uint8_t* flag_reset;   // [Kpad] column flags of the scan: zeroed again by workgroup 0
 };
 
 // Workgroup 0 of the kernel that ends a call puts the scan's column flags back to zero (the next
@@ -36,7 +34,7 @@ struct GemmArgs {
 __device__ inline void reset_column_flags(uint8_t* flags, int Kpad) {
   if (blockIdx.x != 0 || flags == nullptr) return;
   v4u* p = reinterpret_cast<v4u*>(flags);
-  const int n = kFlagReplicas * Kpad / 16;
+  const int n = Kpad / 16;
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = v4u{0, 0, 0, 0};
 }
 

@@ -27,7 +27,7 @@ struct SkinnyArgs {
   int ldy;
   float* partial;         // workspace for split K
   int32_t* tap_acc;       // [M][N] or null
-  uint8_t* flag_reset;    // [kFlagReplicas][Kpad] column flags of the scan: zeroed again by workgroup 0
+  uint8_t* flag_reset;    // [Kpad] column flags of the scan: zeroed again by workgroup 0
   int n_slabs, tiles_n, slabs_per_split;   // filled by the launcher
 };
 
