@@ -173,26 +173,47 @@ __device__ inline uint32_t midpoints_below(float v, uint32_t cells_biased) {
   return cell[1] + (r > cell[0] ? 1u : 0u);
 }
 
+// f32(low or high fp16 half of `word`) * inv as one instruction: a fused multiply-add that reads the
+// half directly, with addend +0.  Same rounding as a multiplication; a zero product may come out
+// as +0 instead of -0, which lands in the same lookup cell with the same count.
+template <bool kHigh>
+__device__ inline float half_times(uint32_t word, float inv) {
+  float v;
+  if constexpr (kHigh)
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(v) : "v"(word), "v"(inv));
+  else
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(v) : "v"(word), "v"(inv));
+  return v;
+}
+
 // eight fp16 values (one 16-byte chunk) -> eight codes (8 bytes)
 __device__ inline v2u encode_chunk(const v4u& raw, float inv, uint32_t cells_biased) {
   uint32_t pair[4];
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
     const uint32_t word = raw[w];
-    const uint32_t n0 = midpoints_below(half_lo_to_float(word) * inv, cells_biased);
-    const uint32_t n1 = midpoints_below(half_hi_to_float(word) * inv, cells_biased);
+    const uint32_t n0 = midpoints_below(half_times<false>(word, inv), cells_biased);
+    const uint32_t n1 = midpoints_below(half_times<true>(word, inv), cells_biased);
     const us2 cnt = __builtin_bit_cast(us2, n0 | (n1 << 16));
-    // 0xffff in the halves where x < 0 (sign bit of each fp16 times 0xffff; no carries)
-    const us2 neg = __builtin_bit_cast(us2, ((word >> 15) & 0x00010001u) * 0xffffu);
-    const us2 cap = neg + (unsigned short)128;                    // 128, or 127 for negatives
-    const us2 off = (unsigned short)255 - cap;                    // 127, or 128 for negatives
-    // x >= 0: 127 + n ;  x < 0: 127 - min(n, 127) = (min(n, 127) ^ 0xffff) + 128  (mod 2^16)
-    pair[w] = __builtin_bit_cast(uint32_t, (us2)((__builtin_elementwise_min(cnt, cap) ^ neg) + off));
+    // 0xffff in the halves where x < 0 (arithmetic shift of each half; written out because the
+    // compiler turns the vector shift into compares and selects)
+    uint32_t neg_bits;
+    // (op_sel_hi: both halves take the shift count from the low half of the constant)
+    asm("v_pk_ashrrev_i16 %0, 15, %1 op_sel_hi:[0,1]" : "=v"(neg_bits) : "v"(word));
+    const us2 neg = __builtin_bit_cast(us2, neg_bits);
+    // x >= 0: 127 + n ;  x < 0: 127 - min(n, 127) = a saturating 127 - n (n <= 128)
+    const us2 up = (cnt & ~neg) + (unsigned short)127;
+    pair[w] = __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(up, (us2)(cnt & neg)));
   }
   // pair[w] holds two codes in its 16-bit halves: gather the low bytes
   return v2u{__builtin_amdgcn_perm(pair[1], pair[0], 0x06040200u), __builtin_amdgcn_perm(pair[3], pair[2], 0x06040200u)};
 }
 
+// A workgroup encodes kSpansPerGroup spans that lie half the tensor apart, all of their loads issued
+// before anything else: every workgroup is short, the chip always holds many workgroups at
+// different stages, and the memory system sees a few long sequential streams.  (Measured on the
+// [8192, 8192] hidden state: 1, 2, 4, 8 spans per workgroup give 4.3, 4.8, 4.6, 4.1 TB/s.)
+constexpr int kSpansPerGroup = 2;
 template <int kLogBlock>
 __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __restrict__ x, size_t n_spans,
                                                             uint8_t* __restrict__ codes,
@@ -200,33 +221,37 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
   static_assert(kLogBlock >= 6 && kLogBlock <= 12, "64 .. 4096");
   __shared__ v2u s_cells[DynamicCode::kCells];
   __shared__ uint32_t s_wave_max[2][kThreads / kWave];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  constexpr int kBlock = 1 << kLogBlock;
+  constexpr int kLanesPerBlock = kBlock / kChunk;                  // lanes of one load that share a block
+
+  // span j of this workgroup; a missing one re-reads the last span and stores nothing
+  v4u raw[kSpansPerGroup][2];
+  size_t span_of[kSpansPerGroup];
+#pragma unroll
+  for (int j = 0; j < kSpansPerGroup; ++j) {
+    span_of[j] = blockIdx.x + (size_t)j * gridDim.x;
+    const size_t sp = span_of[j] < n_spans ? span_of[j] : n_spans - 1;
+    const uint16_t* base = x + sp * kSpanMax + wave * 1024 + lane * kChunk;
+    raw[j][0] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base));
+    raw[j][1] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base + 512));
+  }
   for (int i = threadIdx.x; i < DynamicCode::kCells; i += kThreads) {
     const CodeCell c = kCodeDev.cell[i];
     s_cells[i] = v2u{c.threshold == kNoThreshold ? kNoThreshold : c.threshold * 2u, c.base};
   }
   __syncthreads();
   const uint32_t cells_biased = (uint32_t)(uintptr_t)s_cells - (uint32_t)DynamicCode::kCellLo * 8u;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  constexpr int kBlock = 1 << kLogBlock;
-  constexpr int kLanesPerBlock = kBlock / kChunk;                  // lanes of one load that share a block
 
-  v4u raw[2], nxt[2];
-  auto load_span = [&](size_t span, v4u (&dst)[2]) {
-    const uint16_t* base = x + span * kSpanMax + wave * 1024 + lane * kChunk;
-    dst[0] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base));
-    dst[1] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base + 512));
-  };
-  size_t span = blockIdx.x;
-  if (span < n_spans) load_span(span, raw);
-  for (int it = 0; span < n_spans; span += gridDim.x, ++it) {
-    const size_t next = span + gridDim.x;
-    if (next < n_spans) load_span(next, nxt);                      // in flight while this span is encoded
-    uint32_t m0 = chunk_absmax_pattern(raw[0]), m1 = chunk_absmax_pattern(raw[1]);
-    const size_t e_wave = span * kSpanMax + wave * 1024;           // first element of this wave's quarter
+#pragma unroll
+  for (int j = 0; j < kSpansPerGroup; ++j) {
+    const bool real = span_of[j] < n_spans;                        // the same for every thread
+    uint32_t m0 = chunk_absmax_pattern(raw[j][0]), m1 = chunk_absmax_pattern(raw[j][1]);
+    const size_t e_wave = span_of[j] * kSpanMax + wave * 1024;     // first element of this wave's quarter
     if constexpr (kLogBlock <= 9) {
       m0 = group_max<kLanesPerBlock>(m0);
       m1 = group_max<kLanesPerBlock>(m1);
-      if ((lane & (kLanesPerBlock - 1)) == 0) {
+      if (real && (lane & (kLanesPerBlock - 1)) == 0) {
         absmax[(e_wave + lane * kChunk) >> kLogBlock] = half_lo_to_float(m0);
         absmax[(e_wave + 512 + lane * kChunk) >> kLogBlock] = half_lo_to_float(m1);
       }
@@ -234,70 +259,83 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
       m0 = group_max<kWave>(max(m0, m1));
       if constexpr (kLogBlock >= 11) {
         // blocks of 2 or 4 waves: exchange through LDS (slot alternates, so one barrier per span)
-        if (lane == 0) s_wave_max[it & 1][wave] = m0;
+        if (lane == 0) s_wave_max[j & 1][wave] = m0;
         __syncthreads();
         if constexpr (kLogBlock == 11)
-          m0 = max(s_wave_max[it & 1][wave & ~1], s_wave_max[it & 1][wave | 1]);
+          m0 = max(s_wave_max[j & 1][wave & ~1], s_wave_max[j & 1][wave | 1]);
         else
-          m0 = max(max(s_wave_max[it & 1][0], s_wave_max[it & 1][1]), max(s_wave_max[it & 1][2], s_wave_max[it & 1][3]));
+          m0 = max(max(s_wave_max[j & 1][0], s_wave_max[j & 1][1]), max(s_wave_max[j & 1][2], s_wave_max[j & 1][3]));
       }
       m1 = m0;
       const bool writer = (kLogBlock == 10) ? lane == 0 : (kLogBlock == 11) ? (lane == 0 && (wave & 1) == 0)
                                                                             : threadIdx.x == 0;
-      if (writer) absmax[e_wave >> kLogBlock] = half_lo_to_float(m0);
+      if (real && writer) absmax[e_wave >> kLogBlock] = half_lo_to_float(m0);
     }
     const float a0 = half_lo_to_float(m0), a1 = half_lo_to_float(m1);
     const float inv0 = (a0 == 0.0f) ? 0.0f : 1.0f / a0;            // IEEE division
     const float inv1 = (kLogBlock >= 10) ? inv0 : ((a1 == 0.0f) ? 0.0f : 1.0f / a1);
-    uint8_t* out = codes + e_wave + lane * kChunk;
-    __builtin_nontemporal_store(encode_chunk(raw[0], inv0, cells_biased), reinterpret_cast<v2u*>(out));
-    __builtin_nontemporal_store(encode_chunk(raw[1], inv1, cells_biased), reinterpret_cast<v2u*>(out + 512));
-    raw[0] = nxt[0];
-    raw[1] = nxt[1];
+    if (real) {
+      uint8_t* out = codes + e_wave + lane * kChunk;
+      __builtin_nontemporal_store(encode_chunk(raw[j][0], inv0, cells_biased), reinterpret_cast<v2u*>(out));
+      __builtin_nontemporal_store(encode_chunk(raw[j][1], inv1, cells_biased), reinterpret_cast<v2u*>(out + 512));
+    }
   }
 }
 
-// 16 codes (16 bytes) per thread per load; the block index of a 16-element group is unique
-// because every block size is a multiple of 64.
-constexpr int kDeqGroup = 16;
+// Decoder.  A group is 8 codes: 8 bytes in, 16 bytes out per lane, so that every load instruction of
+// a wave reads 512 and every store instruction writes 1024 consecutive bytes.  The block index of a
+// group is unique because every block size is a multiple of 64.
+constexpr int kDeqGroup = 8;
+__device__ inline v4u decode_group(const v2u& c, float a, const float* s_T) {
+  uint32_t o[4];
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const uint32_t cw = c[w];
+    const float f0 = s_T[cw & 0xffu] * a;
+    const float f1 = s_T[(cw >> 8) & 0xffu] * a;
+    const float f2 = s_T[(cw >> 16) & 0xffu] * a;
+    const float f3 = s_T[cw >> 24] * a;
+    o[2 * w] = rounded_float_to_half_bits(f0) | (rounded_float_to_half_bits(f1) << 16);
+    o[2 * w + 1] = rounded_float_to_half_bits(f2) | (rounded_float_to_half_bits(f3) << 16);
+  }
+  return v4u{o[0], o[1], o[2], o[3]};
+}
+
+// Whole groups only.  A thread decodes kDeqPerThread groups that lie an eighth of the tensor apart,
+// all loads first (same launch shape as the encoder).
+constexpr int kDeqPerThread = 8;
 __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
-    const uint8_t* __restrict__ codes, const float* __restrict__ absmax, size_t n, int block,
+    const uint8_t* __restrict__ codes, const float* __restrict__ absmax, int block,
     int log_block /* -1 if block is not a power of two */, uint16_t* __restrict__ out, size_t n_groups) {
   __shared__ float s_T[256];
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t g0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  v2u c[kDeqPerThread];
+  float a[kDeqPerThread];
+#pragma unroll
+  for (int j = 0; j < kDeqPerThread; ++j) {
+    const size_t g = g0 + j * stride;
+    const size_t e0 = (g < n_groups ? g : n_groups - 1) * kDeqGroup;   // a missing group re-reads the last one
+    c[j] = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(codes + e0));
+    a[j] = absmax[(log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block)];
+  }
   s_T[threadIdx.x] = kCodeDev.T[threadIdx.x];
   __syncthreads();
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < n_groups; g += stride) {
-    const size_t e0 = g * kDeqGroup;
-    const size_t b = (log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block);
-    const float a = absmax[b];
-    const int valid = (int)min((size_t)kDeqGroup, n - e0);
-    v4u c = v4u{0, 0, 0, 0};
-    if (valid == kDeqGroup) {
-      c = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(codes + e0));
-    } else {
-      uint32_t tmp[4] = {0, 0, 0, 0};
-      for (int t = 0; t < valid; ++t) tmp[t >> 2] |= (uint32_t)codes[e0 + t] << (8 * (t & 3));
-      c = v4u{tmp[0], tmp[1], tmp[2], tmp[3]};
-    }
-    uint32_t o[8];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const uint32_t cw = c[w];
-      const float f0 = s_T[cw & 0xffu] * a;
-      const float f1 = s_T[(cw >> 8) & 0xffu] * a;
-      const float f2 = s_T[(cw >> 16) & 0xffu] * a;
-      const float f3 = s_T[cw >> 24] * a;
-      o[2 * w] = rounded_float_to_half_bits(f0) | (rounded_float_to_half_bits(f1) << 16);
-      o[2 * w + 1] = rounded_float_to_half_bits(f2) | (rounded_float_to_half_bits(f3) << 16);
-    }
-    if (valid == kDeqGroup) {
-      *reinterpret_cast<v4u*>(out + e0) = v4u{o[0], o[1], o[2], o[3]};
-      *reinterpret_cast<v4u*>(out + e0 + 8) = v4u{o[4], o[5], o[6], o[7]};
-    } else {
-      for (int t = 0; t < valid; ++t) out[e0 + t] = (uint16_t)(o[t >> 1] >> (16 * (t & 1)));
-    }
+  for (int j = 0; j < kDeqPerThread; ++j) {
+    const size_t g = g0 + j * stride;
+    if (g >= n_groups) break;
+    __builtin_nontemporal_store(decode_group(c[j], a[j], s_T), reinterpret_cast<v4u*>(out + g * kDeqGroup));
   }
+}
+
+// The last, short group of a tensor whose length is not a multiple of 8: one thread.
+__global__ void k_dequantize_tail(const uint8_t* __restrict__ codes, const float* __restrict__ absmax, size_t e0, int valid,
+                                  int block, uint16_t* __restrict__ out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float a = absmax[e0 / (size_t)block];
+  for (int t = 0; t < valid; ++t)
+    out[e0 + t] = (uint16_t)rounded_float_to_half_bits(kCodeDev.T[codes[e0 + t]] * a);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -327,8 +365,7 @@ hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uin
   // through the generic kernel
   const size_t n_spans = n / kSpanMax;
   if (n_spans > 0) {
-    const size_t max_grid = (size_t)device_cu_count() * 8;
-    const dim3 grid((unsigned)(n_spans < max_grid ? n_spans : max_grid));
+    const dim3 grid((unsigned)((n_spans + kSpansPerGroup - 1) / kSpansPerGroup));
 #define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L>), grid, dim3(kThreads), 0, stream, x, n_spans, codes, absmax)
     switch (log_block) {
       case 6: MMD8_Q(6); break;
@@ -351,13 +388,21 @@ hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uin
 
 hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block,
                                        uint16_t* out, hipStream_t stream) {
-  const size_t n_groups = (n + kDeqGroup - 1) / kDeqGroup;
-  const size_t wgs = (n_groups + kThreads - 1) / kThreads;
-  const size_t max_grid = (size_t)device_cu_count() * 8;
-  const dim3 grid((unsigned)(wgs < max_grid ? wgs : max_grid));
-  hipLaunchKernelGGL(k_dequantize_blockwise, grid, dim3(kThreads), 0, stream, codes, absmax, n, block,
-                     log2_exact(block), out, n_groups);
-  return hipGetLastError();
+  const size_t n_groups = n / kDeqGroup;                         // whole groups
+  if (n_groups > 0) {
+    const size_t per_wg = (size_t)kThreads * kDeqPerThread;
+    const dim3 grid((unsigned)((n_groups + per_wg - 1) / per_wg));
+    hipLaunchKernelGGL(k_dequantize_blockwise, grid, dim3(kThreads), 0, stream, codes, absmax, block, log2_exact(block), out,
+                       n_groups);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int rest = (int)(n - n_groups * kDeqGroup);
+  if (rest > 0) {
+    hipLaunchKernelGGL(k_dequantize_tail, dim3(1), dim3(64), 0, stream, codes, absmax, n_groups * kDeqGroup, rest, block, out);
+    return hipGetLastError();
+  }
+  return hipSuccess;
 }
 
 }  // namespace mmd8
