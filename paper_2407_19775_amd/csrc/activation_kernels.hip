@@ -8,6 +8,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "operand_layout.h"
+#include "skinny.h"
 
 namespace mmd8 {
 
@@ -314,9 +315,9 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
           fa[w] = in_k ? (a[i][w] & ma) : 0u;
           fb[w] = in_k ? (b[i][w] & mb) : 0u;
         }
-        uint16_t* dst = Xf + (size_t)m * (n_slabs * kSlabBytes) + k0;
-        *reinterpret_cast<v4u*>(dst) = v4u{fa[0], fa[1], fa[2], fa[3]};
-        *reinterpret_cast<v4u*>(dst + 8) = v4u{fb[0], fb[1], fb[2], fb[3]};
+        int8_t* xf_bytes = reinterpret_cast<int8_t*>(Xf);
+        *reinterpret_cast<v4u*>(xf_bytes + xf_group_offset(m, k0)) = v4u{fa[0], fa[1], fa[2], fa[3]};
+        *reinterpret_cast<v4u*>(xf_bytes + xf_group_offset(m, k0 + 8)) = v4u{fb[0], fb[1], fb[2], fb[3]};
       }
     }
   }

@@ -306,5 +306,6 @@ uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau);
 
 // Tuning hook (not part of the documented interface): force a GEMM tile configuration; -1 = automatic.
 void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
+void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
 
 }  // extern "C"

@@ -60,6 +60,16 @@ __device__ inline uint32_t wave_max_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)wave_max_u32_to_lane63(v), 63);
 }
 
+// One 16-byte-per-lane global -> LDS copy (no registers in between).  Lane i's 16 bytes land at
+// lds_addr + 16 i.  Issued through asm so that the compiler does not serialise later LDS reads
+// behind it: completion is tracked by hand with vmcnt.
+__device__ inline void dma16(const void* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_addr)
+               : "memory");
+}
+
 int device_cu_count();   // compute units of the current device (cached per device)
 
 }  // namespace mmd8

@@ -70,16 +70,6 @@ struct GemmCfg {
   static_assert((BM + BN) * 32 <= RING_BYTES, "epilogue staging must fit in the slab buffers");
 };
 
-// One 16-byte-per-lane global -> LDS copy (no registers in between).  Lane i's 16 bytes land at
-// lds_addr + 16 i.  Issued through asm so that the compiler does not serialise later LDS reads
-// behind it: completion is tracked by hand with vmcnt.
-__device__ inline void dma16(const void* src, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
-               : "v"(src), "s"(lds_addr)
-               : "memory");
-}
-
 // own requests older than the newest kVm have landed, own LDS reads have returned; after the
 // barrier that holds for every wave of the workgroup
 template <int kVm>

@@ -7,17 +7,29 @@ namespace mmd8 {
 
 constexpr int kSkinnyMaxM = 64;
 
+// Xf, the 16-bit operand of the decode kernels, is stored per 64-column slab as 8 KB =
+// [32-row group 0..1][piece p = 2 (k-step) + t][lane = 32 (lane group) + row % 32] x 8 halves, which is
+// the order in which the lanes of v_mfma_f32_32x32x16_f16 take them next to the int8 fragments
+// (lane group g of k-step ks holds columns 32 ks + 16 g + 8 t .. + 8 in piece t).  Byte offset of the
+// 8 halves that start at column k (a multiple of 8) of row m:
+__host__ __device__ constexpr inline size_t xf_group_offset(int m, int k) {
+  return (size_t)(k >> 6) * 8192 + (size_t)(m >> 5) * 4096 + (size_t)(2 * ((k >> 5) & 1) + ((k >> 3) & 1)) * 1024 +
+         (size_t)(32 * ((k >> 4) & 1) + (m & 31)) * 16;
+}
+
 struct SkinnyPlan {
+  int waves;               // 0: 32-column tiles (up to 16 rows); 4 or 8: panel kernel with that many waves per workgroup
   int n_slabs, tiles_n, splits, slabs_per_split;
   size_t partial_bytes;    // fp32 [splits][M][N] when splits > 1
 };
 // how the K range is split between workgroups for this shape (depends on the device's CU count)
 SkinnyPlan plan_skinny(int M, int K, int N);
+void set_panel_waves(int waves);   // tuning hook: force 4 or 8 waves per panel workgroup (0 = automatic)
 
 struct SkinnyArgs {
   const int8_t* Xq;       // activation codes, blocked layout, rows 0..63 of panel 0
   const int8_t* Wt;       // weight codes, blocked layout
-  const uint16_t* Xf;     // [64][Kpad] fp16: X with the non-critical columns (and the K padding) zeroed
+  const uint16_t* Xf;     // fp16 X with the non-critical columns (and the K padding) zeroed, blocked: xf_group_offset
   const uint8_t* mask;    // [Kpad] 1 = critical column
   int M, N, Kpad;
   const float* r;         // [>= 64]

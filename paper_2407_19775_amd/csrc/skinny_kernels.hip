@@ -7,11 +7,10 @@
 // No weight byte is used by more than one wave, so the weights go straight from HBM into the
 // registers of the lane that feeds them to the MFMA (no LDS): a wave owns 32 rows of Wt (32 output
 // columns) and reads their 64-byte slabs; the blocked layout is fragment-major, so each of the two
-// loads per slab is 1 KB of consecutive addresses.  The
-// eight waves of a workgroup share the 32 rows and take every eighth slab; their partial results
-// are added in a fixed order through LDS.  When there are too few 32-row tiles to fill the chip,
-// the K range is also split between workgroups, which write fp32 partial outputs that a second
-// small kernel adds (again in a fixed order, so the result does not depend on timing).
+// loads per slab is 1 KB of consecutive addresses.  The activation side of a slab is shared by the
+// waves of a workgroup through LDS.  When there are too few weight panels to give every CU a
+// workgroup, the K range is split between workgroups, which write fp32 partial outputs that a
+// second small kernel adds in a fixed order (the result does not depend on timing).
 //
 // Heavy-tailed decode activations flag a large share of the feature dimensions, so the 16-bit part
 // is a second product over the same weights rather than a small correction.  For a slab that holds
@@ -22,18 +21,13 @@
 // c[n]/127 is applied in fp32 to the accumulated sum: the sum over the critical columns of
 // X[m,k] q[n,k] c[n]/127 with one rounding at the end, instead of rounding each dequantized weight
 // to fp16 first.  The two differ by at most the fp16 rounding of the weights (2^-11 relative per
-// term), far inside the tolerance of the fp16 output.
-// A wave whose slabs mostly hold critical columns runs the 16-bit part for every slab (adding
-// exact zeros where nothing is flagged), which keeps all loads unconditional and pipelined; a wave
-// with few flagged slabs branches around it.
+// term), far inside the tolerance of the fp16 output.  A slab without a critical column skips the
+// 16-bit part (the same decision for the whole workgroup).
 #include "common.h"
 #include "operand_layout.h"
 #include "skinny.h"
 
 namespace mmd8 {
-
-constexpr int kSkinnyWaves = 8;
-constexpr int kSkinnyThreads = kSkinnyWaves * kWave;
 
 // eight weight codes (bytes [8 t, 8 t + 8) of the lane's 16, already XORed with 0x80: u = q + 128)
 // -> the integers q as fp16.  The fp16 number 1024 + u has the bit pattern 0x6400 | u.
@@ -53,45 +47,80 @@ __device__ inline v8h codes_to_half8(const v4u& wu, int t) {
   return __builtin_bit_cast(v8h, out);
 }
 
-template <int MT>
-struct SkinnyFrags {
-  v4i w[2];          // weight codes of the two k-steps
-  v4i x[MT][2];      // activation codes
-};
-template <int MT>
-struct SkinnyFragsF {
-  v8h xf[MT][4];     // critical columns of X (fp16), pieces (ks, t)
+// ------------------------------------------------------------------------------------------------
+// If every wave fetched its own copy of the activation fragments from L2, that would be up to 6
+// times the bytes of the weights it streams (64 rows).  So the kWaves waves of a workgroup own
+// neighbouring 32-column groups of one weight panel and walk the same slabs together: the
+// activation side of a slab (int8 codes and the fp16 critical columns, kMT 32-row groups each) is
+// fetched once per workgroup, parked in LDS (a ring of four buffers) and read from there by every
+// wave; the weights go from HBM straight into the registers of the lane that feeds them to the
+// MFMA, three slabs ahead.  All waits are the compiler's.  Measured per workgroup: about 19 GB/s
+// of weights at 64 rows (the MFMAs and the code-to-fp16 conversions of a slab take about as long
+// as its 16 KB take to arrive), so every CU must have a workgroup.
+// ------------------------------------------------------------------------------------------------
+template <int MT, int WAVES>
+struct PanelCfg {
+  static constexpr int kMT = MT, kWaves = WAVES;
+  static constexpr int kThreads = WAVES * kWave;
+  static constexpr int kCols = WAVES * 32;
+  static constexpr int XQ_BYTES = MT * 2048, XF_BYTES = MT * 4096, STAGE_BYTES = XQ_BYTES + XF_BYTES;
+  static constexpr int kPieces = STAGE_BYTES / 1024;               // 1 KB pieces of a slab's activation side
+  static constexpr int kFetch = (kPieces + WAVES - 1) / WAVES;     // per wave and slab; surplus ones repeat the last
+  static constexpr int kMaxSlabs = MMD8_MAX_K / kSlabBytes;        // flags "slab holds a critical column"
 };
 
-template <int MT, bool kSplit, bool kTap>
-__global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(const SkinnyArgs a) {
-  extern __shared__ __attribute__((aligned(16))) float s_red[];    // [wave][MT * 16][64]
+template <class Cfg, bool kSplit, bool kTap>
+__global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArgs a) {
+  constexpr int MT = Cfg::kMT, WAVES = Cfg::kWaves;
+  __shared__ __attribute__((aligned(16))) int8_t s_x[4][Cfg::STAGE_BYTES];
+  __shared__ uint8_t s_any[Cfg::kMaxSlabs];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int lr = lane & 31, lg = lane >> 5;
   reset_column_flags(a.flag_reset, a.Kpad);
   const int tile = blockIdx.x % a.tiles_n, split = blockIdx.x / a.tiles_n;
-  const int n = tile * 32 + lr;                                    // < Npad
+  const int n0 = tile * Cfg::kCols + wave * 32;                    // < Npad: the padding rows of Wt are zero
+  const int n = n0 + lr;
   const int s_begin = split * a.slabs_per_split;
-  const int s_end = min(a.n_slabs, s_begin + a.slabs_per_split);
+  const int cnt = min(a.n_slabs, s_begin + a.slabs_per_split) - s_begin;   // >= 1 by construction of the plan
 
-  // a wave's operand fragment of one k-step is 1 KB contiguous: group of 32 rows, [k-step][lane]
-  const int8_t* wgrp = a.Wt + (size_t)(n >> 8) * a.n_slabs * kBlockBytes + (size_t)((n & 255) >> 5) * 2048 + lane * 16;
-  const int8_t* xgrp = a.Xq + lane * 16;                           // + mt * 2048: rows 32 mt .. of panel 0
-
-  // Which of this wave's slabs (s_begin + wave + 8 j) hold a critical column: lane j (and j + 64)
-  // ORs the 64 mask bytes of its slab, two ballots give up to 128 bits.
-  uint64_t any_bits[2];
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int sj = s_begin + wave + kSkinnyWaves * (lane + 64 * h);
-    v4u m = v4u{0, 0, 0, 0};
-    if (sj < s_end) {
-      const v4u* mk = reinterpret_cast<const v4u*>(a.mask + (size_t)sj * kSlabBytes);
-      m = mk[0] | mk[1] | mk[2] | mk[3];
-    }
-    any_bits[h] = __builtin_amdgcn_ballot_w64((m[0] | m[1] | m[2] | m[3]) != 0);
+  const int8_t* wgrp = a.Wt + (size_t)(n0 >> 8) * a.n_slabs * kBlockBytes + (size_t)((n0 & 255) >> 5) * 2048 + lane * 16 +
+                       (size_t)s_begin * kBlockBytes;
+  for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) {
+    const v4u* mk = reinterpret_cast<const v4u*>(a.mask + (size_t)(s_begin + t) * kSlabBytes);
+    const v4u m = mk[0] | mk[1] | mk[2] | mk[3];
+    s_any[t] = (m[0] | m[1] | m[2] | m[3]) != 0;
   }
+
+  // piece i of a slab's activation side: first the int8 codes (MT 32-row groups x 2 k-steps), then
+  // the fp16 pieces (MT groups x 4); the first MT groups of a slab are contiguous in both arrays
+  const int8_t* x_src[Cfg::kFetch];
+  int x_dst[Cfg::kFetch], x_step[Cfg::kFetch];
+#pragma unroll
+  for (int d = 0; d < Cfg::kFetch; ++d) {
+    const int i = min(wave + d * WAVES, Cfg::kPieces - 1);
+    const bool codes = i < MT * 2;
+    x_src[d] = (codes ? a.Xq + (size_t)s_begin * kBlockBytes + i * 1024
+                      : reinterpret_cast<const int8_t*>(a.Xf) + (size_t)s_begin * 8192 + (i - MT * 2) * 1024) + lane * 16;
+    x_step[d] = codes ? kBlockBytes : 8192;
+    x_dst[d] = i * 1024 + lane * 16;
+  }
+  auto fetch_x = [&](int j, v4i (&xr)[Cfg::kFetch]) {
+#pragma unroll
+    for (int d = 0; d < Cfg::kFetch; ++d) xr[d] = *reinterpret_cast<const v4i*>(x_src[d] + (size_t)j * x_step[d]);
+  };
+  auto park_x = [&](int stage, const v4i (&xr)[Cfg::kFetch]) {
+#pragma unroll
+    for (int d = 0; d < Cfg::kFetch; ++d) *reinterpret_cast<v4i*>(&s_x[stage][x_dst[d]]) = xr[d];
+  };
+  struct W2 {
+    v4i w[2];
+  };
+  auto fetch_w = [&](int j, W2& f) {
+    const int8_t* p = wgrp + (size_t)j * kBlockBytes;
+    f.w[0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+    f.w[1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p + 1024));
+  };
 
   v16i acc[MT];
   v16f accf[MT];
@@ -100,278 +129,103 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(const SkinnyArgs
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[mt][e] = 0, accf[mt][e] = 0.0f;
 
-  auto load = [&](int s, SkinnyFrags<MT>& f) {
-    const int8_t* wp = wgrp + (size_t)s * kBlockBytes;
-    const int8_t* xp = xgrp + (size_t)s * kBlockBytes;
-    f.w[0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp));
-    f.w[1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + 1024));
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      f.x[mt][0] = *reinterpret_cast<const v4i*>(xp + mt * 2048);
-      f.x[mt][1] = *reinterpret_cast<const v4i*>(xp + mt * 2048 + 1024);
-    }
+  struct Frags {
+    v4i x[MT][2];      // int8 codes, k-steps 0 and 1
+    v8h xf[MT][4];     // fp16 critical columns, pieces 2 ks + t (valid when the slab has any)
   };
-  // the lane's bytes [8 t, 8 t + 8) of piece 2 ks + lg are k = 64 s + 16 (2 ks + lg) + 8 t ...
-  const uint16_t* xf_lane = a.Xf + (size_t)lr * a.Kpad + 16 * lg;
-  auto load_f = [&](int s, SkinnyFragsF<MT>& f) {
+  auto read_frags = [&](int stage, bool any, Frags& g) {
+    const int8_t* base = &s_x[stage][lane * 16];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+      for (int ks = 0; ks < 2; ++ks) g.x[mt][ks] = *reinterpret_cast<const v4i*>(base + mt * 2048 + ks * 1024);
+    if (any) {                                                     // the same for the whole workgroup
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-          f.xf[mt][2 * ks + t] = *reinterpret_cast<const v8h*>(xf_lane + (size_t)mt * 32 * a.Kpad + s * kSlabBytes + 32 * ks + 8 * t);
-  };
-  auto mfma_i8 = [&](const SkinnyFrags<MT>& f) {
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      acc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.x[mt][0], f.w[0], acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.x[mt][1], f.w[1], acc[mt], 0, 0, 0);
+        for (int p = 0; p < 4; ++p)
+          g.xf[mt][p] = *reinterpret_cast<const v8h*>(base + Cfg::XQ_BYTES + mt * 4096 + p * 1024);
     }
   };
-  auto mfma_f16 = [&](const SkinnyFrags<MT>& f, const SkinnyFragsF<MT>& ff) {
+  auto multiply = [&](bool any, const Frags& g, const W2& f) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const v4u wu = __builtin_bit_cast(v4u, f.w[ks]) ^ 0x80808080u;
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const v8h wh = codes_to_half8(wu, t);
+      for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(g.x[mt][ks], f.w[ks], acc[mt], 0, 0, 0);
+    if (any) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          accf[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ff.xf[mt][2 * ks + t], wh, accf[mt], 0, 0, 0);
+      for (int ks = 0; ks < 2; ++ks) {
+        const v4u wu = __builtin_bit_cast(v4u, f.w[ks]) ^ 0x80808080u;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const v8h wh = codes_to_half8(wu, t);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) accf[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g.xf[mt][2 * ks + t], wh, accf[mt], 0, 0, 0);
+        }
       }
     }
   };
 
-  // this wave's slabs: s0 + 8 j, j < cnt.  Loads run kDepth - 1 slabs ahead and are unconditional
-  // (past the end they re-read the last slab), so the compiler can count them.
-  constexpr int W8 = kSkinnyWaves;
-  constexpr int kDepth = (MT == 1) ? 3 : 2;
-  const int s0 = s_begin + wave;
-  const int cnt = (s0 < s_end) ? (s_end - s0 + W8 - 1) / W8 : 0;
-  const int flagged = __builtin_popcountll(any_bits[0]) + __builtin_popcountll(any_bits[1]);
-  if (cnt > 0) {
-    const int s_last = s0 + W8 * (cnt - 1);
-    SkinnyFrags<MT> f[kDepth];
-    if (2 * flagged > cnt) {
-      // ---- most slabs hold a critical column: the 16-bit part runs for every slab
-      SkinnyFragsF<MT> ff[kDepth];
+  // Software pipeline (past the end the requests repeat the last slab: L2 hits, uniform loop body).
+  // In iteration j: request the activation pieces and the weights of slab j + 3; read the fragments
+  // of slab j + 1 from LDS (they overlap the MFMAs of slab j, whose fragments were read an iteration
+  // ago); park the pieces of slab j + 2 (requested an iteration ago) in the buffer that slab j - 1
+  // used (a ring of four, so that every index is static in a loop unrolled four times); barrier.
+  const int last = cnt - 1;
+  W2 f[4];
+  v4i xr[2][Cfg::kFetch];
+  Frags fr[2];
+  fetch_x(0, xr[0]);
+  fetch_x(min(1, last), xr[1]);
+  fetch_w(0, f[0]);
+  fetch_w(min(1, last), f[1]);
+  fetch_w(min(2, last), f[2]);
+  park_x(0, xr[0]);
+  park_x(1, xr[1]);
+  fetch_x(min(2, last), xr[1]);                                    // parked in iteration 0
+  __syncthreads();
+  bool any_next = s_any[0];
+  read_frags(0, any_next, fr[0]);
+  for (int j0 = 0; j0 < cnt; j0 += 4) {
 #pragma unroll
-      for (int d = 0; d < kDepth - 1; ++d) {
-        load(min(s0 + W8 * d, s_last), f[d]);
-        load_f(min(s0 + W8 * d, s_last), ff[d]);
-      }
-      for (int j = 0; j < cnt; j += kDepth) {
-#pragma unroll
-        for (int u = 0; u < kDepth; ++u) {
-          const int sn = min(s0 + W8 * (j + u + kDepth - 1), s_last);
-          load(sn, f[(u + kDepth - 1) % kDepth]);
-          load_f(sn, ff[(u + kDepth - 1) % kDepth]);
-          if (j + u < cnt) {
-            mfma_i8(f[u]);
-            mfma_f16(f[u], ff[u]);
-          }
-        }
-      }
-    } else {
-      // ---- few flagged slabs: branch around the 16-bit part (its loads stall the wave when taken)
-#pragma unroll
-      for (int d = 0; d < kDepth - 1; ++d) load(min(s0 + W8 * d, s_last), f[d]);
-      for (int j = 0; j < cnt; j += kDepth) {
-#pragma unroll
-        for (int u = 0; u < kDepth; ++u) {
-          load(min(s0 + W8 * (j + u + kDepth - 1), s_last), f[(u + kDepth - 1) % kDepth]);
-          if (j + u < cnt) {
-            mfma_i8(f[u]);
-            if ((any_bits[(j + u) >> 6] >> ((j + u) & 63)) & 1) {
-              SkinnyFragsF<MT> ff;
-              load_f(s0 + W8 * (j + u), ff);
-              mfma_f16(f[u], ff);
-            }
-          }
-        }
-      }
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u;
+      if (j >= cnt) break;
+      const bool any_cur = any_next;
+      any_next = s_any[min(j + 1, last)];
+      fetch_x(min(j + 3, last), xr[u & 1]);
+      fetch_w(min(j + 3, last), f[(u + 3) & 3]);
+      read_frags((u + 1) & 3, any_next, fr[(u + 1) & 1]);
+      multiply(any_cur, fr[u & 1], f[u & 3]);
+      park_x((u + 2) & 3, xr[(u + 1) & 1]);
+      __syncthreads();
     }
   }
 
-  // ---- add the eight waves' results.  C layout of the 32x32 MFMA: lane = column n (lane % 32),
-  // register e = row m = 8 (e / 4) + 4 (lane / 32) + (e % 4).
+  // ---- outputs.  C layout of the 32x32 MFMA: lane = column n (lane % 32), register e = row
+  // 8 (e / 4) + 4 (lane / 32) + (e % 4).
   const float cs = (n < a.N) ? a.c[n] / 16129.0f : 0.0f;
   const float step = (n < a.N) ? a.c[n] / 127.0f : 0.0f;
-  constexpr int kPairs = MT * 16;                                   // (m-tile, register) pairs
-  float* mine = s_red + (size_t)wave * kPairs * kWave;
+  const float b = (!kSplit && a.bias && n < a.N) ? half_lo_to_float(a.bias[n]) : 0.0f;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int m = mt * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-      const float y = (float)acc[mt][e] * (a.r[m] * cs) + accf[mt][e] * step;
-      mine[(mt * 16 + e) * kWave + lane] = y;
-    }
-  __syncthreads();
-  constexpr int kPairsPerWave = kPairs / kSkinnyWaves;              // 2 or 4
-#pragma unroll
-  for (int i = 0; i < kPairsPerWave; ++i) {
-    const int pr = wave * kPairsPerWave + i, mt = pr >> 4, e = pr & 15;
-    float y = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kSkinnyWaves; ++w) y += s_red[((size_t)w * kPairs + pr) * kWave + lane];
-    const int m = mt * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-    if (m < a.M && n < a.N) {
-      if constexpr (kSplit) {
-        a.partial[((size_t)split * a.M + m) * a.N + n] = y;
-      } else {
-        const float b = a.bias ? half_lo_to_float(a.bias[n]) : 0.0f;
-        a.Y[(size_t)m * a.ldy + n] = (uint16_t)float_to_half_bits(y + b);
-      }
-    }
-  }
-  if constexpr (kTap) {
-    // the raw integer accumulators, added the same way (exact in any order)
-    __syncthreads();
-    int* mine_i = reinterpret_cast<int*>(mine);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mine_i[(mt * 16 + e) * kWave + lane] = acc[mt][e];
-    __syncthreads();
-    const int* red_i = reinterpret_cast<const int*>(s_red);
-#pragma unroll
-    for (int i = 0; i < kPairsPerWave; ++i) {
-      const int pr = wave * kPairsPerWave + i, mt = pr >> 4, e = pr & 15;
-      int v = 0;
-#pragma unroll
-      for (int w = 0; w < kSkinnyWaves; ++w) v += red_i[((size_t)w * kPairs + pr) * kWave + lane];
-      const int m = mt * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
       if (m < a.M && n < a.N) {
+        const float y = (float)acc[mt][e] * (a.r[m] * cs) + accf[mt][e] * step;
         if constexpr (kSplit)
-          atomicAdd(a.tap_acc + (size_t)m * a.N + n, v);           // tap buffer zeroed by the caller
+          a.partial[((size_t)split * a.M + m) * a.N + n] = y;
         else
-          a.tap_acc[(size_t)m * a.N + n] = v;
+          a.Y[(size_t)m * a.ldy + n] = (uint16_t)float_to_half_bits(y + b);
+        if constexpr (kTap) {
+          if constexpr (kSplit)
+            atomicAdd(a.tap_acc + (size_t)m * a.N + n, acc[mt][e]);   // tap buffer zeroed by the launcher
+          else
+            a.tap_acc[(size_t)m * a.N + n] = acc[mt][e];
+        }
       }
     }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// At most 16 rows: v_mfma_i32_16x16x64_i8 takes a whole 64-byte slab of 16 rows per instruction, so
-// the activation side needs half the registers and loads of the 32-row form, which leaves room
-// for 16 waves per CU with three slabs of weights in flight each.  The 16-bit part runs for every
-// slab (exact zeros where nothing is flagged): all loads are unconditional.
-//   operands: lane = 16 (16-byte piece of the slab) + row;  result: lane = 16 (row / 4) + column,
-//   register = row % 4.
-// For the fp16 product (v_mfma_f32_16x16x32_f16, 8 halves per lane) lane group G uses bytes
-// [8 h, 8 h + 8) of its own piece G in half-slab pass h: any k order is fine as long as both
-// operands agree.
-// ------------------------------------------------------------------------------------------------
-__device__ inline v8h codes_to_half8_of(const v4i& w, int t) { return codes_to_half8(__builtin_bit_cast(v4u, w) ^ 0x80808080u, t); }
-
-template <bool kSplit, bool kTap>
-__global__ __launch_bounds__(kSkinnyThreads, 4) void k_gemm_skinny16(const SkinnyArgs a) {
-  __shared__ float s_red[kSkinnyWaves][8][kWave];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int l16 = lane & 15, grp = lane >> 4;
-  reset_column_flags(a.flag_reset, a.Kpad);
-  const int tile = blockIdx.x % a.tiles_n, split = blockIdx.x / a.tiles_n;
-  const int n_base = tile * 32;
-  const int s_begin = split * a.slabs_per_split;
-  const int s_end = min(a.n_slabs, s_begin + a.slabs_per_split);
-
-  // piece `grp` of row rho of a 32-row group sits at (grp / 2) * 1024 + ((grp % 2) * 32 + rho) * 16
-  const int piece = (grp >> 1) * 1024 + ((grp & 1) * 32 + l16) * 16;
-  const int8_t* wgrp = a.Wt + (size_t)(n_base >> 8) * a.n_slabs * kBlockBytes + (size_t)((n_base & 255) >> 5) * 2048 + piece;
-  const int8_t* xgrp = a.Xq + piece;
-  const uint16_t* xf_lane = a.Xf + (size_t)l16 * a.Kpad + 16 * grp;
-
-  struct Frags {
-    v4i w[2];      // n rows n_base + 16 h + l16
-    v4i x;         // m row l16
-    v8h xf[2];     // half-slab passes
-  };
-  auto load = [&](int s, Frags& f) {
-    const int8_t* wp = wgrp + (size_t)s * kBlockBytes;
-    f.w[0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp));
-    f.w[1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + 256));
-    f.x = *reinterpret_cast<const v4i*>(xgrp + (size_t)s * kBlockBytes);
-    f.xf[0] = *reinterpret_cast<const v8h*>(xf_lane + s * kSlabBytes);
-    f.xf[1] = *reinterpret_cast<const v8h*>(xf_lane + s * kSlabBytes + 8);
-  };
-  v4i acc[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};
-  v4f accf[2] = {v4f{0, 0, 0, 0}, v4f{0, 0, 0, 0}};
-  auto compute = [&](const Frags& f) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      acc[h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f.x, f.w[h], acc[h], 0, 0, 0);
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        accf[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f.xf[t], codes_to_half8_of(f.w[h], t), accf[h], 0, 0, 0);
-    }
-  };
-
-  constexpr int W8 = kSkinnyWaves, kDepth = 4;
-  const int s0 = s_begin + wave;
-  const int cnt = (s0 < s_end) ? (s_end - s0 + W8 - 1) / W8 : 0;
-  if (cnt > 0) {
-    const int s_last = s0 + W8 * (cnt - 1);
-    Frags f[kDepth];
-#pragma unroll
-    for (int d = 0; d < kDepth - 1; ++d) load(min(s0 + W8 * d, s_last), f[d]);
-    for (int j = 0; j < cnt; j += kDepth) {
-#pragma unroll
-      for (int u = 0; u < kDepth; ++u) {
-        load(min(s0 + W8 * (j + u + kDepth - 1), s_last), f[(u + kDepth - 1) % kDepth]);
-        if (j + u < cnt) compute(f[u]);
-      }
-    }
-  }
-
-  // ---- add the eight waves' results (fixed order); lane: n = n_base + 16 h + l16, m = 4 grp + e
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int n = n_base + 16 * h + l16;
-    const float cs = (n < a.N) ? a.c[n] / 16129.0f : 0.0f;
-    const float step = (n < a.N) ? a.c[n] / 127.0f : 0.0f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      s_red[wave][h * 4 + e][lane] = (float)acc[h][e] * (a.r[4 * grp + e] * cs) + accf[h][e] * step;
-  }
-  __syncthreads();
-  {
-    const int pr = wave, h = pr >> 2, e = pr & 3;                 // 8 (h, e) pairs, one per wave
-    float y = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kSkinnyWaves; ++w) y += s_red[w][pr][lane];
-    const int m = 4 * grp + e, n = n_base + 16 * h + l16;
-    if (m < a.M && n < a.N) {
-      if constexpr (kSplit) {
-        a.partial[((size_t)split * a.M + m) * a.N + n] = y;
-      } else {
-        const float b = a.bias ? half_lo_to_float(a.bias[n]) : 0.0f;
-        a.Y[(size_t)m * a.ldy + n] = (uint16_t)float_to_half_bits(y + b);
-      }
-    }
-  }
-  if constexpr (kTap) {
-    __syncthreads();
-    int (*red_i)[8][kWave] = reinterpret_cast<int (*)[8][kWave]>(s_red);
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) red_i[wave][h * 4 + e][lane] = acc[h][e];
-    __syncthreads();
-    const int pr = wave, h = pr >> 2, e = pr & 3;
-    int v = 0;
-#pragma unroll
-    for (int w = 0; w < kSkinnyWaves; ++w) v += red_i[w][pr][lane];
-    const int m = 4 * grp + e, n = n_base + 16 * h + l16;
-    if (m < a.M && n < a.N) {
-      if constexpr (kSplit)
-        atomicAdd(a.tap_acc + (size_t)m * a.N + n, v);
-      else
-        a.tap_acc[(size_t)m * a.N + n] = v;
-    }
-  }
 }
 
 // Y[m,n] = f16( sum_s partial[s][m][n] + bias[n] ), splits added in index order
@@ -392,39 +246,52 @@ __global__ void k_fill_i32(int32_t* __restrict__ p, size_t n) {
   if (i < n) p[i] = 0;
 }
 
-SkinnyPlan plan_skinny(int M, int K, int N) {
+// Decode plan: `waves` neighbouring 32-column groups per workgroup.
+static int g_panel_waves, g_panel_splits;
+static SkinnyPlan plan_panel(int M, int K, int N, int waves) {
   SkinnyPlan p;
+  p.waves = waves;
   p.n_slabs = packed_k(K) / kSlabBytes;
-  p.tiles_n = packed_n(N) / 32;
-  // Two workgroups fit on a CU.  Pick the K split that minimises (rounds of workgroups) x (slabs per
-  // workgroup + a fixed start-up and drain cost worth about 6 slabs), with at least 2 slabs per wave.
-  const int slots = 2 * device_cu_count();
-  const int max_splits = max(1, p.n_slabs / (2 * kSkinnyWaves));
-  int splits = 1;
-  long best = -1;
-  for (int cand = 1; cand <= min(max_splits, 16); ++cand) {
-    const int per = ceil_div(p.n_slabs, cand), real = ceil_div(p.n_slabs, per);
-    const long cost = (long)ceil_div(p.tiles_n * real, slots) * (per + 6);
-    if (best < 0 || cost < best) best = cost, splits = real;
-  }
-  p.slabs_per_split = ceil_div(p.n_slabs, splits);
+  p.tiles_n = packed_n(N) / (32 * waves);
+  // as many workgroups as the chip holds at once (two of four waves or one of eight per CU), every
+  // workgroup with at least 8 slabs, no second round
+  const int slots = device_cu_count() * (waves == 4 ? 2 : 1);
+  const int want = g_panel_splits > 0 ? min(g_panel_splits, p.n_slabs) : max(1, min(p.n_slabs / 8, slots / p.tiles_n));
+  p.slabs_per_split = ceil_div(p.n_slabs, want);
   p.splits = ceil_div(p.n_slabs, p.slabs_per_split);
   p.partial_bytes = p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
   return p;
 }
+// tuning hook: 0 = automatic
+void set_panel_waves(int w) {                        // waves + 100 * (forced number of K splits)
+  g_panel_splits = w / 100;
+  w %= 100;
+  g_panel_waves = (w == 4 || w == 8) ? w : 0;
+}
+SkinnyPlan plan_skinny(int M, int K, int N) {
+  const SkinnyPlan p4 = plan_panel(M, K, N, 4), p8 = plan_panel(M, K, N, 8);
+  // measured on the Llama-7B linears: eight waves per panel beat four (half the LDS fills per weight byte)
+  SkinnyPlan p = (g_panel_waves == 4) ? p4 : p8;
+  p.partial_bytes = max(p4.partial_bytes, p8.partial_bytes);     // the workspace serves either
+  return p;
+}
 
-template <int MT, bool kSplit, bool kTap>
-static hipError_t launch_one(const SkinnyArgs& a, int splits, hipStream_t stream) {
-  const size_t lds = (size_t)kSkinnyWaves * MT * 16 * kWave * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<MT, kSplit, kTap>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((k_gemm_skinny<MT, kSplit, kTap>), dim3(a.tiles_n * splits), dim3(kSkinnyThreads), lds, stream, a);
+template <class Cfg, bool kSplit, bool kTap>
+static hipError_t launch_panel_one(const SkinnyArgs& a, int splits, hipStream_t stream) {
+  hipLaunchKernelGGL((k_gemm_panel<Cfg, kSplit, kTap>), dim3(a.tiles_n * splits), dim3(Cfg::kThreads), 0, stream, a);
   return hipGetLastError();
+}
+template <class Cfg>
+static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t stream) {
+  const bool split = splits > 1, tap = a.tap_acc != nullptr;
+  if (split) return tap ? launch_panel_one<Cfg, true, true>(a, splits, stream) : launch_panel_one<Cfg, true, false>(a, splits, stream);
+  return tap ? launch_panel_one<Cfg, false, true>(a, splits, stream) : launch_panel_one<Cfg, false, false>(a, splits, stream);
+}
+static hipError_t launch_panel(const SkinnyArgs& a, const SkinnyPlan& plan, hipStream_t stream) {
+  const bool two = a.M > 32;
+  if (plan.waves == 8)
+    return two ? launch_panel_cfg<PanelCfg<2, 8>>(a, plan.splits, stream) : launch_panel_cfg<PanelCfg<1, 8>>(a, plan.splits, stream);
+  return two ? launch_panel_cfg<PanelCfg<2, 4>>(a, plan.splits, stream) : launch_panel_cfg<PanelCfg<1, 4>>(a, plan.splits, stream);
 }
 
 hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t stream) {
@@ -432,34 +299,11 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   a.tiles_n = plan.tiles_n;
   a.slabs_per_split = plan.slabs_per_split;
   const bool split = plan.splits > 1, tap = a.tap_acc != nullptr;
-  const int mt = a.M <= 32 ? 1 : 2;
-  if (split && tap) {
-    const size_t n = (size_t)a.M * a.N;
-    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
-  }
-  hipError_t e;
-#define MMD8_SK(MT_, S_, T_) e = launch_one<MT_, S_, T_>(a, plan.splits, stream)
-  if (a.M <= 16) {
-    const dim3 grid(a.tiles_n * plan.splits), block(kSkinnyThreads);
-    if (split) {
-      if (tap) hipLaunchKernelGGL((k_gemm_skinny16<true, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((k_gemm_skinny16<true, false>), grid, block, 0, stream, a);
-    } else {
-      if (tap) hipLaunchKernelGGL((k_gemm_skinny16<false, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((k_gemm_skinny16<false, false>), grid, block, 0, stream, a);
-    }
-    e = hipGetLastError();
-  } else if (mt == 1) {
-    if (split) { if (tap) MMD8_SK(1, true, true); else MMD8_SK(1, true, false); }
-    else       { if (tap) MMD8_SK(1, false, true); else MMD8_SK(1, false, false); }
-  } else {
-    if (split) { if (tap) MMD8_SK(2, true, true); else MMD8_SK(2, true, false); }
-    else       { if (tap) MMD8_SK(2, false, true); else MMD8_SK(2, false, false); }
-  }
-#undef MMD8_SK
+  const size_t n = (size_t)a.M * a.N;
+  if (split && tap) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
+  hipError_t e = launch_panel(a, plan, stream);
   if (e != hipSuccess) return e;
   if (split) {
-    const size_t n = (size_t)a.M * a.N;
     hipLaunchKernelGGL(k_skinny_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial, plan.splits,
                        a.M, a.N, a.bias, a.Y, a.ldy);
     e = hipGetLastError();
