@@ -20,6 +20,11 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per GEMM launch (mean over the five launches of a decoder layer) from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE, scaled by a plain copy of known size (profiles/gemm_llama7b_prefill_hbm_traffic.txt).  Valid
+# for the GEMM source it was measured on: reported as null once that file has changed.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 207.0e6
+GEMM_TRAFFIC_SOURCE_SHA256 = "51ab9bf7cb5adbcab78684584206471fb9a194575c97375958103bf8adc7f5c7"
 
 
 def parse():
@@ -55,6 +60,16 @@ class HipEvents:
         ms = ctypes.c_float()
         assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
         return ms.value
+
+
+def gemm_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_2407_19775_amd", "csrc", "gemm_kernels.hip")
+    try:
+        same = hashlib.sha256(open(src, "rb").read()).hexdigest() == GEMM_TRAFFIC_SOURCE_SHA256
+    except OSError:
+        same = False
+    return GEMM_TRAFFIC_BYTES_PER_LAUNCH if same else None
 
 
 def cpu_baseline(wl, layers_sample=1):
@@ -243,7 +258,7 @@ def main():
         "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
         "roofline": {"bound": "mfma", "kernel": "k_gemm_mixed (int8 MFMA GEMM + fused epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None},
+                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": gemm_traffic()},
         "per_linear": per_shape,
         "codec": {"quantize_gbs": round(big_bytes / qb_ms / 1e6, 1), "dequantize_gbs": round(big_bytes / db_ms / 1e6, 1),
                   "quantize_pct_hbm": round(100 * big_bytes / qb_ms / 1e6 / HBM_PEAK_GBS, 1),
