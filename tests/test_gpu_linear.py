@@ -90,6 +90,17 @@ def test_row_stride_larger_than_k():
     assert_y_close(Y, o["Y"])
 
 
+@pytest.mark.parametrize("M", [3, 70])
+def test_k_too_large_for_one_pass_preparation(M):
+    """K above 32768: the rows no longer fit the one-pass preparation kernel, so the scan and pack
+    kernels run instead (for the decode kernel and for the tiled one)."""
+    K, N = 32768 + 64, 72
+    rng = np.random.default_rng([M, K])
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.integers(0, K, 40)] *= 12.0
+    check_linear(wl.to_fp16(x), wl.gaussian_weight(K, N, 0.02, rng), 6.0)
+
+
 def test_empty_batch():
     pw = binding.prequantize_weight(to_gpu(wl.gaussian_weight(64, 16, 0.02, np.random.default_rng(0))))
     Y = binding.mixed_int8_linear(torch.empty((0, 64), dtype=torch.float16, device="cuda"), pw, 6.0)
