@@ -168,6 +168,17 @@ def test_every_gemm_tile_configuration(variant):
         L.mmd8_set_gemm_variant(-1)
 
 
+@pytest.mark.parametrize("shape", wl.VIT_L_LINEARS, ids=lambda s: s.name)
+def test_vit_shaped_linears_with_bias(shape):
+    """ViT-L-shaped linears (width 1024, 4 images of 197 tokens: a ragged M) with a bias vector."""
+    rng = np.random.default_rng([197, shape.K, shape.N])
+    M = 4 * 197
+    x = rng.standard_normal((M, shape.K)).astype(np.float32)
+    x[:, rng.choice(shape.K, max(1, shape.K // 500), replace=False)] *= rng.uniform(8.0, 40.0)
+    W = wl.gaussian_weight(shape.K, shape.N, 0.02, rng)
+    check_linear(wl.to_fp16(x), W, wl.TAU, bias=wl.gaussian_bias(shape.N, 0.1, rng))
+
+
 def test_one_workspace_serves_calls_of_different_shapes():
     """The head of the workspace (column flags) is standing state: every call must leave it
     ready for the next one, whatever the shapes and however many columns were flagged."""
