@@ -132,6 +132,23 @@ int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
                            void* workspace /*DEVICE*/, size_t workspace_bytes,
                            const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* The same layer applied to activations that arrive in blockwise-coded form (the hidden state a
+ * shard receives from its predecessor: "Compression techniques", item 1 feeding item 2):
+ *     X = dequantize_blockwise(codes, absmax, block)        as [M, K], contiguous (ldx = K)
+ *     Y = mixed_int8_linear(X, ...)
+ * with every value identical to the two calls made one after the other.  X_decoded (DEVICE [M*K],
+ * 16-byte aligned) receives X, which the caller usually needs as well (residual connection).  For more
+ * than 64 rows and K <= 32768 the decoding happens inside the preparation kernel of the layer: the
+ * hidden state is read once, as codes.  Requirements: those of both calls (block a multiple of 64 in
+ * [64, 4096]; codes 16-byte aligned; K % 16 == 0; ...). */
+int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, const float* absmax /*DEVICE [ceil(M*K/block)]*/,
+                                      int block, int M, int K, mmd8_half* X_decoded /*DEVICE [M*K], written*/,
+                                      const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                      const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                      mmd8_half* Y /*DEVICE*/, int ldy,
+                                      void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                      const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* HOST helper: the bit pattern of the smallest non-negative fp16 value that is >= tau (0 for
  * tau <= 0, 0x7c00 = +inf when no finite fp16 value reaches tau).  The outlier scan compares fp16
  * magnitudes against this pattern, which is equivalent to |x| >= tau for every fp16 x. */

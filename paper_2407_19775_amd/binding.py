@@ -18,7 +18,7 @@ EXPORTS = (
     "mmd8_status_string", "mmd8_quantize_blockwise", "mmd8_dequantize_blockwise", "mmd8_code_table",
     "mmd8_code_midpoints", "mmd8_packed_weight_layout", "mmd8_packed_weight_bytes", "mmd8_prequantize_weight",
     "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
-    "mmd8_threshold_fp16_pattern",
+    "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes",
 )
 
 
@@ -55,6 +55,8 @@ def lib():
         L.mmd8_linear_workspace_init.argtypes = [vp, sz, vp]
         L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, sz,
                                              ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, f32, vp, i32, vp, sz,
+                                                        ctypes.POINTER(DebugTaps), vp]
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
         L.mmd8_set_gemm_variant.argtypes = [i32]
@@ -153,13 +155,17 @@ def linear_workspace(M: int, K: int, N: int, device) -> torch.Tensor:
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
-                      events=None):
+                      events=None, coded=None):
     """Y = X W through the mixed decomposition.  With taps=True also returns a dict of the
-    intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx)."""
+    intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx).
+    coded=(codes, absmax, block): the activations arrive blockwise-coded; X is then the contiguous
+    [M, K] fp16 buffer that receives the decoded values."""
     _dev(X, torch.float16, "X")
     M, K = X.shape
     if K != pw.K or X.stride(1) != 1:
         raise Mmd8Error("X must be [M, %d] with unit stride along K" % pw.K)
+    if coded is not None and not X.is_contiguous():
+        raise Mmd8Error("the buffer for the decoded activations must be contiguous")
     N = pw.N
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
@@ -179,6 +185,16 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
             outlier_idx=torch.zeros(K, dtype=torch.int32, device=dev),
         )
         tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
+    if coded is not None:
+        codes, absmax, block = coded
+        _dev(codes, torch.uint8, "codes")
+        _dev(absmax, torch.float32, "absmax")
+        _check(lib().mmd8_mixed_int8_linear_from_codes(
+            codes.data_ptr(), absmax.data_ptr(), int(block), M, K, X.data_ptr(), pw.blob.data_ptr(),
+            pw.col_absmax.data_ptr(), N, bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(),
+            out.stride(0) if M > 0 else N, workspace.data_ptr(), workspace.numel(),
+            ctypes.byref(tp) if tp is not None else None, _stream()))
+        return (out, tensors) if taps else out
     _check(lib().mmd8_mixed_int8_linear(
         X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
         bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(), out.stride(0) if M > 0 else N,

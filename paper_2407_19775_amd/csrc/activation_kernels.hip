@@ -6,6 +6,7 @@
 // and  t = a - th  (mod 2^16) has its top bit set exactly for the sub-threshold entries while
 // keeping their order; a single unsigned max of t therefore yields the row scale.
 #include "common.h"
+#include "dynamic_code.h"
 #include "gemm.h"
 #include "operand_layout.h"
 #include "skinny.h"
@@ -13,6 +14,18 @@
 namespace mmd8 {
 
 constexpr int kThreads = 256;
+
+// the 256 values of the dynamic code, for the preparation kernel that takes coded activations
+struct CodeValues {
+  float v[256];
+};
+constexpr CodeValues make_code_values() {
+  CodeValues c{};
+  const DynamicCode d = make_dynamic_code();
+  for (int i = 0; i < 256; ++i) c.v[i] = d.T[i];
+  return c;
+}
+__device__ const CodeValues kCodeValuesDev = make_code_values();
 
 struct PackOutliers {   // the critical columns: compaction outputs and the operands of their fp16 slab
   int32_t* idx;          // ascending critical columns
@@ -334,12 +347,23 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
 // piece 16 (q kWaves + wave) + l / 4 of that row: a load instruction reads 512 contiguous bytes of
 // each of four rows, and a store instruction writes 64-byte runs (the four rows of a piece are
 // neighbours in the blocked layout).
-template <int kWaves, int kPasses>
-__global__ __launch_bounds__(kWaves * kWave) void k_prep(const uint16_t* __restrict__ X, int M, int K, int ldx, uint32_t th,
+//
+// kFromCodes: the activations arrive as a blockwise-coded hidden state ("Compression techniques",
+// item 1: codes + per-block absmax, contiguous [M][K]).  The kernel decodes them first, exactly as
+// the decoder does (f16(T[code] * absmax), fp32 product, then round), writes the fp16 values to X
+// (which is then an output: the decoded hidden state, ldx = K) and carries on with them.
+struct CodedInput {
+  const uint8_t* codes;
+  const float* absmax;
+  int block;
+};
+template <int kWaves, int kPasses, bool kFromCodes>
+__global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ X, int M, int K, int ldx, uint32_t th,
                                                          int n_slabs, uint8_t* __restrict__ flag,
                                                          float* __restrict__ r_out, int8_t* __restrict__ Xq,
-                                                         int8_t* __restrict__ tap_xq) {
+                                                         int8_t* __restrict__ tap_xq, const CodedInput coded) {
   __shared__ uint32_t s_part[kWaves][4];
+  __shared__ float s_T[kFromCodes ? 256 : 1];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int j = lane & 3, i = lane >> 2;
   const int m = blockIdx.x * 4 + j;
@@ -351,13 +375,46 @@ __global__ __launch_bounds__(kWaves * kWave) void k_prep(const uint16_t* __restr
   // every load is unconditional (a lane without data re-reads the first piece of row 0, and what
   // it derives from that is discarded), so that all of them are in flight together
   v4u a[kPasses], b[kPasses];
+  if constexpr (!kFromCodes) {
 #pragma unroll
-  for (int q = 0; q < kPasses; ++q) {
-    const int piece = (q * kWaves + wave) * 16 + i;
-    const bool ok = row_ok && piece < k_pieces;
-    const uint16_t* src = X + (ok ? (size_t)m * ldx + piece * 16 : (size_t)0);
-    a[q] = *reinterpret_cast<const v4u*>(src);
-    b[q] = *reinterpret_cast<const v4u*>(src + 8);
+    for (int q = 0; q < kPasses; ++q) {
+      const int piece = (q * kWaves + wave) * 16 + i;
+      const bool ok = row_ok && piece < k_pieces;
+      const uint16_t* src = X + (ok ? (size_t)m * ldx + piece * 16 : (size_t)0);
+      a[q] = *reinterpret_cast<const v4u*>(src);
+      b[q] = *reinterpret_cast<const v4u*>(src + 8);
+    }
+  } else {
+    v4u cq[kPasses];
+    float sc[kPasses];
+#pragma unroll
+    for (int q = 0; q < kPasses; ++q) {
+      const int piece = (q * kWaves + wave) * 16 + i;
+      const bool ok = row_ok && piece < k_pieces;
+      const uint32_t e0 = ok ? (uint32_t)m * (uint32_t)K + piece * 16 : 0u;   // a piece lies inside one block
+      cq[q] = *reinterpret_cast<const v4u*>(coded.codes + e0);
+      sc[q] = coded.absmax[e0 / (uint32_t)coded.block];
+    }
+    for (int t = threadIdx.x; t < 256; t += kWaves * kWave) s_T[t] = kCodeValuesDev.v[t];
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPasses; ++q) {
+      const int piece = (q * kWaves + wave) * 16 + i;
+      uint32_t h[8];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t cw = cq[q][w];
+        h[2 * w] = rounded_float_to_half_bits(s_T[cw & 0xffu] * sc[q]) | (rounded_float_to_half_bits(s_T[(cw >> 8) & 0xffu] * sc[q]) << 16);
+        h[2 * w + 1] = rounded_float_to_half_bits(s_T[(cw >> 16) & 0xffu] * sc[q]) | (rounded_float_to_half_bits(s_T[cw >> 24] * sc[q]) << 16);
+      }
+      a[q] = v4u{h[0], h[1], h[2], h[3]};
+      b[q] = v4u{h[4], h[5], h[6], h[7]};
+      if (row_ok && piece < k_pieces) {
+        uint16_t* dst = X + (size_t)m * ldx + piece * 16;
+        *reinterpret_cast<v4u*>(dst) = a[q];
+        *reinterpret_cast<v4u*>(dst + 8) = b[q];
+      }
+    }
   }
 
   // ---- row scale and column flags (packed 16-bit compares, see the top of the file)
@@ -536,12 +593,21 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
 // a row to be held in the registers of one workgroup (the caller then uses scan + pack).
 bool prep_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 8; }
 
-hipError_t launch_prep(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
-                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, hipStream_t stream) {
+// coded: null, or the blockwise-coded form of the activations (X is then written, not read).
+hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
+                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes, n_pieces = Kpad / 16;
   const dim3 grid(ceil_div(M, 4));
-#define MMD8_PREP(W_, P_)                                                                                      \
-  hipLaunchKernelGGL((k_prep<W_, P_>), grid, dim3(W_ * kWave), 0, stream, X, M, K, ldx, th, n_slabs, flag, r, Xq, tap_xq)
+  const CodedInput ci = coded ? *coded : CodedInput{};
+#define MMD8_PREP(W_, P_)                                                                                                \
+  do {                                                                                                                   \
+    if (coded)                                                                                                           \
+      hipLaunchKernelGGL((k_prep<W_, P_, true>), grid, dim3(W_ * kWave), 0, stream, X, M, K, ldx, th, n_slabs, flag, r, \
+                         Xq, tap_xq, ci);                                                                                \
+    else                                                                                                                 \
+      hipLaunchKernelGGL((k_prep<W_, P_, false>), grid, dim3(W_ * kWave), 0, stream, X, M, K, ldx, th, n_slabs, flag, r, \
+                         Xq, tap_xq, ci);                                                                                \
+  } while (0)
   if (n_pieces <= 64) MMD8_PREP(4, 1);
   else if (n_pieces <= 128) MMD8_PREP(4, 2);
   else if (n_pieces <= 256) MMD8_PREP(4, 4);

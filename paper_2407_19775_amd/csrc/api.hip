@@ -34,8 +34,13 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
 hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*, uint16_t*,
                        const PackOutliers&, hipStream_t);
 bool prep_fits(int K);
-hipError_t launch_prep(const uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, int8_t*, int8_t*, const PackOutliers&,
-                       hipStream_t);
+struct CodedInput {
+  const uint8_t* codes;
+  const float* absmax;
+  int block;
+};
+hipError_t launch_prep(uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, int8_t*, int8_t*, const PackOutliers&,
+                       const CodedInput*, hipStream_t);
 hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
 hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
 hipError_t launch_weight_unpack(const int8_t*, int, int, int8_t*, hipStream_t);
@@ -214,9 +219,11 @@ int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* st
              : MMD8_E_HIP;
 }
 
-int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                           const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
-                           void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+// The layer.  coded: null, or the blockwise-coded form of the activations, in which case X is the
+// buffer that receives the decoded activations (ldx == K) before the layer reads them.
+static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, const float* col_absmax, int N,
+                      const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
+                      const mmd8_debug_taps* taps, const CodedInput* coded, void* stream) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
@@ -242,9 +249,17 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
                            Wq_packed, col_absmax, N, ws.xo, ws.wo};
   const bool skinny = M <= kSkinnyMaxM;
-  if (!skinny && prep_fits(K)) {
+  // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
+  // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
+  const bool one_pass = !skinny && prep_fits(K);
+  const bool fused_decode = coded && one_pass && (size_t)M * K < ((size_t)1 << 31);
+  if (coded && !fused_decode &&
+      launch_dequantize_blockwise(coded->codes, coded->absmax, (size_t)M * K, coded->block, X, st) != hipSuccess)
+    return MMD8_E_HIP;
+  if (one_pass) {
     // one pass over X: scales, flags and codes together, then the critical columns are cleared
-    if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, st) != hipSuccess)
+    if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, fused_decode ? coded : nullptr,
+                    st) != hipSuccess)
       return MMD8_E_HIP;
   } else {
     if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
@@ -300,6 +315,25 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   }
   if (!record(t.event_gemm_end)) return MMD8_E_HIP;
   return MMD8_OK;
+}
+
+int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                           const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                           void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  // X is only read on this path
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+                    workspace_bytes, taps, nullptr, stream);
+}
+
+int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax, int block, int M, int K,
+                                      mmd8_half* X_decoded, const int8_t* Wq_packed, const float* col_absmax, int N,
+                                      const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace,
+                                      size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  if (M > 0 && (!codes || !absmax || !aligned(codes, 16) || !aligned(absmax, 4))) return MMD8_E_ARG;
+  const CodedInput coded = {codes, absmax, block};
+  return run_linear(X_decoded, M, K, K, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace, workspace_bytes, taps,
+                    &coded, stream);
 }
 
 uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau); }

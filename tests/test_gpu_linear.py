@@ -199,3 +199,34 @@ def test_one_workspace_serves_calls_of_different_shapes():
             assert np.array_equal(to_np(taps["outlier_mask"]).astype(bool), o["flag"]), (rep, M, K, N)
             assert np.array_equal(to_np(taps["acc"]), o["acc"]), (rep, M, K, N)
             assert_y_close(to_np(Y), o["Y"])
+
+
+@pytest.mark.parametrize("M,K,N,block", [(300, 1040, 264, 64), (2048, 4096, 512, 1024), (40, 512, 72, 256), (130, 272, 40, 4096)])
+def test_layer_on_blockwise_coded_activations(M, K, N, block):
+    """The layer fed with a coded hidden state: identical, bit for bit, to decoding first and
+    calling the layer on the result (for more than 64 rows the decoding happens inside the
+    preparation kernel), and equal to the oracle's two steps."""
+    from oracle import blockwise_codec as bc
+    rng = np.random.default_rng([M, K, N, block])
+    h = rng.standard_t(3, (M, K)).astype(np.float32)
+    h[:, rng.integers(0, K, max(1, K // 200))] *= 20.0
+    H = wl.to_fp16(h)
+    W = wl.gaussian_weight(K, N, 0.02, rng)
+    codes_o, absmax_o = bc.quantize_blockwise(H.reshape(-1), block)
+    X_o = bc.dequantize_blockwise(codes_o, absmax_o, block).reshape(M, K)
+    pw, Wq_o, c_o = check_weight(W)
+    codes, absmax = to_gpu(codes_o), to_gpu(absmax_o)
+    Xd = torch.empty((M, K), dtype=torch.float16, device="cuda")
+    Y, taps = binding.mixed_int8_linear(Xd, pw, wl.TAU, taps=True, coded=(codes, absmax, block))
+    # the two separate calls
+    X2 = binding.dequantize_blockwise(codes, absmax, block).view(M, K)
+    Y2 = binding.mixed_int8_linear(X2, pw, wl.TAU)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(Xd).view(np.uint16), X_o.view(np.uint16)), "decoded activations"
+    assert np.array_equal(to_np(Y).view(np.uint16), to_np(Y2).view(np.uint16)), "fused and two-step outputs differ"
+    o = ml.mixed_int8_linear(X_o, Wq_o, c_o, wl.TAU)
+    assert np.array_equal(to_np(taps["outlier_mask"]).astype(bool), o["flag"])
+    assert np.array_equal(to_np(taps["row_absmax"]).view(np.uint32), o["r"].view(np.uint32))
+    assert np.array_equal(to_np(taps["xq"]), o["Xq"])
+    assert np.array_equal(to_np(taps["acc"]), o["acc"])
+    assert_y_close(to_np(Y), o["Y"])
