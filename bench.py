@@ -187,8 +187,8 @@ def main():
         ms = np.mean([gemm_ms[l * len(shapes) + j] for l in range(args.layers)])
         pm = np.mean([prep_ms[l * len(shapes) + j] for l in range(args.layers)])
         per_shape[shp.name] = {"gemm_us": round(ms * 1e3, 1), "gemm_tops": round(2.0 * M * shp.K * shp.N / ms / 1e9, 1),
-                               "scan_pack_us": round(pm * 1e3, 1),
-                               "scan_pack_gbs": round(3.0 * M * shp.K / pm / 1e6, 1)}
+                               "prep_us": round(pm * 1e3, 1),
+                               "prep_gbs": round(3.0 * M * shp.K / pm / 1e6, 1)}
 
     def timed(fn, n=20):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -246,6 +246,38 @@ def main():
                                                   "weight_gbs": round(shp.K * shp.N / t / 1e6, 1),
                                                   "pct_hbm": round(100.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
 
+    # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
+    # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
+    del weights, Xs, Ys
+    torch.cuda.empty_cache()
+    prefill_70b, M5 = {}, 4096
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    ops5 = t5 = 0.0
+    for shp in wl.LLAMA_70B_LINEARS:
+        W = torch.empty((shp.K, shp.N), dtype=torch.float16, device=dev)
+        W.normal_(0.0, 0.015, generator=gen)
+        pw5 = binding.prequantize_weight(W)
+        del W
+        X5, _ = wl.prefill_activation(5, 10 + shp.K % 5, M5, shp.K)
+        X5 = torch.from_numpy(X5).to(dev)
+        Y5 = torch.empty((M5, shp.N), dtype=torch.float16, device=dev)
+        ws5 = binding.linear_workspace(M5, shp.K, shp.N, dev)
+        ts, ps = [], []
+        for it in range(7):
+            binding.mixed_int8_linear(X5, pw5, wl.TAU, out=Y5, workspace=ws5, events=dev_events)
+            torch.cuda.synchronize()
+            ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
+            ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
+        t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
+        o5 = 2.0 * M5 * shp.K * shp.N
+        ops5, t5 = ops5 + o5, t5 + t + pm
+        prefill_70b[shp.name] = {"gemm_us": round(t * 1e3, 1), "gemm_tops": round(o5 / t / 1e9, 1),
+                                 "pct_int8_peak": round(100.0 * o5 / t / 1e9 / INT8_PEAK_TOPS, 1),
+                                 "prep_us": round(pm * 1e3, 1), "prep_gbs": round(3.0 * M5 * shp.K / pm / 1e6, 1)}
+        del pw5, X5, Y5, ws5
+    prefill_70b["layer_tops_end_to_end"] = round(ops5 / t5 / 1e9, 1)
+
     out = {
         "metric": "mixed int8 linear TOPS (+% int8 MFMA peak); blockwise codec GB/s (+% HBM)",
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -270,6 +302,7 @@ def main():
                                   "dequantize_gbs": round(codec_bytes / d_ms / 1e6, 1), "elements": nel,
                                   "note": "the step's own [2048,4096] hidden state: 25 MB per call, launch-bound"}},
         "decode": decode,
+        "prefill_70b": prefill_70b,
     }
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
