@@ -246,6 +246,26 @@ def main():
                                                   "weight_gbs": round(shp.K * shp.N / t / 1e6, 1),
                                                   "pct_hbm": round(100.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
 
+    # ---- the prefill linears with a rank-16 adapter (W' = W + B A, fp16 factors): "prep" now includes the
+    # down-projection T = X A^T, the GEMM multiplies one more fp16 slab (T, B) per tile
+    adapter, r_ad = {}, 16
+    big_ad = max(shapes, key=lambda s: binding.lib().mmd8_linear_lora_workspace_bytes(M, s.K, s.N, r_ad))
+    ws_ad = binding.linear_workspace(M, big_ad.K, big_ad.N, dev, lora_rank=r_ad)
+    for j, shp in enumerate(shapes):
+        A_np, B_np = wl.adapter_factors(2, 40 + j, shp.K, shp.N, r_ad)
+        A_ad, B_ad = torch.from_numpy(A_np).to(dev), torch.from_numpy(B_np).to(dev)
+        ts, ps = [], []
+        for it in range(10):
+            binding.mixed_int8_linear(Xs[shp.K], weights[it % args.layers][j], wl.TAU, out=Ys[shp.name], workspace=ws_ad,
+                                      events=dev_events, lora=(A_ad, B_ad))
+            torch.cuda.synchronize()
+            ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
+            ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
+        t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
+        adapter[shp.name] = {"rank": r_ad, "gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
+                             "gemm_tops": round(2.0 * M * shp.K * shp.N / t / 1e9, 1)}
+    del ws_ad
+
     # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
     # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
     del weights, Xs, Ys
@@ -303,6 +323,7 @@ def main():
                                   "note": "the step's own [2048,4096] hidden state: 25 MB per call, launch-bound"}},
         "decode": decode,
         "prefill_70b": prefill_70b,
+        "adapter": adapter,
     }
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()

@@ -149,6 +149,27 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, con
                                       void* workspace /*DEVICE*/, size_t workspace_bytes,
                                       const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* The layer with a low-rank adapter ("BSNS with parameter-efficient fine-tuning via adapters":
+ * W' = W + B A with A in R^{r x n}, B in R^{n x r}, r << n), the base weight staying in its 8-bit form:
+ *     T[m,j] = f16( sum_k X[m,k] * A[j,k] )                      (fp32 accumulation, one rounding)
+ *     Y[m,n] = f16( the three terms of mmd8_mixed_int8_linear + sum_j T[m,j] * B[n,j] )
+ * lora_A: [r][K] fp16, row-major, contiguous; lora_B: [N][r] fp16, row-major, contiguous (a scale
+ * such as alpha / r is the caller's to fold into B); lora_T: NULL, or [M][r] fp16 that receives T.
+ * Requirements: those of mmd8_mixed_int8_linear; r a multiple of 8 with 8 <= r <= MMD8_MAX_LORA_RANK
+ * (else MMD8_E_SHAPE; pad a smaller adapter with zero rows of A and zero columns of B); lora_A, lora_B,
+ * lora_T 16-byte aligned; workspace of at least mmd8_linear_lora_workspace_bytes(M, K, N, r) bytes,
+ * set up and reused like any other workspace of the layer. */
+#define MMD8_MAX_LORA_RANK 64
+size_t mmd8_linear_lora_workspace_bytes(int M, int K, int N, int r);
+int mmd8_mixed_int8_linear_lora(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                const mmd8_half* lora_A /*DEVICE [r*K]*/, const mmd8_half* lora_B /*DEVICE [N*r]*/, int r,
+                                mmd8_half* lora_T /*DEVICE [M*r] or NULL, written*/,
+                                mmd8_half* Y /*DEVICE*/, int ldy,
+                                void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* HOST helper: the bit pattern of the smallest non-negative fp16 value that is >= tau (0 for
  * tau <= 0, 0x7c00 = +inf when no finite fp16 value reaches tau).  The outlier scan compares fp16
  * magnitudes against this pattern, which is equivalent to |x| >= tau for every fp16 x. */

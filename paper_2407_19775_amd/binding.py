@@ -18,7 +18,8 @@ EXPORTS = (
     "mmd8_status_string", "mmd8_quantize_blockwise", "mmd8_dequantize_blockwise", "mmd8_code_table",
     "mmd8_code_midpoints", "mmd8_packed_weight_layout", "mmd8_packed_weight_bytes", "mmd8_prequantize_weight",
     "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
-    "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes",
+    "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
+    "mmd8_mixed_int8_linear_lora",
 )
 
 
@@ -57,6 +58,10 @@ def lib():
                                              ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, f32, vp, i32, vp, sz,
                                                         ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_linear_lora_workspace_bytes.restype = sz
+        L.mmd8_linear_lora_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.mmd8_mixed_int8_linear_lora.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, sz,
+                                                  ctypes.POINTER(DebugTaps), vp]
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
         L.mmd8_set_gemm_variant.argtypes = [i32]
@@ -143,9 +148,11 @@ def unpack_weight(pw: PackedWeight) -> torch.Tensor:
     return out
 
 
-def linear_workspace(M: int, K: int, N: int, device) -> torch.Tensor:
-    """Allocates and sets up a workspace large enough for one [M,K] x [K,N] call."""
-    nbytes = lib().mmd8_linear_workspace_bytes(M, K, N)
+def linear_workspace(M: int, K: int, N: int, device, lora_rank: int = 0) -> torch.Tensor:
+    """Allocates and sets up a workspace large enough for one [M,K] x [K,N] call (with an adapter of
+    rank lora_rank, if not 0)."""
+    nbytes = (lib().mmd8_linear_lora_workspace_bytes(M, K, N, lora_rank) if lora_rank
+              else lib().mmd8_linear_workspace_bytes(M, K, N))
     if nbytes == 0:
         _check(-2)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -155,11 +162,12 @@ def linear_workspace(M: int, K: int, N: int, device) -> torch.Tensor:
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
-                      events=None, coded=None):
+                      events=None, coded=None, lora=None):
     """Y = X W through the mixed decomposition.  With taps=True also returns a dict of the
     intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx).
     coded=(codes, absmax, block): the activations arrive blockwise-coded; X is then the contiguous
-    [M, K] fp16 buffer that receives the decoded values."""
+    [M, K] fp16 buffer that receives the decoded values.
+    lora=(A [r, K], B [N, r]) or (A, B, T_out [M, r]), fp16: adds the low-rank term of W' = W + B A."""
     _dev(X, torch.float16, "X")
     M, K = X.shape
     if K != pw.K or X.stride(1) != 1:
@@ -169,8 +177,10 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     N = pw.N
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if coded is not None and lora is not None:
+        raise Mmd8Error("coded activations and an adapter cannot be combined in one call")
     if workspace is None:
-        workspace = linear_workspace(M, K, N, X.device)
+        workspace = linear_workspace(M, K, N, X.device, lora[0].shape[0] if lora is not None else 0)
     tp, tensors = None, None
     if events is not None:                      # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
         tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
@@ -194,6 +204,23 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
             pw.col_absmax.data_ptr(), N, bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(),
             out.stride(0) if M > 0 else N, workspace.data_ptr(), workspace.numel(),
             ctypes.byref(tp) if tp is not None else None, _stream()))
+        return (out, tensors) if taps else out
+    if lora is not None:
+        A, B = lora[0], lora[1]
+        T_out = lora[2] if len(lora) > 2 else None
+        _dev(A, torch.float16, "lora A")
+        _dev(B, torch.float16, "lora B")
+        r = A.shape[0]
+        if A.shape != (r, K) or B.shape != (N, r) or not (A.is_contiguous() and B.is_contiguous()):
+            raise Mmd8Error("adapter factors must be contiguous A [r, %d] and B [%d, r]" % (K, N))
+        if T_out is not None and not (T_out.is_cuda and T_out.dtype == torch.float16 and T_out.shape == (M, r)
+                                      and T_out.is_contiguous()):
+            raise Mmd8Error("T_out must be a contiguous GPU fp16 tensor [M, r]")
+        _check(lib().mmd8_mixed_int8_linear_lora(
+            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+            bias.data_ptr() if bias is not None else None, float(tau), A.data_ptr(), B.data_ptr(), int(r),
+            T_out.data_ptr() if T_out is not None else None, out.data_ptr(), out.stride(0) if M > 0 else N,
+            workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
     _check(lib().mmd8_mixed_int8_linear(
         X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmd8.so")
 SOURCES = ["api.hip", "codec_kernels.hip", "activation_kernels.hip", "weight_kernels.hip", "gemm_kernels.hip",
-           "skinny_kernels.hip"]
+           "skinny_kernels.hip", "lora_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

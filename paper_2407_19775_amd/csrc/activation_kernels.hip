@@ -39,6 +39,7 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
   int N;
   uint16_t* Xo;
   uint16_t* Wo;
+  int f_slabs;           // fp16 slabs per panel in Xo / Wo (the critical columns are slab 0)
 };
 
 __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
@@ -232,7 +233,7 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
     for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + max(kcol[t], 0)];
 #pragma unroll
     for (int t = 0; t < 8; ++t) out[t >> 1] |= (kcol[t] >= 0 ? (uint32_t)v[t] : 0u) << (16 * (t & 1));
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, 1)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, o.f_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
@@ -245,7 +246,7 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
       const uint32_t h = rounded_float_to_half_bits((float)q[t] * step);
       out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
     }
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, 1)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, o.f_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   }
 }

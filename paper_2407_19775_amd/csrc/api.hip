@@ -6,6 +6,7 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "lora.h"
 #include "operand_layout.h"
 #include "skinny.h"
 
@@ -30,6 +31,7 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
   int N;
   uint16_t* Xo;
   uint16_t* Wo;
+  int f_slabs;
 };
 hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*, uint16_t*,
                        const PackOutliers&, hipStream_t);
@@ -83,6 +85,7 @@ static uint32_t threshold_pattern(float tau) {
 
 static inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+static int check_lora_rank(int r) { return (r >= 8 && r <= kLoraMaxRank && (r % 8) == 0) ? MMD8_OK : MMD8_E_SHAPE; }
 static int check_linear_shape(int K, int N) {
   if (K < 16 || K > MMD8_MAX_K || (K % 16) != 0 || N < 8 || (N % 8) != 0) return MMD8_E_SHAPE;
   return MMD8_OK;
@@ -98,14 +101,16 @@ struct Workspace {
   uint8_t* mask;       // [Kpad]
   int32_t* idx;        // [Kpad]
   float* r;            // [Mpad + 256]
-  uint16_t* xo;        // [Mpad][kOutlierSlab]
-  uint16_t* wo;        // [Npad][kOutlierSlab]
+  uint16_t* xo;        // [Mpad][kOutlierSlab] per fp16 slab, blocked like the codes
+  uint16_t* wo;        // [Npad][kOutlierSlab] per fp16 slab
+  int f_slabs;         // fp16 slabs: the critical columns, then the low-rank operands of an adapter of rank r
+  uint16_t* lora_t;    // adapter only: [M][kLoraMaxRank] fp16
   int8_t* xq;          // Mpad x Kpad codes, blocked layout
   uint16_t* xf;        // decode path only: [64][Kpad] fp16
   float* partial;      // decode path only: split-K partial outputs
   size_t bytes;
 };
-static Workspace carve(void* base, int M, int K, int N) {
+static Workspace carve(void* base, int M, int K, int N, int r = 0) {
   const size_t Kpad = packed_k(K), Mpad = packed_n(M), Npad = packed_n(N);
   Workspace w;
   size_t off = 0;
@@ -120,16 +125,19 @@ static Workspace carve(void* base, int M, int K, int N) {
   w.mask = take(Kpad);
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
   w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
-  w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2));
-  w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2));
+  w.f_slabs = 1 + lora_slabs(r);
+  w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2 * w.f_slabs));
+  w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2 * w.f_slabs));
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
   w.xf = nullptr;
   w.partial = nullptr;
   if (M > 0 && M <= kSkinnyMaxM) {
     w.xf = reinterpret_cast<uint16_t*>(take((size_t)kSkinnyMaxM * Kpad * 2));
-    const size_t pb = plan_skinny(M, K, N).partial_bytes;
+    size_t pb = plan_skinny(M, K, N).partial_bytes;
+    if (r > 0 && pb == 0) pb = (size_t)M * N * sizeof(float);     // the low-rank term is added where the partial outputs are summed
     if (pb) w.partial = reinterpret_cast<float*>(take(pb));
   }
+  w.lora_t = r > 0 ? reinterpret_cast<uint16_t*>(take((size_t)M * kLoraMaxRank * 2)) : nullptr;
   w.bytes = off;
   return w;
 }
@@ -209,6 +217,10 @@ size_t mmd8_linear_workspace_bytes(int M, int K, int N) {
   if (M < 0 || check_linear_shape(K, N) != MMD8_OK) return 0;
   return carve(nullptr, M, K, N).bytes;
 }
+size_t mmd8_linear_lora_workspace_bytes(int M, int K, int N, int r) {
+  if (M < 0 || check_linear_shape(K, N) != MMD8_OK || check_lora_rank(r) != MMD8_OK) return 0;
+  return carve(nullptr, M, K, N, r).bytes;
+}
 
 int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace || !aligned(workspace, 256)) return MMD8_E_ARG;
@@ -219,11 +231,19 @@ int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* st
              : MMD8_E_HIP;
 }
 
+struct Adapter {   // low-rank factors of W' = W + B A
+  const mmd8_half* A;   // [r][K]
+  const mmd8_half* B;   // [N][r]
+  int r;
+  mmd8_half* T_out;     // [M][r] or null
+};
+
 // The layer.  coded: null, or the blockwise-coded form of the activations, in which case X is the
 // buffer that receives the decoded activations (ldx == K) before the layer reads them.
+// lora: null, or the adapter whose term is added to the output.
 static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, const float* col_absmax, int N,
                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
-                      const mmd8_debug_taps* taps, const CodedInput* coded, void* stream) {
+                      const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, void* stream) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
@@ -234,7 +254,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       !aligned(col_absmax, 4) || (bias && !aligned(bias, 2)))
     return MMD8_E_ARG;
   if (static_cast<const void*>(X) == static_cast<const void*>(Y)) return MMD8_E_ARG;
-  const Workspace ws = carve(workspace, M, K, N);
+  if (lora && (!lora->A || !lora->B || !aligned(lora->A, 16) || !aligned(lora->B, 16) ||
+               (lora->T_out && !aligned(lora->T_out, 16))))
+    return MMD8_E_ARG;
+  const Workspace ws = carve(workspace, M, K, N, lora ? lora->r : 0);
   if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -247,7 +270,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
-                           Wq_packed, col_absmax, N, ws.xo, ws.wo};
+                           Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs};
   const bool skinny = M <= kSkinnyMaxM;
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
@@ -270,6 +293,25 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       hipMemcpyAsync(t.row_absmax, ws.r, (size_t)M * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MMD8_E_HIP;
 
+  if (lora) {
+    // T = f16(X A^T); for the tiled GEMM T and B also go into the fp16 slabs behind the critical columns
+    LoraArgs l = {};
+    l.X = X;
+    l.M = M;
+    l.K = K;
+    l.ldx = ldx;
+    l.A = lora->A;
+    l.B = lora->B;
+    l.r = lora->r;
+    l.N = N;
+    l.T = ws.lora_t;
+    l.T_user = lora->T_out;
+    l.Xo = skinny ? nullptr : ws.xo;
+    l.Wo = skinny ? nullptr : ws.wo;
+    l.f_slabs = ws.f_slabs;
+    if (launch_lora_down(l, st) != hipSuccess) return MMD8_E_HIP;
+  }
+
   if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
   if (skinny) {
     SkinnyArgs g = {};
@@ -288,6 +330,12 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.partial = ws.partial;
     g.tap_acc = t.acc;
     g.flag_reset = ws.flag;
+    if (lora) {
+      g.lora_T = ws.lora_t;
+      g.lora_ldt = kLoraMaxRank;
+      g.lora_B = lora->B;
+      g.lora_r = lora->r;
+    }
     if (launch_gemm_skinny(g, plan_skinny(M, K, N), st) != hipSuccess) return MMD8_E_HIP;
   } else {
     GemmArgs g;
@@ -305,6 +353,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.n_out = ws.n_out;
     g.Xo = ws.xo;
     g.Wo = ws.wo;
+    g.f_slabs = ws.f_slabs;
     g.Y = Y;
     g.ldy = ldy;
     g.tap_acc = t.acc;
@@ -322,7 +371,18 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
                            void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   // X is only read on this path
   return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
-                    workspace_bytes, taps, nullptr, stream);
+                    workspace_bytes, taps, nullptr, nullptr, stream);
+}
+
+int mmd8_mixed_int8_linear_lora(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                                const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                const mmd8_half* lora_A, const mmd8_half* lora_B, int r, mmd8_half* lora_T,
+                                mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
+                                const mmd8_debug_taps* taps, void* stream) {
+  if (check_lora_rank(r) != MMD8_OK) return MMD8_E_SHAPE;
+  const Adapter lora = {lora_A, lora_B, r, lora_T};
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+                    workspace_bytes, taps, nullptr, &lora, stream);
 }
 
 int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax, int block, int M, int K,
@@ -333,7 +393,7 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax,
   if (M > 0 && (!codes || !absmax || !aligned(codes, 16) || !aligned(absmax, 4))) return MMD8_E_ARG;
   const CodedInput coded = {codes, absmax, block};
   return run_linear(X_decoded, M, K, K, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace, workspace_bytes, taps,
-                    &coded, stream);
+                    &coded, nullptr, stream);
 }
 
 uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau); }

@@ -21,6 +21,8 @@ struct GemmArgs {
   const int32_t* n_out;  // their count
   const uint16_t* Xo;    // one slab of fp16 per row, blocked like the codes: X[m, O_j], zero for j >= n_out
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
+  int f_slabs;           // fp16 slabs per panel in Xo / Wo: 1, or 1 + those of a low-rank adapter (at most 3), whose
+                         // operands follow the critical columns and are multiplied in the same way
   uint16_t* Y;
   int ldy;
   int32_t* tap_acc;      // [M][tap_ld] or null

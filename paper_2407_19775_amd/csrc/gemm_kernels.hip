@@ -189,6 +189,52 @@ __device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<C
   }
 }
 
+// The fp16 slabs behind the one of the critical columns (the operands of a low-rank adapter: T on the
+// activation side, B on the weight side), one after the other through the first slab buffer: request,
+// wait, multiply.  Not overlapped with anything: two or three extra slabs next to the K / 64 of the codes.
+template <class Cfg>
+__device__ inline void low_rank_slabs(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+                                      int8_t* smem) {
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
+  // everything here is derived after this point (nothing of it is kept in registers through the main loop)
+  int lane = p.lane, wm = p.wm, wn = p.wn;
+  asm volatile("" : "+v"(lane), "+s"(wm), "+s"(wn));
+  const int wave = wm * Cfg::WAVES_N + wn;
+  const uint32_t base = (uint32_t)(uintptr_t)smem + wave * (kWave * 16);
+  __syncthreads();                                               // every wave is done with the slab buffers
+  for (int f = 1; f < a.f_slabs; ++f) {
+#pragma unroll
+    for (int j = 0; j < Cfg::A_DMA; ++j)
+      dma16(dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, a.f_slabs, j, Cfg::kWaves, wave, lane) +
+                (size_t)f * kBlockBytes,
+            base + j * Cfg::kWaves * (kWave * 16));
+#pragma unroll
+    for (int j = 0; j < Cfg::B_DMA; ++j)
+      dma16(dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane) +
+                (size_t)f * kBlockBytes,
+            base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
+    wait_slab_and_sync<0>();
+#pragma unroll
+    for (int ks = 0; ks < Cfg::NKS; ++ks) {
+      // group of 32 rows: 2 KB = [k-step][lane] 16-byte pieces, as in the main loop
+      const int8_t* fa = smem + (wm * Cfg::WM / 32) * 2048 + ks * 1024 + lane * 16;
+      const int8_t* fb = smem + Cfg::A_BYTES + (wn * Cfg::WN / 32) * 2048 + ks * 1024 + lane * 16;
+      v8h xa[TI], xb[TJ];
+#pragma unroll
+      for (int i = 0; i < TI; ++i) xa[i] = *reinterpret_cast<const v8h*>(fa + i * 32 * BK);
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) xb[j] = *reinterpret_cast<const v8h*>(fb + j * 32 * BK);
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+          acc[i][j] = __builtin_bit_cast(
+              v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[i], xb[j], __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
+    }
+    __syncthreads();                                             // the buffer is read before the next slab lands in it
+  }
+}
+
 // bias, rounding to fp16, and stores.  Neighbouring lanes hold neighbouring columns of the same
 // rows; an even/odd lane pair swaps halves so that each lane stores two adjacent columns (4
 // bytes): the even lane of row e, the odd lane of row e + 1.
@@ -262,12 +308,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
 #pragma unroll
   for (int j = 0; j < Cfg::A_DMA; ++j) {
     srcA[j] = dma_source(a.Xq, p.m0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, 1, j, Cfg::kWaves, wave, lane);
+    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, a.f_slabs, j, Cfg::kWaves, wave, lane);
   }
 #pragma unroll
   for (int j = 0; j < Cfg::B_DMA; ++j) {
     srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, 1, j, Cfg::kWaves, wave, lane);
+    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane);
   }
   // request d (0 .. DMA_PER_SLAB-1) of a slab: the A rows first, then the B rows
   auto issue_dma = [&](int slab, int stage, int d) {
@@ -402,6 +448,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
   // free for the gather staging, which starts with a barrier of its own before writing them
   if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
+  if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
   store_tile<Cfg, kFull>(a, p, acc, bn);
 }
 
@@ -460,12 +507,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
 #pragma unroll
   for (int j = 0; j < Cfg::A_DMA; ++j) {
     srcA[j] = dma_source(a.Xq, p.m0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, 1, j, Cfg::kWaves, wave, lane);
+    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, a.f_slabs, j, Cfg::kWaves, wave, lane);
   }
 #pragma unroll
   for (int j = 0; j < Cfg::B_DMA; ++j) {
     srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, 1, j, Cfg::kWaves, wave, lane);
+    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane);
   }
   auto issue_slab = [&](int slab, int stage) {
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
@@ -577,6 +624,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
   if (grp == 0) sync_only();                                       // as many barriers as group 1
 
   if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
+  if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
   store_tile<Cfg, kFull>(a, p, acc, bn);
 }
 
@@ -629,7 +677,7 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
   GemmArgs b = a;
   const size_t panels = (size_t)n0 / kPanelRows;
   b.Wt = a.Wt + panels * (size_t)(a.Kpad / BK) * kBlockBytes;
-  b.Wo = a.Wo + panels * (kBlockBytes / 2);
+  b.Wo = a.Wo + panels * a.f_slabs * (kBlockBytes / 2);            // uint16_t elements
   b.c = a.c + n0;
   b.bias = a.bias ? a.bias + n0 : nullptr;
   b.Y = a.Y + n0;

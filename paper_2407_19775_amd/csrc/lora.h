@@ -1,0 +1,27 @@
+// Low-rank adapter on top of the int8 layer (see lora_kernels.hip).
+#pragma once
+#include "common.h"
+
+namespace mmd8 {
+
+// Rank limit: the low-rank operands travel through the GEMM as fp16 slabs of 32 columns behind
+// the slab of critical columns, and the GEMM's request window covers three slabs past the codes.
+constexpr int kLoraMaxRank = MMD8_MAX_LORA_RANK;
+__host__ __device__ constexpr inline int lora_slabs(int r) { return ceil_div(r, 32); }
+
+struct LoraArgs {
+  const uint16_t* X;     // [M][ldx] fp16
+  int M, K, ldx;
+  const uint16_t* A;     // [r][K] fp16
+  const uint16_t* B;     // [N][r] fp16
+  int r, N;
+  uint16_t* T;           // [M][kLoraMaxRank] fp16, columns >= r zero: T = f16(X A^T)
+  uint16_t* T_user;      // [M][r] or null
+  uint16_t* Xo;          // fp16 slabs of the GEMM's activation side (slab 0: critical columns), or null
+  uint16_t* Wo;          // likewise, weight side
+  int f_slabs;           // slabs per panel in Xo / Wo: 1 + lora_slabs(r)
+};
+// T for every row (and, where Xo is given, T and B in the GEMM's slab layout)
+hipError_t launch_lora_down(const LoraArgs& a, hipStream_t stream);
+
+}  // namespace mmd8

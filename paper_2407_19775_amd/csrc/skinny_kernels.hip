@@ -228,9 +228,13 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
     }
 }
 
-// Y[m,n] = f16( sum_s partial[s][m][n] + bias[n] ), splits added in index order
+// Y[m,n] = f16( sum_s partial[s][m][n] + bias[n] + sum_j T[m][j] B[n][j] ), splits added in index
+// order, then the bias, then the low-rank term (T: [M][ldt] fp16, B: [N][r] fp16, r a multiple of 8;
+// r == 0: no such term).
 __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict__ partial, int splits, int M, int N,
                                                          const uint16_t* __restrict__ bias,
+                                                         const uint16_t* __restrict__ T, int ldt,
+                                                         const uint16_t* __restrict__ B, int r,
                                                          uint16_t* __restrict__ Y, int ldy) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)M * N) return;
@@ -238,6 +242,17 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
   float y = 0.0f;
   for (int s = 0; s < splits; ++s) y += partial[(size_t)s * M * N + i];
   if (bias) y += half_lo_to_float(bias[n]);
+  if (r > 0) {
+    float low = 0.0f;
+    for (int j = 0; j < r; j += 8) {
+      const v4u t = *reinterpret_cast<const v4u*>(T + (size_t)m * ldt + j);
+      const v4u b = *reinterpret_cast<const v4u*>(B + (size_t)n * r + j);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        low += half_lo_to_float(t[e]) * half_lo_to_float(b[e]) + half_hi_to_float(t[e]) * half_hi_to_float(b[e]);
+    }
+    y += low;
+  }
   Y[(size_t)m * ldy + n] = (uint16_t)float_to_half_bits(y);
 }
 
@@ -283,7 +298,7 @@ static hipError_t launch_panel_one(const SkinnyArgs& a, int splits, hipStream_t 
 }
 template <class Cfg>
 static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t stream) {
-  const bool split = splits > 1, tap = a.tap_acc != nullptr;
+  const bool split = splits > 1 || a.lora_r > 0, tap = a.tap_acc != nullptr;
   if (split) return tap ? launch_panel_one<Cfg, true, true>(a, splits, stream) : launch_panel_one<Cfg, true, false>(a, splits, stream);
   return tap ? launch_panel_one<Cfg, false, true>(a, splits, stream) : launch_panel_one<Cfg, false, false>(a, splits, stream);
 }
@@ -298,14 +313,15 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   a.n_slabs = plan.n_slabs;
   a.tiles_n = plan.tiles_n;
   a.slabs_per_split = plan.slabs_per_split;
-  const bool split = plan.splits > 1, tap = a.tap_acc != nullptr;
+  // with a low-rank term the output always goes through the partial buffer: the kernel that sums it adds the term
+  const bool split = plan.splits > 1 || a.lora_r > 0, tap = a.tap_acc != nullptr;
   const size_t n = (size_t)a.M * a.N;
   if (split && tap) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
   hipError_t e = launch_panel(a, plan, stream);
   if (e != hipSuccess) return e;
   if (split) {
     hipLaunchKernelGGL(k_skinny_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial, plan.splits,
-                       a.M, a.N, a.bias, a.Y, a.ldy);
+                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.Y, a.ldy);
     e = hipGetLastError();
   }
   return e;

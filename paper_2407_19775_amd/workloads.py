@@ -129,6 +129,15 @@ def boundary_hidden_state(rows: int = 8192, cols: int = 8192, tensor_id: int = 0
     return student_t_with_outlier_dims(rows, cols, 3.0, 0.0005, 50.0, rng_for(4, tensor_id))
 
 
+def adapter_factors(config_id: int, tensor_id: int, K: int, N: int, r: int, std: float = 0.02):
+    """Low-rank factors of a trained adapter: A [r, K] and B [N, r], fp16, both ~ N(0, std^2) (after
+    fine-tuning neither factor is zero)."""
+    rng = rng_for(config_id, tensor_id)
+    A = to_fp16(rng.standard_normal((r, K), dtype=np.float32) * np.float32(std))
+    B = to_fp16(rng.standard_normal((N, r), dtype=np.float32) * np.float32(std))
+    return A, B
+
+
 def linear_ops(M: int, shapes) -> int:
     """Integer multiply-add operations (2 per MAC) of one pass over the given linears."""
     return sum(2 * M * s.K * s.N for s in shapes)

@@ -107,3 +107,24 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert call(M=-1) == -1
     assert call(M=0, X=None, Y=None, ws=None, wsb=0) == 0                          # empty is fine
     assert b"workspace" in L.mmd8_status_string(-3)
+
+
+def test_adapter_arguments_are_rejected_before_any_launch():
+    L = binding.lib()
+    fake, y = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    odd = ctypes.c_void_p(0x1008)
+    assert L.mmd8_linear_lora_workspace_bytes(8, 128, 64, 16) > L.mmd8_linear_workspace_bytes(8, 128, 64)
+    assert L.mmd8_linear_lora_workspace_bytes(2048, 4096, 4096, 64) > L.mmd8_linear_workspace_bytes(2048, 4096, 4096)
+    for bad_r in (0, 4, 12, 72, -8):
+        assert L.mmd8_linear_lora_workspace_bytes(8, 128, 64, bad_r) == 0
+    ws = L.mmd8_linear_lora_workspace_bytes(8, 128, 64, 16)
+
+    def call(A=fake, B=fake, r=16, T=None, wsb=ws, K=128):
+        return L.mmd8_mixed_int8_linear_lora(fake, 8, K, 128, fake, fake, 64, None, 6.0, A, B, r, T, y, 64, fake, wsb,
+                                             None, None)
+
+    assert call(r=4) == -2 and call(r=20) == -2 and call(r=128) == -2
+    assert call(A=None) == -1 and call(B=None) == -1
+    assert call(A=odd) == -1 and call(T=odd) == -1
+    assert call(K=100) == -2
+    assert call(wsb=L.mmd8_linear_workspace_bytes(8, 128, 64)) == -3               # sized without the adapter
