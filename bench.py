@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE, scaled by a plain copy of known size (profiles/gemm_llama7b_prefill_hbm_traffic.txt).  Valid
 # for the GEMM source it was measured on: reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 207.0e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "51ab9bf7cb5adbcab78684584206471fb9a194575c97375958103bf8adc7f5c7"
+GEMM_TRAFFIC_SOURCE_SHA256 = "0edc6a1b3b988d7e6bd04803f968df82fcb614a7e966c1d18dc5dd1cd9101384"
 
 
 def parse():
@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--codec-block", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-step", action="store_true",
+                    help="profiling aid: skip the extra sections (large codec tensor, decode, 70B, adapter)")
     ap.add_argument("--gemm-variant", type=int, default=-1, help="tuning: force a GEMM tile configuration (-1 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a kernel of known HBM traffic, to scale rocprofv3 "
@@ -206,97 +208,98 @@ def main():
     q_ms = timed(lambda: binding.quantize_blockwise(Ys["down"], block, codes=codes_out, absmax=absmax_out))
     d_ms = timed(lambda: binding.dequantize_blockwise(codes_in, absmax_in, block, out=hidden_in.view(-1)))
 
-    # ---- the codec at the size of a shard-boundary hidden state [8192, 8192] (134 MB of fp16: HBM
-    # traffic, buffers rotated so that nothing is served from the last-level cache)
-    nb, big = 3, 8192 * 8192
-    xs = [torch.randn(big, device=dev, dtype=torch.float16) for _ in range(nb)]
-    cs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(nb)]
-    am = [torch.empty(big // block, dtype=torch.float32, device=dev) for _ in range(nb)]
-    big_bytes = 3.0 * big + 4.0 * big / block
-    turn = [0]
+    if not args.only_step:
+        # ---- the codec at the size of a shard-boundary hidden state [8192, 8192] (134 MB of fp16: HBM
+        # traffic, buffers rotated so that nothing is served from the last-level cache)
+        nb, big = 3, 8192 * 8192
+        xs = [torch.randn(big, device=dev, dtype=torch.float16) for _ in range(nb)]
+        cs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(nb)]
+        am = [torch.empty(big // block, dtype=torch.float32, device=dev) for _ in range(nb)]
+        big_bytes = 3.0 * big + 4.0 * big / block
+        turn = [0]
 
-    def q_big():
-        i = turn[0] = (turn[0] + 1) % nb
-        binding.quantize_blockwise(xs[i], block, codes=cs[i], absmax=am[i])
+        def q_big():
+            i = turn[0] = (turn[0] + 1) % nb
+            binding.quantize_blockwise(xs[i], block, codes=cs[i], absmax=am[i])
 
-    def d_big():
-        i = turn[0] = (turn[0] + 1) % nb
-        binding.dequantize_blockwise(cs[i], am[i], block, out=xs[i])
+        def d_big():
+            i = turn[0] = (turn[0] + 1) % nb
+            binding.dequantize_blockwise(cs[i], am[i], block, out=xs[i])
 
-    qb_ms, db_ms = timed(q_big, 12), timed(d_big, 12)
-    del xs, cs, am
+        qb_ms, db_ms = timed(q_big, 12), timed(d_big, 12)
+        del xs, cs, am
 
-    # ---- decode shapes: the same linears with 1 and 64 tokens, heavy-tailed activations; the four
-    # layers' weights take turns (360 MB of codes per shape family: cold)
-    decode = {}
-    dev_events = [he.create() for _ in range(3)]
-    for j, shp in enumerate(shapes):
-        for Md in (1, 64):
-            Xd = torch.from_numpy(wl.decode_activation(Md, Md, shp.K)).to(dev)
-            Yd = torch.empty((Md, shp.N), dtype=torch.float16, device=dev)
-            wsd = binding.linear_workspace(Md, shp.K, shp.N, dev)
+        # ---- decode shapes: the same linears with 1 and 64 tokens, heavy-tailed activations; the four
+        # layers' weights take turns (360 MB of codes per shape family: cold)
+        decode = {}
+        dev_events = [he.create() for _ in range(3)]
+        for j, shp in enumerate(shapes):
+            for Md in (1, 64):
+                Xd = torch.from_numpy(wl.decode_activation(Md, Md, shp.K)).to(dev)
+                Yd = torch.empty((Md, shp.N), dtype=torch.float16, device=dev)
+                wsd = binding.linear_workspace(Md, shp.K, shp.N, dev)
+                ts, ps = [], []
+                for it in range(10):
+                    binding.mixed_int8_linear(Xd, weights[it % args.layers][j], wl.TAU, out=Yd, workspace=wsd, events=dev_events)
+                    torch.cuda.synchronize()
+                    ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
+                    ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
+                t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
+                decode["%s_M%d" % (shp.name, Md)] = {"gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
+                                                      "weight_gbs": round(shp.K * shp.N / t / 1e6, 1),
+                                                      "pct_hbm": round(100.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
+
+        # ---- the prefill linears with a rank-16 adapter (W' = W + B A, fp16 factors): "prep" now includes the
+        # down-projection T = X A^T, the GEMM multiplies one more fp16 slab (T, B) per tile
+        adapter, r_ad = {}, 16
+        big_ad = max(shapes, key=lambda s: binding.lib().mmd8_linear_lora_workspace_bytes(M, s.K, s.N, r_ad))
+        ws_ad = binding.linear_workspace(M, big_ad.K, big_ad.N, dev, lora_rank=r_ad)
+        for j, shp in enumerate(shapes):
+            A_np, B_np = wl.adapter_factors(2, 40 + j, shp.K, shp.N, r_ad)
+            A_ad, B_ad = torch.from_numpy(A_np).to(dev), torch.from_numpy(B_np).to(dev)
             ts, ps = [], []
             for it in range(10):
-                binding.mixed_int8_linear(Xd, weights[it % args.layers][j], wl.TAU, out=Yd, workspace=wsd, events=dev_events)
+                binding.mixed_int8_linear(Xs[shp.K], weights[it % args.layers][j], wl.TAU, out=Ys[shp.name], workspace=ws_ad,
+                                          events=dev_events, lora=(A_ad, B_ad))
                 torch.cuda.synchronize()
                 ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
                 ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
             t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
-            decode["%s_M%d" % (shp.name, Md)] = {"gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
-                                                  "weight_gbs": round(shp.K * shp.N / t / 1e6, 1),
-                                                  "pct_hbm": round(100.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
+            adapter[shp.name] = {"rank": r_ad, "gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
+                                 "gemm_tops": round(2.0 * M * shp.K * shp.N / t / 1e9, 1)}
+        del ws_ad
 
-    # ---- the prefill linears with a rank-16 adapter (W' = W + B A, fp16 factors): "prep" now includes the
-    # down-projection T = X A^T, the GEMM multiplies one more fp16 slab (T, B) per tile
-    adapter, r_ad = {}, 16
-    big_ad = max(shapes, key=lambda s: binding.lib().mmd8_linear_lora_workspace_bytes(M, s.K, s.N, r_ad))
-    ws_ad = binding.linear_workspace(M, big_ad.K, big_ad.N, dev, lora_rank=r_ad)
-    for j, shp in enumerate(shapes):
-        A_np, B_np = wl.adapter_factors(2, 40 + j, shp.K, shp.N, r_ad)
-        A_ad, B_ad = torch.from_numpy(A_np).to(dev), torch.from_numpy(B_np).to(dev)
-        ts, ps = [], []
-        for it in range(10):
-            binding.mixed_int8_linear(Xs[shp.K], weights[it % args.layers][j], wl.TAU, out=Ys[shp.name], workspace=ws_ad,
-                                      events=dev_events, lora=(A_ad, B_ad))
-            torch.cuda.synchronize()
-            ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
-            ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
-        t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
-        adapter[shp.name] = {"rank": r_ad, "gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
-                             "gemm_tops": round(2.0 * M * shp.K * shp.N / t / 1e9, 1)}
-    del ws_ad
-
-    # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
-    # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
-    del weights, Xs, Ys
-    torch.cuda.empty_cache()
-    prefill_70b, M5 = {}, 4096
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(5)
-    ops5 = t5 = 0.0
-    for shp in wl.LLAMA_70B_LINEARS:
-        W = torch.empty((shp.K, shp.N), dtype=torch.float16, device=dev)
-        W.normal_(0.0, 0.015, generator=gen)
-        pw5 = binding.prequantize_weight(W)
-        del W
-        X5, _ = wl.prefill_activation(5, 10 + shp.K % 5, M5, shp.K)
-        X5 = torch.from_numpy(X5).to(dev)
-        Y5 = torch.empty((M5, shp.N), dtype=torch.float16, device=dev)
-        ws5 = binding.linear_workspace(M5, shp.K, shp.N, dev)
-        ts, ps = [], []
-        for it in range(7):
-            binding.mixed_int8_linear(X5, pw5, wl.TAU, out=Y5, workspace=ws5, events=dev_events)
-            torch.cuda.synchronize()
-            ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
-            ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
-        t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
-        o5 = 2.0 * M5 * shp.K * shp.N
-        ops5, t5 = ops5 + o5, t5 + t + pm
-        prefill_70b[shp.name] = {"gemm_us": round(t * 1e3, 1), "gemm_tops": round(o5 / t / 1e9, 1),
-                                 "pct_int8_peak": round(100.0 * o5 / t / 1e9 / INT8_PEAK_TOPS, 1),
-                                 "prep_us": round(pm * 1e3, 1), "prep_gbs": round(3.0 * M5 * shp.K / pm / 1e6, 1)}
-        del pw5, X5, Y5, ws5
-    prefill_70b["layer_tops_end_to_end"] = round(ops5 / t5 / 1e9, 1)
+        # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
+        # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
+        del weights, Xs, Ys
+        torch.cuda.empty_cache()
+        prefill_70b, M5 = {}, 4096
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(5)
+        ops5 = t5 = 0.0
+        for shp in wl.LLAMA_70B_LINEARS:
+            W = torch.empty((shp.K, shp.N), dtype=torch.float16, device=dev)
+            W.normal_(0.0, 0.015, generator=gen)
+            pw5 = binding.prequantize_weight(W)
+            del W
+            X5, _ = wl.prefill_activation(5, 10 + shp.K % 5, M5, shp.K)
+            X5 = torch.from_numpy(X5).to(dev)
+            Y5 = torch.empty((M5, shp.N), dtype=torch.float16, device=dev)
+            ws5 = binding.linear_workspace(M5, shp.K, shp.N, dev)
+            ts, ps = [], []
+            for it in range(7):
+                binding.mixed_int8_linear(X5, pw5, wl.TAU, out=Y5, workspace=ws5, events=dev_events)
+                torch.cuda.synchronize()
+                ps.append(he.elapsed_ms(dev_events[0], dev_events[1]))
+                ts.append(he.elapsed_ms(dev_events[1], dev_events[2]))
+            t, pm = float(np.median(ts[2:])), float(np.median(ps[2:]))
+            o5 = 2.0 * M5 * shp.K * shp.N
+            ops5, t5 = ops5 + o5, t5 + t + pm
+            prefill_70b[shp.name] = {"gemm_us": round(t * 1e3, 1), "gemm_tops": round(o5 / t / 1e9, 1),
+                                     "pct_int8_peak": round(100.0 * o5 / t / 1e9 / INT8_PEAK_TOPS, 1),
+                                     "prep_us": round(pm * 1e3, 1), "prep_gbs": round(3.0 * M5 * shp.K / pm / 1e6, 1)}
+            del pw5, X5, Y5, ws5
+        prefill_70b["layer_tops_end_to_end"] = round(ops5 / t5 / 1e9, 1)
 
     out = {
         "metric": "mixed int8 linear TOPS (+% int8 MFMA peak); blockwise codec GB/s (+% HBM)",
@@ -313,18 +316,18 @@ def main():
                      "achieved": round(gemm_tops, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": gemm_traffic()},
         "per_linear": per_shape,
-        "codec": {"quantize_gbs": round(big_bytes / qb_ms / 1e6, 1), "dequantize_gbs": round(big_bytes / db_ms / 1e6, 1),
-                  "quantize_pct_hbm": round(100 * big_bytes / qb_ms / 1e6 / HBM_PEAK_GBS, 1),
-                  "dequantize_pct_hbm": round(100 * big_bytes / db_ms / 1e6 / HBM_PEAK_GBS, 1),
-                  "elements": big, "block": block,
-                  "note": "shard-boundary hidden state [8192,8192], rotating buffers (HBM traffic)",
-                  "step_tensor": {"quantize_gbs": round(codec_bytes / q_ms / 1e6, 1),
-                                  "dequantize_gbs": round(codec_bytes / d_ms / 1e6, 1), "elements": nel,
+        "codec": {"step_tensor": {"quantize_gbs": round(codec_bytes / q_ms / 1e6, 1),
+                                  "dequantize_gbs": round(codec_bytes / d_ms / 1e6, 1), "elements": nel, "block": block,
                                   "note": "the step's own [2048,4096] hidden state: 25 MB per call, launch-bound"}},
-        "decode": decode,
-        "prefill_70b": prefill_70b,
-        "adapter": adapter,
     }
+    if not args.only_step:
+        out["codec"].update({
+            "quantize_gbs": round(big_bytes / qb_ms / 1e6, 1), "dequantize_gbs": round(big_bytes / db_ms / 1e6, 1),
+            "quantize_pct_hbm": round(100 * big_bytes / qb_ms / 1e6 / HBM_PEAK_GBS, 1),
+            "dequantize_pct_hbm": round(100 * big_bytes / db_ms / 1e6 / HBM_PEAK_GBS, 1),
+            "elements": big, "block": block,
+            "note": "shard-boundary hidden state [8192,8192], rotating buffers (HBM traffic)"})
+        out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

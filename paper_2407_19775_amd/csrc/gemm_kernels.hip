@@ -631,16 +631,18 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
 // ------------------------------------------------------------------------------------------------
 template <class Cfg, bool kTap, bool kFull, bool kPingPong>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
-  static bool attr_set = false;
+  static bool attr_set[64] = {};                                   // per device: the attribute belongs to the device's code object
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   const void* fn;
   if constexpr (kPingPong)
     fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull>);
   else
     fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull>);
-  if (!attr_set) {
+  if (!attr_set[dev]) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   const int grid = ceil_div(a.tiles_m * a.tiles_n, 8) * 8;
   if constexpr (kPingPong)

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kLoraThreads) void k_lora_down(const LoraArgs a, in
   for (int t = 0; t < kTiles; ++t) acc[t] = v4f{0, 0, 0, 0};
 
   const int steps = ceil_div(a.K, 64);
-  constexpr int U = 2;
+  constexpr int U = kTiles <= 2 ? 4 : 2;
   for (int s0 = wave; s0 < steps; s0 += kLoraWaves * U) {
     v4u xf[U][2], af[U][kTiles][2];
     // every load is issued before the first use; a step past the end re-reads step 0 and is masked
