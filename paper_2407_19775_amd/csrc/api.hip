@@ -105,6 +105,7 @@ struct Workspace {
   uint16_t* wo;        // [Npad][kOutlierSlab] per fp16 slab
   int f_slabs;         // fp16 slabs: the critical columns, then the low-rank operands of an adapter of rank r
   uint16_t* lora_t;    // adapter only: [M][kLoraMaxRank] fp16
+  float* lora_part;    // adapter only: partial sums of the down-projection when K is split between workgroups
   int8_t* xq;          // Mpad x Kpad codes, blocked layout
   uint16_t* xf;        // decode path only: [64][Kpad] fp16
   float* partial;      // decode path only: split-K partial outputs
@@ -138,6 +139,11 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0) {
     if (pb) w.partial = reinterpret_cast<float*>(take(pb));
   }
   w.lora_t = r > 0 ? reinterpret_cast<uint16_t*>(take((size_t)M * kLoraMaxRank * 2)) : nullptr;
+  w.lora_part = nullptr;
+  if (r > 0 && M > 0) {
+    const size_t lb = plan_lora(M, K).partial_bytes;
+    if (lb) w.lora_part = reinterpret_cast<float*>(take(lb));
+  }
   w.bytes = off;
   return w;
 }
@@ -309,7 +315,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     l.Xo = skinny ? nullptr : ws.xo;
     l.Wo = skinny ? nullptr : ws.wo;
     l.f_slabs = ws.f_slabs;
-    if (launch_lora_down(l, st) != hipSuccess) return MMD8_E_HIP;
+    if (launch_lora_down(l, plan_lora(M, K), ws.lora_part, st) != hipSuccess) return MMD8_E_HIP;
   }
 
   if (!record(t.event_gemm_begin)) return MMD8_E_HIP;

@@ -21,7 +21,13 @@ struct LoraArgs {
   uint16_t* Wo;          // likewise, weight side
   int f_slabs;           // slabs per panel in Xo / Wo: 1 + lora_slabs(r)
 };
+// how K is split between workgroups for this shape (depends on the device's CU count)
+struct LoraPlan {
+  int splits, steps_per_split;   // ranges of K, each this many 64-column steps
+  size_t partial_bytes;          // fp32 [splits][M][kLoraMaxRank] when splits > 1
+};
+LoraPlan plan_lora(int M, int K);
 // T for every row (and, where Xo is given, T and B in the GEMM's slab layout)
-hipError_t launch_lora_down(const LoraArgs& a, hipStream_t stream);
+hipError_t launch_lora_down(const LoraArgs& a, const LoraPlan& plan, float* partial, hipStream_t stream);
 
 }  // namespace mmd8
