@@ -8,6 +8,7 @@
 #include "common.h"
 #include "dynamic_code.h"
 #include "gemm.h"
+#include "launchers.h"
 #include "operand_layout.h"
 #include "skinny.h"
 
@@ -26,21 +27,6 @@ constexpr CodeValues make_code_values() {
   return c;
 }
 __device__ const CodeValues kCodeValuesDev = make_code_values();
-
-struct PackOutliers {   // the critical columns: compaction outputs and the operands of their fp16 slab
-  int32_t* idx;          // ascending critical columns
-  int32_t* n_out;        // [1]
-  uint8_t* mask;         // [Kpad] 1 = critical column (padding 0)
-  uint8_t* tap_mask;     // [K] or null
-  int32_t* tap_idx;      // or null
-  int32_t* tap_n;        // or null
-  const int8_t* Wt;
-  const float* c;
-  int N;
-  uint16_t* Xo;
-  uint16_t* Wo;
-  int f_slabs;           // fp16 slabs per panel in Xo / Wo (the critical columns are slab 0)
-};
 
 __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -353,11 +339,6 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
 // item 1: codes + per-block absmax, contiguous [M][K]).  The kernel decodes them first, exactly as
 // the decoder does (f16(T[code] * absmax), fp32 product, then round), writes the fp16 values to X
 // (which is then an output: the decoded hidden state, ldx = K) and carries on with them.
-struct CodedInput {
-  const uint8_t* codes;
-  const float* absmax;
-  int block;
-};
 template <int kWaves, int kPasses, bool kFromCodes>
 __global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ X, int M, int K, int ldx, uint32_t th,
                                                          int n_slabs, uint8_t* __restrict__ flag,
@@ -590,11 +571,8 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
   return hipGetLastError();
 }
 
-// One-pass preparation for inputs taller than the decode kernels take; false when K is too large for
-// a row to be held in the registers of one workgroup (the caller then uses scan + pack).
 bool prep_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 8; }
 
-// coded: null, or the blockwise-coded form of the activations (X is then written, not read).
 hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
                        int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes, n_pieces = Kpad / 16;

@@ -6,46 +6,12 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "launchers.h"
 #include "lora.h"
 #include "operand_layout.h"
 #include "skinny.h"
 
 namespace mmd8 {
-
-// launchers defined next to their kernels
-const float* code_table_host();
-const float* code_midpoints_host();
-hipError_t launch_quantize_blockwise(const uint16_t*, size_t, int, uint8_t*, float*, hipStream_t);
-hipError_t launch_dequantize_blockwise(const uint8_t*, const float*, size_t, int, uint16_t*, hipStream_t);
-hipError_t launch_fill_u32(uint32_t*, uint32_t, int, hipStream_t);
-hipError_t launch_scan(const uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, hipStream_t);
-struct PackOutliers {   // the critical columns: compaction outputs and the operands of their fp16 slab
-  int32_t* idx;
-  int32_t* n_out;
-  uint8_t* mask;
-  uint8_t* tap_mask;
-  int32_t* tap_idx;
-  int32_t* tap_n;
-  const int8_t* Wt;
-  const float* c;
-  int N;
-  uint16_t* Xo;
-  uint16_t* Wo;
-  int f_slabs;
-};
-hipError_t launch_pack(const uint16_t*, int, int, int, const uint8_t*, const float*, int8_t*, int, int8_t*, uint16_t*,
-                       const PackOutliers&, hipStream_t);
-bool prep_fits(int K);
-struct CodedInput {
-  const uint8_t* codes;
-  const float* absmax;
-  int block;
-};
-hipError_t launch_prep(uint16_t*, int, int, int, uint32_t, int, uint8_t*, float*, int8_t*, int8_t*, const PackOutliers&,
-                       const CodedInput*, hipStream_t);
-hipError_t launch_col_absmax(const uint16_t*, int, int, int, float*, hipStream_t);
-hipError_t launch_weight_quant_pack(const uint16_t*, int, int, int, const float*, int8_t*, hipStream_t);
-hipError_t launch_weight_unpack(const int8_t*, int, int, int8_t*, hipStream_t);
 
 int device_cu_count() {
   static std::mutex mu;

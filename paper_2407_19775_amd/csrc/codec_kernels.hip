@@ -6,6 +6,7 @@
 // lookup tables are staged into LDS once per workgroup, not once per span.
 #include "common.h"
 #include "dynamic_code.h"
+#include "launchers.h"
 
 namespace mmd8 {
 

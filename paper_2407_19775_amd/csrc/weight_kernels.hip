@@ -5,6 +5,7 @@
 // what the int8 MFMA fragments want, 16 consecutive k per lane) in the blocked order described in
 // operand_layout.h; padding is zero.
 #include "common.h"
+#include "launchers.h"
 #include "operand_layout.h"
 
 namespace mmd8 {
