@@ -101,6 +101,46 @@ def test_k_too_large_for_one_pass_preparation(M):
     check_linear(wl.to_fp16(x), wl.gaussian_weight(K, N, 0.02, rng), 6.0)
 
 
+@pytest.mark.parametrize("M", [2, 130])
+def test_largest_k(M):
+    """K = MMD8_MAX_K (65536): the int32 accumulators stay far from overflow (K * 127^2 < 2^31), the column
+    flags fill their region of the workspace head."""
+    K, N = 65536, 40
+    rng = np.random.default_rng([M, K, 1])
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[0, [0, K - 1, 40000]] = [9.0, -11.0, 200.0]                   # first, last and a middle column critical
+    X = wl.to_fp16(x)
+    o_flag = ml.outlier_mask(X, 6.0)
+    assert o_flag[0] and o_flag[K - 1]
+    check_linear(X, wl.gaussian_weight(K, N, 0.02, rng), 6.0)
+
+
+def test_two_streams_with_their_own_workspaces():
+    """Calls on different streams with different workspaces do not share state: interleaved on two streams they
+    give what each gives alone."""
+    rng = np.random.default_rng(12)
+    cases = []
+    for (M, K, N) in [(300, 1040, 520), (40, 2048, 264)]:
+        x = rng.standard_t(3.0, size=(M, K)).astype(np.float32)
+        X, W = to_gpu(wl.to_fp16(x)), wl.gaussian_weight(K, N, 0.02, rng)
+        pw = binding.prequantize_weight(to_gpu(W))
+        cases.append(dict(X=X, pw=pw, ws=binding.linear_workspace(M, K, N, "cuda"),
+                          Y=torch.empty((M, N), dtype=torch.float16, device="cuda")))
+    alone = []
+    for c in cases:
+        alone.append(binding.mixed_int8_linear(c["X"], c["pw"], 6.0, workspace=c["ws"]).clone())
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(5):
+        for c, st in zip(cases, streams):
+            with torch.cuda.stream(st):
+                for _ in range(3):
+                    binding.mixed_int8_linear(c["X"], c["pw"], 6.0, out=c["Y"], workspace=c["ws"])
+        torch.cuda.synchronize()
+        for c, ref in zip(cases, alone):
+            assert torch.equal(c["Y"], ref), rep
+
+
 def test_empty_batch():
     pw = binding.prequantize_weight(to_gpu(wl.gaussian_weight(64, 16, 0.02, np.random.default_rng(0))))
     Y = binding.mixed_int8_linear(torch.empty((0, 64), dtype=torch.float16, device="cuda"), pw, 6.0)
