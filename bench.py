@@ -75,9 +75,10 @@ def gemm_traffic():
     return GEMM_TRAFFIC_BYTES_PER_LAUNCH if same else None
 
 
-def cpu_baseline(wl, layers_sample=1):
-    """The CPU oracle on a bounded sample of the same workload: one decoder layer's four linears
-    at full size plus the codec round trip of one hidden state."""
+def cpu_baseline(wl, passes=4):
+    """The CPU oracle on a bounded sample of the same workload: the step's sixteen linears at full size
+    (one decoder layer's tensors, `passes` times: the oracle's time does not depend on the values) plus as
+    many codec round trips of one hidden state."""
     import numpy as np
     from oracle import blockwise_codec as bc
     from oracle import mixed_linear as ml
@@ -92,19 +93,20 @@ def cpu_baseline(wl, layers_sample=1):
         ops += 2 * M * shp.K * shp.N
     hidden = prepared[0][0]
     t0 = time.perf_counter()
-    codes, a = bc.quantize_blockwise(hidden, 1024)
-    bc.dequantize_blockwise(codes, a, 1024)
-    for X, Wq, c in prepared:
-        ml.mixed_int8_linear(X, Wq, c, wl.TAU)
+    for _ in range(passes):
+        codes, a = bc.quantize_blockwise(hidden, 1024)
+        bc.dequantize_blockwise(codes, a, 1024)
+        for X, Wq, c in prepared:
+            ml.mixed_int8_linear(X, Wq, c, wl.TAU)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
-            "sample": "1 of 4 decoder layers (4 linears, 2048 tokens, full size) + codec round trip of one "
-                      "[2048,4096] hidden state; %.1f s" % dt}
+    return {"value": passes * ops / dt / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
+            "sample": "%d passes over one decoder layer (4 linears, 2048 tokens, full size) + as many codec round "
+                      "trips of one [2048,4096] hidden state: the step's amount of work; %.1f s" % (passes, dt)}
 
 
 def main():
@@ -248,6 +250,30 @@ def main():
                 decode["%s_M%d" % (shp.name, Md)] = {"gemm_us": round(t * 1e3, 1), "prep_us": round(pm * 1e3, 1),
                                                       "weight_gbs": round(shp.K * shp.N / t / 1e6, 1),
                                                       "pct_hbm": round(100.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
+
+        # whole decoder layers at 1 and 64 tokens, wall time of back-to-back calls (no events in between):
+        # all four layers' weights in turn, 810 MB of codes per pass
+        layer_bytes = float(sum(s.K * s.N for s in shapes))
+        for Md in (1, 64):
+            Xd = {K: torch.from_numpy(wl.decode_activation(Md, Md, K)).to(dev) for K in sorted({s.K for s in shapes})}
+            Yd = {s.name: torch.empty((Md, s.N), dtype=torch.float16, device=dev) for s in shapes}
+            wsd = binding.linear_workspace(Md, biggest.K, biggest.N, dev)
+
+            def decode_pass():
+                for layer in range(args.layers):
+                    for j, shp in enumerate(shapes):
+                        binding.mixed_int8_linear(Xd[shp.K], weights[layer][j], wl.TAU, out=Yd[shp.name], workspace=wsd)
+
+            for _ in range(3):
+                decode_pass()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                decode_pass()
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) / 20 / args.layers * 1e6
+            decode["layer_M%d" % Md] = {"us_per_layer": round(us, 1), "weight_gbs": round(layer_bytes / us / 1e3, 1),
+                                        "pct_hbm": round(100.0 * layer_bytes / us / 1e3 / HBM_PEAK_GBS, 1)}
 
         # ---- the prefill linears with a rank-16 adapter (W' = W + B A, fp16 factors): "prep" now includes the
         # down-projection T = X A^T, the GEMM multiplies one more fp16 slab (T, B) per tile
