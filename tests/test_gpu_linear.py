@@ -160,7 +160,7 @@ def test_repeated_calls_are_deterministic():
         assert h == ref
 
 
-@pytest.mark.parametrize("M", [1, 8, 32, 64])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 32, 64])
 @pytest.mark.parametrize("shape", wl.LLAMA_7B_LINEARS, ids=lambda s: s.name)
 def test_config3_decode_shapes(M, shape):
     """Student-t decode activations: up to ~45 % of the feature dimensions are critical."""
