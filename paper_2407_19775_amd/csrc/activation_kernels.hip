@@ -572,6 +572,8 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
 }
 
 bool prep_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 8; }
+// the variant that decodes coded activations holds more per lane: rows up to 16384 columns without spilling
+bool prep_from_codes_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 4; }
 
 hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
                        int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream) {
@@ -592,7 +594,9 @@ hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad
   else if (n_pieces <= 256) MMD8_PREP(4, 4);
   else if (n_pieces <= 512) MMD8_PREP(8, 4);
   else if (n_pieces <= 1024) MMD8_PREP(16, 4);
-  else MMD8_PREP(16, 8);
+  else if (coded) return hipErrorInvalidValue;                     // the caller decodes first (prep_from_codes_fits)
+  else hipLaunchKernelGGL((k_prep<16, 8, false>), grid, dim3(16 * kWave), 0, stream, X, M, K, ldx, th, n_slabs, flag, r, Xq,
+                          tap_xq, ci);
 #undef MMD8_PREP
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

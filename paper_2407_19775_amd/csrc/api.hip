@@ -247,7 +247,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K);
-  const bool fused_decode = coded && one_pass && (size_t)M * K < ((size_t)1 << 31);
+  const bool fused_decode = coded && one_pass && prep_from_codes_fits(K) && (size_t)M * K < ((size_t)1 << 31);
   if (coded && !fused_decode &&
       launch_dequantize_blockwise(coded->codes, coded->absmax, (size_t)M * K, coded->block, X, st) != hipSuccess)
     return MMD8_E_HIP;

@@ -47,6 +47,7 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
 // One-pass preparation for inputs taller than the decode kernels take; prep_fits is false when K is too
 // large for a row to be held in the registers of one workgroup (the caller then uses scan + pack).
 bool prep_fits(int K);
+bool prep_from_codes_fits(int K);   // likewise for launch_prep with coded activations (a smaller bound)
 // coded: null, or the blockwise-coded form of the activations (X is then written, not read).
 hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
                        int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream);
