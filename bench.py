@@ -214,20 +214,55 @@ def main():
         # ---- the codec at the size of a shard-boundary hidden state [8192, 8192] (134 MB of fp16: HBM
         # traffic, buffers rotated so that nothing is served from the last-level cache)
         nb, big = 3, 8192 * 8192
-        xs = [torch.randn(big, device=dev, dtype=torch.float16) for _ in range(nb)]
+        gen4 = torch.Generator(device=dev)
+        gen4.manual_seed(4)
+
+        def student_t3(n):
+            # Student-t with 3 degrees of freedom drawn on the device: z / sqrt(chi2_3 / 3)
+            z = torch.randn(n, device=dev, generator=gen4)
+            c2 = torch.zeros(n, device=dev)
+            for _ in range(3):
+                c2 += torch.randn(n, device=dev, generator=gen4) ** 2
+            return z * torch.rsqrt(c2 / 3.0)
+
+        xs = []
+        for _ in range(nb):
+            t = student_t3(big).view(8192, 8192)
+            t[:, torch.randint(0, 8192, (4,), device=dev, generator=gen4)] *= 50.0     # 0.05 % of the feature dimensions
+            xs.append(t.clamp_(-65504.0, 65504.0).to(torch.float16).view(-1))
+            del t
         cs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(nb)]
-        am = [torch.empty(big // block, dtype=torch.float32, device=dev) for _ in range(nb)]
+        am = [torch.empty(big // 256, dtype=torch.float32, device=dev) for _ in range(nb)]
         big_bytes = 3.0 * big + 4.0 * big / block
         turn = [0]
+        blk = [block]
 
         def q_big():
             i = turn[0] = (turn[0] + 1) % nb
-            binding.quantize_blockwise(xs[i], block, codes=cs[i], absmax=am[i])
+            binding.quantize_blockwise(xs[i], blk[0], codes=cs[i], absmax=am[i])
 
         def d_big():
             i = turn[0] = (turn[0] + 1) % nb
-            binding.dequantize_blockwise(cs[i], am[i], block, out=xs[i])
+            binding.dequantize_blockwise(cs[i], am[i], blk[0], out=xs[i])
 
+        def round_trip():
+            q_big()
+            binding.dequantize_blockwise(cs[turn[0]], am[turn[0]], blk[0], out=xs[turn[0]])
+
+        by_block = {}
+        for b in (256, 1024, 4096):
+            blk[0] = b
+            for i in range(nb):                                   # codes and scales of this block size in every buffer
+                binding.quantize_blockwise(xs[i], b, codes=cs[i], absmax=am[i])
+            tq, td, trt = timed(q_big, 12), timed(d_big, 12), timed(round_trip, 12)
+            nbytes = 3.0 * big + 4.0 * big / b
+            by_block[str(b)] = {"quantize_gbs": round(nbytes / tq / 1e6, 1), "dequantize_gbs": round(nbytes / td / 1e6, 1),
+                                "round_trip_gbs": round(2.0 * nbytes / trt / 1e6, 1),
+                                "quantize_pct_hbm": round(100 * nbytes / tq / 1e6 / HBM_PEAK_GBS, 1),
+                                "dequantize_pct_hbm": round(100 * nbytes / td / 1e6 / HBM_PEAK_GBS, 1)}
+        blk[0] = block
+        for i in range(nb):
+            binding.quantize_blockwise(xs[i], block, codes=cs[i], absmax=am[i])
         qb_ms, db_ms = timed(q_big, 12), timed(d_big, 12)
         del xs, cs, am
 
@@ -352,7 +387,9 @@ def main():
             "quantize_pct_hbm": round(100 * big_bytes / qb_ms / 1e6 / HBM_PEAK_GBS, 1),
             "dequantize_pct_hbm": round(100 * big_bytes / db_ms / 1e6 / HBM_PEAK_GBS, 1),
             "elements": big, "block": block,
-            "note": "shard-boundary hidden state [8192,8192], rotating buffers (HBM traffic)"})
+            "by_block": by_block,
+            "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50), three buffer "
+                    "sets taking turns (HBM traffic); after the first pass the values are codec outputs"})
         out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
