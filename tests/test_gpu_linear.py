@@ -115,6 +115,18 @@ def test_largest_k(M):
     check_linear(X, wl.gaussian_weight(K, N, 0.02, rng), 6.0)
 
 
+def test_many_row_panels():
+    """20001 rows: 79 panels of 256 rows, the last one with a single row; several rounds of tiles per CU."""
+    M, K, N = 20001, 528, 264
+    rng = np.random.default_rng([M, K, N])
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, [5, 300]] *= 12.0
+    x[20000, 17] = 300.0                                            # a column made critical by the very last row only
+    X = wl.to_fp16(x)
+    assert ml.outlier_mask(X, 6.0)[17]
+    check_linear(X, wl.gaussian_weight(K, N, 0.02, rng), 6.0)
+
+
 def test_two_streams_with_their_own_workspaces():
     """Calls on different streams with different workspaces do not share state: interleaved on two streams they
     give what each gives alone."""
