@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per GEMM launch (mean over the five launches of a decoder layer) from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE, scaled by a plain copy of known size (profiles/gemm_llama7b_prefill_hbm_traffic.txt).  Valid
 # for the GEMM source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 201.0e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "08cc36363f5cb9198e14d9f1ccb3d957a8de8faf368f5ceba87a015f85610df8"
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 200.0e6
+GEMM_TRAFFIC_SOURCE_SHA256 = "00ec2bc882f6a1d9fb6b729500d94766de791bac95797455651f526c05c424f1"
 
 
 def parse():

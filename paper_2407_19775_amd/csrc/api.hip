@@ -59,6 +59,7 @@ static int check_linear_shape(int K, int N) {
 
 // Workspace layout.  The head (counters and the column flags, sized for the largest K so that
 // its place does not depend on the shape) is standing state: zero between calls.
+constexpr int kSkinnyChunkedMaxM = 2 * kSkinnyMaxM;   // most rows the decode kernels are used for (in passes of kSkinnyMaxM)
 constexpr size_t kHeadCounters = 256;
 constexpr size_t kHeadBytes = kHeadCounters + MMD8_MAX_K;
 struct Workspace {
@@ -98,10 +99,11 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0) {
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
   w.xf = nullptr;
   w.partial = nullptr;
-  if (M > 0 && M <= kSkinnyMaxM) {
+  if (M > 0 && M <= kSkinnyChunkedMaxM) {
+    const int Mc = M < kSkinnyMaxM ? M : kSkinnyMaxM;              // rows per pass of the decode kernels
     w.xf = reinterpret_cast<uint16_t*>(take((size_t)kSkinnyMaxM * Kpad * 2));
-    size_t pb = plan_skinny(M, K, N).partial_bytes;
-    if (r > 0 && pb == 0) pb = (size_t)M * N * sizeof(float);     // the low-rank term is added where the partial outputs are summed
+    size_t pb = plan_skinny(Mc, K, N).partial_bytes;
+    if (r > 0 && pb == 0) pb = (size_t)Mc * N * sizeof(float);     // the low-rank term is added where the partial outputs are summed
     if (pb) w.partial = reinterpret_cast<float*>(take(pb));
   }
   w.lora_t = r > 0 ? reinterpret_cast<uint16_t*>(take((size_t)M * kLoraMaxRank * 2)) : nullptr;
@@ -243,7 +245,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (!record(t.event_begin)) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
                            Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs};
-  const bool skinny = M <= kSkinnyMaxM;
+  // Up to 128 rows go through the decode kernels, 64 rows at a time (the weights are streamed twice for more
+  // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
+  // with heavy-tailed activations (hundreds of critical columns) it is ten times faster.
+  const bool skinny = M <= kSkinnyChunkedMaxM;
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K);
@@ -258,7 +263,8 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       return MMD8_E_HIP;
   } else {
     if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
-    if (launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, skinny ? ws.xf : nullptr, po, st) != hipSuccess)
+    // (the decode kernels' operands are packed 64 rows at a time, below)
+    if (!skinny && launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, nullptr, po, st) != hipSuccess)
       return MMD8_E_HIP;
   }
   if (t.row_absmax &&
@@ -284,32 +290,42 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     if (launch_lora_down(l, plan_lora(M, K), ws.lora_part, st) != hipSuccess) return MMD8_E_HIP;
   }
 
-  if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
   if (skinny) {
-    SkinnyArgs g = {};
-    g.Xq = ws.xq;
-    g.Wt = Wq_packed;
-    g.Xf = ws.xf;
-    g.mask = ws.mask;
-    g.M = M;
-    g.N = N;
-    g.Kpad = Kpad;
-    g.r = ws.r;
-    g.c = col_absmax;
-    g.bias = bias;
-    g.Y = Y;
-    g.ldy = ldy;
-    g.partial = ws.partial;
-    g.tap_acc = t.acc;
-    g.flag_reset = ws.flag;
-    if (lora) {
-      g.lora_T = ws.lora_t;
-      g.lora_ldt = kLoraMaxRank;
-      g.lora_B = lora->B;
-      g.lora_r = lora->r;
+    const SkinnyPlan plan = plan_skinny(M < kSkinnyMaxM ? M : kSkinnyMaxM, K, N);
+    for (int row0 = 0; row0 < M; row0 += kSkinnyMaxM) {
+      const int Mc = M - row0 < kSkinnyMaxM ? M - row0 : kSkinnyMaxM;
+      // codes and the fp16 copy of these rows, masked with the flags of all M rows; the list of critical columns is
+      // published again with every pass (the same list)
+      if (launch_pack(X + (size_t)row0 * ldx, Mc, K, ldx, ws.flag, ws.r + row0, ws.xq, Kpad,
+                      t.xq ? t.xq + (size_t)row0 * K : nullptr, ws.xf, po, st) != hipSuccess)
+        return MMD8_E_HIP;
+      if (row0 == 0 && !record(t.event_gemm_begin)) return MMD8_E_HIP;
+      SkinnyArgs g = {};
+      g.Xq = ws.xq;
+      g.Wt = Wq_packed;
+      g.Xf = ws.xf;
+      g.mask = ws.mask;
+      g.M = Mc;
+      g.N = N;
+      g.Kpad = Kpad;
+      g.r = ws.r + row0;
+      g.c = col_absmax;
+      g.bias = bias;
+      g.Y = Y + (size_t)row0 * ldy;
+      g.ldy = ldy;
+      g.partial = ws.partial;
+      g.tap_acc = t.acc ? t.acc + (size_t)row0 * N : nullptr;
+      g.flag_reset = row0 + kSkinnyMaxM >= M ? ws.flag : nullptr;   // the last pass zeroes the column flags again
+      if (lora) {
+        g.lora_T = ws.lora_t + (size_t)row0 * kLoraMaxRank;
+        g.lora_ldt = kLoraMaxRank;
+        g.lora_B = lora->B;
+        g.lora_r = lora->r;
+      }
+      if (launch_gemm_skinny(g, plan, st) != hipSuccess) return MMD8_E_HIP;
     }
-    if (launch_gemm_skinny(g, plan_skinny(M, K, N), st) != hipSuccess) return MMD8_E_HIP;
   } else {
+    if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
     GemmArgs g;
     g.Xq = ws.xq;
     g.Wt = Wq_packed;

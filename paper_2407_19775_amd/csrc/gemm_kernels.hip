@@ -146,30 +146,55 @@ __device__ inline void dequantize_in_place(const WavePos<Cfg>& p, v16i (&acc)[Cf
 
 // Critical columns j_begin .. n_out-1, 16 at a time: every thread helps to stage X[m, O_j] (fp16)
 // and f16(Wt[n, O_j] c[n] / 127) for the whole tile in LDS as [row][16] fp16, then one 32x32x16
-// fp16 MFMA per output tile.  Slow (gathers) and general; the slab buffers must be free.
+// fp16 MFMA per output tile.  General (any number of columns); the slab buffers must be free.
+// A thread owns one of the 16 columns and every (kThreads / 16)-th row; all its gathers of a step are
+// issued together (clamped addresses, results masked), so a step costs a few memory latencies, not one
+// per element.
 template <class Cfg>
 __device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                               int8_t* smem, int j_begin, int n_out) {
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ, TILE_M = Cfg::BM, TILE_N = Cfg::BN;
+  constexpr int RSTEP = Cfg::kThreads / 16;                        // rows between a thread's items
+  constexpr int NX = TILE_M / RSTEP, NW = TILE_N / RSTEP;          // its rows of X, then of Wt
+  static_assert(TILE_M % RSTEP == 0 && TILE_N % RSTEP == 0, "whole rows per thread");
   uint16_t* sXo = reinterpret_cast<uint16_t*>(smem);             // [TILE_M][16], then [TILE_N][16]
   uint16_t* sWo = sXo + TILE_M * 16;
+  const int kk = threadIdx.x & 15, r0 = threadIdx.x >> 4;
+  const int n_slabs = a.Kpad / BK;
   __syncthreads();                                               // every wave is done with the slab ring
   for (int j0 = j_begin; j0 < n_out; j0 += 16) {
-    for (int t = threadIdx.x; t < (TILE_M + TILE_N) * 16; t += Cfg::kThreads) {
-      const int row = t >> 4, kk = t & 15;
-      const int k = (j0 + kk < n_out) ? a.idx[j0 + kk] : -1;
-      uint16_t v = 0;
-      if (row < TILE_M) {
-        const int m = p.m0 + row;
-        if (k >= 0 && m < a.M) v = a.X[(size_t)m * a.ldx + k];
-      } else {
-        const int n = p.n0 + row - TILE_M;
-        if (k >= 0 && n < a.N) {
-          const float step = a.c[n] / 127.0f;
-          v = (uint16_t)rounded_float_to_half_bits((float)a.Wt[packed_offset(n, k, a.Kpad / BK)] * step);
-        }
+    const bool col_ok = j0 + kk < n_out;
+    const int k = col_ok ? a.idx[j0 + kk] : 0;
+    // eight rows at a time: enough loads in flight, few registers next to the accumulators
+    constexpr int BX = NX < 8 ? NX : 8, BW = NW < 8 ? NW : 8;
+    static_assert(NX % BX == 0 && NW % BW == 0, "whole batches");
+#pragma unroll 1
+    for (int ib = 0; ib < NX; ib += BX) {
+      uint16_t xv[BX];
+#pragma unroll
+      for (int i = 0; i < BX; ++i) xv[i] = a.X[(size_t)min(p.m0 + r0 + (ib + i) * RSTEP, a.M - 1) * a.ldx + k];
+#pragma unroll
+      for (int i = 0; i < BX; ++i) {
+        const int row = r0 + (ib + i) * RSTEP;
+        sXo[row * 16 + kk] = (col_ok && p.m0 + row < a.M) ? xv[i] : (uint16_t)0;
       }
-      sXo[t] = v;
+    }
+#pragma unroll 1
+    for (int ib = 0; ib < NW; ib += BW) {
+      int8_t wq[BW];
+      float wc[BW];
+#pragma unroll
+      for (int i = 0; i < BW; ++i) {
+        const int n = min(p.n0 + r0 + (ib + i) * RSTEP, a.N - 1);
+        wq[i] = a.Wt[packed_offset(n, k, n_slabs)];
+        wc[i] = a.c[n];
+      }
+#pragma unroll
+      for (int i = 0; i < BW; ++i) {
+        const int row = r0 + (ib + i) * RSTEP;
+        const uint16_t v = (uint16_t)rounded_float_to_half_bits((float)wq[i] * (wc[i] / 127.0f));
+        sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? v : (uint16_t)0;
+      }
     }
     __syncthreads();
     v8h fxa[TI], fxb[TJ];
@@ -692,7 +717,7 @@ static hipError_t launch_variant(const GemmArgs& a, int variant, hipStream_t str
     case 5: return launch_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>(a, stream);
     case 6: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>(a, stream);
     case 7: return launch_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>(a, stream);
-    default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 2>, false>(a, stream);
+    default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 3>, false>(a, stream);   // 49 KB of LDS: three workgroups per CU
   }
 }
 
