@@ -138,7 +138,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
  *     Y = mixed_int8_linear(X, ...)
  * with every value identical to the two calls made one after the other.  X_decoded (DEVICE [M*K],
  * 16-byte aligned) receives X, which the caller usually needs as well (residual connection).  For more
- * than 64 rows and K <= 16384 the decoding happens inside the preparation kernel of the layer: the
+ * than 128 rows and K <= 16384 the decoding happens inside the preparation kernel of the layer: the
  * hidden state is read once, as codes.  Requirements: those of both calls (block a multiple of 64 in
  * [64, 4096]; codes 16-byte aligned; K % 16 == 0; ...). */
 int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, const float* absmax /*DEVICE [ceil(M*K/block)]*/,

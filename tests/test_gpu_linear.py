@@ -257,7 +257,7 @@ def test_one_workspace_serves_calls_of_different_shapes():
                                          (70, 16384, 40, 1024), (70, 16448, 40, 64)])
 def test_layer_on_blockwise_coded_activations(M, K, N, block):
     """The layer fed with a coded hidden state: identical, bit for bit, to decoding first and
-    calling the layer on the result (for more than 64 rows the decoding happens inside the
+    calling the layer on the result (for more than 128 rows the decoding happens inside the
     preparation kernel), and equal to the oracle's two steps."""
     from oracle import blockwise_codec as bc
     rng = np.random.default_rng([M, K, N, block])
