@@ -254,7 +254,7 @@ def test_one_workspace_serves_calls_of_different_shapes():
 
 
 @pytest.mark.parametrize("M,K,N,block", [(300, 1040, 264, 64), (2048, 4096, 512, 1024), (40, 512, 72, 256), (130, 272, 40, 4096),
-                                         (70, 16384, 40, 1024), (70, 16448, 40, 64)])
+                                         (130, 16384, 40, 1024), (130, 16448, 40, 64), (100, 528, 72, 256)])
 def test_layer_on_blockwise_coded_activations(M, K, N, block):
     """The layer fed with a coded hidden state: identical, bit for bit, to decoding first and
     calling the layer on the result (for more than 128 rows the decoding happens inside the
