@@ -149,6 +149,30 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, con
                                       void* workspace /*DEVICE*/, size_t workspace_bytes,
                                       const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* The same layer with its result leaving in blockwise-coded form (the hidden state a shard hands to its
+ * successor: "Compression techniques", item 2 feeding item 1):
+ *     Y = mixed_int8_linear(X, ...)                           fp16, as above
+ *     H[m,n] = f16( Y[m,n] + residual[m,n] )                  fp16 addition; H = Y when residual is NULL
+ *     (codes, absmax) = quantize_blockwise(H as M*N contiguous elements, row after row, block)
+ * with every value identical to those steps made one after the other.  residual: NULL, or DEVICE [M][ldr]
+ * fp16 (the residual stream the layer's output is added to), 16-byte aligned, ldr >= N, ldr % 8 == 0.
+ * codes: DEVICE [M*N], 16-byte aligned; absmax: DEVICE [ceil(M*N/block)].  H: NULL, or DEVICE [M*N] fp16
+ * (contiguous, 16-byte aligned) that receives the encoded tensor itself.  The layer's last kernel does the
+ * encoding where no block is shared between its workgroups: up to 64 rows always, up to 128 rows when
+ * 64*N % block == 0, more rows when block is 64, 128 or 256 and divides N; otherwise the encoder runs after
+ * the layer.  Requirements: those of mmd8_mixed_int8_linear and of mmd8_quantize_blockwise; workspace of at
+ * least mmd8_linear_to_codes_workspace_bytes(M, K, N, block) bytes, set up and reused like any other
+ * workspace of the layer.  Errors as for the two calls; nothing is launched when one is returned. */
+size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block);
+int mmd8_mixed_int8_linear_to_codes(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                    const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                    const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                    const mmd8_half* residual /*DEVICE [M][ldr] or NULL*/, int ldr, int block,
+                                    uint8_t* codes /*DEVICE [M*N], written*/, float* absmax /*DEVICE, written*/,
+                                    mmd8_half* H /*DEVICE [M*N] or NULL, written*/,
+                                    void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                    const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* The layer with a low-rank adapter ("BSNS with parameter-efficient fine-tuning via adapters":
  * W' = W + B A with A in R^{r x n}, B in R^{n x r}, r << n), the base weight staying in its 8-bit form:
  *     T[m,j] = f16( sum_k X[m,k] * A[j,k] )                      (fp32 accumulation, one rounding)

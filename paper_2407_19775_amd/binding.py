@@ -19,7 +19,7 @@ EXPORTS = (
     "mmd8_code_midpoints", "mmd8_packed_weight_layout", "mmd8_packed_weight_bytes", "mmd8_prequantize_weight",
     "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
     "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
-    "mmd8_mixed_int8_linear_lora",
+    "mmd8_mixed_int8_linear_lora", "mmd8_linear_to_codes_workspace_bytes", "mmd8_mixed_int8_linear_to_codes",
 )
 
 
@@ -62,6 +62,10 @@ def lib():
         L.mmd8_linear_lora_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.mmd8_mixed_int8_linear_lora.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, sz,
                                                   ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_linear_to_codes_workspace_bytes.restype = sz
+        L.mmd8_linear_to_codes_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.mmd8_mixed_int8_linear_to_codes.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, i32, vp, vp, vp, vp, sz,
+                                                      ctypes.POINTER(DebugTaps), vp]
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
         L.mmd8_set_gemm_variant.argtypes = [i32]
@@ -148,16 +152,71 @@ def unpack_weight(pw: PackedWeight) -> torch.Tensor:
     return out
 
 
-def linear_workspace(M: int, K: int, N: int, device, lora_rank: int = 0) -> torch.Tensor:
+def linear_workspace(M: int, K: int, N: int, device, lora_rank: int = 0, exit_block: int = 0) -> torch.Tensor:
     """Allocates and sets up a workspace large enough for one [M,K] x [K,N] call (with an adapter of
-    rank lora_rank, if not 0)."""
+    rank lora_rank, if not 0; for an output leaving in coded form with blocks of exit_block, if not 0)."""
+    if lora_rank and exit_block:
+        raise Mmd8Error("an adapter and a coded output cannot be combined in one call")
     nbytes = (lib().mmd8_linear_lora_workspace_bytes(M, K, N, lora_rank) if lora_rank
+              else lib().mmd8_linear_to_codes_workspace_bytes(M, K, N, exit_block) if exit_block
               else lib().mmd8_linear_workspace_bytes(M, K, N))
     if nbytes == 0:
         _check(-2)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
     _check(lib().mmd8_linear_workspace_init(ws.data_ptr(), ws.numel(), _stream()))
     return ws
+
+
+def _taps(M, K, N, dev):
+    return dict(
+        outlier_mask=torch.zeros(K, dtype=torch.uint8, device=dev),
+        row_absmax=torch.zeros(M, dtype=torch.float32, device=dev),
+        xq=torch.zeros((M, K), dtype=torch.int8, device=dev),
+        acc=torch.zeros((M, N), dtype=torch.int32, device=dev),
+        n_outliers=torch.zeros(1, dtype=torch.int32, device=dev),
+        outlier_idx=torch.zeros(K, dtype=torch.int32, device=dev),
+    )
+
+
+def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, block: int, bias: torch.Tensor = None,
+                               residual: torch.Tensor = None, codes: torch.Tensor = None, absmax: torch.Tensor = None,
+                               H: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False):
+    """The layer with its result leaving blockwise-coded: H = Y (+ residual, an fp16 addition), flattened row by
+    row and encoded with blocks of `block` elements.  Returns (codes [M N] uint8, absmax float32); H, if given
+    (contiguous [M, N] fp16), receives the encoded tensor itself.  With taps=True the intermediates of the layer
+    come back as a third value."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    if K != pw.K or X.stride(1) != 1:
+        raise Mmd8Error("X must be [M, %d] with unit stride along K" % pw.K)
+    N = pw.N
+    n = M * N
+    if codes is None:
+        codes = torch.empty(n, dtype=torch.uint8, device=X.device)
+    if absmax is None:
+        absmax = torch.empty((n + block - 1) // max(block, 1), dtype=torch.float32, device=X.device)
+    _dev(codes, torch.uint8, "codes")
+    _dev(absmax, torch.float32, "absmax")
+    if codes.numel() < n or absmax.numel() < (n + block - 1) // max(block, 1):
+        raise Mmd8Error("codes / absmax too small")
+    if residual is not None:
+        _dev(residual, torch.float16, "residual")
+        if residual.shape != (M, N) or residual.stride(1) != 1:
+            raise Mmd8Error("residual must be [M, N] with unit stride along N")
+    if H is not None and not (H.is_cuda and H.dtype == torch.float16 and H.shape == (M, N) and H.is_contiguous()):
+        raise Mmd8Error("H must be a contiguous GPU fp16 tensor [M, N]")
+    if workspace is None:
+        workspace = linear_workspace(M, K, N, X.device, exit_block=block)
+    tensors = _taps(M, K, N, X.device) if taps else None
+    tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()}) if taps else None
+    _check(lib().mmd8_mixed_int8_linear_to_codes(
+        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+        bias.data_ptr() if bias is not None else None, float(tau),
+        residual.data_ptr() if residual is not None else None,
+        residual.stride(0) if residual is not None and M > 0 else N, int(block), codes.data_ptr(), absmax.data_ptr(),
+        H.data_ptr() if H is not None else None, workspace.data_ptr(), workspace.numel(),
+        ctypes.byref(tp) if tp is not None else None, _stream()))
+    return (codes, absmax, tensors) if taps else (codes, absmax)
 
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
@@ -185,15 +244,7 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     if events is not None:                      # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
         tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
     if taps:
-        dev = X.device
-        tensors = dict(
-            outlier_mask=torch.zeros(K, dtype=torch.uint8, device=dev),
-            row_absmax=torch.zeros(M, dtype=torch.float32, device=dev),
-            xq=torch.zeros((M, K), dtype=torch.int8, device=dev),
-            acc=torch.zeros((M, N), dtype=torch.int32, device=dev),
-            n_outliers=torch.zeros(1, dtype=torch.int32, device=dev),
-            outlier_idx=torch.zeros(K, dtype=torch.int32, device=dev),
-        )
+        tensors = _taps(M, K, N, X.device)
         tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
     if coded is not None:
         codes, absmax, block = coded

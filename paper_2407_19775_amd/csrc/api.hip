@@ -76,9 +76,12 @@ struct Workspace {
   int8_t* xq;          // Mpad x Kpad codes, blocked layout
   uint16_t* xf;        // decode path only: [64][Kpad] fp16
   float* partial;      // decode path only: split-K partial outputs
+  uint16_t* h;         // coded output only, where the encoder runs as a kernel of its own: [M][N] fp16
   size_t bytes;
 };
-static Workspace carve(void* base, int M, int K, int N, int r = 0) {
+// r: rank of an adapter (0: none).  exit_block: block size of a coded output (0: plain output).
+static bool exit_fuses(int M, int N, int block);
+static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_block = 0) {
   const size_t Kpad = packed_k(K), Mpad = packed_n(M), Npad = packed_n(N);
   Workspace w;
   size_t off = 0;
@@ -103,7 +106,8 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0) {
     const int Mc = M < kSkinnyMaxM ? M : kSkinnyMaxM;              // rows per pass of the decode kernels
     w.xf = reinterpret_cast<uint16_t*>(take((size_t)kSkinnyMaxM * Kpad * 2));
     size_t pb = plan_skinny(Mc, K, N).partial_bytes;
-    if (r > 0 && pb == 0) pb = (size_t)Mc * N * sizeof(float);     // the low-rank term is added where the partial outputs are summed
+    // the low-rank term is added, and a coded output is encoded, where the partial outputs are summed
+    if ((r > 0 || exit_block > 0) && pb == 0) pb = (size_t)Mc * N * sizeof(float);
     if (pb) w.partial = reinterpret_cast<float*>(take(pb));
   }
   w.lora_t = r > 0 ? reinterpret_cast<uint16_t*>(take((size_t)M * kLoraMaxRank * 2)) : nullptr;
@@ -112,8 +116,17 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0) {
     const size_t lb = plan_lora(M, K).partial_bytes;
     if (lb) w.lora_part = reinterpret_cast<float*>(take(lb));
   }
+  w.h = nullptr;
+  if (exit_block > 0 && M > 0 && !exit_fuses(M, N, exit_block)) w.h = reinterpret_cast<uint16_t*>(take((size_t)M * N * 2));
   w.bytes = off;
   return w;
+}
+// A coded output is produced by the kernel that ends the layer when no block of it is shared between
+// workgroups: the tiled GEMM needs blocks inside its 256-column tiles; the decode path encodes where it sums
+// its partial outputs, any block size, as long as its second pass of 64 rows starts on a block boundary.
+static bool exit_fuses(int M, int N, int block) {
+  if (M <= kSkinnyChunkedMaxM) return M <= kSkinnyMaxM || ((size_t)kSkinnyMaxM * N) % block == 0;
+  return (block == 64 || block == 128 || block == 256) && N % block == 0;
 }
 
 static int g_gemm_variant = -1;
@@ -205,6 +218,14 @@ int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* st
              : MMD8_E_HIP;
 }
 
+struct CodedExit {   // the output leaving in blockwise-coded form, with an optional residual added first
+  const mmd8_half* residual;   // [M][ldr] or null
+  int ldr;
+  int block;
+  uint8_t* codes;              // [M N]
+  float* absmax;               // [ceil(M N / block)]
+};
+
 struct Adapter {   // low-rank factors of W' = W + B A
   const mmd8_half* A;   // [r][K]
   const mmd8_half* B;   // [N][r]
@@ -215,15 +236,21 @@ struct Adapter {   // low-rank factors of W' = W + B A
 // The layer.  coded: null, or the blockwise-coded form of the activations, in which case X is the
 // buffer that receives the decoded activations (ldx == K) before the layer reads them.
 // lora: null, or the adapter whose term is added to the output.
+// exit: null, or where the coded form of the output goes; Y (contiguous, ldy == N) then receives the tensor that
+// is encoded and may be null.
 static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, const float* col_absmax, int N,
                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
-                      const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, void* stream) {
+                      const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, const CodedExit* exit,
+                      void* stream) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
   if (M == 0) return MMD8_OK;
-  if (!X || !Wq_packed || !col_absmax || !Y || !workspace) return MMD8_E_ARG;
+  if (!X || !Wq_packed || !col_absmax || (!Y && !exit) || !workspace) return MMD8_E_ARG;
   if (ldx < K || ldy < N || (ldx % 8) != 0 || (ldy % 8) != 0) return MMD8_E_ARG;
+  if (exit && (!exit->codes || !exit->absmax || !aligned(exit->codes, 16) || !aligned(exit->absmax, 4) || ldy != N ||
+               (exit->residual && (exit->ldr < N || (exit->ldr % 8) != 0 || !aligned(exit->residual, 16)))))
+    return MMD8_E_ARG;
   if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(Wq_packed, 256) || !aligned(workspace, 256) ||
       !aligned(col_absmax, 4) || (bias && !aligned(bias, 2)))
     return MMD8_E_ARG;
@@ -231,8 +258,11 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (lora && (!lora->A || !lora->B || !aligned(lora->A, 16) || !aligned(lora->B, 16) ||
                (lora->T_out && !aligned(lora->T_out, 16))))
     return MMD8_E_ARG;
-  const Workspace ws = carve(workspace, M, K, N, lora ? lora->r : 0);
+  const Workspace ws = carve(workspace, M, K, N, lora ? lora->r : 0, exit ? exit->block : 0);
   if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
+  // a coded output is written by the layer's last kernel where that is possible, otherwise by the encoder after it
+  const bool exit_fused = exit && exit_fuses(M, N, exit->block);
+  if (exit && !exit_fused && !Y) Y = ws.h;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int Kpad = packed_k(K);
@@ -311,8 +341,17 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       g.r = ws.r + row0;
       g.c = col_absmax;
       g.bias = bias;
-      g.Y = Y + (size_t)row0 * ldy;
+      g.Y = Y ? Y + (size_t)row0 * ldy : nullptr;
       g.ldy = ldy;
+      if (exit) {
+        g.residual = exit->residual ? exit->residual + (size_t)row0 * exit->ldr : nullptr;
+        g.ldr = exit->ldr;
+        if (exit_fused) {
+          g.codes = exit->codes + (size_t)row0 * N;
+          g.code_absmax = exit->absmax + (size_t)row0 * N / exit->block;
+          g.code_block = exit->block;
+        }
+      }
       g.partial = ws.partial;
       g.tap_acc = t.acc ? t.acc + (size_t)row0 * N : nullptr;
       g.flag_reset = row0 + kSkinnyMaxM >= M ? ws.flag : nullptr;   // the last pass zeroes the column flags again
@@ -326,7 +365,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     }
   } else {
     if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
-    GemmArgs g;
+    GemmArgs g = {};
     g.Xq = ws.xq;
     g.Wt = Wq_packed;
     g.M = M;
@@ -348,8 +387,21 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.tap_ld = N;
     g.tiles_m = g.tiles_n = 0;
     g.flag_reset = ws.flag;
+    if (exit) {
+      g.residual = exit->residual;
+      g.ldr = exit->ldr;
+      if (exit_fused) {
+        g.codes = exit->codes;
+        g.code_absmax = exit->absmax;
+        g.code_ld = N;
+        g.code_log_block = exit->block == 64 ? 6 : exit->block == 128 ? 7 : 8;
+      }
+    }
     if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
   }
+  if (exit && !exit_fused &&
+      launch_quantize_blockwise(Y, (size_t)M * N, exit->block, exit->codes, exit->absmax, st) != hipSuccess)
+    return MMD8_E_HIP;
   if (!record(t.event_gemm_end)) return MMD8_E_HIP;
   return MMD8_OK;
 }
@@ -359,7 +411,23 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
                            void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   // X is only read on this path
   return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
-                    workspace_bytes, taps, nullptr, nullptr, stream);
+                    workspace_bytes, taps, nullptr, nullptr, nullptr, stream);
+}
+
+size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block) {
+  if (M < 0 || check_linear_shape(K, N) != MMD8_OK || check_block(block) != MMD8_OK) return 0;
+  return carve(nullptr, M, K, N, 0, block).bytes;
+}
+
+int mmd8_mixed_int8_linear_to_codes(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                                    const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                    const mmd8_half* residual, int ldr, int block, uint8_t* codes, float* absmax,
+                                    mmd8_half* H, void* workspace, size_t workspace_bytes,
+                                    const mmd8_debug_taps* taps, void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  const CodedExit exit = {residual, ldr, block, codes, absmax};
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, H, N, workspace,
+                    workspace_bytes, taps, nullptr, nullptr, &exit, stream);
 }
 
 int mmd8_mixed_int8_linear_lora(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
@@ -370,7 +438,7 @@ int mmd8_mixed_int8_linear_lora(const mmd8_half* X, int M, int K, int ldx, const
   if (check_lora_rank(r) != MMD8_OK) return MMD8_E_SHAPE;
   const Adapter lora = {lora_A, lora_B, r, lora_T};
   return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
-                    workspace_bytes, taps, nullptr, &lora, stream);
+                    workspace_bytes, taps, nullptr, &lora, nullptr, stream);
 }
 
 int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax, int block, int M, int K,
@@ -381,7 +449,7 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax,
   if (M > 0 && (!codes || !absmax || !aligned(codes, 16) || !aligned(absmax, 4))) return MMD8_E_ARG;
   const CodedInput coded = {codes, absmax, block};
   return run_linear(X_decoded, M, K, K, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace, workspace_bytes, taps,
-                    &coded, nullptr, stream);
+                    &coded, nullptr, nullptr, stream);
 }
 
 uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau); }

@@ -23,8 +23,17 @@ struct GemmArgs {
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   int f_slabs;           // fp16 slabs per panel in Xo / Wo: 1, or 1 + those of a low-rank adapter (at most 3), whose
                          // operands follow the critical columns and are multiplied in the same way
-  uint16_t* Y;
+  uint16_t* Y;           // may be null when `codes` is given (only the coded form of the output is wanted)
   int ldy;
+  // The output leaving in coded form (the shard's last linear): H = Y, or f16(Y + residual) when a residual is
+  // given; H is what Y receives and what is encoded blockwise, the blocks running over the flattened [M][code_ld]
+  // tensor.  Blocks of 64, 128 or 256 elements that divide N and the tile width, so that no block leaves a tile.
+  const uint16_t* residual;   // [M][ldr] fp16 or null
+  int ldr;
+  uint8_t* codes;        // [M][code_ld] or null
+  float* code_absmax;    // [M code_ld / block]
+  int code_ld;           // elements per row of the coded tensor
+  int code_log_block;    // 6, 7 or 8
   int32_t* tap_acc;      // [M][tap_ld] or null
   int tap_ld;
   int tiles_m, tiles_n;

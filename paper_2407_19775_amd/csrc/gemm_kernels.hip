@@ -21,11 +21,15 @@
 //                    phase and an MFMA phase, so the matrix pipe always has a wave feeding it
 #include <type_traits>
 
+#include "codec_device.h"
 #include "common.h"
 #include "gemm.h"
 #include "operand_layout.h"
 
 namespace mmd8 {
+
+// the code table of the blockwise encoder, for outputs that leave in coded form
+__device__ const DynamicCode kExitCode = make_dynamic_code();
 
 constexpr int BK = 64;                  // bytes of K per slab
 constexpr int CPR = BK / 16;            // 16-byte chunks per LDS row
@@ -312,6 +316,106 @@ __device__ inline void store_tile(const GemmArgs& a, const WavePos<Cfg>& p, v16i
   }
 }
 
+// The same, for an output that leaves in coded form ("Compression techniques", item 1 applied to the result of
+// item 2): H = f16(Y + residual) (or Y), written where wanted, and its blockwise 8-bit codes.  Rows are parked
+// as in store_tile.  Phase A (each wave on its own rows): add the residual in place, store H.  After a barrier,
+// phase B: a lane takes 16 neighbouring columns of one row of the workgroup tile, whichever wave parked them,
+// so that the lanes of a block are neighbours (4, 8 or 16 of them: the block maximum is a few DPP steps) and a
+// wave instruction writes whole 256-byte (128-byte) rows of codes.
+template <class Cfg, bool kFull>
+__device__ inline void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+                                        const float (&bn)[Cfg::TJ], int8_t* smem, int wave) {
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
+  constexpr int STRIDE = Cfg::WN * 2 + 16;
+  constexpr int CELL_BYTES = DynamicCode::kCells * 8;
+  constexpr int IP = (TI >= 2 && Cfg::kWaves * 64 * STRIDE + CELL_BYTES <= Cfg::RING_BYTES) ? 2 : 1;
+  constexpr int RP = 32 * IP;
+  constexpr int CH = Cfg::WN / 8;
+  constexpr int PARK_BYTES = Cfg::kWaves * RP * STRIDE;
+  static_assert(PARK_BYTES + CELL_BYTES <= Cfg::RING_BYTES, "output staging and the code table must fit in the slab buffers");
+  static_assert((RP * CH) % kWave == 0, "whole store instructions");
+  constexpr int LPR = Cfg::BN / 16;                                  // lanes per row of the workgroup tile in phase B
+  constexpr int TASKS = Cfg::WAVES_M * RP * LPR;
+  static_assert(TASKS % Cfg::kThreads == 0 && (LPR == 8 || LPR == 16), "phase B covers the parked rows in whole rounds");
+  int8_t* base = smem + wave * (RP * STRIDE);
+  v2u* s_cells = reinterpret_cast<v2u*>(smem + PARK_BYTES);
+  const int odd = p.lane & 1;
+  const int lb = a.code_log_block;
+  __syncthreads();                                                  // every wave is done with the slab buffers
+  if (a.codes) stage_code_cells(s_cells, kExitCode, threadIdx.x, Cfg::kThreads);
+  const uint32_t cells_biased = biased_cell_base(s_cells);
+#pragma unroll
+  for (int i0 = 0; i0 < TI; i0 += IP) {
+#pragma unroll
+    for (int ii = 0; ii < IP; ++ii) {
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) {
+        const v16f y = __builtin_bit_cast(v16f, acc[i0 + ii][j]);
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          const uint32_t h = float_to_half_bits(y[e] + bn[j]) | (float_to_half_bits(y[e + 1] + bn[j]) << 16);
+          const uint32_t q = (uint32_t)__builtin_amdgcn_mov_dpp((int)h, 0xb1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+          const uint32_t out = odd ? ((q >> 16) | (h & 0xffff0000u)) : ((h & 0xffffu) | (q << 16));
+          const int row = ii * 32 + 8 * (e / 4) + (e % 4) + 4 * p.lg + odd;
+          *reinterpret_cast<uint32_t*>(base + row * STRIDE + (j * 32 + (p.lr & ~1)) * 2) = out;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // ---- phase A
+    if (a.residual || a.Y) {
+#pragma unroll
+      for (int it = 0; it < RP * CH / kWave; ++it) {
+        const int idx = it * kWave + p.lane, row = idx / CH, ch = idx % CH;
+        int8_t* cell = base + row * STRIDE + ch * 16;
+        v4u v = *reinterpret_cast<const v4u*>(cell);
+        const int gm = p.mw + i0 * 32 + row, gn = p.nw + ch * 8;
+        bool ok = true;
+        if constexpr (!kFull) ok = gm < a.M && gn < a.N;
+        if (a.residual) {
+          v4u res = v4u{0, 0, 0, 0};
+          if (ok) res = *reinterpret_cast<const v4u*>(a.residual + (size_t)gm * a.ldr + gn);
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            v[w] = float_to_half_bits(half_lo_to_float(v[w]) + half_lo_to_float(res[w])) |
+                   (float_to_half_bits(half_hi_to_float(v[w]) + half_hi_to_float(res[w])) << 16);
+          *reinterpret_cast<v4u*>(cell) = v;
+        }
+        if (a.Y && ok) *reinterpret_cast<v4u*>(a.Y + (size_t)gm * a.ldy + gn) = v;
+      }
+    }
+    __syncthreads();                                                // the parked rows of every wave are final
+    // ---- phase B
+    if (a.codes) {
+#pragma unroll
+      for (int q = 0; q < TASKS / Cfg::kThreads; ++q) {
+        const int t = q * Cfg::kThreads + threadIdx.x;
+        const int col = (t % LPR) * 16, rowp = t / LPR, wm2 = rowp / RP, row = rowp % RP;
+        const int8_t* src = smem + (wm2 * Cfg::WAVES_N + col / Cfg::WN) * (RP * STRIDE) + row * STRIDE + (col % Cfg::WN) * 2;
+        const v4u h0 = *reinterpret_cast<const v4u*>(src), h1 = *reinterpret_cast<const v4u*>(src + 16);
+        uint32_t m = max(chunk_absmax_pattern(h0), chunk_absmax_pattern(h1));
+        m = dpp_max<0xB1>(m);                                       // 2 lanes
+        m = dpp_max<0x4E>(m);                                       // 4 lanes: 64 elements
+        if (lb >= 7) m = dpp_max<0x141>(m);                         // 8 lanes
+        if (lb >= 8) m = dpp_max<0x140>(m);                         // 16 lanes
+        const int gm = p.m0 + wm2 * Cfg::WM + i0 * 32 + row, gn = p.n0 + col;
+        bool ok = true;
+        if constexpr (!kFull) ok = gm < a.M && gn < a.N;
+        const float am = half_lo_to_float(m);
+        const float inv = (am == 0.0f) ? 0.0f : 1.0f / am;          // IEEE division
+        if (ok) {
+          const size_t e = (size_t)gm * a.code_ld + gn;
+          if ((gn & ((1 << lb) - 1)) == 0) a.code_absmax[e >> lb] = am;
+          const v2u c0 = encode_chunk(h0, inv, cells_biased), c1 = encode_chunk(h1, inv, cells_biased);
+          *reinterpret_cast<v4u*>(a.codes + e) = v4u{c0[0], c0[1], c1[0], c1[1]};
+        }
+      }
+    }
+    __syncthreads();                                                // the next pass parks over these rows
+  }
+}
+
 template <class Cfg>
 __device__ inline void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& p, float (&cs)[Cfg::TJ],
                                          float (&bn)[Cfg::TJ]) {
@@ -327,8 +431,9 @@ __device__ inline void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& 
 // Generic kernel: 4 waves, one wave per SIMD or two workgroups per CU, small tiles.
 // kFull: M and N are multiples of the tile, so no output store needs a bounds check.
 // kTap: also write the raw int32 accumulators (parity checks).
+// kCoded: the output takes a residual and / or leaves in blockwise-coded form (store_tile_coded).
 // ------------------------------------------------------------------------------------------------
-template <class Cfg, bool kTap, bool kFull>
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages;
@@ -496,7 +601,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   // free for the gather staging, which starts with a barrier of its own before writing them
   if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
   if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
-  store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
+  if constexpr (kCoded)
+    store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
+  else
+    store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -520,7 +628,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
 // fragment reads, fp16 MFMAs onto the already dequantized accumulators.  The row scales of the
 // tile are brought into LDS by one extra request at the very start.
 // ------------------------------------------------------------------------------------------------
-template <class Cfg, bool kTap, bool kFull>
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_pingpong(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages, AHEAD = Cfg::kAhead;
@@ -672,20 +780,23 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
 
   if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
   if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
-  store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
+  if constexpr (kCoded)
+    store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
+  else
+    store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
 }
 
 // ------------------------------------------------------------------------------------------------
-template <class Cfg, bool kTap, bool kFull, bool kPingPong>
+template <class Cfg, bool kTap, bool kFull, bool kPingPong, bool kCoded>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
   static bool attr_set[64] = {};                                   // per device: the attribute belongs to the device's code object
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   const void* fn;
   if constexpr (kPingPong)
-    fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull>);
+    fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull, kCoded>);
   else
-    fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull>);
+    fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull, kCoded>);
   if (!attr_set[dev]) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
@@ -693,9 +804,9 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
   }
   const int grid = ceil_div(a.tiles_m * a.tiles_n, 8) * 8;
   if constexpr (kPingPong)
-    hipLaunchKernelGGL((k_gemm_pingpong<Cfg, kTap, kFull>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
+    hipLaunchKernelGGL((k_gemm_pingpong<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
   else
-    hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
+    hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
@@ -703,12 +814,21 @@ template <class Cfg, bool kPingPong>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   a.tiles_m = ceil_div(a.M, Cfg::BM);
   a.tiles_n = ceil_div(a.N, Cfg::BN);
-  if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong>(a, stream);
   const bool full = (a.M % Cfg::BM == 0) && (a.N % Cfg::BN == 0);
-  return full ? launch_one<Cfg, false, true, kPingPong>(a, stream) : launch_one<Cfg, false, false, kPingPong>(a, stream);
+  if (a.codes || a.residual) {
+    if (a.codes && Cfg::BN % (1 << a.code_log_block) != 0) return hipErrorInvalidValue;   // a block would leave the tile
+    if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, true>(a, stream);
+    return full ? launch_one<Cfg, false, true, kPingPong, true>(a, stream)
+                : launch_one<Cfg, false, false, kPingPong, true>(a, stream);
+  }
+  if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, false>(a, stream);
+  return full ? launch_one<Cfg, false, true, kPingPong, false>(a, stream)
+              : launch_one<Cfg, false, false, kPingPong, false>(a, stream);
 }
 
 static hipError_t launch_variant(const GemmArgs& a, int variant, hipStream_t stream) {
+  // coded output with blocks wider than the 128-column tiles: the 256-column tile of the same height class
+  if (a.codes && a.code_log_block > 7 && (variant == 0 || variant == 1)) variant = 2;
   switch (variant) {
     case 1: return launch_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>(a, stream);
     case 2: return launch_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>(a, stream);
@@ -729,7 +849,10 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
   b.Wo = a.Wo + panels * a.f_slabs * (kBlockBytes / 2);            // uint16_t elements
   b.c = a.c + n0;
   b.bias = a.bias ? a.bias + n0 : nullptr;
-  b.Y = a.Y + n0;
+  b.Y = a.Y ? a.Y + n0 : nullptr;
+  b.residual = a.residual ? a.residual + n0 : nullptr;
+  b.codes = a.codes ? a.codes + n0 : nullptr;
+  b.code_absmax = a.codes ? a.code_absmax + (n0 >> a.code_log_block) : nullptr;   // n0 is a multiple of 256
   b.tap_acc = a.tap_acc ? a.tap_acc + n0 : nullptr;
   b.N = n;
   return b;

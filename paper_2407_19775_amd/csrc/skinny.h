@@ -43,6 +43,13 @@ struct SkinnyArgs {
   const uint16_t* lora_T; // low-rank term T B^T added to the output: T [M][lora_ldt] fp16, B [N][lora_r] fp16
   const uint16_t* lora_B;
   int lora_ldt, lora_r;   // lora_r == 0: none
+  // The output with a residual added, H = f16(Y + residual), and / or leaving in blockwise-coded form (the rows
+  // of this call as one flattened tensor of M N elements; Y, where given, is then contiguous: ldy == N).
+  const uint16_t* residual;   // [M][ldr] fp16 or null
+  int ldr;
+  uint8_t* codes;         // [M N] or null
+  float* code_absmax;     // [ceil(M N / code_block)]
+  int code_block;         // a multiple of 64, at most 4096
   int n_slabs, tiles_n, slabs_per_split;   // filled by the launcher
 };
 

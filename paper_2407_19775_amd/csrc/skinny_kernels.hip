@@ -23,6 +23,7 @@
 // to fp16 first.  The two differ by at most the fp16 rounding of the weights (2^-11 relative per
 // term), far inside the tolerance of the fp16 output.  A slab without a critical column skips the
 // 16-bit part (the same decision for the whole workgroup).
+#include "codec_device.h"
 #include "common.h"
 #include "operand_layout.h"
 #include "skinny.h"
@@ -235,6 +236,7 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
                                                          const uint16_t* __restrict__ bias,
                                                          const uint16_t* __restrict__ T, int ldt,
                                                          const uint16_t* __restrict__ B, int r,
+                                                         const uint16_t* __restrict__ residual, int ldr,
                                                          uint16_t* __restrict__ Y, int ldy) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)M * N) return;
@@ -253,7 +255,56 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
     }
     y += low;
   }
-  Y[(size_t)m * ldy + n] = (uint16_t)float_to_half_bits(y);
+  uint32_t h = float_to_half_bits(y);
+  if (residual) h = float_to_half_bits(half_lo_to_float(h) + half_lo_to_float(residual[(size_t)m * ldr + n]));
+  Y[(size_t)m * ldy + n] = (uint16_t)h;
+}
+
+// The same sum as the source of the blockwise encoder (output leaving in coded form, no low-rank term): eight
+// neighbouring columns of a row per call; H = f16(Y + residual) is stored where wanted and handed to the encoder.
+__device__ const DynamicCode kExitCode = make_dynamic_code();
+struct FinalizedHalves {
+  const float* partial;
+  int splits, N;
+  size_t MN;
+  const uint16_t* bias;
+  const uint16_t* residual;
+  int ldr;
+  uint16_t* H;            // [M N] or null
+  __device__ v4u chunk(size_t e0, int /*valid: N is a multiple of 8, chunks are whole*/) const {
+    const int m = (int)(e0 / N), n = (int)(e0 % N);
+    float y[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] = 0.0f;
+    for (int s = 0; s < splits; ++s) {
+      const v4f p0 = *reinterpret_cast<const v4f*>(partial + (size_t)s * MN + e0);
+      const v4f p1 = *reinterpret_cast<const v4f*>(partial + (size_t)s * MN + e0 + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) y[i] += p0[i], y[4 + i] += p1[i];
+    }
+    if (bias) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] += half_lo_to_float(bias[n + i]);
+    }
+    v4u h;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) h[w] = float_to_half_bits(y[2 * w]) | (float_to_half_bits(y[2 * w + 1]) << 16);
+    if (residual) {
+      const v4u res = *reinterpret_cast<const v4u*>(residual + (size_t)m * ldr + n);
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        h[w] = float_to_half_bits(half_lo_to_float(h[w]) + half_lo_to_float(res[w])) |
+               (float_to_half_bits(half_hi_to_float(h[w]) + half_hi_to_float(res[w])) << 16);
+    }
+    if (H) *reinterpret_cast<v4u*>(H + e0) = h;
+    return h;
+  }
+};
+__global__ __launch_bounds__(kCodecThreads) void k_skinny_finalize_coded(const FinalizedHalves src, int block,
+                                                                         uint8_t* __restrict__ codes,
+                                                                         float* __restrict__ absmax,
+                                                                         int blocks_per_span, size_t n_spans) {
+  encode_spans(src, src.MN, block, codes, absmax, blocks_per_span, n_spans, kExitCode);
 }
 
 __global__ void k_fill_i32(int32_t* __restrict__ p, size_t n) {
@@ -298,7 +349,7 @@ static hipError_t launch_panel_one(const SkinnyArgs& a, int splits, hipStream_t 
 }
 template <class Cfg>
 static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t stream) {
-  const bool split = splits > 1 || a.lora_r > 0, tap = a.tap_acc != nullptr;
+  const bool split = splits > 1 || a.lora_r > 0 || a.residual || a.codes, tap = a.tap_acc != nullptr;
   if (split) return tap ? launch_panel_one<Cfg, true, true>(a, splits, stream) : launch_panel_one<Cfg, true, false>(a, splits, stream);
   return tap ? launch_panel_one<Cfg, false, true>(a, splits, stream) : launch_panel_one<Cfg, false, false>(a, splits, stream);
 }
@@ -313,15 +364,24 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   a.n_slabs = plan.n_slabs;
   a.tiles_n = plan.tiles_n;
   a.slabs_per_split = plan.slabs_per_split;
-  // with a low-rank term the output always goes through the partial buffer: the kernel that sums it adds the term
-  const bool split = plan.splits > 1 || a.lora_r > 0, tap = a.tap_acc != nullptr;
+  // with a low-rank term, a residual or a coded output the result always goes through the partial buffer: the
+  // kernel that sums it adds the term and encodes
+  const bool split = plan.splits > 1 || a.lora_r > 0 || a.residual || a.codes, tap = a.tap_acc != nullptr;
   const size_t n = (size_t)a.M * a.N;
   if (split && tap) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
   hipError_t e = launch_panel(a, plan, stream);
   if (e != hipSuccess) return e;
-  if (split) {
+  if (split && a.codes) {
+    // spans of about 1024 elements: enough workgroups at decode sizes, whole blocks each
+    const int blocks_per_span = a.code_block >= 1024 ? 1 : 1024 / a.code_block;
+    const size_t span = (size_t)blocks_per_span * a.code_block, n_spans = (n + span - 1) / span;
+    const FinalizedHalves src = {a.partial, plan.splits, a.N, n, a.bias, a.residual, a.ldr, a.Y};
+    hipLaunchKernelGGL(k_skinny_finalize_coded, dim3((unsigned)n_spans), dim3(kCodecThreads), 0, stream, src, a.code_block,
+                       a.codes, a.code_absmax, blocks_per_span, n_spans);
+    e = hipGetLastError();
+  } else if (split) {
     hipLaunchKernelGGL(k_skinny_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial, plan.splits,
-                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.Y, a.ldy);
+                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.residual, a.ldr, a.Y, a.ldy);
     e = hipGetLastError();
   }
   return e;
