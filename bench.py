@@ -4,8 +4,8 @@ A step is one pass of a Llama-7B-shaped shard over one prefill batch: the incomi
 is decoded from its blockwise 8-bit form (inside the first linear's preparation kernel), the 16
 linears of 4 decoder layers (QKV 4096->12288,
 O 4096->4096, gate/up 4096->22016, down 11008->4096; 2048 tokens) run through the mixed int8
-decomposition (scan, pack, int8 GEMM with fused epilogue), and the outgoing hidden state is
-encoded again.  Weights are pre-quantized before the timed region (they are static).  Inputs are
+decomposition (scan, pack, int8 GEMM with fused epilogue), and the outgoing hidden state (the last
+linear's output plus the residual stream) is encoded again in that linear's epilogue.  Weights are pre-quantized before the timed region (they are static).  Inputs are
 seeded synthetic tensors resident in HBM.  Prints one JSON line.
 """
 import argparse
@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=4)
-    ap.add_argument("--codec-block", type=int, default=1024)
+    ap.add_argument("--codec-block", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-step", action="store_true",
                     help="profiling aid: skip the extra sections (large codec tensor, decode, 70B, adapter)")
@@ -146,6 +146,9 @@ def main():
     hidden_in = torch.empty((M, 4096), dtype=torch.float16, device=dev)
     codes_out = torch.empty(M * 4096, dtype=torch.uint8, device=dev)
     absmax_out = torch.empty((M * 4096 + block - 1) // block, dtype=torch.float32, device=dev)
+    last = shapes[-1]                           # the shard's last linear hands its result on in coded form
+    assert last.N == 4096
+    ws_exit = binding.linear_workspace(M, last.K, last.N, dev, exit_block=block)
     torch.cuda.synchronize()
 
     def step(events=None):
@@ -153,11 +156,16 @@ def main():
         for layer in range(args.layers):
             for i, shp in enumerate(shapes):
                 first = layer == 0 and i == 0      # the shard's first linear takes the coded hidden state and decodes it
-                binding.mixed_int8_linear(hidden_in if first else Xs[shp.K], weights[layer][i], wl.TAU, out=Ys[shp.name],
-                                          workspace=workspace, events=events[n] if events else None,
-                                          coded=(codes_in, absmax_in, block) if first else None)
+                if layer == args.layers - 1 and i == len(shapes) - 1:
+                    # the last one adds the residual stream (here: the decoded incoming hidden state) and encodes
+                    binding.mixed_int8_linear_to_codes(Xs[shp.K], weights[layer][i], wl.TAU, block, residual=hidden_in,
+                                                       codes=codes_out, absmax=absmax_out, workspace=ws_exit,
+                                                       events=events[n] if events else None)
+                else:
+                    binding.mixed_int8_linear(hidden_in if first else Xs[shp.K], weights[layer][i], wl.TAU,
+                                              out=Ys[shp.name], workspace=workspace, events=events[n] if events else None,
+                                              coded=(codes_in, absmax_in, block) if first else None)
                 n += 1
-        binding.quantize_blockwise(Ys["down"], block, codes=codes_out, absmax=absmax_out)
 
     for _ in range(args.warmup):
         step()
@@ -330,6 +338,28 @@ def main():
                                  "gemm_tops": round(2.0 * M * shp.K * shp.N / t / 1e9, 1)}
         del ws_ad
 
+        # ---- the shard's last linear (down-projection + residual) handing on its result in coded form: one call
+        # against layer, fp16 addition (a torch kernel) and encoder as three steps; whole calls, same buffers
+        boundary_exit = {}
+        for Mb in (M, 64, 1):
+            Xb = Xs[last.K][:Mb] if Mb < M else Xs[last.K]
+            Rb, Yb = hidden_in[:Mb], Ys[last.name][:Mb]
+            Hb = torch.empty((Mb, last.N), dtype=torch.float16, device=dev)
+            cb, ab = codes_out[:Mb * last.N], absmax_out
+            wsb = binding.linear_workspace(Mb, last.K, last.N, dev, exit_block=block)
+
+            def fused():
+                binding.mixed_int8_linear_to_codes(Xb, weights[0][-1], wl.TAU, block, residual=Rb, codes=cb, absmax=ab,
+                                                   workspace=wsb)
+
+            def separate():
+                binding.mixed_int8_linear(Xb, weights[0][-1], wl.TAU, out=Yb, workspace=wsb)
+                torch.add(Yb, Rb, out=Hb)
+                binding.quantize_blockwise(Hb, block, codes=cb, absmax=ab)
+
+            boundary_exit["M%d" % Mb] = {"one_call_us": round(timed(fused, 30) * 1e3, 1),
+                                         "three_steps_us": round(timed(separate, 30) * 1e3, 1), "block": block}
+
         # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
         # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
         del weights, Xs, Ys
@@ -390,7 +420,7 @@ def main():
             "by_block": by_block,
             "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50), three buffer "
                     "sets taking turns (HBM traffic); after the first pass the values are codec outputs"})
-        out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter})
+        out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter, "boundary_exit": boundary_exit})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -180,7 +180,8 @@ def _taps(M, K, N, dev):
 
 def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, block: int, bias: torch.Tensor = None,
                                residual: torch.Tensor = None, codes: torch.Tensor = None, absmax: torch.Tensor = None,
-                               H: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False):
+                               H: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
+                               events=None):
     """The layer with its result leaving blockwise-coded: H = Y (+ residual, an fp16 addition), flattened row by
     row and encoded with blocks of `block` elements.  Returns (codes [M N] uint8, absmax float32); H, if given
     (contiguous [M, N] fp16), receives the encoded tensor itself.  With taps=True the intermediates of the layer
@@ -209,6 +210,8 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
         workspace = linear_workspace(M, K, N, X.device, exit_block=block)
     tensors = _taps(M, K, N, X.device) if taps else None
     tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()}) if taps else None
+    if events is not None and not taps:         # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
+        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
     _check(lib().mmd8_mixed_int8_linear_to_codes(
         X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
         bias.data_ptr() if bias is not None else None, float(tau),

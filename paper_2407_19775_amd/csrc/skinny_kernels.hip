@@ -276,7 +276,21 @@ struct FinalizedHalves {
     float y[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) y[i] = 0.0f;
-    for (int s = 0; s < splits; ++s) {
+    // four splits' loads in flight at a time; the additions stay in split order
+    int s = 0;
+    for (; s + 4 <= splits; s += 4) {
+      v4f p0[4], p1[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        p0[u] = *reinterpret_cast<const v4f*>(partial + (size_t)(s + u) * MN + e0);
+        p1[u] = *reinterpret_cast<const v4f*>(partial + (size_t)(s + u) * MN + e0 + 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[i] += p0[u][i], y[4 + i] += p1[u][i];
+    }
+    for (; s < splits; ++s) {
       const v4f p0 = *reinterpret_cast<const v4f*>(partial + (size_t)s * MN + e0);
       const v4f p1 = *reinterpret_cast<const v4f*>(partial + (size_t)s * MN + e0 + 4);
 #pragma unroll
@@ -372,8 +386,8 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   hipError_t e = launch_panel(a, plan, stream);
   if (e != hipSuccess) return e;
   if (split && a.codes) {
-    // spans of about 1024 elements: enough workgroups at decode sizes, whole blocks each
-    const int blocks_per_span = a.code_block >= 1024 ? 1 : 1024 / a.code_block;
+    // spans of about 2048 elements (every thread of the workgroup has a chunk), whole blocks each
+    const int blocks_per_span = a.code_block >= 2048 ? 1 : 2048 / a.code_block;
     const size_t span = (size_t)blocks_per_span * a.code_block, n_spans = (n + span - 1) / span;
     const FinalizedHalves src = {a.partial, plan.splits, a.N, n, a.bias, a.residual, a.ldr, a.Y};
     hipLaunchKernelGGL(k_skinny_finalize_coded, dim3((unsigned)n_spans), dim3(kCodecThreads), 0, stream, src, a.code_block,

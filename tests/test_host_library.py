@@ -128,3 +128,31 @@ def test_adapter_arguments_are_rejected_before_any_launch():
     assert call(A=odd) == -1 and call(T=odd) == -1
     assert call(K=100) == -2
     assert call(wsb=L.mmd8_linear_workspace_bytes(8, 128, 64)) == -3               # sized without the adapter
+
+
+def test_coded_output_arguments_are_rejected_before_any_launch():
+    L = binding.lib()
+    fake, out = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    odd = ctypes.c_void_p(0x1008)
+    base = L.mmd8_linear_workspace_bytes
+    wsb = L.mmd8_linear_to_codes_workspace_bytes
+    # the layer's last kernel encodes: nothing beyond what the decode path keeps for its partial outputs
+    assert wsb(300, 128, 512, 256) == base(300, 128, 512)
+    assert wsb(8, 128, 520, 4096) >= base(8, 128, 520)
+    # the encoder runs after the layer: room for the fp16 tensor it reads
+    assert wsb(300, 128, 512, 1024) >= base(300, 128, 512) + 300 * 512 * 2
+    assert wsb(300, 128, 520, 64) >= base(300, 128, 520) + 300 * 520 * 2
+    assert wsb(100, 128, 520, 4096) >= base(100, 128, 520) + 100 * 520 * 2
+    for bad_block in (0, 32, 100, 8192, -64):
+        assert wsb(8, 128, 64, bad_block) == 0
+    ws = wsb(8, 128, 64, 64)
+
+    def call(res=None, ldr=64, block=64, codes=out, absmax=out, H=None, wsb_=ws, K=128):
+        return L.mmd8_mixed_int8_linear_to_codes(fake, 8, K, 128, fake, fake, 64, None, 6.0, res, ldr, block, codes, absmax, H,
+                                                 fake, wsb_, None, None)
+
+    assert call(block=48) == -2 and call(block=8192) == -2 and call(K=100) == -2
+    assert call(codes=None) == -1 and call(absmax=None) == -1 and call(codes=odd) == -1
+    assert call(res=fake, ldr=56) == -1 and call(res=fake, ldr=68) == -1 and call(res=odd) == -1
+    assert call(H=odd) == -1
+    assert call(wsb_=ws - 256) == -3
