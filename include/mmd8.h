@@ -149,6 +149,18 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, con
                                       void* workspace /*DEVICE*/, size_t workspace_bytes,
                                       const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* The same layer followed by the GELU activation (the first linear of a transformer MLP block, e.g. of a
+ * ViT: bias, then GELU), applied in the kernel that writes the output:
+ *     Y[m,n] = f16( gelu( f16(the three terms of mmd8_mixed_int8_linear) ) ),   gelu(x) = x Phi(x) = x erfc(-x/sqrt 2)/2
+ * i.e. the exact (erf-based) form evaluated in fp32 on the fp16 layer output, as the two steps made one after
+ * the other give.  Arguments, requirements, workspace and errors as for mmd8_mixed_int8_linear. */
+int mmd8_mixed_int8_linear_gelu(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                mmd8_half* Y /*DEVICE*/, int ldy,
+                                void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* The same layer with its result leaving in blockwise-coded form (the hidden state a shard hands to its
  * successor: "Compression techniques", item 2 feeding item 1):
  *     Y = mixed_int8_linear(X, ...)                           fp16, as above

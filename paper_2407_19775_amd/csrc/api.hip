@@ -106,8 +106,9 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_bloc
     const int Mc = M < kSkinnyMaxM ? M : kSkinnyMaxM;              // rows per pass of the decode kernels
     w.xf = reinterpret_cast<uint16_t*>(take((size_t)kSkinnyMaxM * Kpad * 2));
     size_t pb = plan_skinny(Mc, K, N).partial_bytes;
-    // the low-rank term is added, and a coded output is encoded, where the partial outputs are summed
-    if ((r > 0 || exit_block > 0) && pb == 0) pb = (size_t)Mc * N * sizeof(float);
+    // a low-rank term is added, an activation applied and a coded output encoded where the partial outputs are
+    // summed: room for one partial output even when K is not split
+    if (pb == 0) pb = (size_t)Mc * N * sizeof(float);
     if (pb) w.partial = reinterpret_cast<float*>(take(pb));
   }
   w.lora_t = r > 0 ? reinterpret_cast<uint16_t*>(take((size_t)M * kLoraMaxRank * 2)) : nullptr;
@@ -241,7 +242,7 @@ struct Adapter {   // low-rank factors of W' = W + B A
 static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, const float* col_absmax, int N,
                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
                       const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, const CodedExit* exit,
-                      void* stream) {
+                      void* stream, bool gelu = false) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
@@ -352,6 +353,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
           g.code_block = exit->block;
         }
       }
+      g.gelu = gelu ? 1 : 0;
       g.partial = ws.partial;
       g.tap_acc = t.acc ? t.acc + (size_t)row0 * N : nullptr;
       g.flag_reset = row0 + kSkinnyMaxM >= M ? ws.flag : nullptr;   // the last pass zeroes the column flags again
@@ -387,6 +389,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.tap_ld = N;
     g.tiles_m = g.tiles_n = 0;
     g.flag_reset = ws.flag;
+    g.gelu = gelu ? 1 : 0;
     if (exit) {
       g.residual = exit->residual;
       g.ldr = exit->ldr;
@@ -412,6 +415,13 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
   // X is only read on this path
   return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, nullptr, nullptr, stream);
+}
+
+int mmd8_mixed_int8_linear_gelu(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                                const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                                void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+                    workspace_bytes, taps, nullptr, nullptr, nullptr, stream, true);
 }
 
 size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block) {

@@ -41,6 +41,15 @@ __device__ inline uint32_t rounded_float_to_half_bits(float f) {
   return float_to_half_bits(f);
 }
 
+// Exact GELU, x Phi(x) = x erfc(-x / sqrt 2) / 2 (the complementary error function keeps the negative tail
+// accurate), of an fp16 value given as fp32; fp16 bit pattern of the result.
+__device__ inline uint32_t gelu_to_half_bits(float x) {
+  return float_to_half_bits(0.5f * x * erfcf(-x * 0.70710678118654752f));
+}
+__device__ inline uint32_t gelu_half_pair(uint32_t w) {
+  return gelu_to_half_bits(half_lo_to_float(w)) | (gelu_to_half_bits(half_hi_to_float(w)) << 16);
+}
+
 // ---- wave-wide max of a u32 held by every lane (DPP row shifts + row broadcasts); result valid in lane 63
 template <int kCtrl>
 __device__ inline uint32_t dpp_mov(uint32_t v) {
@@ -63,7 +72,7 @@ __device__ inline uint32_t wave_max_u32(uint32_t v) {
 // One 16-byte-per-lane global -> LDS copy (no registers in between).  Lane i's 16 bytes land at
 // lds_addr + 16 i.  Issued through asm so that the compiler does not serialise later LDS reads
 // behind it: completion is tracked by hand with vmcnt.
-__device__ inline void dma16(const void* src, uint32_t lds_addr) {
+__device__ __forceinline__ void dma16(const void* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(src), "s"(lds_addr)

@@ -30,6 +30,7 @@ struct GemmArgs {
   // tensor.  Blocks of 64, 128 or 256 elements that divide N and the tile width, so that no block leaves a tile.
   const uint16_t* residual;   // [M][ldr] fp16 or null
   int ldr;
+  int gelu;              // 1: Y := f16(gelu(Y)) (exact, erf-based), before a residual is added
   uint8_t* codes;        // [M][code_ld] or null
   float* code_absmax;    // [M code_ld / block]
   int code_ld;           // elements per row of the coded tensor

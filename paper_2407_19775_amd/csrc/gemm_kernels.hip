@@ -39,7 +39,7 @@ static_assert(BK == kSlabBytes, "one LDS slab is one slab of the packed operands
 
 // Address of the first byte that DMA instruction j of `wave` copies for slab 0 of an operand tile
 // whose first row is row0 (a multiple of 16 inside one panel): 16 rows x 64 bytes, contiguous.
-__device__ inline const int8_t* dma_source(const int8_t* base, int row0, int n_slabs, int j, int waves, int wave,
+__device__ __forceinline__ const int8_t* dma_source(const int8_t* base, int row0, int n_slabs, int j, int waves, int wave,
                                            int lane) {
   return base + (size_t)(row0 >> 8) * n_slabs * kBlockBytes +
          (size_t)((row0 & 255) + (j * waves + wave) * ROWS_PER_DMA) * kSlabBytes + lane * 16;
@@ -110,7 +110,7 @@ struct WavePos {
 };
 
 template <class Cfg>
-__device__ inline void tap_accumulators(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ]) {
+__device__ __forceinline__ void tap_accumulators(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ]) {
 #pragma unroll
   for (int i = 0; i < Cfg::TI; ++i)
 #pragma unroll
@@ -127,7 +127,7 @@ __device__ inline void tap_accumulators(const GemmArgs& a, const WavePos<Cfg>& p
 // acc := bits( acc * r[m] * (c[n] / 127^2) ).  r_tile points at the 256 (or fewer) row scales of
 // this workgroup tile, in LDS or in global memory.
 template <class Cfg, class RPtr>
-__device__ inline void dequantize_in_place(const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ], RPtr r_tile,
+__device__ __forceinline__ void dequantize_in_place(const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ], RPtr r_tile,
                                            const float (&cs)[Cfg::TJ]) {
 #pragma unroll
   for (int i = 0; i < Cfg::TI; ++i) {
@@ -155,7 +155,7 @@ __device__ inline void dequantize_in_place(const WavePos<Cfg>& p, v16i (&acc)[Cf
 // issued together (clamped addresses, results masked), so a step costs a few memory latencies, not one
 // per element.
 template <class Cfg>
-__device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+__device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                               int8_t* smem, int j_begin, int n_out) {
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ, TILE_M = Cfg::BM, TILE_N = Cfg::BN;
   constexpr int RSTEP = Cfg::kThreads / 16;                        // rows between a thread's items
@@ -222,7 +222,7 @@ __device__ inline void gather_outlier_columns(const GemmArgs& a, const WavePos<C
 // activation side, B on the weight side), one after the other through the first slab buffer: request,
 // wait, multiply.  Not overlapped with anything: two or three extra slabs next to the K / 64 of the codes.
 template <class Cfg>
-__device__ inline void low_rank_slabs(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+__device__ __forceinline__ void low_rank_slabs(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                       int8_t* smem) {
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
   // everything here is derived after this point (nothing of it is kept in registers through the main loop)
@@ -272,7 +272,7 @@ __device__ inline void low_rank_slabs(const GemmArgs& a, const WavePos<Cfg>& p, 
 // takes four times as many store instructions and writes half lines that do not always meet in L2 before
 // write-back: 2-5 % slower on the 256 x 256 tiles, 1.3 times the output in HBM write traffic.)
 template <class Cfg, bool kFull>
-__device__ inline void store_tile(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+__device__ __forceinline__ void store_tile(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                       const float (&bn)[Cfg::TJ], int8_t* smem, int wave) {
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
   constexpr int STRIDE = Cfg::WN * 2 + 16;                          // bytes per parked row (16 more: bank spread, 16-byte aligned)
@@ -323,7 +323,7 @@ __device__ inline void store_tile(const GemmArgs& a, const WavePos<Cfg>& p, v16i
 // so that the lanes of a block are neighbours (4, 8 or 16 of them: the block maximum is a few DPP steps) and a
 // wave instruction writes whole 256-byte (128-byte) rows of codes.
 template <class Cfg, bool kFull>
-__device__ inline void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+__device__ __forceinline__ void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                         const float (&bn)[Cfg::TJ], int8_t* smem, int wave) {
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
   constexpr int STRIDE = Cfg::WN * 2 + 16;
@@ -364,7 +364,7 @@ __device__ inline void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     // ---- phase A
-    if (a.residual || a.Y) {
+    if (a.gelu || a.residual || a.Y) {
 #pragma unroll
       for (int it = 0; it < RP * CH / kWave; ++it) {
         const int idx = it * kWave + p.lane, row = idx / CH, ch = idx % CH;
@@ -373,6 +373,11 @@ __device__ inline void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p
         const int gm = p.mw + i0 * 32 + row, gn = p.nw + ch * 8;
         bool ok = true;
         if constexpr (!kFull) ok = gm < a.M && gn < a.N;
+        if (a.gelu) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) v[w] = gelu_half_pair(v[w]);
+          if (!a.residual) *reinterpret_cast<v4u*>(cell) = v;
+        }
         if (a.residual) {
           v4u res = v4u{0, 0, 0, 0};
           if (ok) res = *reinterpret_cast<const v4u*>(a.residual + (size_t)gm * a.ldr + gn);
@@ -417,7 +422,7 @@ __device__ inline void store_tile_coded(const GemmArgs& a, const WavePos<Cfg>& p
 }
 
 template <class Cfg>
-__device__ inline void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& p, float (&cs)[Cfg::TJ],
+__device__ __forceinline__ void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& p, float (&cs)[Cfg::TJ],
                                          float (&bn)[Cfg::TJ]) {
 #pragma unroll
   for (int j = 0; j < Cfg::TJ; ++j) {
@@ -431,7 +436,8 @@ __device__ inline void load_column_terms(const GemmArgs& a, const WavePos<Cfg>& 
 // Generic kernel: 4 waves, one wave per SIMD or two workgroups per CU, small tiles.
 // kFull: M and N are multiples of the tile, so no output store needs a bounds check.
 // kTap: also write the raw int32 accumulators (parity checks).
-// kCoded: the output takes a residual and / or leaves in blockwise-coded form (store_tile_coded).
+// kCoded: the output goes through an activation, takes a residual and / or leaves in blockwise-coded form
+// (store_tile_coded).
 // ------------------------------------------------------------------------------------------------
 template <class Cfg, bool kTap, bool kFull, bool kCoded>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
@@ -815,7 +821,7 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   a.tiles_m = ceil_div(a.M, Cfg::BM);
   a.tiles_n = ceil_div(a.N, Cfg::BN);
   const bool full = (a.M % Cfg::BM == 0) && (a.N % Cfg::BN == 0);
-  if (a.codes || a.residual) {
+  if (a.codes || a.residual || a.gelu) {
     if (a.codes && Cfg::BN % (1 << a.code_log_block) != 0) return hipErrorInvalidValue;   // a block would leave the tile
     if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, true>(a, stream);
     return full ? launch_one<Cfg, false, true, kPingPong, true>(a, stream)

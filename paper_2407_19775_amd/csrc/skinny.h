@@ -47,6 +47,7 @@ struct SkinnyArgs {
   // of this call as one flattened tensor of M N elements; Y, where given, is then contiguous: ldy == N).
   const uint16_t* residual;   // [M][ldr] fp16 or null
   int ldr;
+  int gelu;               // 1: Y := f16(gelu(Y)) before a residual is added
   uint8_t* codes;         // [M N] or null
   float* code_absmax;     // [ceil(M N / code_block)]
   int code_block;         // a multiple of 64, at most 4096

@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
                                                          const uint16_t* __restrict__ bias,
                                                          const uint16_t* __restrict__ T, int ldt,
                                                          const uint16_t* __restrict__ B, int r,
-                                                         const uint16_t* __restrict__ residual, int ldr,
+                                                         const uint16_t* __restrict__ residual, int ldr, int gelu,
                                                          uint16_t* __restrict__ Y, int ldy) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)M * N) return;
@@ -256,6 +256,7 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
     y += low;
   }
   uint32_t h = float_to_half_bits(y);
+  if (gelu) h = gelu_to_half_bits(half_lo_to_float(h));
   if (residual) h = float_to_half_bits(half_lo_to_float(h) + half_lo_to_float(residual[(size_t)m * ldr + n]));
   Y[(size_t)m * ldy + n] = (uint16_t)h;
 }
@@ -363,7 +364,7 @@ static hipError_t launch_panel_one(const SkinnyArgs& a, int splits, hipStream_t 
 }
 template <class Cfg>
 static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t stream) {
-  const bool split = splits > 1 || a.lora_r > 0 || a.residual || a.codes, tap = a.tap_acc != nullptr;
+  const bool split = splits > 1 || a.lora_r > 0 || a.residual || a.codes || a.gelu, tap = a.tap_acc != nullptr;
   if (split) return tap ? launch_panel_one<Cfg, true, true>(a, splits, stream) : launch_panel_one<Cfg, true, false>(a, splits, stream);
   return tap ? launch_panel_one<Cfg, false, true>(a, splits, stream) : launch_panel_one<Cfg, false, false>(a, splits, stream);
 }
@@ -378,9 +379,9 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   a.n_slabs = plan.n_slabs;
   a.tiles_n = plan.tiles_n;
   a.slabs_per_split = plan.slabs_per_split;
-  // with a low-rank term, a residual or a coded output the result always goes through the partial buffer: the
-  // kernel that sums it adds the term and encodes
-  const bool split = plan.splits > 1 || a.lora_r > 0 || a.residual || a.codes, tap = a.tap_acc != nullptr;
+  // with a low-rank term, an activation, a residual or a coded output the result always goes through the partial
+  // buffer: the kernel that sums it adds the term, applies the activation and encodes
+  const bool split = plan.splits > 1 || a.lora_r > 0 || a.residual || a.codes || a.gelu, tap = a.tap_acc != nullptr;
   const size_t n = (size_t)a.M * a.N;
   if (split && tap) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
   hipError_t e = launch_panel(a, plan, stream);
@@ -395,7 +396,7 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
     e = hipGetLastError();
   } else if (split) {
     hipLaunchKernelGGL(k_skinny_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial, plan.splits,
-                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.residual, a.ldr, a.Y, a.ldy);
+                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.residual, a.ldr, a.gelu, a.Y, a.ldy);
     e = hipGetLastError();
   }
   return e;
