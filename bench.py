@@ -360,6 +360,34 @@ def main():
             boundary_exit["M%d" % Mb] = {"one_call_us": round(timed(fused, 30) * 1e3, 1),
                                          "three_steps_us": round(timed(separate, 30) * 1e3, 1), "block": block}
 
+        # ---- ViT-L-shaped block (width 1024, 8 images x 197 tokens, bias everywhere): the four linears, the first
+        # MLP linear with GELU applied in its own kernels against the same layer followed by a separate fp16
+        # activation kernel (torch's).  Weights N(0, 0.02^2) drawn on the device, whole calls.
+        vit, Mv = {}, 8 * 197
+        genv = torch.Generator(device=dev)
+        genv.manual_seed(7)
+        for shp in wl.VIT_L_LINEARS:
+            Wv = torch.empty((shp.K, shp.N), dtype=torch.float16, device=dev).normal_(0.0, 0.02, generator=genv)
+            pwv = binding.prequantize_weight(Wv)
+            del Wv
+            Xv = torch.empty((Mv, shp.K), dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=genv)
+            Xv[:, :2] *= 20.0
+            bv = torch.empty(shp.N, dtype=torch.float16, device=dev).normal_(0.0, 0.1, generator=genv)
+            Yv = torch.empty((Mv, shp.N), dtype=torch.float16, device=dev)
+            wsv = binding.linear_workspace(Mv, shp.K, shp.N, dev)
+            t = timed(lambda: binding.mixed_int8_linear(Xv, pwv, wl.TAU, bias=bv, out=Yv, workspace=wsv), 30)
+            vit[shp.name] = {"call_us": round(t * 1e3, 1), "tops": round(2.0 * Mv * shp.K * shp.N / t / 1e9, 1)}
+            if shp.name == "fc1":
+                def two_steps():
+                    binding.mixed_int8_linear(Xv, pwv, wl.TAU, bias=bv, out=Yv, workspace=wsv)
+                    torch.nn.functional.gelu(Yv)
+
+                vit["fc1_gelu"] = {
+                    "one_call_us": round(timed(lambda: binding.mixed_int8_linear(Xv, pwv, wl.TAU, bias=bv, out=Yv,
+                                                                                 workspace=wsv, gelu=True), 30) * 1e3, 1),
+                    "two_steps_us": round(timed(two_steps, 30) * 1e3, 1)}
+        vit["tokens"] = Mv
+
         # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
         # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
         del weights, Xs, Ys
@@ -420,7 +448,8 @@ def main():
             "by_block": by_block,
             "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50), three buffer "
                     "sets taking turns (HBM traffic); after the first pass the values are codec outputs"})
-        out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter, "boundary_exit": boundary_exit})
+        out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter, "boundary_exit": boundary_exit,
+                    "vit_l_block": vit})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

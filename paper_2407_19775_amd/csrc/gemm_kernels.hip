@@ -316,8 +316,9 @@ __device__ __forceinline__ void store_tile(const GemmArgs& a, const WavePos<Cfg>
   }
 }
 
-// The same, for an output that leaves in coded form ("Compression techniques", item 1 applied to the result of
-// item 2): H = f16(Y + residual) (or Y), written where wanted, and its blockwise 8-bit codes.  Rows are parked
+// The same with more behind the layer: an activation (GELU, applied to the rounded output before it is parked), a
+// residual, and / or an output that leaves in coded form ("Compression techniques", item 1 applied to the result
+// of item 2): H = f16(Y + residual) (or Y), written where wanted, and its blockwise 8-bit codes.  Rows are parked
 // as in store_tile.  Phase A (each wave on its own rows): add the residual in place, store H.  After a barrier,
 // phase B: a lane takes 16 neighbouring columns of one row of the workgroup tile, whichever wave parked them,
 // so that the lanes of a block are neighbours (4, 8 or 16 of them: the block maximum is a few DPP steps) and a
@@ -353,7 +354,8 @@ __device__ __forceinline__ void store_tile_coded(const GemmArgs& a, const WavePo
         const v16f y = __builtin_bit_cast(v16f, acc[i0 + ii][j]);
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
-          const uint32_t h = float_to_half_bits(y[e] + bn[j]) | (float_to_half_bits(y[e + 1] + bn[j]) << 16);
+          uint32_t h = float_to_half_bits(y[e] + bn[j]) | (float_to_half_bits(y[e + 1] + bn[j]) << 16);
+          if (a.gelu) h = gelu_half_pair(h);                         // the activation, on the rounded layer output
           const uint32_t q = (uint32_t)__builtin_amdgcn_mov_dpp((int)h, 0xb1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
           const uint32_t out = odd ? ((q >> 16) | (h & 0xffff0000u)) : ((h & 0xffffu) | (q << 16));
           const int row = ii * 32 + 8 * (e / 4) + (e % 4) + 4 * p.lg + odd;
@@ -364,7 +366,7 @@ __device__ __forceinline__ void store_tile_coded(const GemmArgs& a, const WavePo
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     // ---- phase A
-    if (a.gelu || a.residual || a.Y) {
+    if (a.residual || a.Y) {
 #pragma unroll
       for (int it = 0; it < RP * CH / kWave; ++it) {
         const int idx = it * kWave + p.lane, row = idx / CH, ch = idx % CH;
@@ -373,11 +375,6 @@ __device__ __forceinline__ void store_tile_coded(const GemmArgs& a, const WavePo
         const int gm = p.mw + i0 * 32 + row, gn = p.nw + ch * 8;
         bool ok = true;
         if constexpr (!kFull) ok = gm < a.M && gn < a.N;
-        if (a.gelu) {
-#pragma unroll
-          for (int w = 0; w < 4; ++w) v[w] = gelu_half_pair(v[w]);
-          if (!a.residual) *reinterpret_cast<v4u*>(cell) = v;
-        }
         if (a.residual) {
           v4u res = v4u{0, 0, 0, 0};
           if (ok) res = *reinterpret_cast<const v4u*>(a.residual + (size_t)gm * a.ldr + gn);
