@@ -388,6 +388,32 @@ def main():
                     "two_steps_us": round(timed(two_steps, 30) * 1e3, 1)}
         vit["tokens"] = Mv
 
+        # ---- the codec on a key/value cache (one layer of the 7B shape: 32 heads x 128, block = one head vector):
+        # a 2048-token context decoded for one generated token (K and V), one token appended, a 2048-token prompt
+        # appended.  Whole calls, eager; the cache of this one layer fits the last-level cache.
+        Hh, Dh, Tc = 32, 128, 2048
+        kv_x = [torch.empty((Tc, Hh, Dh), dtype=torch.float16, device=dev).normal_(0.0, 1.0, generator=genv) for _ in range(2)]
+        kv_c = [torch.empty((Tc, Hh, Dh), dtype=torch.uint8, device=dev) for _ in range(2)]
+        kv_a = [torch.empty((Tc, Hh), dtype=torch.float32, device=dev) for _ in range(2)]
+
+        def kv_append(t0, n):
+            for i in range(2):
+                binding.quantize_blockwise(kv_x[i][t0:t0 + n], Dh, codes=kv_c[i][t0:t0 + n].view(-1), absmax=kv_a[i][t0:t0 + n].view(-1))
+
+        def kv_read():
+            for i in range(2):
+                binding.dequantize_blockwise(kv_c[i].view(-1), kv_a[i].view(-1), Dh, out=kv_x[i].view(-1))
+
+        kv_append(0, Tc)
+        kv_bytes = 2.0 * (3.0 + 4.0 / Dh) * Tc * Hh * Dh
+        t_read, t_tok, t_prompt = timed(kv_read, 30), timed(lambda: kv_append(Tc - 1, 1), 30), timed(lambda: kv_append(0, Tc), 30)
+        kv_cache = {"heads": Hh, "head_dim": Dh, "context": Tc,
+                    "read_context_us": round(t_read * 1e3, 1), "read_context_gbs": round(kv_bytes / t_read / 1e6, 1),
+                    "append_token_us": round(t_tok * 1e3, 1),
+                    "append_prompt_us": round(t_prompt * 1e3, 1), "append_prompt_gbs": round(kv_bytes / t_prompt / 1e6, 1),
+                    "coded_fraction": (1 + 4.0 / Dh) / 2}
+        del kv_x, kv_c, kv_a
+
         # ---- 70B-shaped shard prefill (4096 tokens, one decoder layer: 856 MB of weight codes), per linear:
         # preparation and GEMM time from the library's events.  Weights drawn on the device (N(0, 0.015^2)).
         del weights, Xs, Ys
@@ -449,7 +475,7 @@ def main():
             "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50), three buffer "
                     "sets taking turns (HBM traffic); after the first pass the values are codec outputs"})
         out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter, "boundary_exit": boundary_exit,
-                    "vit_l_block": vit})
+                    "vit_l_block": vit, "kv_cache": kv_cache})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
