@@ -71,6 +71,7 @@ def lib():
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
         L.mmd8_set_gemm_variant.argtypes = [i32]
+        L.mmd8_set_panel_prep.argtypes = [i32]
         _lib = L
     return _lib
 
@@ -169,7 +170,13 @@ def linear_workspace(M: int, K: int, N: int, device, lora_rank: int = 0, exit_bl
     return ws
 
 
-def _taps(M, K, N, dev):
+def _taps(M, K, N, dev, only=None):
+    """Buffers for the debug taps; only: names to keep (the others are not asked for)."""
+    all_taps = _all_taps(M, K, N, dev)
+    return all_taps if only is None else {k: all_taps[k] for k in only}
+
+
+def _all_taps(M, K, N, dev):
     return dict(
         outlier_mask=torch.zeros(K, dtype=torch.uint8, device=dev),
         row_absmax=torch.zeros(M, dtype=torch.float32, device=dev),
@@ -227,7 +234,8 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
                       events=None, coded=None, lora=None, gelu: bool = False):
-    """Y = X W through the mixed decomposition (gelu=True: followed by the exact GELU, in the same kernels).  With taps=True also returns a dict of the
+    """Y = X W through the mixed decomposition (gelu=True: followed by the exact GELU, in the same kernels).
+    taps: True for every intermediate, or a tuple of tap names.  With taps=True also returns a dict of the
     intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx).
     coded=(codes, absmax, block): the activations arrive blockwise-coded; X is then the contiguous
     [M, K] fp16 buffer that receives the decoded values.
@@ -251,7 +259,7 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     if events is not None:                      # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
         tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
     if taps:
-        tensors = _taps(M, K, N, X.device)
+        tensors = _taps(M, K, N, X.device, None if taps is True else tuple(taps))
         tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
     if coded is not None:
         codes, absmax, block = coded

@@ -121,11 +121,6 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
 constexpr int kPackRowSteps = 2;
 constexpr int kPackRows = 32 * kPackRowSteps;          // rows per workgroup
 constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (one per wave)
-__device__ inline uint32_t to_code_byte(float x, float scale) {
-  float q = __builtin_rintf(x * scale);
-  q = fminf(fmaxf(q, -127.0f), 127.0f);
-  return (uint32_t)((int)q) & 0xffu;
-}
 // 16 column flags (bytes 0 / 1) starting at column k0
 __device__ inline v4u flags16(const uint8_t* __restrict__ flag, int k0) {
   return *reinterpret_cast<const v4u*>(flag + k0) & 0x01010101u;

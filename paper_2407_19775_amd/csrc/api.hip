@@ -131,6 +131,7 @@ static bool exit_fuses(int M, int N, int block) {
 }
 
 static int g_gemm_variant = -1;
+static bool g_panel_prep = true;
 
 }  // namespace mmd8
 
@@ -280,6 +281,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
   // with heavy-tailed activations (hundreds of critical columns) it is ten times faster.
   const bool skinny = M <= kSkinnyChunkedMaxM;
+  // One or two rows: the decode GEMM kernel prepares its own operands (scales, codes, critical columns) from X,
+  // and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
+  const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
+  const bool own_prep = skinny && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K);
@@ -292,7 +297,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, fused_decode ? coded : nullptr,
                     st) != hipSuccess)
       return MMD8_E_HIP;
-  } else {
+  } else if (!own_prep) {
     if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
     // (the decode kernels' operands are packed 64 rows at a time, below)
     if (!skinny && launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, nullptr, po, st) != hipSuccess)
@@ -327,8 +332,8 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       const int Mc = M - row0 < kSkinnyMaxM ? M - row0 : kSkinnyMaxM;
       // codes and the fp16 copy of these rows, masked with the flags of all M rows; the list of critical columns is
       // published again with every pass (the same list)
-      if (launch_pack(X + (size_t)row0 * ldx, Mc, K, ldx, ws.flag, ws.r + row0, ws.xq, Kpad,
-                      t.xq ? t.xq + (size_t)row0 * K : nullptr, ws.xf, po, st) != hipSuccess)
+      if (!own_prep && launch_pack(X + (size_t)row0 * ldx, Mc, K, ldx, ws.flag, ws.r + row0, ws.xq, Kpad,
+                                   t.xq ? t.xq + (size_t)row0 * K : nullptr, ws.xf, po, st) != hipSuccess)
         return MMD8_E_HIP;
       if (row0 == 0 && !record(t.event_gemm_begin)) return MMD8_E_HIP;
       SkinnyArgs g = {};
@@ -356,7 +361,13 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       g.gelu = gelu ? 1 : 0;
       g.partial = ws.partial;
       g.tap_acc = t.acc ? t.acc + (size_t)row0 * N : nullptr;
-      g.flag_reset = row0 + kSkinnyMaxM >= M ? ws.flag : nullptr;   // the last pass zeroes the column flags again
+      g.flag_reset = (!own_prep && row0 + kSkinnyMaxM >= M) ? ws.flag : nullptr;   // the last pass zeroes the column flags again
+      if (own_prep) {
+        g.X = X;
+        g.ldx = ldx;
+        g.K = K;
+        g.th = threshold_pattern(tau);
+      }
       if (lora) {
         g.lora_T = ws.lora_t + (size_t)row0 * kLoraMaxRank;
         g.lora_ldt = kLoraMaxRank;
@@ -467,5 +478,7 @@ uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau);
 // Tuning hook (not part of the documented interface): force a GEMM tile configuration; -1 = automatic.
 void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
 void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
+// ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for one or two rows)
+void mmd8_set_panel_prep(int on) { g_panel_prep = on != 0; }
 
 }  // extern "C"

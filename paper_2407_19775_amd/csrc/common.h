@@ -41,6 +41,13 @@ __device__ inline uint32_t rounded_float_to_half_bits(float f) {
   return float_to_half_bits(f);
 }
 
+// activation value -> int8 code (as an unsigned byte) with the row's scale 127 / r: round to nearest even, clamp
+__device__ inline uint32_t to_code_byte(float x, float scale) {
+  float q = __builtin_rintf(x * scale);
+  q = fminf(fmaxf(q, -127.0f), 127.0f);
+  return (uint32_t)((int)q) & 0xffu;
+}
+
 // Exact GELU, x Phi(x), of an fp16 value given as fp32; fp16 bit pattern of the result.  Branch-free:
 //   Phi(-|x|) = erfc(z) / 2, z = |x| / sqrt 2,   erfc(z) = t exp(-z^2 + g(t)), t = 1 / (1 + z / 2),
 // with g a degree-8 polynomial fitted to ln(exp(z^2) erfc(z) / t) on the t range of |x| <= 13.5 (beyond that the

@@ -70,11 +70,21 @@ struct PanelCfg {
   static constexpr int kMaxSlabs = MMD8_MAX_K / kSlabBytes;        // flags "slab holds a critical column"
 };
 
-template <class Cfg, bool kSplit, bool kTap>
+// kPrep (one or two rows): the activation side is not fetched from packed operands but made here.  Every
+// workgroup streams the rows of X once for the row scales (the maximum of the magnitudes below the threshold,
+// as the scan kernel finds it), keeps the columns of its own K range in LDS, and writes the codes and the fp16
+// critical columns of a slab into the ring two slabs ahead of the MFMAs: wave w owns the 16-column piece w % 4
+// of the slab (lane = column) for rows w / 4, w / 4 + kWaves / 4, ...  The arithmetic is the pack kernel's
+// (IEEE 127 / r, rint, clamp; critical columns zero in the codes and kept in the fp16 copy).  Rows of the
+// ring beyond M are zeroed once and never written.
+template <class Cfg, bool kSplit, bool kTap, bool kPrep>
 __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArgs a) {
   constexpr int MT = Cfg::kMT, WAVES = Cfg::kWaves;
+  static_assert(!kPrep || MT == 1, "own preparation is for one or two rows");
   __shared__ __attribute__((aligned(16))) int8_t s_x[4][Cfg::STAGE_BYTES];
   __shared__ uint8_t s_any[Cfg::kMaxSlabs];
+  __shared__ __attribute__((aligned(16))) uint16_t s_row[kPrep ? kPanelPrepMaxM * kPanelPrepMaxSlabs * kSlabBytes : 8];
+  __shared__ uint32_t s_part[kPanelPrepMaxM][WAVES];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int lr = lane & 31, lg = lane >> 5;
@@ -87,10 +97,12 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
 
   const int8_t* wgrp = a.Wt + (size_t)(n0 >> 8) * a.n_slabs * kBlockBytes + (size_t)((n0 & 255) >> 5) * 2048 + lane * 16 +
                        (size_t)s_begin * kBlockBytes;
-  for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) {
-    const v4u* mk = reinterpret_cast<const v4u*>(a.mask + (size_t)(s_begin + t) * kSlabBytes);
-    const v4u m = mk[0] | mk[1] | mk[2] | mk[3];
-    s_any[t] = (m[0] | m[1] | m[2] | m[3]) != 0;
+  if constexpr (!kPrep) {
+    for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) {
+      const v4u* mk = reinterpret_cast<const v4u*>(a.mask + (size_t)(s_begin + t) * kSlabBytes);
+      const v4u m = mk[0] | mk[1] | mk[2] | mk[3];
+      s_any[t] = (m[0] | m[1] | m[2] | m[3]) != 0;
+    }
   }
 
   // piece i of a slab's activation side: first the int8 codes (MT 32-row groups x 2 k-steps), then
@@ -107,12 +119,43 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
     x_dst[d] = i * 1024 + lane * 16;
   }
   auto fetch_x = [&](int j, v4i (&xr)[Cfg::kFetch]) {
+    if constexpr (kPrep) return;
 #pragma unroll
     for (int d = 0; d < Cfg::kFetch; ++d) xr[d] = *reinterpret_cast<const v4i*>(x_src[d] + (size_t)j * x_step[d]);
   };
-  auto park_x = [&](int stage, const v4i (&xr)[Cfg::kFetch]) {
+  // kPrep: the row scales and this workgroup's columns of X (LDS), see the kernel's header comment
+  constexpr int kRowStride = kPanelPrepMaxSlabs * kSlabBytes;      // elements of s_row per row
+  float scale[kPanelPrepMaxM] = {}, r_row[kPanelPrepMaxM] = {};
+  auto make_slab = [&](int j, int stage) {                         // slab j of the workgroup's range -> ring buffer `stage`
+    const int ch = wave & 3, ks = ch >> 1, g = ch & 1;
+    if (lane < 16) {
+      const int kl = j * kSlabBytes + ch * 16 + lane;
+      uint32_t x[kPanelPrepMaxM];
+      bool crit = false;
 #pragma unroll
-    for (int d = 0; d < Cfg::kFetch; ++d) *reinterpret_cast<v4i*>(&s_x[stage][x_dst[d]]) = xr[d];
+      for (int m = 0; m < kPanelPrepMaxM; ++m) {
+        x[m] = (m < a.M) ? (uint32_t)s_row[m * kRowStride + kl] : 0u;
+        crit = crit || (m < a.M && (x[m] & 0x7fffu) >= a.th);
+      }
+#pragma unroll
+      for (int m = 0; m < kPanelPrepMaxM; ++m) {
+        if (m < a.M && (m % (WAVES / 4)) == (wave >> 2) % (WAVES / 4)) {   // the rows of this wave
+          const uint32_t code = crit ? 0u : to_code_byte(half_lo_to_float(x[m]), scale[m]);
+          s_x[stage][ks * 1024 + (32 * g + m) * 16 + lane] = (int8_t)code;
+          *reinterpret_cast<uint16_t*>(&s_x[stage][Cfg::XQ_BYTES + (2 * ks + (lane >> 3)) * 1024 + (32 * g + m) * 16 +
+                                                   (lane & 7) * 2]) = crit ? (uint16_t)x[m] : (uint16_t)0;
+        }
+      }
+      if (crit) s_any[j] = 1;
+    }
+  };
+  auto park_x = [&](int stage, const v4i (&xr)[Cfg::kFetch], int j) {   // j: the slab these pieces belong to
+    if constexpr (kPrep) {
+      make_slab(j, stage);
+    } else {
+#pragma unroll
+      for (int d = 0; d < Cfg::kFetch; ++d) *reinterpret_cast<v4i*>(&s_x[stage][x_dst[d]]) = xr[d];
+    }
   };
   struct W2 {
     v4i w[2];
@@ -181,8 +224,48 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
   fetch_w(0, f[0]);
   fetch_w(min(1, last), f[1]);
   fetch_w(min(2, last), f[2]);
-  park_x(0, xr[0]);
-  park_x(1, xr[1]);
+  if constexpr (kPrep) {
+    // (the weight requests above are in flight meanwhile)
+    for (int i = threadIdx.x; i < 4 * Cfg::STAGE_BYTES / 16; i += Cfg::kThreads)
+      reinterpret_cast<v4u*>(&s_x[0][0])[i] = v4u{0, 0, 0, 0};
+    for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) s_any[t] = 0;
+    const us2 th2 = __builtin_bit_cast(us2, a.th | (a.th << 16));
+#pragma unroll
+    for (int m = 0; m < kPanelPrepMaxM; ++m) {
+      us2 best = __builtin_bit_cast(us2, 0u);
+      if (m < a.M) {
+        const uint16_t* row = a.X + (size_t)m * a.ldx;
+        for (int c = threadIdx.x; c < a.K / 8; c += Cfg::kThreads) {
+          const v4u raw = *reinterpret_cast<const v4u*>(row + c * 8);
+#pragma unroll
+          for (int w = 0; w < 4; ++w)   // per half, wraps mod 2^16: entries below the threshold get the top bit
+            best = __builtin_elementwise_max(best, (us2)(__builtin_bit_cast(us2, raw[w] & 0x7fff7fffu) - th2));
+        }
+        // this workgroup's columns (the K padding reads as zero)
+        for (int c = threadIdx.x; c < cnt * (kSlabBytes / 8); c += Cfg::kThreads) {
+          const int k = s_begin * kSlabBytes + c * 8;
+          v4u raw = v4u{0, 0, 0, 0};
+          if (k < a.K) raw = *reinterpret_cast<const v4u*>(row + k);
+          *reinterpret_cast<v4u*>(&s_row[m * kRowStride + c * 8]) = raw;
+        }
+      }
+      const uint32_t both = __builtin_bit_cast(uint32_t, best);
+      const uint32_t wmax = wave_max_u32(max(both & 0xffffu, both >> 16));
+      if (lane == 0) s_part[m][wave] = wmax;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < kPanelPrepMaxM; ++m) {
+      uint32_t mm = 0;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) mm = max(mm, s_part[m][w]);
+      // top bit set: an entry below the threshold exists and its pattern is mm + th (mod 2^16)
+      r_row[m] = (mm & 0x8000u) ? half_lo_to_float((mm + a.th) & 0xffffu) : 0.0f;
+      scale[m] = (r_row[m] == 0.0f) ? 0.0f : 127.0f / r_row[m];     // IEEE division
+    }
+  }
+  park_x(0, xr[0], 0);
+  park_x(1, xr[1], min(1, last));
   fetch_x(min(2, last), xr[1]);                                    // parked in iteration 0
   __syncthreads();
   bool any_next = s_any[0];
@@ -198,7 +281,7 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
       fetch_w(min(j + 3, last), f[(u + 3) & 3]);
       read_frags((u + 1) & 3, any_next, fr[(u + 1) & 1]);
       multiply(any_cur, fr[u & 1], f[u & 3]);
-      park_x((u + 2) & 3, xr[(u + 1) & 1]);
+      park_x((u + 2) & 3, xr[(u + 1) & 1], min(j + 2, last));
       __syncthreads();
     }
   }
@@ -214,7 +297,8 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
     for (int e = 0; e < 16; ++e) {
       const int m = mt * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
       if (m < a.M && n < a.N) {
-        const float y = (float)acc[mt][e] * (a.r[m] * cs) + accf[mt][e] * step;
+        const float rm = kPrep ? (m == 0 ? r_row[0] : r_row[1]) : a.r[m];
+        const float y = (float)acc[mt][e] * (rm * cs) + accf[mt][e] * step;
         if constexpr (kSplit)
           a.partial[((size_t)split * a.M + m) * a.N + n] = y;
         else
@@ -357,22 +441,32 @@ SkinnyPlan plan_skinny(int M, int K, int N) {
   return p;
 }
 
-template <class Cfg, bool kSplit, bool kTap>
+template <class Cfg, bool kSplit, bool kTap, bool kPrep>
 static hipError_t launch_panel_one(const SkinnyArgs& a, int splits, hipStream_t stream) {
-  hipLaunchKernelGGL((k_gemm_panel<Cfg, kSplit, kTap>), dim3(a.tiles_n * splits), dim3(Cfg::kThreads), 0, stream, a);
+  hipLaunchKernelGGL((k_gemm_panel<Cfg, kSplit, kTap, kPrep>), dim3(a.tiles_n * splits), dim3(Cfg::kThreads), 0, stream, a);
   return hipGetLastError();
 }
-template <class Cfg>
+template <class Cfg, bool kPrep>
 static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t stream) {
   const bool split = splits > 1 || a.lora_r > 0 || a.residual || a.codes || a.gelu, tap = a.tap_acc != nullptr;
-  if (split) return tap ? launch_panel_one<Cfg, true, true>(a, splits, stream) : launch_panel_one<Cfg, true, false>(a, splits, stream);
-  return tap ? launch_panel_one<Cfg, false, true>(a, splits, stream) : launch_panel_one<Cfg, false, false>(a, splits, stream);
+  if (split)
+    return tap ? launch_panel_one<Cfg, true, true, kPrep>(a, splits, stream)
+               : launch_panel_one<Cfg, true, false, kPrep>(a, splits, stream);
+  return tap ? launch_panel_one<Cfg, false, true, kPrep>(a, splits, stream)
+             : launch_panel_one<Cfg, false, false, kPrep>(a, splits, stream);
 }
 static hipError_t launch_panel(const SkinnyArgs& a, const SkinnyPlan& plan, hipStream_t stream) {
   const bool two = a.M > 32;
+  if (a.X) {                                                         // the kernel prepares its own operands
+    if (two || a.M > kPanelPrepMaxM || plan.slabs_per_split > kPanelPrepMaxSlabs) return hipErrorInvalidValue;
+    return plan.waves == 8 ? launch_panel_cfg<PanelCfg<1, 8>, true>(a, plan.splits, stream)
+                           : launch_panel_cfg<PanelCfg<1, 4>, true>(a, plan.splits, stream);
+  }
   if (plan.waves == 8)
-    return two ? launch_panel_cfg<PanelCfg<2, 8>>(a, plan.splits, stream) : launch_panel_cfg<PanelCfg<1, 8>>(a, plan.splits, stream);
-  return two ? launch_panel_cfg<PanelCfg<2, 4>>(a, plan.splits, stream) : launch_panel_cfg<PanelCfg<1, 4>>(a, plan.splits, stream);
+    return two ? launch_panel_cfg<PanelCfg<2, 8>, false>(a, plan.splits, stream)
+               : launch_panel_cfg<PanelCfg<1, 8>, false>(a, plan.splits, stream);
+  return two ? launch_panel_cfg<PanelCfg<2, 4>, false>(a, plan.splits, stream)
+             : launch_panel_cfg<PanelCfg<1, 4>, false>(a, plan.splits, stream);
 }
 
 hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t stream) {

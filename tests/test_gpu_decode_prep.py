@@ -1,0 +1,106 @@
+"""One or two rows: the decode GEMM kernel prepares its own operands (row scales, codes, critical columns) and
+the scan and pack kernels are left out.  The result must equal, bit for bit, the one obtained with those kernels
+(forced through the tuning hook, or by asking for their taps), the int32 accumulators must equal the oracle's, and
+the output must meet the oracle's to the fp16 bar; with every companion of the layer (bias, adapter, activation,
+coded input, coded output)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import blockwise_codec as bc
+from oracle import mixed_linear as ml
+from paper_2407_19775_amd import binding, workloads as wl
+from gpu_util import assert_y_close, to_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def own_prep_on():
+    binding.lib().mmd8_set_panel_prep(1)
+    yield
+    binding.lib().mmd8_set_panel_prep(1)
+
+
+def case(M, K, N, seed, heavy):
+    rng = np.random.default_rng([M, K, N, seed])
+    x = (rng.standard_t(3.0, size=(M, K)) if heavy else rng.standard_normal((M, K))).astype(np.float32)
+    x[:, rng.integers(0, K, max(1, K // 200))] *= 20.0
+    return wl.to_fp16(x), wl.gaussian_weight(K, N, 0.02, rng), wl.gaussian_bias(N, 0.3, rng), rng
+
+
+@pytest.mark.parametrize("M", [1, 2])
+@pytest.mark.parametrize("K,N", [(64, 8), (528, 264), (4096, 4096), (4096, 12288), (11008, 4096), (1040, 22016),
+                                 (16448, 72), (65536, 32), (8192, 57344)])
+def test_own_preparation_equals_the_separate_kernels(M, K, N):
+    for rep, tau in enumerate([wl.TAU, 0.0, np.inf, 2.0]):
+        X, W, b, _ = case(M, K, N, rep, heavy=bool(rep % 2))
+        if rep == 2:
+            X[M - 1] = 0                                             # a zero row: scale 0
+        pw = binding.prequantize_weight(to_gpu(W))
+        Xbuf = torch.zeros((M, K + 8), dtype=torch.float16, device="cuda")
+        Xg = Xbuf[:, :K]
+        Xg.copy_(to_gpu(X))
+        bg = to_gpu(b)
+        Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))      # own preparation + accumulators
+        Y_taps, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)        # scan + pack (their taps asked for)
+        binding.lib().mmd8_set_panel_prep(0)
+        Y_off = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                          # scan + pack (hook)
+        binding.lib().mmd8_set_panel_prep(1)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_off) and torch.equal(Y, Y_taps), (M, K, N, tau)
+        assert torch.equal(t_acc["acc"], taps["acc"])
+        if K * N <= 4096 * 4096:
+            Wq_o, c_o = ml.prequantize_weight(W)
+            o = ml.mixed_int8_linear(X, Wq_o, c_o, tau, b)
+            assert np.array_equal(to_np(t_acc["acc"]), o["acc"])
+            assert_y_close(to_np(Y), o["Y"])
+
+
+@pytest.mark.parametrize("M", [1, 2])
+def test_companions_of_the_layer(M):
+    K, N = 2048, 1024
+    X, W, b, rng = case(M, K, N, 7, heavy=True)
+    pw = binding.prequantize_weight(to_gpu(W))
+    Xg, bg = to_gpu(X), to_gpu(b)
+    A = to_gpu(wl.to_fp16(rng.standard_normal((16, K)).astype(np.float32) * 0.05))
+    B = to_gpu(wl.to_fp16(rng.standard_normal((N, 16)).astype(np.float32) * 0.05))
+    R = to_gpu(wl.to_fp16(rng.standard_normal((M, N)).astype(np.float32)))
+    codes_o, absmax_o = bc.quantize_blockwise(X.reshape(-1), 256)
+    cg, ag = to_gpu(codes_o), to_gpu(absmax_o)
+
+    def run_all():
+        out = [binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, lora=(A, B)),
+               binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, gelu=True)]
+        Xd = torch.empty((M, K), dtype=torch.float16, device="cuda")
+        out.append(binding.mixed_int8_linear(Xd, pw, wl.TAU, bias=bg, coded=(cg, ag, 256)))
+        out.append(Xd)
+        out.extend(binding.mixed_int8_linear_to_codes(Xg, pw, wl.TAU, 1024, bias=bg, residual=R))
+        torch.cuda.synchronize()
+        return out
+
+    on = run_all()
+    binding.lib().mmd8_set_panel_prep(0)
+    off = run_all()
+    binding.lib().mmd8_set_panel_prep(1)
+    for i, (a, b_) in enumerate(zip(on, off)):
+        assert torch.equal(a, b_), i
+
+
+def test_same_workspace_alternates_between_both_ways():
+    M, K, N = 1, 4096, 4096
+    X, W, b, _ = case(M, K, N, 3, heavy=True)
+    pw = binding.prequantize_weight(to_gpu(W))
+    ws = binding.linear_workspace(64, K, N, torch.device("cuda:0"))
+    Xg = to_gpu(X)
+    X64 = to_gpu(wl.to_fp16(np.random.default_rng(1).standard_t(3.0, size=(64, K)).astype(np.float32)))
+    ys = []
+    for i in range(3):
+        ys.append(binding.mixed_int8_linear(Xg, pw, wl.TAU, workspace=ws))
+        y64 = binding.mixed_int8_linear(X64, pw, wl.TAU, workspace=ws)           # scan + pack, leaves the flags zero again
+        if i == 0:
+            y64_first = y64
+        else:
+            assert torch.equal(y64, y64_first)
+    torch.cuda.synchronize()
+    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
