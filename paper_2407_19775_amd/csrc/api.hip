@@ -281,8 +281,8 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
   // with heavy-tailed activations (hundreds of critical columns) it is ten times faster.
   const bool skinny = M <= kSkinnyChunkedMaxM;
-  // One or two rows: the decode GEMM kernel prepares its own operands (scales, codes, critical columns) from X,
-  // and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
+  // A few rows (at most kPanelPrepMaxM): the decode GEMM kernel prepares its own operands (scales, codes, critical
+  // columns) from X, and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
   const bool own_prep = skinny && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
@@ -478,7 +478,7 @@ uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau);
 // Tuning hook (not part of the documented interface): force a GEMM tile configuration; -1 = automatic.
 void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
 void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
-// ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for one or two rows)
+// ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for a few rows)
 void mmd8_set_panel_prep(int on) { g_panel_prep = on != 0; }
 
 }  // extern "C"

@@ -51,19 +51,21 @@ struct SkinnyArgs {
   uint8_t* codes;         // [M N] or null
   float* code_absmax;     // [ceil(M N / code_block)]
   int code_block;         // a multiple of 64, at most 4096
-  // One or two rows: the panel kernel prepares its activation operands itself (no scan and pack kernels before
-  // it): every workgroup finds the row scales from X, and the codes / critical columns of its own K range.
-  // Then Xq, Xf and mask are not read; r is not read either.
+  // A few rows: the panel kernel prepares its activation operands itself (no scan and pack kernels before it):
+  // every workgroup finds the row scales from X, and the codes / critical columns of its own K range.
+  // Then Xq, Xf, mask and r are not read.
   const uint16_t* X;      // [M][ldx] fp16, or null: operands prepared by the pack kernel
   int ldx, K;
   uint32_t th;            // fp16 pattern of the threshold
   int n_slabs, tiles_n, slabs_per_split;   // filled by the launcher
 };
-constexpr int kPanelPrepMaxM = 2;          // rows up to which the panel kernel can prepare its own operands
-constexpr int kPanelPrepMaxSlabs = 128;    // ... and slabs per workgroup (its rows of X are held in LDS)
+constexpr int kPanelPrepMaxM = 8;          // rows up to which the panel kernel can prepare its own operands
+constexpr int kPanelPrepMaxSlabs = 128;    // ... slabs per workgroup (one flag per column in LDS)
+constexpr int kPanelPrepMaxRowSlabs = 256; // ... and rows x slabs per workgroup (its columns of X are held in LDS: 32 KB)
 // whether launch_gemm_skinny may be given X instead of packed operands for this plan
 inline bool panel_prep_fits(int M, const SkinnyPlan& plan) {
-  return M <= kPanelPrepMaxM && plan.waves != 0 && plan.slabs_per_split <= kPanelPrepMaxSlabs;
+  return M <= kPanelPrepMaxM && plan.waves != 0 && plan.slabs_per_split <= kPanelPrepMaxSlabs &&
+         M * plan.slabs_per_split <= kPanelPrepMaxRowSlabs;
 }
 
 hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t stream);

@@ -70,21 +70,23 @@ struct PanelCfg {
   static constexpr int kMaxSlabs = MMD8_MAX_K / kSlabBytes;        // flags "slab holds a critical column"
 };
 
-// kPrep (one or two rows): the activation side is not fetched from packed operands but made here.  Every
-// workgroup streams the rows of X once for the row scales (the maximum of the magnitudes below the threshold,
-// as the scan kernel finds it), keeps the columns of its own K range in LDS, and writes the codes and the fp16
-// critical columns of a slab into the ring two slabs ahead of the MFMAs: wave w owns the 16-column piece w % 4
-// of the slab (lane = column) for rows w / 4, w / 4 + kWaves / 4, ...  The arithmetic is the pack kernel's
-// (IEEE 127 / r, rint, clamp; critical columns zero in the codes and kept in the fp16 copy).  Rows of the
-// ring beyond M are zeroed once and never written.
+// kPrep (at most kPanelPrepMaxM rows): the activation side is not fetched from packed operands but made here.
+// Every workgroup streams the rows of X once for the row scales (the maximum of the magnitudes below the
+// threshold, as the scan kernel finds it), keeps the columns of its own K range in LDS with one "critical" flag
+// per column, and writes the codes and the fp16 critical columns of a slab into the ring two slabs ahead of the
+// MFMAs: wave w owns the 16-column piece w % 4 of the slab, a lane one column of one of four rows.  The
+// arithmetic is the pack kernel's (IEEE 127 / r, rint, clamp; critical columns zero in the codes and kept in the
+// fp16 copy).  Rows of the ring beyond M are zeroed once and never written.
 template <class Cfg, bool kSplit, bool kTap, bool kPrep>
 __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArgs a) {
   constexpr int MT = Cfg::kMT, WAVES = Cfg::kWaves;
-  static_assert(!kPrep || MT == 1, "own preparation is for one or two rows");
+  static_assert(!kPrep || MT == 1, "own preparation is for a few rows");
   __shared__ __attribute__((aligned(16))) int8_t s_x[4][Cfg::STAGE_BYTES];
   __shared__ uint8_t s_any[Cfg::kMaxSlabs];
-  __shared__ __attribute__((aligned(16))) uint16_t s_row[kPrep ? kPanelPrepMaxM * kPanelPrepMaxSlabs * kSlabBytes : 8];
+  __shared__ __attribute__((aligned(16))) uint16_t s_row[kPrep ? kPanelPrepMaxRowSlabs * kSlabBytes : 8];   // [M][cnt x 64]
+  __shared__ uint8_t s_crit[kPrep ? kPanelPrepMaxSlabs * kSlabBytes : 8];                                    // [cnt x 64]
   __shared__ uint32_t s_part[kPanelPrepMaxM][WAVES];
+  __shared__ float s_r[kPanelPrepMaxM], s_scale[kPanelPrepMaxM];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int lr = lane & 31, lg = lane >> 5;
@@ -123,31 +125,20 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
 #pragma unroll
     for (int d = 0; d < Cfg::kFetch; ++d) xr[d] = *reinterpret_cast<const v4i*>(x_src[d] + (size_t)j * x_step[d]);
   };
-  // kPrep: the row scales and this workgroup's columns of X (LDS), see the kernel's header comment
-  constexpr int kRowStride = kPanelPrepMaxSlabs * kSlabBytes;      // elements of s_row per row
-  float scale[kPanelPrepMaxM] = {}, r_row[kPanelPrepMaxM] = {};
-  auto make_slab = [&](int j, int stage) {                         // slab j of the workgroup's range -> ring buffer `stage`
-    const int ch = wave & 3, ks = ch >> 1, g = ch & 1;
-    if (lane < 16) {
-      const int kl = j * kSlabBytes + ch * 16 + lane;
-      uint32_t x[kPanelPrepMaxM];
-      bool crit = false;
-#pragma unroll
-      for (int m = 0; m < kPanelPrepMaxM; ++m) {
-        x[m] = (m < a.M) ? (uint32_t)s_row[m * kRowStride + kl] : 0u;
-        crit = crit || (m < a.M && (x[m] & 0x7fffu) >= a.th);
-      }
-#pragma unroll
-      for (int m = 0; m < kPanelPrepMaxM; ++m) {
-        if (m < a.M && (m % (WAVES / 4)) == (wave >> 2) % (WAVES / 4)) {   // the rows of this wave
-          const uint32_t code = crit ? 0u : to_code_byte(half_lo_to_float(x[m]), scale[m]);
-          s_x[stage][ks * 1024 + (32 * g + m) * 16 + lane] = (int8_t)code;
-          *reinterpret_cast<uint16_t*>(&s_x[stage][Cfg::XQ_BYTES + (2 * ks + (lane >> 3)) * 1024 + (32 * g + m) * 16 +
-                                                   (lane & 7) * 2]) = crit ? (uint16_t)x[m] : (uint16_t)0;
-        }
-      }
-      if (crit) s_any[j] = 1;
+  // kPrep: slab j of the workgroup's range -> ring buffer `stage` (see the kernel's header comment)
+  const int row_stride = cnt * kSlabBytes;                         // elements of s_row per row
+  auto make_slab = [&](int j, int stage) {
+    const int ch = wave & 3, ks = ch >> 1, g = ch & 1, col = lane & 15;
+    const int kl = j * kSlabBytes + ch * 16 + col;
+    const bool crit = s_crit[kl] != 0;
+    for (int m = (wave >> 2) * 4 + (lane >> 4); m < a.M; m += WAVES) {
+      const uint32_t x = s_row[m * row_stride + kl];
+      const uint32_t code = crit ? 0u : to_code_byte(half_lo_to_float(x), s_scale[m]);
+      s_x[stage][ks * 1024 + (32 * g + m) * 16 + col] = (int8_t)code;
+      *reinterpret_cast<uint16_t*>(&s_x[stage][Cfg::XQ_BYTES + (2 * ks + (col >> 3)) * 1024 + (32 * g + m) * 16 +
+                                               (col & 7) * 2]) = crit ? (uint16_t)x : (uint16_t)0;
     }
+    if (crit) s_any[j] = 1;
   };
   auto park_x = [&](int stage, const v4i (&xr)[Cfg::kFetch], int j) {   // j: the slab these pieces belong to
     if constexpr (kPrep) {
@@ -230,39 +221,42 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
       reinterpret_cast<v4u*>(&s_x[0][0])[i] = v4u{0, 0, 0, 0};
     for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) s_any[t] = 0;
     const us2 th2 = __builtin_bit_cast(us2, a.th | (a.th << 16));
-#pragma unroll
-    for (int m = 0; m < kPanelPrepMaxM; ++m) {
+    for (int m = 0; m < a.M; ++m) {
       us2 best = __builtin_bit_cast(us2, 0u);
-      if (m < a.M) {
-        const uint16_t* row = a.X + (size_t)m * a.ldx;
-        for (int c = threadIdx.x; c < a.K / 8; c += Cfg::kThreads) {
-          const v4u raw = *reinterpret_cast<const v4u*>(row + c * 8);
+      const uint16_t* row = a.X + (size_t)m * a.ldx;
+      for (int c = threadIdx.x; c < a.K / 8; c += Cfg::kThreads) {
+        const v4u raw = *reinterpret_cast<const v4u*>(row + c * 8);
 #pragma unroll
-          for (int w = 0; w < 4; ++w)   // per half, wraps mod 2^16: entries below the threshold get the top bit
-            best = __builtin_elementwise_max(best, (us2)(__builtin_bit_cast(us2, raw[w] & 0x7fff7fffu) - th2));
-        }
-        // this workgroup's columns (the K padding reads as zero)
-        for (int c = threadIdx.x; c < cnt * (kSlabBytes / 8); c += Cfg::kThreads) {
-          const int k = s_begin * kSlabBytes + c * 8;
-          v4u raw = v4u{0, 0, 0, 0};
-          if (k < a.K) raw = *reinterpret_cast<const v4u*>(row + k);
-          *reinterpret_cast<v4u*>(&s_row[m * kRowStride + c * 8]) = raw;
-        }
+        for (int w = 0; w < 4; ++w)   // per half, wraps mod 2^16: entries below the threshold get the top bit
+          best = __builtin_elementwise_max(best, (us2)(__builtin_bit_cast(us2, raw[w] & 0x7fff7fffu) - th2));
+      }
+      // this workgroup's columns (the K padding reads as zero)
+      for (int c = threadIdx.x; c < cnt * (kSlabBytes / 8); c += Cfg::kThreads) {
+        const int k = s_begin * kSlabBytes + c * 8;
+        v4u raw = v4u{0, 0, 0, 0};
+        if (k < a.K) raw = *reinterpret_cast<const v4u*>(row + k);
+        *reinterpret_cast<v4u*>(&s_row[m * row_stride + c * 8]) = raw;
       }
       const uint32_t both = __builtin_bit_cast(uint32_t, best);
       const uint32_t wmax = wave_max_u32(max(both & 0xffffu, both >> 16));
       if (lane == 0) s_part[m][wave] = wmax;
     }
     __syncthreads();
-#pragma unroll
-    for (int m = 0; m < kPanelPrepMaxM; ++m) {
+    for (int c = threadIdx.x; c < row_stride; c += Cfg::kThreads) {
+      bool crit = false;
+      for (int m = 0; m < a.M; ++m) crit = crit || (s_row[m * row_stride + c] & 0x7fffu) >= a.th;
+      s_crit[c] = crit ? 1 : 0;
+    }
+    if ((int)threadIdx.x < a.M) {
       uint32_t mm = 0;
 #pragma unroll
-      for (int w = 0; w < WAVES; ++w) mm = max(mm, s_part[m][w]);
+      for (int w = 0; w < WAVES; ++w) mm = max(mm, s_part[threadIdx.x][w]);
       // top bit set: an entry below the threshold exists and its pattern is mm + th (mod 2^16)
-      r_row[m] = (mm & 0x8000u) ? half_lo_to_float((mm + a.th) & 0xffffu) : 0.0f;
-      scale[m] = (r_row[m] == 0.0f) ? 0.0f : 127.0f / r_row[m];     // IEEE division
+      const float r = (mm & 0x8000u) ? half_lo_to_float((mm + a.th) & 0xffffu) : 0.0f;
+      s_r[threadIdx.x] = r;
+      s_scale[threadIdx.x] = (r == 0.0f) ? 0.0f : 127.0f / r;       // IEEE division
     }
+    __syncthreads();
   }
   park_x(0, xr[0], 0);
   park_x(1, xr[1], min(1, last));
@@ -297,7 +291,7 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
     for (int e = 0; e < 16; ++e) {
       const int m = mt * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
       if (m < a.M && n < a.N) {
-        const float rm = kPrep ? (m == 0 ? r_row[0] : r_row[1]) : a.r[m];
+        const float rm = kPrep ? s_r[m] : a.r[m];
         const float y = (float)acc[mt][e] * (rm * cs) + accf[mt][e] * step;
         if constexpr (kSplit)
           a.partial[((size_t)split * a.M + m) * a.N + n] = y;
@@ -458,7 +452,7 @@ static hipError_t launch_panel_cfg(const SkinnyArgs& a, int splits, hipStream_t 
 static hipError_t launch_panel(const SkinnyArgs& a, const SkinnyPlan& plan, hipStream_t stream) {
   const bool two = a.M > 32;
   if (a.X) {                                                         // the kernel prepares its own operands
-    if (two || a.M > kPanelPrepMaxM || plan.slabs_per_split > kPanelPrepMaxSlabs) return hipErrorInvalidValue;
+    if (two || !panel_prep_fits(a.M, plan)) return hipErrorInvalidValue;
     return plan.waves == 8 ? launch_panel_cfg<PanelCfg<1, 8>, true>(a, plan.splits, stream)
                            : launch_panel_cfg<PanelCfg<1, 4>, true>(a, plan.splits, stream);
   }

@@ -1,4 +1,4 @@
-"""One or two rows: the decode GEMM kernel prepares its own operands (row scales, codes, critical columns) and
+"""Up to eight rows: the decode GEMM kernel prepares its own operands (row scales, codes, critical columns) and
 the scan and pack kernels are left out.  The result must equal, bit for bit, the one obtained with those kernels
 (forced through the tuning hook, or by asking for their taps), the int32 accumulators must equal the oracle's, and
 the output must meet the oracle's to the fp16 bar; with every companion of the layer (bias, adapter, activation,
@@ -29,35 +29,40 @@ def case(M, K, N, seed, heavy):
     return wl.to_fp16(x), wl.gaussian_weight(K, N, 0.02, rng), wl.gaussian_bias(N, 0.3, rng), rng
 
 
-@pytest.mark.parametrize("M", [1, 2])
 @pytest.mark.parametrize("K,N", [(64, 8), (528, 264), (4096, 4096), (4096, 12288), (11008, 4096), (1040, 22016),
                                  (16448, 72), (65536, 32), (8192, 57344)])
-def test_own_preparation_equals_the_separate_kernels(M, K, N):
-    for rep, tau in enumerate([wl.TAU, 0.0, np.inf, 2.0]):
-        X, W, b, _ = case(M, K, N, rep, heavy=bool(rep % 2))
-        if rep == 2:
-            X[M - 1] = 0                                             # a zero row: scale 0
-        pw = binding.prequantize_weight(to_gpu(W))
-        Xbuf = torch.zeros((M, K + 8), dtype=torch.float16, device="cuda")
-        Xg = Xbuf[:, :K]
-        Xg.copy_(to_gpu(X))
-        bg = to_gpu(b)
-        Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))      # own preparation + accumulators
-        Y_taps, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)        # scan + pack (their taps asked for)
-        binding.lib().mmd8_set_panel_prep(0)
-        Y_off = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                          # scan + pack (hook)
-        binding.lib().mmd8_set_panel_prep(1)
-        torch.cuda.synchronize()
-        assert torch.equal(Y, Y_off) and torch.equal(Y, Y_taps), (M, K, N, tau)
-        assert torch.equal(t_acc["acc"], taps["acc"])
-        if K * N <= 4096 * 4096:
-            Wq_o, c_o = ml.prequantize_weight(W)
-            o = ml.mixed_int8_linear(X, Wq_o, c_o, tau, b)
-            assert np.array_equal(to_np(t_acc["acc"]), o["acc"])
-            assert_y_close(to_np(Y), o["Y"])
+def test_own_preparation_equals_the_separate_kernels(K, N):
+    rng = np.random.default_rng([K, N])
+    W = wl.gaussian_weight(K, N, 0.02, rng)
+    b = wl.gaussian_bias(N, 0.3, rng)
+    pw = binding.prequantize_weight(to_gpu(W))
+    bg = to_gpu(b)
+    with_oracle = K * N <= 4096 * 4096
+    if with_oracle:
+        Wq_o, c_o = ml.prequantize_weight(W)
+    for M in (1, 2, 3, 5, 8):
+        for rep, tau in enumerate([wl.TAU, 0.0, np.inf, 2.0]):
+            X = case(M, K, 8, rep, heavy=bool(rep % 2))[0]
+            if rep == 2:
+                X[M - 1] = 0                                         # a zero row: scale 0
+            Xbuf = torch.zeros((M, K + 8), dtype=torch.float16, device="cuda")
+            Xg = Xbuf[:, :K]
+            Xg.copy_(to_gpu(X))
+            Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))   # own preparation + accumulators
+            Y_taps, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)     # scan + pack (their taps asked for)
+            binding.lib().mmd8_set_panel_prep(0)
+            Y_off = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                       # scan + pack (hook)
+            binding.lib().mmd8_set_panel_prep(1)
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y_off) and torch.equal(Y, Y_taps), (M, K, N, tau)
+            assert torch.equal(t_acc["acc"], taps["acc"]), (M, K, N, tau)
+            if with_oracle:
+                o = ml.mixed_int8_linear(X, Wq_o, c_o, tau, b)
+                assert np.array_equal(to_np(t_acc["acc"]), o["acc"])
+                assert_y_close(to_np(Y), o["Y"])
 
 
-@pytest.mark.parametrize("M", [1, 2])
+@pytest.mark.parametrize("M", [1, 2, 4, 7, 8])
 def test_companions_of_the_layer(M):
     K, N = 2048, 1024
     X, W, b, rng = case(M, K, N, 7, heavy=True)
