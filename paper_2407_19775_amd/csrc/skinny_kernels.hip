@@ -221,25 +221,43 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
       reinterpret_cast<v4u*>(&s_x[0][0])[i] = v4u{0, 0, 0, 0};
     for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) s_any[t] = 0;
     const us2 th2 = __builtin_bit_cast(us2, a.th | (a.th << 16));
-    for (int m = 0; m < a.M; ++m) {
-      us2 best = __builtin_bit_cast(us2, 0u);
-      const uint16_t* row = a.X + (size_t)m * a.ldx;
-      for (int c = threadIdx.x; c < a.K / 8; c += Cfg::kThreads) {
-        const v4u raw = *reinterpret_cast<const v4u*>(row + c * 8);
+    // rows innermost, so that the loads of all rows are in flight together
+    us2 best[kPanelPrepMaxM];
+#pragma unroll
+    for (int m = 0; m < kPanelPrepMaxM; ++m) best[m] = __builtin_bit_cast(us2, 0u);
+    for (int c = threadIdx.x; c < a.K / 8; c += Cfg::kThreads) {
+      v4u raw[kPanelPrepMaxM];
+#pragma unroll
+      for (int m = 0; m < kPanelPrepMaxM; ++m) {
+        raw[m] = v4u{0, 0, 0, 0};
+        if (m < a.M) raw[m] = *reinterpret_cast<const v4u*>(a.X + (size_t)m * a.ldx + c * 8);
+      }
+#pragma unroll
+      for (int m = 0; m < kPanelPrepMaxM; ++m)
 #pragma unroll
         for (int w = 0; w < 4; ++w)   // per half, wraps mod 2^16: entries below the threshold get the top bit
-          best = __builtin_elementwise_max(best, (us2)(__builtin_bit_cast(us2, raw[w] & 0x7fff7fffu) - th2));
+          best[m] = __builtin_elementwise_max(best[m], (us2)(__builtin_bit_cast(us2, raw[m][w] & 0x7fff7fffu) - th2));
+    }
+    // this workgroup's columns (the K padding reads as zero)
+    for (int c = threadIdx.x; c < cnt * (kSlabBytes / 8); c += Cfg::kThreads) {
+      const int k = s_begin * kSlabBytes + c * 8;
+      v4u raw[kPanelPrepMaxM];
+#pragma unroll
+      for (int m = 0; m < kPanelPrepMaxM; ++m) {
+        raw[m] = v4u{0, 0, 0, 0};
+        if (m < a.M && k < a.K) raw[m] = *reinterpret_cast<const v4u*>(a.X + (size_t)m * a.ldx + k);
       }
-      // this workgroup's columns (the K padding reads as zero)
-      for (int c = threadIdx.x; c < cnt * (kSlabBytes / 8); c += Cfg::kThreads) {
-        const int k = s_begin * kSlabBytes + c * 8;
-        v4u raw = v4u{0, 0, 0, 0};
-        if (k < a.K) raw = *reinterpret_cast<const v4u*>(row + k);
-        *reinterpret_cast<v4u*>(&s_row[m * row_stride + c * 8]) = raw;
+#pragma unroll
+      for (int m = 0; m < kPanelPrepMaxM; ++m)
+        if (m < a.M) *reinterpret_cast<v4u*>(&s_row[m * row_stride + c * 8]) = raw[m];
+    }
+#pragma unroll
+    for (int m = 0; m < kPanelPrepMaxM; ++m) {
+      if (m < a.M) {                                                  // the same for every lane
+        const uint32_t both = __builtin_bit_cast(uint32_t, best[m]);
+        const uint32_t wmax = wave_max_u32(max(both & 0xffffu, both >> 16));
+        if (lane == 0) s_part[m][wave] = wmax;
       }
-      const uint32_t both = __builtin_bit_cast(uint32_t, best);
-      const uint32_t wmax = wave_max_u32(max(both & 0xffffu, both >> 16));
-      if (lane == 0) s_part[m][wave] = wmax;
     }
     __syncthreads();
     for (int c = threadIdx.x; c < row_stride; c += Cfg::kThreads) {
