@@ -79,6 +79,15 @@ def test_random_layer(seed):
     assert_y_close(to_np(Yg), o["Y"])
     if c["pad_y"]:
         assert torch.all(ybuf[:, N:] == 7.0), "columns past N were written"
+    # without the taps the library may take shortcuts (up to 8 rows the decode kernel prepares its own operands):
+    # the output must not change by a bit
+    y_tapped = Yg.clone()
+    if c["mode"] == "coded":
+        Xg.zero_()
+    Yg.fill_(0)
+    binding.mixed_int8_linear(Xg, pw, tau, bias=bg, out=Yg, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(Yg, y_tapped), "output differs without taps"
 
 
 @pytest.mark.parametrize("seed", range(24))
