@@ -112,7 +112,7 @@ def cpu_baseline(wl, passes=4):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        print("bench.py measures one GPU: this library has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
@@ -297,7 +297,7 @@ def main():
         # whole decoder layers at 1 and 64 tokens, wall time of back-to-back calls (no events in between):
         # all four layers' weights in turn, 810 MB of codes per pass
         layer_bytes = float(sum(s.K * s.N for s in shapes))
-        for Md in (1, 64):
+        for Md in (1, 8, 64):
             Xd = {K: torch.from_numpy(wl.decode_activation(Md, Md, K)).to(dev) for K in sorted({s.K for s in shapes})}
             Yd = {s.name: torch.empty((Md, s.N), dtype=torch.float16, device=dev) for s in shapes}
             wsd = binding.linear_workspace(Md, biggest.K, biggest.N, dev)
