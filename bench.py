@@ -357,8 +357,17 @@ def main():
                 torch.add(Yb, Rb, out=Hb)
                 binding.quantize_blockwise(Hb, block, codes=cb, absmax=ab)
 
+            def with_residual():                  # the same linear inside the shard: residual added, fp16 out
+                binding.mixed_int8_linear(Xb, weights[0][-1], wl.TAU, out=Hb, workspace=wsb, residual=Rb)
+
+            def layer_then_add():
+                binding.mixed_int8_linear(Xb, weights[0][-1], wl.TAU, out=Yb, workspace=wsb)
+                torch.add(Yb, Rb, out=Hb)
+
             boundary_exit["M%d" % Mb] = {"one_call_us": round(timed(fused, 30) * 1e3, 1),
-                                         "three_steps_us": round(timed(separate, 30) * 1e3, 1), "block": block}
+                                         "three_steps_us": round(timed(separate, 30) * 1e3, 1), "block": block,
+                                         "residual_one_call_us": round(timed(with_residual, 30) * 1e3, 1),
+                                         "residual_two_steps_us": round(timed(layer_then_add, 30) * 1e3, 1)}
 
         # ---- ViT-L-shaped block (width 1024, 8 images x 197 tokens, bias everywhere): the four linears, the first
         # MLP linear with GELU applied in its own kernels against the same layer followed by a separate fp16

@@ -161,6 +161,20 @@ int mmd8_mixed_int8_linear_gelu(const mmd8_half* X /*DEVICE*/, int M, int K, int
                                 void* workspace /*DEVICE*/, size_t workspace_bytes,
                                 const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* The same layer added onto a residual stream (the attention output projection and the second MLP linear of
+ * a transformer block), in the kernel that writes the output:
+ *     Y[m,n] = f16( f16(the three terms of mmd8_mixed_int8_linear) + residual[m,n] )        an fp16 addition
+ * as the layer followed by an fp16 addition gives.  residual: DEVICE [M][ldr] fp16, 16-byte aligned, ldr >= N,
+ * ldr % 8 == 0; it may be the very buffer Y (with ldr == ldy): the stream is then updated in place.  Other
+ * arguments, requirements, workspace and errors as for mmd8_mixed_int8_linear. */
+int mmd8_mixed_int8_linear_residual(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                    const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                    const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                    const mmd8_half* residual /*DEVICE [M][ldr]*/, int ldr,
+                                    mmd8_half* Y /*DEVICE*/, int ldy,
+                                    void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                    const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* The same layer with its result leaving in blockwise-coded form (the hidden state a shard hands to its
  * successor: "Compression techniques", item 2 feeding item 1):
  *     Y = mixed_int8_linear(X, ...)                           fp16, as above

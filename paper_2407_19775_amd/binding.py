@@ -20,7 +20,7 @@ EXPORTS = (
     "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
     "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
     "mmd8_mixed_int8_linear_lora", "mmd8_linear_to_codes_workspace_bytes", "mmd8_mixed_int8_linear_to_codes",
-    "mmd8_mixed_int8_linear_gelu",
+    "mmd8_mixed_int8_linear_gelu", "mmd8_mixed_int8_linear_residual",
 )
 
 
@@ -64,6 +64,8 @@ def lib():
         L.mmd8_mixed_int8_linear_lora.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, sz,
                                                   ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_gelu.argtypes = L.mmd8_mixed_int8_linear.argtypes
+        L.mmd8_mixed_int8_linear_residual.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, i32, vp, sz,
+                                                      ctypes.POINTER(DebugTaps), vp]
         L.mmd8_linear_to_codes_workspace_bytes.restype = sz
         L.mmd8_linear_to_codes_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.mmd8_mixed_int8_linear_to_codes.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, i32, vp, vp, vp, vp, sz,
@@ -233,8 +235,9 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
-                      events=None, coded=None, lora=None, gelu: bool = False):
+                      events=None, coded=None, lora=None, gelu: bool = False, residual: torch.Tensor = None):
     """Y = X W through the mixed decomposition (gelu=True: followed by the exact GELU, in the same kernels).
+    residual: fp16 [M, N] added to the output as an fp16 addition, in the same kernels (may be `out` itself).
     taps: True for every intermediate, or a tuple of tap names.  With taps=True also returns a dict of the
     intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx).
     coded=(codes, absmax, block): the activations arrive blockwise-coded; X is then the contiguous
@@ -253,6 +256,12 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
         raise Mmd8Error("coded activations and an adapter cannot be combined in one call")
     if gelu and (coded is not None or lora is not None):
         raise Mmd8Error("the activation cannot be combined with coded activations or an adapter in one call")
+    if residual is not None:
+        if gelu or coded is not None or lora is not None:
+            raise Mmd8Error("the residual cannot be combined with an activation, coded activations or an adapter in one call")
+        _dev(residual, torch.float16, "residual")
+        if residual.shape != (M, N) or residual.stride(1) != 1:
+            raise Mmd8Error("residual must be [M, N] with unit stride along N")
     if workspace is None:
         workspace = linear_workspace(M, K, N, X.device, lora[0].shape[0] if lora is not None else 0)
     tp, tensors = None, None
@@ -286,6 +295,13 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
             X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
             bias.data_ptr() if bias is not None else None, float(tau), A.data_ptr(), B.data_ptr(), int(r),
             T_out.data_ptr() if T_out is not None else None, out.data_ptr(), out.stride(0) if M > 0 else N,
+            workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
+        return (out, tensors) if taps else out
+    if residual is not None:
+        _check(lib().mmd8_mixed_int8_linear_residual(
+            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+            bias.data_ptr() if bias is not None else None, float(tau), residual.data_ptr(),
+            residual.stride(0) if M > 0 else N, out.data_ptr(), out.stride(0) if M > 0 else N,
             workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
     fn = lib().mmd8_mixed_int8_linear_gelu if gelu else lib().mmd8_mixed_int8_linear

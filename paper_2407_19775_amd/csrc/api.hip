@@ -220,10 +220,10 @@ int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* st
              : MMD8_E_HIP;
 }
 
-struct CodedExit {   // the output leaving in blockwise-coded form, with an optional residual added first
+struct CodedExit {   // a residual added to the output and / or the output leaving in blockwise-coded form
   const mmd8_half* residual;   // [M][ldr] or null
   int ldr;
-  int block;
+  int block;                   // 0: the output is not encoded (codes and absmax unused)
   uint8_t* codes;              // [M N]
   float* absmax;               // [ceil(M N / block)]
 };
@@ -250,7 +250,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (M == 0) return MMD8_OK;
   if (!X || !Wq_packed || !col_absmax || (!Y && !exit) || !workspace) return MMD8_E_ARG;
   if (ldx < K || ldy < N || (ldx % 8) != 0 || (ldy % 8) != 0) return MMD8_E_ARG;
-  if (exit && (!exit->codes || !exit->absmax || !aligned(exit->codes, 16) || !aligned(exit->absmax, 4) || ldy != N ||
+  if (exit && exit->block > 0 &&
+      (!exit->codes || !exit->absmax || !aligned(exit->codes, 16) || !aligned(exit->absmax, 4) || ldy != N))
+    return MMD8_E_ARG;
+  if (exit && ((exit->block == 0 && (!exit->residual || !Y)) ||
                (exit->residual && (exit->ldr < N || (exit->ldr % 8) != 0 || !aligned(exit->residual, 16)))))
     return MMD8_E_ARG;
   if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(Wq_packed, 256) || !aligned(workspace, 256) ||
@@ -263,8 +266,9 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   const Workspace ws = carve(workspace, M, K, N, lora ? lora->r : 0, exit ? exit->block : 0);
   if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
   // a coded output is written by the layer's last kernel where that is possible, otherwise by the encoder after it
-  const bool exit_fused = exit && exit_fuses(M, N, exit->block);
-  if (exit && !exit_fused && !Y) Y = ws.h;
+  const bool encodes = exit && exit->block > 0;
+  const bool exit_fused = encodes && exit_fuses(M, N, exit->block);
+  if (encodes && !exit_fused && !Y) Y = ws.h;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int Kpad = packed_k(K);
@@ -413,7 +417,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     }
     if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
   }
-  if (exit && !exit_fused &&
+  if (encodes && !exit_fused &&
       launch_quantize_blockwise(Y, (size_t)M * N, exit->block, exit->codes, exit->absmax, st) != hipSuccess)
     return MMD8_E_HIP;
   if (!record(t.event_gemm_end)) return MMD8_E_HIP;
@@ -433,6 +437,15 @@ int mmd8_mixed_int8_linear_gelu(const mmd8_half* X, int M, int K, int ldx, const
                                 void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, nullptr, nullptr, stream, true);
+}
+
+int mmd8_mixed_int8_linear_residual(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
+                                    const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                    const mmd8_half* residual, int ldr, mmd8_half* Y, int ldy, void* workspace,
+                                    size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  const CodedExit exit = {residual, ldr, 0, nullptr, nullptr};
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+                    workspace_bytes, taps, nullptr, nullptr, &exit, stream);
 }
 
 size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block) {

@@ -332,8 +332,8 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
                                                          const uint16_t* __restrict__ bias,
                                                          const uint16_t* __restrict__ T, int ldt,
                                                          const uint16_t* __restrict__ B, int r,
-                                                         const uint16_t* __restrict__ residual, int ldr, int gelu,
-                                                         uint16_t* __restrict__ Y, int ldy) {
+                                                         const uint16_t* residual /* may alias Y */, int ldr, int gelu,
+                                                         uint16_t* Y, int ldy) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)M * N) return;
   const int m = (int)(i / N), n = (int)(i % N);

@@ -156,3 +156,16 @@ def test_coded_output_arguments_are_rejected_before_any_launch():
     assert call(res=fake, ldr=56) == -1 and call(res=fake, ldr=68) == -1 and call(res=odd) == -1
     assert call(H=odd) == -1
     assert call(wsb_=ws - 256) == -3
+
+
+def test_residual_arguments_are_rejected_before_any_launch():
+    L = binding.lib()
+    fake, y = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    odd = ctypes.c_void_p(0x1008)
+    ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
+
+    def call(res=fake, ldr=64, Y=y, K=128):
+        return L.mmd8_mixed_int8_linear_residual(fake, 8, K, 128, fake, fake, 64, None, 6.0, res, ldr, Y, 64, fake, ws, None, None)
+
+    assert call(res=None) == -1 and call(res=odd) == -1 and call(ldr=56) == -1 and call(ldr=68) == -1
+    assert call(Y=None) == -1 and call(K=100) == -2
