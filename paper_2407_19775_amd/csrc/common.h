@@ -56,17 +56,17 @@ __device__ inline uint32_t to_code_byte(float x, float scale) {
 // form keeps the negative tail accurate, where x Phi(x) is tiny but not zero.
 __device__ inline uint32_t gelu_to_half_bits(float x) {
   const float z = __builtin_fabsf(x) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(1.0f + 0.5f * z);
-  float g = 8.510084172e-02f;
-  g = g * t + -5.867012528e-01f;
-  g = g * t + 1.540184314e+00f;
-  g = g * t + -1.856008460e+00f;
-  g = g * t + 9.031074855e-01f;
-  g = g * t + -2.573335189e-01f;
-  g = g * t + 4.445369191e-01f;
-  g = g * t + 9.922661813e-01f;
-  g = g * t + -1.265152659e+00f;
-  const float q = 0.5f * t * __builtin_amdgcn_exp2f((g - z * z) * 1.4426950408889634f);   // Phi(-|x|)
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.5f, z, 1.0f));
+  float g = 8.510084172e-02f;                                        // Horner, fused multiply-adds
+  g = __builtin_fmaf(g, t, -5.867012528e-01f);
+  g = __builtin_fmaf(g, t, 1.540184314e+00f);
+  g = __builtin_fmaf(g, t, -1.856008460e+00f);
+  g = __builtin_fmaf(g, t, 9.031074855e-01f);
+  g = __builtin_fmaf(g, t, -2.573335189e-01f);
+  g = __builtin_fmaf(g, t, 4.445369191e-01f);
+  g = __builtin_fmaf(g, t, 9.922661813e-01f);
+  g = __builtin_fmaf(g, t, -1.265152659e+00f);
+  const float q = 0.5f * t * __builtin_amdgcn_exp2f(__builtin_fmaf(-z, z, g) * 1.4426950408889634f);   // Phi(-|x|)
   return float_to_half_bits(x * (x < 0.0f ? q : 1.0f - q));
 }
 __device__ inline uint32_t gelu_half_pair(uint32_t w) {

@@ -2,7 +2,8 @@
 
 erfc(z) = t exp(-z^2 + g(t)) with t = 1 / (1 + z / 2): g(t) = ln(exp(z^2) erfc(z) / t) is smooth on (0, 1], and a
 Chebyshev fit of degree 8 on the t range that |x| <= 13.5 maps to (z = |x| / sqrt 2) is converted to a power
-series.  The error is measured on the kernel's own arithmetic: float32, Horner with separate multiply and add.
+series.  The error is measured on the kernel's own arithmetic: float32, Horner with fused multiply-adds (emulated
+here as a float64 product and sum rounded once to float32).
 Run: python gelu_coefficients.py"""
 import numpy as np
 from scipy.special import erfc, erfcx   # erfcx(z) = exp(z^2) erfc(z)
@@ -26,12 +27,15 @@ def fit():
 def error(coef):
     f = np.float32
     x = np.linspace(0.0, X_MAX, 200001)
+    def fma(a, b, c):
+        return (a.astype(np.float64) * np.asarray(b, np.float64) + np.asarray(c, np.float64)).astype(f)
+
     z = (x.astype(f) * f(0.70710678118654752)).astype(f)
-    t = (f(1) / (f(1) + f(0.5) * z)).astype(f)
+    t = (f(1) / fma(z, f(0.5), f(1))).astype(f)
     g = np.full_like(t, f(coef[-1]))
     for c in coef[-2::-1]:
-        g = (g * t).astype(f) + f(c)
-    arg = (g - (z * z).astype(f)).astype(f)
+        g = fma(g, t, f(c))
+    arg = fma(-z, z, g)
     got = (t * np.exp(arg.astype(np.float64))).astype(f)
     ref = erfc(x / np.sqrt(2.0))
     rel = np.abs(got - ref) / ref
