@@ -9,6 +9,11 @@ measured (study_row_scale.py); neither is built on the GPU.
   non_critical    r[m] = max{ |X[m,k]| : column k not critical }           needs the flags of all rows first
   all             r[m] = max_k |X[m,k]|                                     plain row absmax: outliers set the scale
 
+And two readings of where the 16-bit weights of the critical dimensions come from:
+
+  dequantized     f16(Wq[k,n] c[n] / 127) re-created from the 8-bit codes      the library's reading: 1 byte per weight
+  master          the original fp16 W[k,n]                                     needs a second, fp16 copy of W (3 bytes)
+
 Entries of a critical column never reach the 8-bit product, so the first two differ only through
 sub-threshold entries that sit in critical columns: non_critical <= sub_threshold <= all, elementwise.
 """
@@ -30,9 +35,10 @@ def row_scale(X: np.ndarray, tau: float, reading: str) -> np.ndarray:
     return np.max(ax[:, keep], axis=1, initial=np.float32(0.0)).astype(np.float32)
 
 
-def mixed_int8_linear_with_row_scale(X, Wq, c, tau, reading, bias=None):
+def mixed_int8_linear_with_row_scale(X, Wq, c, tau, reading, bias=None, master_W=None):
     """The layer of mixed_linear.mixed_int8_linear with the row scale of `reading`; same steps otherwise
-    (codes, exact integer product, outer-product dequantization, fp16 product on the critical columns)."""
+    (codes, exact integer product, outer-product dequantization, fp16 product on the critical columns).
+    master_W: the original fp16 weights [K, N]; if given, their rows multiply the critical columns."""
     flag = ml.outlier_mask(X, tau)
     r = row_scale(X, tau, reading)
     Xq = ml.quantize_activations(X, flag, r)
@@ -40,7 +46,8 @@ def mixed_int8_linear_with_row_scale(X, Wq, c, tau, reading, bias=None):
     Y64 = acc.astype(np.float64) * r.astype(np.float64)[:, None] * c.astype(np.float64)[None, :] / 16129.0
     idx = np.flatnonzero(flag)
     if idx.size:
-        Wt = ml.dequantized_weight_fp16(Wq[idx, :], c)
+        Wt = ml.dequantized_weight_fp16(Wq[idx, :], c) if master_W is None else master_W[idx, :]
+        assert Wt.dtype == np.float16
         Y64 = Y64 + X[:, idx].astype(np.float64) @ Wt.astype(np.float64)
     if bias is not None:
         Y64 = Y64 + bias.astype(np.float64)[None, :]

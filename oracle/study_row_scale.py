@@ -1,7 +1,8 @@
 """What the reading of the row scale costs in accuracy (CPU only; prints a table).  python -m oracle.study_row_scale
 
 Output error of the int8 layer, as the relative Frobenius distance to the exact product of X with the fp16
-weights, for the three row scales of readings.py, for the pure 8-bit layer (no critical columns: tau = inf) and
+weights, for the three row scales of readings.py, for critical weight rows taken from an fp16 master copy instead of the
+codes, for the pure 8-bit layer (no critical columns: tau = inf) and
 for the fp16 rounding of the exact result alone.  Inputs as in the parity workloads: Gaussian activations with a
 few feature dimensions scaled by 8-60 (the prefill recipe), and Student-t(3) activations (the decode recipe)."""
 import numpy as np
@@ -37,6 +38,8 @@ def main():
         for reading in rd.ROW_SCALES:
             o = rd.mixed_int8_linear_with_row_scale(X, Wq, c, tau, reading)
             rows.append(("mixed, r = " + reading, np.linalg.norm(o["Y64"] - exact) / norm, float(o["r"].mean())))
+        o = rd.mixed_int8_linear_with_row_scale(X, Wq, c, tau, "sub_threshold", master_W=W)
+        rows.append(("mixed, fp16 master rows", np.linalg.norm(o["Y64"] - exact) / norm, float(o["r"].mean())))
         o = rd.mixed_int8_linear_with_row_scale(X, Wq, c, np.inf, "all")
         rows.append(("8-bit only (tau = inf)", np.linalg.norm(o["Y64"] - exact) / norm, float(o["r"].mean())))
         crit = int(ml.outlier_mask(X, tau).sum())

@@ -45,3 +45,19 @@ def test_scales_are_ordered_and_meet_where_they_must():
     X1 = X0.copy()
     X1[:, 9] = np.float16(50.0)
     assert np.array_equal(rd.row_scale(X1, 6.0, "sub_threshold"), rd.row_scale(X1, 6.0, "non_critical"))
+
+
+def test_master_rows_make_tau_zero_the_exact_fp16_product():
+    # every column critical: with the original rows the layer is X W exactly (rounded once); with the re-created
+    # rows it is X times the dequantized weights, within c / 254 * sum |x| of it
+    rng = np.random.default_rng(5)
+    X = wl.to_fp16(rng.standard_normal((7, 64)).astype(np.float32))
+    W = wl.to_fp16(rng.standard_normal((64, 24)).astype(np.float32) * 0.05)
+    Wq, c = ml.prequantize_weight(W)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    a = rd.mixed_int8_linear_with_row_scale(X, Wq, c, 0.0, "sub_threshold", master_W=W)
+    assert np.array_equal(a["Y"], exact.astype(np.float16)) and not a["acc"].any()
+    b = rd.mixed_int8_linear_with_row_scale(X, Wq, c, 0.0, "sub_threshold")
+    bound = (c.astype(np.float64) / 254.0)[None, :] * np.abs(X.astype(np.float64)).sum(axis=1)[:, None]
+    assert np.all(np.abs(b["Y64"] - exact) <= bound * (1 + 2.0 ** -9) + 1e-12)
+    assert np.any(b["Y"] != a["Y"])
