@@ -185,3 +185,12 @@ def test_monotone_and_power_of_two_scale_invariant():
         # scaling by 2^j is exact unless a value drops into the fp16 subnormal range
         normal = np.abs(x.astype(np.float32)) * 2.0 ** min(j, 0) >= 2.0 ** -14
         assert np.array_equal(cs[normal], codes[normal])
+
+
+def test_block_scales_are_fp16_numbers():
+    # a block's absmax is the magnitude of one of its fp16 elements: keeping it in 2 bytes instead of 4 would
+    # lose nothing (the library stores fp32; the note in the design document gives the byte counts)
+    rng = np.random.default_rng(11)
+    x = (rng.standard_t(3.0, size=5000) * 7.0).astype(np.float16)
+    _, a = bc.quantize_blockwise(x, 64)
+    assert np.array_equal(a, a.astype(np.float16).astype(np.float32))
