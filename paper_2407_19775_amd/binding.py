@@ -74,6 +74,7 @@ def lib():
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
         L.mmd8_set_gemm_variant.argtypes = [i32]
         L.mmd8_set_panel_prep.argtypes = [i32]
+        L.mmd8_set_rows_kernel.argtypes = [i32]
         _lib = L
     return _lib
 

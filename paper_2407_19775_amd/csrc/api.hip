@@ -80,7 +80,7 @@ struct Workspace {
   size_t bytes;
 };
 // r: rank of an adapter (0: none).  exit_block: block size of a coded output (0: plain output).
-static bool exit_fuses(int M, int N, int block);
+static bool exit_fuses(int M, int K, int N, int block);
 static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_block = 0) {
   const size_t Kpad = packed_k(K), Mpad = packed_n(M), Npad = packed_n(N);
   Workspace w;
@@ -118,20 +118,23 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_bloc
     if (lb) w.lora_part = reinterpret_cast<float*>(take(lb));
   }
   w.h = nullptr;
-  if (exit_block > 0 && M > 0 && !exit_fuses(M, N, exit_block)) w.h = reinterpret_cast<uint16_t*>(take((size_t)M * N * 2));
+  if (exit_block > 0 && M > 0 && !exit_fuses(M, K, N, exit_block)) w.h = reinterpret_cast<uint16_t*>(take((size_t)M * N * 2));
   w.bytes = off;
   return w;
 }
 // A coded output is produced by the kernel that ends the layer when no block of it is shared between
 // workgroups: the tiled GEMM needs blocks inside its 256-column tiles; the decode path encodes where it sums
-// its partial outputs, any block size, as long as its second pass of 64 rows starts on a block boundary.
-static bool exit_fuses(int M, int N, int block) {
+// its partial outputs, any block size, as long as its second pass of 64 rows starts on a block boundary.  One or
+// two rows are a single kernel with 32 columns per workgroup and nothing to sum afterwards: the encoder follows it.
+static bool exit_fuses(int M, int K, int N, int block) {
+  if (rows_kernel_fits(M, packed_k(K))) return false;
   if (M <= kSkinnyChunkedMaxM) return M <= kSkinnyMaxM || ((size_t)kSkinnyMaxM * N) % block == 0;
   return (block == 64 || block == 128 || block == 256) && N % block == 0;
 }
 
 static int g_gemm_variant = -1;
 static bool g_panel_prep = true;
+static bool g_rows_kernel = true;
 
 }  // namespace mmd8
 
@@ -267,7 +270,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (workspace_bytes < ws.bytes) return MMD8_E_WORKSPACE;
   // a coded output is written by the layer's last kernel where that is possible, otherwise by the encoder after it
   const bool encodes = exit && exit->block > 0;
-  const bool exit_fused = encodes && exit_fuses(M, N, exit->block);
+  const bool exit_fused = encodes && exit_fuses(M, K, N, exit->block);
   if (encodes && !exit_fused && !Y) Y = ws.h;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -288,7 +291,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // A few rows (at most kPanelPrepMaxM): the decode GEMM kernel prepares its own operands (scales, codes, critical
   // columns) from X, and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
-  const bool own_prep = skinny && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
+  // One or two rows without an adapter: the whole layer is one kernel (k_gemm_rows).  When the taps of the
+  // preparation are asked for, the scan and pack kernels run ahead of it for their sake only.
+  const bool rows_path = g_panel_prep && g_rows_kernel && rows_kernel_fits(M, Kpad) && !lora;
+  const bool own_prep = skinny && !rows_path && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K);
@@ -301,7 +307,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, fused_decode ? coded : nullptr,
                     st) != hipSuccess)
       return MMD8_E_HIP;
-  } else if (!own_prep) {
+  } else if (!own_prep && (!rows_path || wants_prep_taps)) {
     if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
     // (the decode kernels' operands are packed 64 rows at a time, below)
     if (!skinny && launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, nullptr, po, st) != hipSuccess)
@@ -330,7 +336,33 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     if (launch_lora_down(l, plan_lora(M, K), ws.lora_part, st) != hipSuccess) return MMD8_E_HIP;
   }
 
-  if (skinny) {
+  if (rows_path) {   // (a coded output: the encoder follows)
+    if (wants_prep_taps &&
+        launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, ws.xf, po, st) != hipSuccess)
+      return MMD8_E_HIP;
+    if (!record(t.event_gemm_begin)) return MMD8_E_HIP;
+    SkinnyArgs g = {};
+    g.flag_reset = wants_prep_taps ? ws.flag : nullptr;               // the scan set them
+    g.Wt = Wq_packed;
+    g.M = M;
+    g.N = N;
+    g.Kpad = Kpad;
+    g.c = col_absmax;
+    g.bias = bias;
+    g.Y = Y;
+    g.ldy = ldy;
+    g.tap_acc = t.acc;
+    g.gelu = gelu ? 1 : 0;
+    if (exit) {
+      g.residual = exit->residual;
+      g.ldr = exit->ldr;
+    }
+    g.X = X;
+    g.ldx = ldx;
+    g.K = K;
+    g.th = threshold_pattern(tau);
+    if (launch_gemm_rows(g, st) != hipSuccess) return MMD8_E_HIP;
+  } else if (skinny) {
     const SkinnyPlan plan = plan_skinny(M < kSkinnyMaxM ? M : kSkinnyMaxM, K, N);
     for (int row0 = 0; row0 < M; row0 += kSkinnyMaxM) {
       const int Mc = M - row0 < kSkinnyMaxM ? M - row0 : kSkinnyMaxM;
@@ -493,5 +525,7 @@ void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
 void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
 // ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for a few rows)
 void mmd8_set_panel_prep(int on) { g_panel_prep = on != 0; }
+// ... and: 0 = never use the one-kernel form for one or two rows
+void mmd8_set_rows_kernel(int on) { g_rows_kernel = on != 0; }
 
 }  // extern "C"

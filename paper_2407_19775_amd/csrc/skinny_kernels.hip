@@ -508,4 +508,245 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   return e;
 }
 
+// ------------------------------------------------------------------------------------------------
+// One or two rows: the whole layer in one kernel.  A workgroup owns 32 output columns (one 32-row group of
+// Wt); wave w of its eight takes slabs w, w + 8, ... of the K range, straight from HBM into registers four
+// slabs ahead, with no barrier in the loop: the activation side is read-only by then.  It is made once per
+// workgroup, for the whole of K, as in the kPrep panel kernel (row scales from a pass over the rows, then
+// codes with the critical columns zero and an fp16 copy that keeps only them), stored as plain rows in LDS;
+// a lane builds its MFMA fragment from the row it stands for and lanes beyond M feed zeros.  The eight partial
+// results meet in LDS: the int32 sums are exact, the fp32 sums of the 16-bit part are added in wave order, so
+// the output does not depend on timing.  No split between workgroups, hence no partial outputs in HBM and no
+// second kernel.
+// ------------------------------------------------------------------------------------------------
+// kGroups: 32-column groups per workgroup.  Only 1 is used: with 2 (meant for shapes with more groups than the chip
+// holds workgroups at once, 688 for the 4096 -> 22016 linear) the weight prefetch has to shrink to two slabs for the
+// registers, and that linear took 29.9 us instead of 21.6.
+template <bool kTap, int kGroups>
+__global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
+  constexpr int WAVES = 8, kThreads = WAVES * kWave, kAhead = kGroups == 1 ? 4 : 2;
+  extern __shared__ __attribute__((aligned(16))) int8_t s_ops[];     // [M][Kpad] codes, then [M][Kpad] fp16
+  __shared__ uint8_t s_any[MMD8_MAX_K / kSlabBytes];
+  __shared__ uint32_t s_part[kRowsMaxM][WAVES];
+  __shared__ float s_r[kRowsMaxM], s_scale[kRowsMaxM];
+  __shared__ uint8_t s_over[kRowsMaxM][kRowsMaxOperandBytes / 3 / 8];   // per 8-column chunk of a row: bits "at or above the threshold"
+  __shared__ int32_t s_acc[WAVES][kRowsMaxM][32 * kGroups];
+  __shared__ float s_accf[WAVES][kRowsMaxM][32 * kGroups];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int lr = lane & 31, lg = lane >> 5;
+  const int n_slabs = a.n_slabs, Kpad = n_slabs * kSlabBytes;
+  reset_column_flags(a.flag_reset, Kpad);
+  const int n0 = blockIdx.x * 32 * kGroups;
+  int8_t* s_code = s_ops;
+  uint16_t* s_xf = reinterpret_cast<uint16_t*>(s_ops + (size_t)a.M * Kpad);
+
+  const int mine = wave < n_slabs ? (n_slabs - wave + WAVES - 1) / WAVES : 0;   // slabs of this wave
+  const int8_t* wgrp[kGroups];
+#pragma unroll
+  for (int g = 0; g < kGroups; ++g) {
+    const int ng = n0 + 32 * g;                                       // < Npad: the grid covers whole groups only
+    wgrp[g] = a.Wt + (size_t)(ng >> 8) * n_slabs * kBlockBytes + (size_t)((ng & 255) >> 5) * 2048 + lane * 16;
+  }
+  struct W2 {
+    v4i w[kGroups][2];
+  };
+  auto fetch_w = [&](int i, W2& f) {                                  // this wave's i-th slab (clamped past the end)
+    const int slab = wave + WAVES * min(i, max(mine - 1, 0));
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      const int8_t* p = wgrp[g] + (size_t)min(slab, n_slabs - 1) * kBlockBytes;
+      f.w[g][0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+      f.w[g][1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p + 1024));
+    }
+  };
+  W2 f[kAhead];
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) fetch_w(i, f[i]);
+
+  // ---- the activation side, once per workgroup (the weight requests above are in flight meanwhile).  The rows
+  // are read once: a thread keeps its 8-column chunks (at most kChunks, rows and columns flattened) in registers
+  // from the pass that finds the row scales to the pass that writes codes and fp16 critical columns.
+  constexpr int kChunks = (kRowsMaxOperandBytes / 3 / 8 + kThreads - 1) / kThreads;    // 6
+  for (int t = threadIdx.x; t < n_slabs; t += kThreads) s_any[t] = 0;
+  const us2 th2 = __builtin_bit_cast(us2, a.th | (a.th << 16));
+  const int row_chunks = Kpad / 8, all_chunks = a.M * row_chunks;
+  v4u raw[kChunks];
+  us2 best[kRowsMaxM];
+#pragma unroll
+  for (int m = 0; m < kRowsMaxM; ++m) best[m] = __builtin_bit_cast(us2, 0u);
+#pragma unroll
+  for (int i = 0; i < kChunks; ++i) {
+    const int q = i * kThreads + threadIdx.x;
+    const int m = q >= row_chunks ? 1 : 0, k = (q - m * row_chunks) * 8;   // (two rows at most)
+    raw[i] = v4u{0, 0, 0, 0};
+    if (q < all_chunks && k < a.K) raw[i] = *reinterpret_cast<const v4u*>(a.X + (size_t)m * a.ldx + k);
+  }
+#pragma unroll
+  for (int i = 0; i < kChunks; ++i) {
+    const int q = i * kThreads + threadIdx.x;
+    us2 t = __builtin_bit_cast(us2, 0u);
+    uint32_t over = 0;                                                // bit j: |element j| >= threshold
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {   // per half, wraps mod 2^16: entries below the threshold get the top bit
+      const us2 d = (us2)(__builtin_bit_cast(us2, raw[i][w] & 0x7fff7fffu) - th2);
+      t = __builtin_elementwise_max(t, d);
+      const uint32_t dd = __builtin_bit_cast(uint32_t, d);
+      over |= ((~dd >> 15) & 1u) << (2 * w) | ((~dd >> 31) & 1u) << (2 * w + 1);
+    }
+    if (q < all_chunks) {                                               // (a chunk of the K padding is all zeros)
+      const int m = q >= row_chunks ? 1 : 0, c = q - m * row_chunks;
+      if (m)
+        best[1] = __builtin_elementwise_max(best[1], t);
+      else
+        best[0] = __builtin_elementwise_max(best[0], t);
+      s_over[m][c] = (c * 8 < a.K) ? (uint8_t)over : (uint8_t)0;        // K padding: never critical
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < kRowsMaxM; ++m) {
+    if (m < a.M) {
+      const uint32_t both = __builtin_bit_cast(uint32_t, best[m]);
+      const uint32_t wmax = wave_max_u32(max(both & 0xffffu, both >> 16));
+      if (lane == 0) s_part[m][wave] = wmax;
+    }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < a.M) {
+    uint32_t mm = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) mm = max(mm, s_part[threadIdx.x][w]);
+    const float r = (mm & 0x8000u) ? half_lo_to_float((mm + a.th) & 0xffffu) : 0.0f;
+    s_r[threadIdx.x] = r;
+    s_scale[threadIdx.x] = (r == 0.0f) ? 0.0f : 127.0f / r;          // IEEE division
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kChunks; ++i) {
+    const int q = i * kThreads + threadIdx.x;
+    // one chunk at a time (the 48 conversions of a thread in flight together would take 190 registers): the
+    // chunk passes through an opaque statement, and such statements keep their order
+    asm volatile("" : "+v"(raw[i][0]), "+v"(raw[i][1]), "+v"(raw[i][2]), "+v"(raw[i][3]) : : "memory");
+    if (q < all_chunks) {
+      const int m = q >= row_chunks ? 1 : 0, c = q - m * row_chunks, k = c * 8;
+      uint32_t crit = s_over[0][c];                                   // bit j: column k + j is critical
+      if (a.M == 2) crit |= s_over[1][c];
+      const float sc = s_scale[m];
+      uint32_t code[2] = {0, 0}, xf[4];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t h = (raw[i][j >> 1] >> (16 * (j & 1))) & 0xffffu;
+        const bool cr = (crit >> j) & 1u;
+        code[j >> 2] |= (cr ? 0u : to_code_byte(half_lo_to_float(h), sc)) << (8 * (j & 3));
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        xf[w] = (((crit >> (2 * w)) & 1u) ? (raw[i][w] & 0xffffu) : 0u) | (((crit >> (2 * w + 1)) & 1u) ? (raw[i][w] & 0xffff0000u) : 0u);
+      *reinterpret_cast<v2u*>(s_code + (size_t)m * Kpad + k) = v2u{code[0], code[1]};
+      *reinterpret_cast<v4u*>(s_xf + (size_t)m * Kpad + k) = v4u{xf[0], xf[1], xf[2], xf[3]};
+      if (crit) s_any[k >> 6] = 1;
+    }
+  }
+  __syncthreads();
+
+  // ---- this wave's slabs
+  v16i acc[kGroups];
+  v16f accf[kGroups];
+#pragma unroll
+  for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[g][e] = 0, accf[g][e] = 0.0f;
+  const bool row_live = lr < a.M;
+  const int row = row_live ? lr : 0;                                  // lanes beyond M read row 0 and feed zeros
+  const int8_t* my_code = s_code + (size_t)row * Kpad + lg * 16;
+  const uint16_t* my_xf = s_xf + (size_t)row * Kpad + lg * 16;
+  for (int i0 = 0; i0 < mine; i0 += kAhead) {
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const int i = i0 + u;
+      if (i >= mine) break;
+      const W2 w = f[u];
+      fetch_w(i + kAhead, f[u]);
+      const int slab = wave + WAVES * i;
+      const bool any = s_any[slab] != 0;                              // the same for the whole wave
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes + ks * 32);
+        if (!row_live) xa = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa, w.w[g][ks], acc[g], 0, 0, 0);
+      }
+      if (any) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + ks * 32 + t * 8);
+            if (!row_live) xr = v4u{0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {
+              const v4u wu = __builtin_bit_cast(v4u, w.w[g][ks]) ^ 0x80808080u;
+              accf[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf[g], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // ---- the eight partial results.  C layout: lane = column (lane % 32); rows 0 and 1 are registers 0 and 1 of
+  // lanes 0..31
+  if (lg == 0) {
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+      for (int m = 0; m < kRowsMaxM; ++m) {
+        s_acc[wave][m][32 * g + lr] = acc[g][m];
+        s_accf[wave][m][32 * g + lr] = accf[g][m];
+      }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < 32 * kGroups * a.M) {
+    const int m = threadIdx.x / (32 * kGroups), col = threadIdx.x % (32 * kGroups), nn = n0 + col;
+    if (nn < a.N) {
+      int32_t sum = 0;
+      float sumf = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) sum += s_acc[w][m][col], sumf += s_accf[w][m][col];
+      const float cn = a.c[nn];
+      float y = (float)sum * (s_r[m] * (cn / 16129.0f)) + sumf * (cn / 127.0f);
+      if (a.bias) y += half_lo_to_float(a.bias[nn]);
+      uint32_t h = float_to_half_bits(y);
+      if (a.gelu) h = gelu_to_half_bits(half_lo_to_float(h));
+      if (a.residual) h = float_to_half_bits(half_lo_to_float(h) + half_lo_to_float(a.residual[(size_t)m * a.ldr + nn]));
+      a.Y[(size_t)m * a.ldy + nn] = (uint16_t)h;
+      if constexpr (kTap) a.tap_acc[(size_t)m * a.N + nn] = sum;
+    }
+  }
+}
+
+hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream) {
+  a.n_slabs = packed_k(a.K) / kSlabBytes;
+  const int Kpad = a.n_slabs * kSlabBytes;
+  if (!a.X || !rows_kernel_fits(a.M, Kpad) || a.lora_r > 0 || a.codes) return hipErrorInvalidValue;
+  const unsigned grid = packed_n(a.N) / 32;
+  const size_t lds = (size_t)3 * a.M * Kpad;
+  static bool attr_set[64] = {};                                   // per device: more than the default 64 KB of LDS
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!attr_set[dev]) {
+    const void* fns[2] = {reinterpret_cast<const void*>(&k_gemm_rows<true, 1>), reinterpret_cast<const void*>(&k_gemm_rows<false, 1>)};
+    for (const void* fn : fns) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxOperandBytes);
+      if (e != hipSuccess) return e;
+    }
+    attr_set[dev] = true;
+  }
+  if (a.tap_acc)
+    hipLaunchKernelGGL((k_gemm_rows<true, 1>), dim3(grid), dim3(512), lds, stream, a);
+  else
+    hipLaunchKernelGGL((k_gemm_rows<false, 1>), dim3(grid), dim3(512), lds, stream, a);
+  return hipGetLastError();
+}
+
 }  // namespace mmd8

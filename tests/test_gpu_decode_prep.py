@@ -2,7 +2,9 @@
 the scan and pack kernels are left out.  The result must equal, bit for bit, the one obtained with those kernels
 (forced through the tuning hook, or by asking for their taps), the int32 accumulators must equal the oracle's, and
 the output must meet the oracle's to the fp16 bar; with every companion of the layer (bias, adapter, activation,
-coded input, coded output)."""
+coded input, coded output).  One or two rows go through a single kernel that shares K out between the waves of a
+workgroup: same integers, and an output that may differ from the split-K kernels' in the last fp16 bit (another
+order of fp32 additions), so it is compared with theirs to a fifth of the usual bar and with the oracle to the usual bar."""
 import numpy as np
 import pytest
 import torch
@@ -18,8 +20,17 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def own_prep_on():
     binding.lib().mmd8_set_panel_prep(1)
+    binding.lib().mmd8_set_rows_kernel(1)
     yield
     binding.lib().mmd8_set_panel_prep(1)
+    binding.lib().mmd8_set_rows_kernel(1)
+
+
+def fp16_steps(a, b):
+    def line(t):
+        u = t.view(torch.int16).to(torch.int32) & 0xffff
+        return torch.where(u >= 0x8000, -(u & 0x7fff), u)
+    return (line(a) - line(b)).abs().max().item() if a.numel() else 0
 
 
 def case(M, K, N, seed, heavy):
@@ -48,14 +59,25 @@ def test_own_preparation_equals_the_separate_kernels(K, N):
             Xbuf = torch.zeros((M, K + 8), dtype=torch.float16, device="cuda")
             Xg = Xbuf[:, :K]
             Xg.copy_(to_gpu(X))
-            Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))   # own preparation + accumulators
+            binding.lib().mmd8_set_rows_kernel(0)
             Y_taps, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)     # scan + pack (their taps asked for)
             binding.lib().mmd8_set_panel_prep(0)
             Y_off = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                       # scan + pack (hook)
             binding.lib().mmd8_set_panel_prep(1)
+            Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))   # own preparation in the panel kernel
+            binding.lib().mmd8_set_rows_kernel(1)
             torch.cuda.synchronize()
             assert torch.equal(Y, Y_off) and torch.equal(Y, Y_taps), (M, K, N, tau)
             assert torch.equal(t_acc["acc"], taps["acc"]), (M, K, N, tau)
+            if M <= 2:                                                                    # the single kernel
+                Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))
+                Y_all, t_all = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)   # scan + pack for their taps only
+                torch.cuda.synchronize()
+                assert torch.equal(t_acc["acc"], taps["acc"]), (M, K, N, tau)
+                assert torch.equal(Y, Y_all), (M, K, N, tau)
+                for name in ("outlier_mask", "row_absmax", "xq", "acc", "n_outliers", "outlier_idx"):
+                    assert torch.equal(t_all[name], taps[name]), name
+                assert_y_close(to_np(Y), to_np(Y_off), rel=2e-3)                           # another order of fp32 additions
             if with_oracle:
                 o = ml.mixed_int8_linear(X, Wq_o, c_o, tau, b)
                 assert np.array_equal(to_np(t_acc["acc"]), o["acc"])
@@ -89,7 +111,23 @@ def test_companions_of_the_layer(M):
     off = run_all()
     binding.lib().mmd8_set_panel_prep(1)
     for i, (a, b_) in enumerate(zip(on, off)):
-        assert torch.equal(a, b_), i
+        if a.dtype == torch.float16 and i == 1 and M <= 2:
+            # GELU of a pre-activation that moved by one fp16 step: many steps of the much smaller output
+            assert torch.allclose(a.float(), b_.float(), rtol=1e-2, atol=1e-3), i
+        elif a.dtype == torch.float16 and M <= 2:
+            assert_y_close(to_np(a), to_np(b_), rel=2e-3)             # (one or two rows: the single kernel where it applies)
+        elif a.dtype == torch.float16:
+            assert torch.equal(a, b_), i
+        elif i < len(on) - 2:
+            assert torch.equal(a, b_), i
+    # the coded output (last two entries) is encoded by the kernel that sums the partial outputs on both ways
+    assert torch.equal(on[-2], off[-2]) and torch.equal(on[-1], off[-1])
+    Rplain = binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, residual=R)
+    binding.lib().mmd8_set_rows_kernel(0)
+    Rpanel = binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, residual=R)
+    binding.lib().mmd8_set_rows_kernel(1)
+    torch.cuda.synchronize()
+    assert_y_close(to_np(Rplain), to_np(Rpanel), rel=2e-3)
 
 
 def test_same_workspace_alternates_between_both_ways():
