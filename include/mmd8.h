@@ -184,7 +184,7 @@ int mmd8_mixed_int8_linear_residual(const mmd8_half* X /*DEVICE*/, int M, int K,
  * fp16 (the residual stream the layer's output is added to), 16-byte aligned, ldr >= N, ldr % 8 == 0.
  * codes: DEVICE [M*N], 16-byte aligned; absmax: DEVICE [ceil(M*N/block)].  H: NULL, or DEVICE [M*N] fp16
  * (contiguous, 16-byte aligned) that receives the encoded tensor itself.  The layer's last kernel does the
- * encoding where no block is shared between its workgroups: 3 to 64 rows always, up to 128 rows when
+ * encoding where no block is shared between its workgroups: up to 64 rows, up to 128 rows when
  * 64*N % block == 0, more rows when block is 64, 128 or 256 and divides N; otherwise (and for one or two rows,
  * where the layer is a single kernel) the encoder runs after the layer.  Requirements: those of mmd8_mixed_int8_linear and of mmd8_quantize_blockwise; workspace of at
  * least mmd8_linear_to_codes_workspace_bytes(M, K, N, block) bytes, set up and reused like any other

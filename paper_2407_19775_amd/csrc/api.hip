@@ -124,8 +124,8 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_bloc
 }
 // A coded output is produced by the kernel that ends the layer when no block of it is shared between
 // workgroups: the tiled GEMM needs blocks inside its 256-column tiles; the decode path encodes where it sums
-// its partial outputs, any block size, as long as its second pass of 64 rows starts on a block boundary.  One or
-// two rows are a single kernel with 32 columns per workgroup and nothing to sum afterwards: the encoder follows it.
+// its partial outputs, any block size, as long as its second pass of 64 rows starts on a block boundary.  The
+// first few rows are a single kernel with 32 columns per workgroup and nothing to sum afterwards: the encoder follows it.
 static bool exit_fuses(int M, int K, int N, int block) {
   if (rows_kernel_fits(M, packed_k(K))) return false;
   if (M <= kSkinnyChunkedMaxM) return M <= kSkinnyMaxM || ((size_t)kSkinnyMaxM * N) % block == 0;
@@ -291,7 +291,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // A few rows (at most kPanelPrepMaxM): the decode GEMM kernel prepares its own operands (scales, codes, critical
   // columns) from X, and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
-  // One or two rows without an adapter: the whole layer is one kernel (k_gemm_rows).  When the taps of the
+  // One or two rows (while their operands fit in LDS) without an adapter: the whole layer is one kernel (k_gemm_rows).  When the taps of the
   // preparation are asked for, the scan and pack kernels run ahead of it for their sake only.
   const bool rows_path = g_panel_prep && g_rows_kernel && rows_kernel_fits(M, Kpad) && !lora;
   const bool own_prep = skinny && !rows_path && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
@@ -525,7 +525,7 @@ void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
 void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
 // ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for a few rows)
 void mmd8_set_panel_prep(int on) { g_panel_prep = on != 0; }
-// ... and: 0 = never use the one-kernel form for one or two rows
+// ... and: 0 = never use the one-kernel form for a few rows
 void mmd8_set_rows_kernel(int on) { g_rows_kernel = on != 0; }
 
 }  // extern "C"

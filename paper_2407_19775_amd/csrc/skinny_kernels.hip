@@ -529,7 +529,7 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   __shared__ uint8_t s_any[MMD8_MAX_K / kSlabBytes];
   __shared__ uint32_t s_part[kRowsMaxM][WAVES];
   __shared__ float s_r[kRowsMaxM], s_scale[kRowsMaxM];
-  __shared__ uint8_t s_over[kRowsMaxM][kRowsMaxOperandBytes / 3 / 8];   // per 8-column chunk of a row: bits "at or above the threshold"
+  __shared__ uint8_t s_over[kRowsMaxOperandBytes / 3 / 8];   // per 8-column chunk, rows one after the other: bits "at or above the threshold"
   __shared__ int32_t s_acc[WAVES][kRowsMaxM][32 * kGroups];
   __shared__ float s_accf[WAVES][kRowsMaxM][32 * kGroups];
   const int lane = threadIdx.x & (kWave - 1);
@@ -578,7 +578,7 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
 #pragma unroll
   for (int i = 0; i < kChunks; ++i) {
     const int q = i * kThreads + threadIdx.x;
-    const int m = q >= row_chunks ? 1 : 0, k = (q - m * row_chunks) * 8;   // (two rows at most)
+    const int m = q / row_chunks, k = (q - m * row_chunks) * 8;
     raw[i] = v4u{0, 0, 0, 0};
     if (q < all_chunks && k < a.K) raw[i] = *reinterpret_cast<const v4u*>(a.X + (size_t)m * a.ldx + k);
   }
@@ -595,12 +595,11 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
       over |= ((~dd >> 15) & 1u) << (2 * w) | ((~dd >> 31) & 1u) << (2 * w + 1);
     }
     if (q < all_chunks) {                                               // (a chunk of the K padding is all zeros)
-      const int m = q >= row_chunks ? 1 : 0, c = q - m * row_chunks;
-      if (m)
-        best[1] = __builtin_elementwise_max(best[1], t);
-      else
-        best[0] = __builtin_elementwise_max(best[0], t);
-      s_over[m][c] = (c * 8 < a.K) ? (uint8_t)over : (uint8_t)0;        // K padding: never critical
+      const int m = q / row_chunks, c = q - m * row_chunks;
+#pragma unroll
+      for (int mm = 0; mm < kRowsMaxM; ++mm)
+        if (mm == m) best[mm] = __builtin_elementwise_max(best[mm], t);
+      s_over[q] = (c * 8 < a.K) ? (uint8_t)over : (uint8_t)0;           // K padding: never critical
     }
   }
 #pragma unroll
@@ -628,9 +627,9 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
     // chunk passes through an opaque statement, and such statements keep their order
     asm volatile("" : "+v"(raw[i][0]), "+v"(raw[i][1]), "+v"(raw[i][2]), "+v"(raw[i][3]) : : "memory");
     if (q < all_chunks) {
-      const int m = q >= row_chunks ? 1 : 0, c = q - m * row_chunks, k = c * 8;
-      uint32_t crit = s_over[0][c];                                   // bit j: column k + j is critical
-      if (a.M == 2) crit |= s_over[1][c];
+      const int m = q / row_chunks, c = q - m * row_chunks, k = c * 8;
+      uint32_t crit = 0;                                              // bit j: column k + j is critical
+      for (int mm = 0; mm < a.M; ++mm) crit |= s_over[mm * row_chunks + c];
       const float sc = s_scale[m];
       uint32_t code[2] = {0, 0}, xf[4];
 #pragma unroll
@@ -694,7 +693,7 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
     }
   }
 
-  // ---- the eight partial results.  C layout: lane = column (lane % 32); rows 0 and 1 are registers 0 and 1 of
+  // ---- the eight partial results.  C layout: lane = column (lane % 32); row m < 4 is register m of
   // lanes 0..31
   if (lg == 0) {
 #pragma unroll
