@@ -47,6 +47,9 @@ def build(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    # the graph partitioner: plain host C++, a library of its own (include/mtpp.h)
+    _run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", os.path.join(HERE, "libmtpp.so"),
+          os.path.join(CSRC, "mtpp.cpp")])
     return LIB
 
 
