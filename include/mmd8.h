@@ -89,7 +89,10 @@ int mmd8_unpack_weight(const int8_t* Wq_packed /*DEVICE*/, int K, int N,
                        int8_t* Wq_rowmajor /*DEVICE [K,N]*/, void* stream);
 
 /* Optional taps that expose the intermediates of one mmd8_mixed_int8_linear call (for parity
- * checks).  Any member may be NULL.  All are DEVICE pointers. */
+ * checks).  Any member may be NULL.  All are DEVICE pointers.  The output of a call does not depend on
+ * which taps are asked for.  (For up to 8 rows the kernels that multiply also prepare their own operands;
+ * asking for outlier_mask, row_absmax, xq, n_outliers or outlier_idx makes the separate preparation kernels
+ * run as well, which produce the same quantities.) */
 typedef struct {
   uint8_t* outlier_mask;  /* [K]    1 = critical feature dimension                         */
   float*   row_absmax;    /* [M]    r[m]                                                   */
