@@ -23,6 +23,8 @@
 // to fp16 first.  The two differ by at most the fp16 rounding of the weights (2^-11 relative per
 // term), far inside the tolerance of the fp16 output.  A slab without a critical column skips the
 // 16-bit part (the same decision for the whole workgroup).
+#include <type_traits>
+
 #include "codec_device.h"
 #include "common.h"
 #include "operand_layout.h"
@@ -519,46 +521,45 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
 // the output does not depend on timing.  No split between workgroups, hence no partial outputs in HBM and no
 // second kernel.
 // ------------------------------------------------------------------------------------------------
-// kGroups: 32-column groups per workgroup.  Only 1 is used: with 2 (meant for shapes with more groups than the chip
-// holds workgroups at once, 688 for the 4096 -> 22016 linear) the weight prefetch has to shrink to two slabs for the
-// registers, and that linear took 29.9 us instead of 21.6.
-template <bool kTap, int kGroups>
+// kCols: output columns per workgroup.  32 (one group of Wt, v_mfma_i32_32x32x32_i8) by default; 16 (half a group,
+// v_mfma_i32_16x16x64_i8 / v_mfma_f32_16x16x32_f16, whose lanes take the same 16-byte pieces of the blocked layout in
+// another order) when 32 would leave compute units without a workgroup (N up to 8192 on 256 of them).  (Two groups
+// per workgroup, for shapes with more groups than the chip holds workgroups at once, was slower: the registers then
+// allow a prefetch of only two slabs, and the 4096 -> 22016 linear took 29.9 us instead of 21.6.)
+template <bool kTap, int kCols>
 __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
-  constexpr int WAVES = 8, kThreads = WAVES * kWave, kAhead = kGroups == 1 ? 4 : 2;
+  static_assert(kCols == 32 || kCols == 16, "one group of 32 weight rows, or half of one");
+  constexpr int WAVES = 8, kThreads = WAVES * kWave, kAhead = 4;
+  constexpr int kPieces = kCols == 32 ? 2 : 1;                       // 16-byte weight pieces per lane and slab
   extern __shared__ __attribute__((aligned(16))) int8_t s_ops[];     // [M][Kpad] codes, then [M][Kpad] fp16
   __shared__ uint8_t s_any[MMD8_MAX_K / kSlabBytes];
   __shared__ uint32_t s_part[kRowsMaxM][WAVES];
   __shared__ float s_r[kRowsMaxM], s_scale[kRowsMaxM];
   __shared__ uint8_t s_over[kRowsMaxOperandBytes / 3 / 8];   // per 8-column chunk, rows one after the other: bits "at or above the threshold"
-  __shared__ int32_t s_acc[WAVES][kRowsMaxM][32 * kGroups];
-  __shared__ float s_accf[WAVES][kRowsMaxM][32 * kGroups];
+  __shared__ int32_t s_acc[WAVES][kRowsMaxM][kCols];
+  __shared__ float s_accf[WAVES][kRowsMaxM][kCols];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int lr = lane & 31, lg = lane >> 5;
+  // the operand row / output column a lane stands for, and which 16-byte piece of the k range it holds
+  const int lr = lane & (kCols - 1), lg = lane / kCols;
   const int n_slabs = a.n_slabs, Kpad = n_slabs * kSlabBytes;
   reset_column_flags(a.flag_reset, Kpad);
-  const int n0 = blockIdx.x * 32 * kGroups;
+  const int n0 = blockIdx.x * kCols;                                 // < Npad: the grid covers whole groups only
   int8_t* s_code = s_ops;
   uint16_t* s_xf = reinterpret_cast<uint16_t*>(s_ops + (size_t)a.M * Kpad);
 
   const int mine = wave < n_slabs ? (n_slabs - wave + WAVES - 1) / WAVES : 0;   // slabs of this wave
-  const int8_t* wgrp[kGroups];
-#pragma unroll
-  for (int g = 0; g < kGroups; ++g) {
-    const int ng = n0 + 32 * g;                                       // < Npad: the grid covers whole groups only
-    wgrp[g] = a.Wt + (size_t)(ng >> 8) * n_slabs * kBlockBytes + (size_t)((ng & 255) >> 5) * 2048 + lane * 16;
-  }
+  // a group of 32 weight rows is 2 KB per slab: [k-step 0..1][lane group 0..1][row 0..31] 16-byte pieces
+  const int8_t* wgrp = a.Wt + (size_t)(n0 >> 8) * n_slabs * kBlockBytes + (size_t)((n0 & 255) >> 5) * 2048 +
+                       (kCols == 32 ? lane * 16 : (lg >> 1) * 1024 + (32 * (lg & 1) + (n0 & 16) + lr) * 16);
   struct W2 {
-    v4i w[kGroups][2];
+    v4i w[kPieces];
   };
   auto fetch_w = [&](int i, W2& f) {                                  // this wave's i-th slab (clamped past the end)
     const int slab = wave + WAVES * min(i, max(mine - 1, 0));
+    const int8_t* p = wgrp + (size_t)min(slab, n_slabs - 1) * kBlockBytes;
 #pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-      const int8_t* p = wgrp[g] + (size_t)min(slab, n_slabs - 1) * kBlockBytes;
-      f.w[g][0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
-      f.w[g][1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p + 1024));
-    }
+    for (int ks = 0; ks < kPieces; ++ks) f.w[ks] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p + ks * 1024));
   };
   W2 f[kAhead];
 #pragma unroll
@@ -649,12 +650,12 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   __syncthreads();
 
   // ---- this wave's slabs
-  v16i acc[kGroups];
-  v16f accf[kGroups];
+  typedef typename std::conditional<kCols == 32, v16i, v4i>::type AccI;
+  typedef typename std::conditional<kCols == 32, v16f, v4f>::type AccF;
+  AccI acc;
+  AccF accf;
 #pragma unroll
-  for (int g = 0; g < kGroups; ++g)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[g][e] = 0, accf[g][e] = 0.0f;
+  for (int e = 0; e < (kCols == 32 ? 16 : 4); ++e) acc[e] = 0, accf[e] = 0.0f;
   const bool row_live = lr < a.M;
   const int row = row_live ? lr : 0;                                  // lanes beyond M read row 0 and feed zeros
   const int8_t* my_code = s_code + (size_t)row * Kpad + lg * 16;
@@ -668,45 +669,57 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
       fetch_w(i + kAhead, f[u]);
       const int slab = wave + WAVES * i;
       const bool any = s_any[slab] != 0;                              // the same for the whole wave
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes + ks * 32);
-        if (!row_live) xa = v4i{0, 0, 0, 0};
-#pragma unroll
-        for (int g = 0; g < kGroups; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa, w.w[g][ks], acc[g], 0, 0, 0);
-      }
-      if (any) {
+      if constexpr (kCols == 32) {
+        // lane group lg of k-step ks holds columns 32 ks + 16 lg .. + 16 of the slab
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
+          v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes + ks * 32);
+          if (!row_live) xa = v4i{0, 0, 0, 0};
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa, w.w[ks], acc, 0, 0, 0);
+        }
+        if (any) {
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const v4u wu = __builtin_bit_cast(v4u, w.w[ks]) ^ 0x80808080u;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+              v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + ks * 32 + t * 8);
+              if (!row_live) xr = v4u{0, 0, 0, 0};
+              accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
+            }
+          }
+        }
+      } else {
+        // lane group lg (0..3) holds columns 16 lg .. + 16 of the slab; the two fp16 instructions take the two
+        // halves of every lane group's piece (any split of the 64 columns does, as long as both operands agree)
+        v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes);
+        if (!row_live) xa = v4i{0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w.w[0], acc, 0, 0, 0);
+        if (any) {
+          const v4u wu = __builtin_bit_cast(v4u, w.w[0]) ^ 0x80808080u;
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + ks * 32 + t * 8);
+            v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + t * 8);
             if (!row_live) xr = v4u{0, 0, 0, 0};
-#pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
-              const v4u wu = __builtin_bit_cast(v4u, w.w[g][ks]) ^ 0x80808080u;
-              accf[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf[g], 0, 0, 0);
-            }
+            accf = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
           }
         }
       }
     }
   }
 
-  // ---- the eight partial results.  C layout: lane = column (lane % 32); row m < 4 is register m of
-  // lanes 0..31
+  // ---- the eight partial results.  C layout of both MFMA shapes: lane = column (lane % kCols); row m < 4 is
+  // register m of the first kCols lanes
   if (lg == 0) {
 #pragma unroll
-    for (int g = 0; g < kGroups; ++g)
-#pragma unroll
-      for (int m = 0; m < kRowsMaxM; ++m) {
-        s_acc[wave][m][32 * g + lr] = acc[g][m];
-        s_accf[wave][m][32 * g + lr] = accf[g][m];
-      }
+    for (int m = 0; m < kRowsMaxM; ++m) {
+      s_acc[wave][m][lr] = acc[m];
+      s_accf[wave][m][lr] = accf[m];
+    }
   }
   __syncthreads();
-  if ((int)threadIdx.x < 32 * kGroups * a.M) {
-    const int m = threadIdx.x / (32 * kGroups), col = threadIdx.x % (32 * kGroups), nn = n0 + col;
+  if ((int)threadIdx.x < kCols * a.M) {
+    const int m = threadIdx.x / kCols, col = threadIdx.x % kCols, nn = n0 + col;
     if (nn < a.N) {
       int32_t sum = 0;
       float sumf = 0.0f;
@@ -728,23 +741,33 @@ hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream) {
   a.n_slabs = packed_k(a.K) / kSlabBytes;
   const int Kpad = a.n_slabs * kSlabBytes;
   if (!a.X || !rows_kernel_fits(a.M, Kpad) || a.lora_r > 0 || a.codes) return hipErrorInvalidValue;
-  const unsigned grid = packed_n(a.N) / 32;
+  // 16 columns per workgroup when 32 would leave compute units without one
+  const bool narrow = packed_n(a.N) / 32 <= device_cu_count();
+  const unsigned grid = packed_n(a.N) / (narrow ? 16 : 32);
   const size_t lds = (size_t)3 * a.M * Kpad;
   static bool attr_set[64] = {};                                   // per device: more than the default 64 KB of LDS
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (!attr_set[dev]) {
-    const void* fns[2] = {reinterpret_cast<const void*>(&k_gemm_rows<true, 1>), reinterpret_cast<const void*>(&k_gemm_rows<false, 1>)};
+    const void* fns[4] = {reinterpret_cast<const void*>(&k_gemm_rows<true, 32>), reinterpret_cast<const void*>(&k_gemm_rows<false, 32>),
+                          reinterpret_cast<const void*>(&k_gemm_rows<true, 16>), reinterpret_cast<const void*>(&k_gemm_rows<false, 16>)};
     for (const void* fn : fns) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxOperandBytes);
       if (e != hipSuccess) return e;
     }
     attr_set[dev] = true;
   }
-  if (a.tap_acc)
-    hipLaunchKernelGGL((k_gemm_rows<true, 1>), dim3(grid), dim3(512), lds, stream, a);
-  else
-    hipLaunchKernelGGL((k_gemm_rows<false, 1>), dim3(grid), dim3(512), lds, stream, a);
+  if (narrow) {
+    if (a.tap_acc)
+      hipLaunchKernelGGL((k_gemm_rows<true, 16>), dim3(grid), dim3(512), lds, stream, a);
+    else
+      hipLaunchKernelGGL((k_gemm_rows<false, 16>), dim3(grid), dim3(512), lds, stream, a);
+  } else {
+    if (a.tap_acc)
+      hipLaunchKernelGGL((k_gemm_rows<true, 32>), dim3(grid), dim3(512), lds, stream, a);
+    else
+      hipLaunchKernelGGL((k_gemm_rows<false, 32>), dim3(grid), dim3(512), lds, stream, a);
+  }
   return hipGetLastError();
 }
 
