@@ -125,7 +125,10 @@ typedef struct {
  * small head of counters and column flags; everything else may hold anything).  Every call
  * leaves the head zeroed again, so the same workspace serves any number of calls of any shape
  * that fits, one after the other on one stream.  Two calls must not use one workspace at the
- * same time.  After a call that returned MMD8_E_HIP, set the workspace up again. */
+ * same time.  After a call that returned MMD8_E_HIP, set the workspace up again.
+ * mmd8_linear_workspace_init also sets the kernels' attributes on the current device; the calls of the layer made
+ * after it allocate nothing, synchronise nothing and change no device state, so they can be captured in a HIP
+ * graph (set the workspace up before the capture starts). */
 size_t mmd8_linear_workspace_bytes(int M, int K, int N);
 int mmd8_linear_workspace_init(void* workspace /*DEVICE*/, size_t workspace_bytes, void* stream);
 int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,

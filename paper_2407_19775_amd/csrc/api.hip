@@ -217,6 +217,8 @@ size_t mmd8_linear_lora_workspace_bytes(int M, int K, int N, int r) {
 int mmd8_linear_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace || !aligned(workspace, 256)) return MMD8_E_ARG;
   if (workspace_bytes < kHeadBytes) return MMD8_E_WORKSPACE;
+  // kernel attributes of this device, so that no later call has to set one (a call may be under stream capture)
+  if (prepare_gemm_kernels() != hipSuccess || prepare_rows_kernels() != hipSuccess) return MMD8_E_HIP;
   return launch_fill_u32(static_cast<uint32_t*>(workspace), 0u, (int)(kHeadBytes / 4),
                          static_cast<hipStream_t>(stream)) == hipSuccess
              ? MMD8_OK

@@ -52,5 +52,8 @@ __device__ inline void reset_column_flags(uint8_t* flags, int Kpad) {
 
 // variant selects a tile configuration (< 0: automatic); every variant computes the same result.
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream);
+// sets the LDS attribute of every GEMM kernel on the current device (otherwise done by a kernel's first launch,
+// which must then not happen while a stream is being captured)
+hipError_t prepare_gemm_kernels();
 
 }  // namespace mmd8

@@ -790,21 +790,27 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_ping
 }
 
 // ------------------------------------------------------------------------------------------------
+// The kernels need more LDS than a kernel gets by default; the attribute is set once per instantiation and device,
+// by prepare_gemm_kernels() (called when a workspace is set up) or else by the first launch.
 template <class Cfg, bool kTap, bool kFull, bool kPingPong, bool kCoded>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
+static hipError_t ensure_lds_attribute() {
   static bool attr_set[64] = {};                                   // per device: the attribute belongs to the device's code object
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (attr_set[dev]) return hipSuccess;
   const void* fn;
   if constexpr (kPingPong)
     fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull, kCoded>);
   else
     fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull, kCoded>);
-  if (!attr_set[dev]) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[dev] = true;
-  }
+  const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+  if (e == hipSuccess) attr_set[dev] = true;
+  return e;
+}
+
+template <class Cfg, bool kTap, bool kFull, bool kPingPong, bool kCoded>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
+  if (hipError_t e = ensure_lds_attribute<Cfg, kTap, kFull, kPingPong, kCoded>(); e != hipSuccess) return e;
   const int grid = ceil_div(a.tiles_m * a.tiles_n, 8) * 8;
   if constexpr (kPingPong)
     hipLaunchKernelGGL((k_gemm_pingpong<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
@@ -827,6 +833,29 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, false>(a, stream);
   return full ? launch_one<Cfg, false, true, kPingPong, false>(a, stream)
               : launch_one<Cfg, false, false, kPingPong, false>(a, stream);
+}
+
+// every instantiation launch_cfg can reach
+template <class Cfg, bool kPingPong>
+static hipError_t prepare_cfg() {
+  hipError_t e = ensure_lds_attribute<Cfg, true, false, kPingPong, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, kPingPong, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, kPingPong, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, true, false, kPingPong, true>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, kPingPong, true>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, kPingPong, true>();
+  return e;
+}
+hipError_t prepare_gemm_kernels() {
+  hipError_t e = prepare_cfg<GemmCfg<128, 128, 2, 2, 3, 3>, false>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, true>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>();
+  if (e == hipSuccess) e = prepare_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>();
+  return e;
 }
 
 static hipError_t launch_variant(const GemmArgs& a, int variant, hipStream_t stream) {

@@ -78,5 +78,6 @@ constexpr int kRowsMaxM = 2;   // (the kernel is written for any small number; m
 constexpr int kRowsMaxOperandBytes = 66 * 1024;   // two rows of K = 11008; two workgroups per compute unit still fit
 inline bool rows_kernel_fits(int M, int Kpad) { return M <= kRowsMaxM && 3 * M * Kpad <= kRowsMaxOperandBytes; }
 hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream);
+hipError_t prepare_rows_kernels();   // its LDS attribute on the current device (else set by the first launch)
 
 }  // namespace mmd8

@@ -737,6 +737,22 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   }
 }
 
+// more than the default 64 KB of LDS: an attribute per kernel and device
+hipError_t prepare_rows_kernels() {
+  static bool attr_set[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (attr_set[dev]) return hipSuccess;
+  const void* fns[4] = {reinterpret_cast<const void*>(&k_gemm_rows<true, 32>), reinterpret_cast<const void*>(&k_gemm_rows<false, 32>),
+                        reinterpret_cast<const void*>(&k_gemm_rows<true, 16>), reinterpret_cast<const void*>(&k_gemm_rows<false, 16>)};
+  for (const void* fn : fns) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxOperandBytes);
+    if (e != hipSuccess) return e;
+  }
+  attr_set[dev] = true;
+  return hipSuccess;
+}
+
 hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream) {
   a.n_slabs = packed_k(a.K) / kSlabBytes;
   const int Kpad = a.n_slabs * kSlabBytes;
@@ -745,18 +761,7 @@ hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream) {
   const bool narrow = packed_n(a.N) / 32 <= device_cu_count();
   const unsigned grid = packed_n(a.N) / (narrow ? 16 : 32);
   const size_t lds = (size_t)3 * a.M * Kpad;
-  static bool attr_set[64] = {};                                   // per device: more than the default 64 KB of LDS
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!attr_set[dev]) {
-    const void* fns[4] = {reinterpret_cast<const void*>(&k_gemm_rows<true, 32>), reinterpret_cast<const void*>(&k_gemm_rows<false, 32>),
-                          reinterpret_cast<const void*>(&k_gemm_rows<true, 16>), reinterpret_cast<const void*>(&k_gemm_rows<false, 16>)};
-    for (const void* fn : fns) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxOperandBytes);
-      if (e != hipSuccess) return e;
-    }
-    attr_set[dev] = true;
-  }
+  if (hipError_t e = prepare_rows_kernels(); e != hipSuccess) return e;
   if (narrow) {
     if (a.tap_acc)
       hipLaunchKernelGGL((k_gemm_rows<true, 16>), dim3(grid), dim3(512), lds, stream, a);
