@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE, scaled by a plain copy of known size (profiles/gemm_llama7b_prefill_hbm_traffic.txt).  Valid
 # for the GEMM source it was measured on: reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 200.0e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "f9497775732cae5458ea0c74b5290136e70e9e6eb05222d6d786976da7b1fdac"
+GEMM_TRAFFIC_SOURCE_SHA256 = "99b6dffbde06008ff7fea89490783a3113f389fdbbe2116e245f541079ff32a1"
 
 
 def parse():
