@@ -293,9 +293,9 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // A few rows (at most kPanelPrepMaxM): the decode GEMM kernel prepares its own operands (scales, codes, critical
   // columns) from X, and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
-  // One or two rows (while their operands fit in LDS) without an adapter: the whole layer is one kernel (k_gemm_rows).  When the taps of the
+  // One or two rows (while their operands fit in LDS): the whole layer is one kernel (k_gemm_rows).  When the taps of the
   // preparation are asked for, the scan and pack kernels run ahead of it for their sake only.
-  const bool rows_path = g_panel_prep && g_rows_kernel && rows_kernel_fits(M, Kpad) && !lora;
+  const bool rows_path = g_panel_prep && g_rows_kernel && rows_kernel_fits(M, Kpad);
   const bool own_prep = skinny && !rows_path && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
@@ -358,6 +358,12 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     if (exit) {
       g.residual = exit->residual;
       g.ldr = exit->ldr;
+    }
+    if (lora) {
+      g.lora_T = ws.lora_t;
+      g.lora_ldt = kLoraMaxRank;
+      g.lora_B = lora->B;
+      g.lora_r = lora->r;
     }
     g.X = X;
     g.ldx = ldx;

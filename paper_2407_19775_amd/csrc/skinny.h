@@ -73,7 +73,8 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
 // One or two rows, whole layer in one kernel (k_gemm_rows): a workgroup owns 32 output columns and its eight
 // waves share out the K range, so nothing is split between workgroups and no second kernel adds partial
 // outputs.  The rows' codes and fp16 critical columns for the whole of K live in LDS (3 bytes per element).
-// Needs a.X (the kernel prepares its operands); takes bias, GELU and a residual; no adapter, no coded output.
+// Needs a.X (the kernel prepares its operands); takes bias, the low-rank term of an adapter, GELU and a residual;
+// no coded output (the encoder follows it).
 constexpr int kRowsMaxM = 2;   // (the kernel is written for any small number; measured with 4: 78.8 us per 7B layer at four rows against 76 with the split-K kernels)
 constexpr int kRowsMaxOperandBytes = 66 * 1024;   // two rows of K = 11008; two workgroups per compute unit still fit
 inline bool rows_kernel_fits(int M, int Kpad) { return M <= kRowsMaxM && 3 * M * Kpad <= kRowsMaxOperandBytes; }

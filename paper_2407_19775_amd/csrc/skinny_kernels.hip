@@ -728,6 +728,17 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
       const float cn = a.c[nn];
       float y = (float)sum * (s_r[m] * (cn / 16129.0f)) + sumf * (cn / 127.0f);
       if (a.bias) y += half_lo_to_float(a.bias[nn]);
+      if (a.lora_r > 0) {                                             // the low-rank term, as k_skinny_finalize adds it
+        float low = 0.0f;
+        for (int j = 0; j < a.lora_r; j += 8) {
+          const v4u t = *reinterpret_cast<const v4u*>(a.lora_T + (size_t)m * a.lora_ldt + j);
+          const v4u b = *reinterpret_cast<const v4u*>(a.lora_B + (size_t)nn * a.lora_r + j);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            low += half_lo_to_float(t[e]) * half_lo_to_float(b[e]) + half_hi_to_float(t[e]) * half_hi_to_float(b[e]);
+        }
+        y += low;
+      }
       uint32_t h = float_to_half_bits(y);
       if (a.gelu) h = gelu_to_half_bits(half_lo_to_float(h));
       if (a.residual) h = float_to_half_bits(half_lo_to_float(h) + half_lo_to_float(a.residual[(size_t)m * a.ldr + nn]));
@@ -756,7 +767,7 @@ hipError_t prepare_rows_kernels() {
 hipError_t launch_gemm_rows(SkinnyArgs a, hipStream_t stream) {
   a.n_slabs = packed_k(a.K) / kSlabBytes;
   const int Kpad = a.n_slabs * kSlabBytes;
-  if (!a.X || !rows_kernel_fits(a.M, Kpad) || a.lora_r > 0 || a.codes) return hipErrorInvalidValue;
+  if (!a.X || !rows_kernel_fits(a.M, Kpad) || a.codes) return hipErrorInvalidValue;
   // 16 columns per workgroup when 32 would leave compute units without one
   const bool narrow = packed_n(a.N) / 32 <= device_cu_count();
   const unsigned grid = packed_n(a.N) / (narrow ? 16 : 32);
