@@ -169,3 +169,19 @@ def test_residual_arguments_are_rejected_before_any_launch():
 
     assert call(res=None) == -1 and call(res=odd) == -1 and call(ldr=56) == -1 and call(ldr=68) == -1
     assert call(Y=None) == -1 and call(K=100) == -2
+
+
+def test_public_headers_are_plain_c():
+    """The boundary is a C ABI: both headers must go through a C99 compiler on their own."""
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "use.c")
+        with open(src, "w") as f:
+            f.write('#include "mmd8.h"\n#include "mtpp.h"\nint main(void) { return mmd8_status_string(0) == 0; }\n')
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                            "-I", os.path.join(ROOT, "include"), src], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
