@@ -397,6 +397,16 @@ def main():
                     "two_steps_us": round(timed(two_steps, 30) * 1e3, 1)}
         vit["tokens"] = Mv
 
+        # ---- weight pre-quantization (offline step, not part of the timed step): column absmax + codes in the blocked
+        # layout; 2 bytes read twice and 1 byte written per weight
+        prequant = {}
+        for shp in shapes:
+            Wp = torch.empty((shp.K, shp.N), dtype=torch.float16, device=dev).normal_(0.0, 0.02, generator=genv)
+            t = timed(lambda: binding.prequantize_weight(Wp), 5)
+            prequant[shp.name] = {"us": round(t * 1e3, 1), "gbs": round(5.0 * shp.K * shp.N / t / 1e6, 1),
+                                  "pct_hbm": round(100.0 * 5.0 * shp.K * shp.N / t / 1e6 / HBM_PEAK_GBS, 1)}
+            del Wp
+
         # ---- the codec on a key/value cache (one layer of the 7B shape: 32 heads x 128, block = one head vector):
         # a 2048-token context decoded for one generated token (K and V), one token appended, a 2048-token prompt
         # appended.  Whole calls, eager; the cache of this one layer fits the last-level cache.
@@ -492,7 +502,7 @@ def main():
             "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50), three buffer "
                     "sets taking turns (HBM traffic); after the first pass the values are codec outputs"})
         out.update({"decode": decode, "prefill_70b": prefill_70b, "adapter": adapter, "boundary_exit": boundary_exit,
-                    "vit_l_block": vit, "kv_cache": kv_cache})
+                    "vit_l_block": vit, "kv_cache": kv_cache, "weight_prequant": prequant})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
