@@ -120,7 +120,6 @@ def main():
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    binding.lib().mmd8_set_gemm_variant(args.gemm_variant)
     M = 2048
     shapes = wl.LLAMA_7B_LINEARS
     block = args.codec_block

@@ -13,7 +13,10 @@
  *   - fp16 data are IEEE binary16 bit patterns (mmd8_half).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
  *     the call returns without synchronising.  Calls on one stream are ordered.
- *   - Return value: MMD8_OK, or a negative status; on error nothing has been enqueued.
+ *   - Return value: MMD8_OK, or a negative status.  MMD8_E_ARG, MMD8_E_SHAPE, MMD8_E_WORKSPACE and
+ *     MMD8_E_VERSION are found before anything is launched: nothing has been enqueued.  MMD8_E_HIP
+ *     (a launch failed) can come after some of a call's kernels were enqueued: outputs are then
+ *     unspecified and a workspace of the layer must be set up again before it is reused.
  *   - Zero-sized problems (M == 0, n == 0) are valid and enqueue nothing.
  *   - Inputs are assumed finite; NaN/Inf give unspecified values but never a fault.
  */
@@ -34,7 +37,8 @@ enum {
   MMD8_E_ARG       = -1,  /* null pointer, negative size, leading dimension too small, misaligned, NaN tau */
   MMD8_E_SHAPE     = -2,  /* unsupported shape: K % 16, N % 8, K above MMD8_MAX_K, bad block size          */
   MMD8_E_WORKSPACE = -3,  /* workspace smaller than mmd8_linear_workspace_bytes()                           */
-  MMD8_E_HIP       = -4   /* a HIP call or kernel launch failed                                             */
+  MMD8_E_HIP       = -4,  /* a HIP call or kernel launch failed                                             */
+  MMD8_E_VERSION   = -5   /* packed weights written under another layout than mmd8_packed_weight_layout()   */
 };
 
 /* Largest supported K.  K * 127^2 must stay below 2^31 so that the int32 accumulators of the
@@ -57,7 +61,7 @@ const char* mmd8_status_string(int status);
  * T is the 256-entry signed dynamic code: magnitudes 10^-e (0.1 + 0.9 (j + 1/2) / 2^(6-e)),
  * e = 0..6, j = 0..2^(6-e)-1, both signs, plus 0 and +1.0; Mid[j] = f32((T[j] + T[j+1]) / 2).
  * `block` must be a multiple of 64 with 64 <= block <= 4096, else MMD8_E_SHAPE.
- * x, out: 16-byte aligned; codes: 8-byte aligned; absmax: 4-byte aligned; else MMD8_E_ARG.
+ * x, out: 16-byte aligned; codes: 8-byte aligned (both directions); absmax: 4-byte aligned; else MMD8_E_ARG.
  * ------------------------------------------------------------------------------------------ */
 int mmd8_quantize_blockwise(const mmd8_half* x /*DEVICE [n]*/, size_t n, int block,
                             uint8_t* codes /*DEVICE [n]*/, float* absmax /*DEVICE [ceil(n/block)]*/,
@@ -76,8 +80,10 @@ const float* mmd8_code_midpoints(void);
  *     Wq[k,n]       = clamp(rint(f32(W[k,n]) * (127.0f / col_absmax[n])), -127, 127)   (0 if absmax 0)
  * W is read as W[k*ldw + n] (ldw >= N).  Wq is written in an opaque layout of
  * mmd8_packed_weight_bytes(K, N) bytes; mmd8_unpack_weight recovers the plain row-major
- * int8 [K,N] matrix (for checking).  mmd8_packed_weight_layout() identifies the layout; a blob
- * written under a different value must be regenerated.
+ * int8 [K,N] matrix (for checking).  mmd8_packed_weight_layout() identifies the layout this build of the
+ * library writes and reads.  Whoever stores a blob stores that value with it and hands it back as
+ * `Wq_layout` to every call that reads the blob: a call given another value returns MMD8_E_VERSION
+ * and launches nothing (the weights must be packed again from W).
  * Requirements: K % 16 == 0, 16 <= K <= MMD8_MAX_K, N % 8 == 0, N >= 8 (else MMD8_E_SHAPE);
  * W 16-byte aligned and ldw % 8 == 0, Wq_packed 256-byte aligned (else MMD8_E_ARG).
  * ------------------------------------------------------------------------------------------ */
@@ -85,7 +91,7 @@ uint32_t mmd8_packed_weight_layout(void);
 size_t   mmd8_packed_weight_bytes(int K, int N);
 int mmd8_prequantize_weight(const mmd8_half* W /*DEVICE*/, int K, int N, int ldw,
                             int8_t* Wq_packed /*DEVICE*/, float* col_absmax /*DEVICE [N]*/, void* stream);
-int mmd8_unpack_weight(const int8_t* Wq_packed /*DEVICE*/, int K, int N,
+int mmd8_unpack_weight(const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, int K, int N,
                        int8_t* Wq_rowmajor /*DEVICE [K,N]*/, void* stream);
 
 /* Optional taps that expose the intermediates of one mmd8_mixed_int8_linear call (for parity
@@ -106,7 +112,15 @@ typedef struct {
   void* event_begin;
   void* event_gemm_begin;
   void* event_gemm_end;
+  /* Kernel choice of this one call, for tests and tuning: 0 = the library's own choice, else an OR of the
+     MMD8_TUNE_* values below.  Every choice computes the same integers (mask, scales, codes, accumulators);
+     Y may differ in the last fp16 bit between choices that add the 16-bit part in another order.  A value
+     that does not fit the shape is ignored.  Per call, no global state: other threads are unaffected.       */
+  uint32_t tuning;
 } mmd8_debug_taps;
+#define MMD8_TUNE_GEMM_TILES(v)    ((uint32_t)((v) + 1) & 0xfu) /* tiled GEMM (more than 128 rows): tile configuration v = 0..5 */
+#define MMD8_TUNE_SEPARATE_PREP    0x10u  /* up to 8 rows: run the scan and pack kernels instead of letting the multiplying kernel prepare its own operands */
+#define MMD8_TUNE_NO_ROWS_KERNEL   0x20u  /* one or two rows: use the split-K kernels instead of the single-kernel form */
 
 /* The layer, per call (tau: threshold; X read as X[m*ldx + k]; Y written as Y[m*ldy + n]):
  *     flag[k]  = any_m |X[m,k]| >= tau
@@ -132,7 +146,7 @@ typedef struct {
 size_t mmd8_linear_workspace_bytes(int M, int K, int N);
 int mmd8_linear_workspace_init(void* workspace /*DEVICE*/, size_t workspace_bytes, void* stream);
 int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
-                           const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                           const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                            const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                            mmd8_half* Y /*DEVICE*/, int ldy,
                            void* workspace /*DEVICE*/, size_t workspace_bytes,
@@ -149,7 +163,7 @@ int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
  * [64, 4096]; codes 16-byte aligned; K % 16 == 0; ...). */
 int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, const float* absmax /*DEVICE [ceil(M*K/block)]*/,
                                       int block, int M, int K, mmd8_half* X_decoded /*DEVICE [M*K], written*/,
-                                      const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                      const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                                       const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                       mmd8_half* Y /*DEVICE*/, int ldy,
                                       void* workspace /*DEVICE*/, size_t workspace_bytes,
@@ -161,7 +175,7 @@ int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes /*DEVICE [M*K]*/, con
  * i.e. the exact (erf-based) form evaluated in fp32 on the fp16 layer output, as the two steps made one after
  * the other give.  Arguments, requirements, workspace and errors as for mmd8_mixed_int8_linear. */
 int mmd8_mixed_int8_linear_gelu(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
-                                const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                                 const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                 mmd8_half* Y /*DEVICE*/, int ldy,
                                 void* workspace /*DEVICE*/, size_t workspace_bytes,
@@ -174,7 +188,7 @@ int mmd8_mixed_int8_linear_gelu(const mmd8_half* X /*DEVICE*/, int M, int K, int
  * ldr % 8 == 0; it may be the very buffer Y (with ldr == ldy): the stream is then updated in place.  Other
  * arguments, requirements, workspace and errors as for mmd8_mixed_int8_linear. */
 int mmd8_mixed_int8_linear_residual(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
-                                    const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                    const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                                     const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                     const mmd8_half* residual /*DEVICE [M][ldr]*/, int ldr,
                                     mmd8_half* Y /*DEVICE*/, int ldy,
@@ -197,7 +211,7 @@ int mmd8_mixed_int8_linear_residual(const mmd8_half* X /*DEVICE*/, int M, int K,
  * workspace of the layer.  Errors as for the two calls; nothing is launched when one is returned. */
 size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block);
 int mmd8_mixed_int8_linear_to_codes(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
-                                    const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                    const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                                     const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                     const mmd8_half* residual /*DEVICE [M][ldr] or NULL*/, int ldr, int block,
                                     uint8_t* codes /*DEVICE [M*N], written*/, float* absmax /*DEVICE, written*/,
@@ -218,7 +232,7 @@ int mmd8_mixed_int8_linear_to_codes(const mmd8_half* X /*DEVICE*/, int M, int K,
 #define MMD8_MAX_LORA_RANK 64
 size_t mmd8_linear_lora_workspace_bytes(int M, int K, int N, int r);
 int mmd8_mixed_int8_linear_lora(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
-                                const int8_t* Wq_packed /*DEVICE*/, const float* col_absmax /*DEVICE [N]*/, int N,
+                                const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
                                 const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                 const mmd8_half* lora_A /*DEVICE [r*K]*/, const mmd8_half* lora_B /*DEVICE [N*r]*/, int r,
                                 mmd8_half* lora_T /*DEVICE [M*r] or NULL, written*/,

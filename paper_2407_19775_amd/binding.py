@@ -27,7 +27,16 @@ EXPORTS = (
 class DebugTaps(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in
                 ("outlier_mask", "row_absmax", "xq", "acc", "n_outliers", "outlier_idx",
-                 "event_begin", "event_gemm_begin", "event_gemm_end")]
+                 "event_begin", "event_gemm_begin", "event_gemm_end")] + [("tuning", ctypes.c_uint32)]
+
+
+# kernel choices of one call (mmd8_debug_taps.tuning, include/mmd8.h)
+TUNE_SEPARATE_PREP = 0x10
+TUNE_NO_ROWS_KERNEL = 0x20
+
+
+def tune_gemm_tiles(v: int) -> int:
+    return (v + 1) & 0xF
 
 
 class Mmd8Error(RuntimeError):
@@ -40,7 +49,7 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise Mmd8Error("libmmd8.so is not built: run `python -m paper_2407_19775_amd.build`")
         L = ctypes.CDLL(LIB_PATH)
-        vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+        vp, sz, i32, f32, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float, ctypes.c_uint32
         L.mmd8_status_string.restype = ctypes.c_char_p
         L.mmd8_status_string.argtypes = [i32]
         L.mmd8_quantize_blockwise.argtypes = [vp, sz, i32, vp, vp, vp]
@@ -51,30 +60,27 @@ def lib():
         L.mmd8_packed_weight_bytes.restype = sz
         L.mmd8_packed_weight_bytes.argtypes = [i32, i32]
         L.mmd8_prequantize_weight.argtypes = [vp, i32, i32, i32, vp, vp, vp]
-        L.mmd8_unpack_weight.argtypes = [vp, i32, i32, vp, vp]
+        L.mmd8_unpack_weight.argtypes = [vp, u32, i32, i32, vp, vp]
         L.mmd8_linear_workspace_bytes.restype = sz
         L.mmd8_linear_workspace_bytes.argtypes = [i32, i32, i32]
         L.mmd8_linear_workspace_init.argtypes = [vp, sz, vp]
-        L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, sz,
+        L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32, vp, sz,
                                              ctypes.POINTER(DebugTaps), vp]
-        L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, f32, vp, i32, vp, sz,
+        L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, u32, vp, i32, vp, f32, vp, i32, vp, sz,
                                                         ctypes.POINTER(DebugTaps), vp]
         L.mmd8_linear_lora_workspace_bytes.restype = sz
         L.mmd8_linear_lora_workspace_bytes.argtypes = [i32, i32, i32, i32]
-        L.mmd8_mixed_int8_linear_lora.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, sz,
+        L.mmd8_mixed_int8_linear_lora.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, sz,
                                                   ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_gelu.argtypes = L.mmd8_mixed_int8_linear.argtypes
-        L.mmd8_mixed_int8_linear_residual.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, vp, i32, vp, sz,
+        L.mmd8_mixed_int8_linear_residual.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32, vp, i32, vp, sz,
                                                       ctypes.POINTER(DebugTaps), vp]
         L.mmd8_linear_to_codes_workspace_bytes.restype = sz
         L.mmd8_linear_to_codes_workspace_bytes.argtypes = [i32, i32, i32, i32]
-        L.mmd8_mixed_int8_linear_to_codes.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, f32, vp, i32, i32, vp, vp, vp, vp, sz,
+        L.mmd8_mixed_int8_linear_to_codes.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32, i32, vp, vp, vp, vp, sz,
                                                       ctypes.POINTER(DebugTaps), vp]
         L.mmd8_threshold_fp16_pattern.restype = ctypes.c_uint32
         L.mmd8_threshold_fp16_pattern.argtypes = [f32]
-        L.mmd8_set_gemm_variant.argtypes = [i32]
-        L.mmd8_set_panel_prep.argtypes = [i32]
-        L.mmd8_set_rows_kernel.argtypes = [i32]
         _lib = L
     return _lib
 
@@ -130,11 +136,12 @@ def dequantize_blockwise(codes: torch.Tensor, absmax: torch.Tensor, block: int, 
 
 # ------------------------------------------------------------------ mixed int8 linear
 class PackedWeight:
-    """Pre-quantized weight: opaque int8 blob + per-column absmax."""
+    """Pre-quantized weight: opaque int8 blob + per-column absmax + the layout tag the blob was written under
+    (handed back to every call that reads the blob, which refuses a tag that is not the library's own)."""
 
-    def __init__(self, blob, col_absmax, K, N):
+    def __init__(self, blob, col_absmax, K, N, layout=None):
         self.blob, self.col_absmax, self.K, self.N = blob, col_absmax, K, N
-        self.layout = lib().mmd8_packed_weight_layout()
+        self.layout = lib().mmd8_packed_weight_layout() if layout is None else int(layout)
 
 
 def prequantize_weight(W: torch.Tensor) -> PackedWeight:
@@ -154,7 +161,7 @@ def prequantize_weight(W: torch.Tensor) -> PackedWeight:
 
 def unpack_weight(pw: PackedWeight) -> torch.Tensor:
     out = torch.empty((pw.K, pw.N), dtype=torch.int8, device=pw.blob.device)
-    _check(lib().mmd8_unpack_weight(pw.blob.data_ptr(), pw.K, pw.N, out.data_ptr(), _stream()))
+    _check(lib().mmd8_unpack_weight(pw.blob.data_ptr(), pw.layout, pw.K, pw.N, out.data_ptr(), _stream()))
     return out
 
 
@@ -193,7 +200,7 @@ def _all_taps(M, K, N, dev):
 def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, block: int, bias: torch.Tensor = None,
                                residual: torch.Tensor = None, codes: torch.Tensor = None, absmax: torch.Tensor = None,
                                H: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
-                               events=None):
+                               events=None, tuning: int = 0):
     """The layer with its result leaving blockwise-coded: H = Y (+ residual, an fp16 addition), flattened row by
     row and encoded with blocks of `block` elements.  Returns (codes [M N] uint8, absmax float32); H, if given
     (contiguous [M, N] fp16), receives the encoded tensor itself.  With taps=True the intermediates of the layer
@@ -224,8 +231,11 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
     tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()}) if taps else None
     if events is not None and not taps:         # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
         tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
+    if tuning:
+        tp = tp if tp is not None else DebugTaps()
+        tp.tuning = int(tuning)
     _check(lib().mmd8_mixed_int8_linear_to_codes(
-        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
         bias.data_ptr() if bias is not None else None, float(tau),
         residual.data_ptr() if residual is not None else None,
         residual.stride(0) if residual is not None and M > 0 else N, int(block), codes.data_ptr(), absmax.data_ptr(),
@@ -236,7 +246,8 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
 
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
-                      events=None, coded=None, lora=None, gelu: bool = False, residual: torch.Tensor = None):
+                      events=None, coded=None, lora=None, gelu: bool = False, residual: torch.Tensor = None,
+                      tuning: int = 0):
     """Y = X W through the mixed decomposition (gelu=True: followed by the exact GELU, in the same kernels).
     residual: fp16 [M, N] added to the output as an fp16 addition, in the same kernels (may be `out` itself).
     taps: True for every intermediate, or a tuple of tap names.  With taps=True also returns a dict of the
@@ -271,13 +282,16 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     if taps:
         tensors = _taps(M, K, N, X.device, None if taps is True else tuple(taps))
         tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
+    if tuning:                                  # kernel choice of this call (TUNE_* above)
+        tp = tp if tp is not None else DebugTaps()
+        tp.tuning = int(tuning)
     if coded is not None:
         codes, absmax, block = coded
         _dev(codes, torch.uint8, "codes")
         _dev(absmax, torch.float32, "absmax")
         _check(lib().mmd8_mixed_int8_linear_from_codes(
             codes.data_ptr(), absmax.data_ptr(), int(block), M, K, X.data_ptr(), pw.blob.data_ptr(),
-            pw.col_absmax.data_ptr(), N, bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(),
+            pw.layout, pw.col_absmax.data_ptr(), N, bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(),
             out.stride(0) if M > 0 else N, workspace.data_ptr(), workspace.numel(),
             ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
@@ -293,21 +307,22 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
                                       and T_out.is_contiguous()):
             raise Mmd8Error("T_out must be a contiguous GPU fp16 tensor [M, r]")
         _check(lib().mmd8_mixed_int8_linear_lora(
-            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
             bias.data_ptr() if bias is not None else None, float(tau), A.data_ptr(), B.data_ptr(), int(r),
             T_out.data_ptr() if T_out is not None else None, out.data_ptr(), out.stride(0) if M > 0 else N,
             workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
     if residual is not None:
         _check(lib().mmd8_mixed_int8_linear_residual(
-            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
             bias.data_ptr() if bias is not None else None, float(tau), residual.data_ptr(),
             residual.stride(0) if M > 0 else N, out.data_ptr(), out.stride(0) if M > 0 else N,
             workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
     fn = lib().mmd8_mixed_int8_linear_gelu if gelu else lib().mmd8_mixed_int8_linear
     _check(fn(
-        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.col_absmax.data_ptr(), N,
+        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
         bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(), out.stride(0) if M > 0 else N,
         workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
     return (out, tensors) if taps else out
+

@@ -132,9 +132,13 @@ static bool exit_fuses(int M, int K, int N, int block) {
   return (block == 64 || block == 128 || block == 256) && N % block == 0;
 }
 
-static int g_gemm_variant = -1;
-static bool g_panel_prep = true;
-static bool g_rows_kernel = true;
+// byte ranges [a, a + na) and [b, b + nb) share a byte
+static inline bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+  return pa < pb + nb && pb < pa + na;
+}
+// bytes from the first to one past the last element of a [rows][ld] fp16 matrix of `cols` columns
+static inline size_t span_bytes(int rows, int cols, int ld) { return rows > 0 ? ((size_t)(rows - 1) * ld + cols) * 2 : 0; }
 
 }  // namespace mmd8
 
@@ -149,6 +153,7 @@ const char* mmd8_status_string(int status) {
     case MMD8_E_SHAPE: return "unsupported shape or block size";
     case MMD8_E_WORKSPACE: return "workspace too small";
     case MMD8_E_HIP: return "HIP runtime or launch error";
+    case MMD8_E_VERSION: return "packed weights written under another layout version";
     default: return "unknown status";
   }
 }
@@ -171,7 +176,7 @@ int mmd8_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t 
                               void* stream) {
   if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
   if (n == 0) return MMD8_OK;
-  if (!codes || !absmax || !out || !aligned(out, 16) || !aligned(codes, 16) || !aligned(absmax, 4)) return MMD8_E_ARG;
+  if (!codes || !absmax || !out || !aligned(out, 16) || !aligned(codes, 8) || !aligned(absmax, 4)) return MMD8_E_ARG;
   return launch_dequantize_blockwise(codes, absmax, n, block, out, static_cast<hipStream_t>(stream)) == hipSuccess
              ? MMD8_OK
              : MMD8_E_HIP;
@@ -197,8 +202,9 @@ int mmd8_prequantize_weight(const mmd8_half* W, int K, int N, int ldw, int8_t* W
   return MMD8_OK;
 }
 
-int mmd8_unpack_weight(const int8_t* Wq_packed, int K, int N, int8_t* Wq_rowmajor, void* stream) {
+int mmd8_unpack_weight(const int8_t* Wq_packed, uint32_t Wq_layout, int K, int N, int8_t* Wq_rowmajor, void* stream) {
   if (int s = check_linear_shape(K, N)) return s;
+  if (Wq_layout != kPackedLayoutTag) return MMD8_E_VERSION;
   if (!Wq_packed || !Wq_rowmajor) return MMD8_E_ARG;
   return launch_weight_unpack(Wq_packed, K, N, Wq_rowmajor, static_cast<hipStream_t>(stream)) == hipSuccess
              ? MMD8_OK
@@ -245,13 +251,14 @@ struct Adapter {   // low-rank factors of W' = W + B A
 // lora: null, or the adapter whose term is added to the output.
 // exit: null, or where the coded form of the output goes; Y (contiguous, ldy == N) then receives the tensor that
 // is encoded and may be null.
-static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, const float* col_absmax, int N,
+static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, uint32_t Wq_layout, const float* col_absmax, int N,
                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
                       const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, const CodedExit* exit,
                       void* stream, bool gelu = false) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
+  if (Wq_layout != kPackedLayoutTag) return MMD8_E_VERSION;
   if (M == 0) return MMD8_OK;
   if (!X || !Wq_packed || !col_absmax || (!Y && !exit) || !workspace) return MMD8_E_ARG;
   if (ldx < K || ldy < N || (ldx % 8) != 0 || (ldy % 8) != 0) return MMD8_E_ARG;
@@ -264,7 +271,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (!aligned(X, 16) || !aligned(Y, 16) || !aligned(Wq_packed, 256) || !aligned(workspace, 256) ||
       !aligned(col_absmax, 4) || (bias && !aligned(bias, 2)))
     return MMD8_E_ARG;
-  if (static_cast<const void*>(X) == static_cast<const void*>(Y)) return MMD8_E_ARG;
+  if (Y && ranges_overlap(X, span_bytes(M, K, ldx), Y, span_bytes(M, N, ldy))) return MMD8_E_ARG;
   if (lora && (!lora->A || !lora->B || !aligned(lora->A, 16) || !aligned(lora->B, 16) ||
                (lora->T_out && !aligned(lora->T_out, 16))))
     return MMD8_E_ARG;
@@ -295,8 +302,9 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
   // One or two rows (while their operands fit in LDS): the whole layer is one kernel (k_gemm_rows).  When the taps of the
   // preparation are asked for, the scan and pack kernels run ahead of it for their sake only.
-  const bool rows_path = g_panel_prep && g_rows_kernel && rows_kernel_fits(M, Kpad);
-  const bool own_prep = skinny && !rows_path && !wants_prep_taps && g_panel_prep && panel_prep_fits(M, plan_skinny(M, K, N));
+  const bool may_own_prep = !(t.tuning & MMD8_TUNE_SEPARATE_PREP);
+  const bool rows_path = may_own_prep && !(t.tuning & MMD8_TUNE_NO_ROWS_KERNEL) && rows_kernel_fits(M, Kpad);
+  const bool own_prep = skinny && !rows_path && !wants_prep_taps && may_own_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K);
@@ -455,7 +463,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
         g.code_log_block = exit->block == 64 ? 6 : exit->block == 128 ? 7 : 8;
       }
     }
-    if (launch_gemm_mixed(g, g_gemm_variant, st) != hipSuccess) return MMD8_E_HIP;
+    if (launch_gemm_mixed(g, (int)(t.tuning & 0xfu) - 1, st) != hipSuccess) return MMD8_E_HIP;
   }
   if (encodes && !exit_fused &&
       launch_quantize_blockwise(Y, (size_t)M * N, exit->block, exit->codes, exit->absmax, st) != hipSuccess)
@@ -465,26 +473,26 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
 }
 
 int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                           const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                           uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
                            void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   // X is only read on this path
-  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, nullptr, nullptr, stream);
 }
 
 int mmd8_mixed_int8_linear_gelu(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                                const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                                uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
                                 void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
-  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, nullptr, nullptr, stream, true);
 }
 
 int mmd8_mixed_int8_linear_residual(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                                    const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                    uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau,
                                     const mmd8_half* residual, int ldr, mmd8_half* Y, int ldy, void* workspace,
                                     size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   const CodedExit exit = {residual, ldr, 0, nullptr, nullptr};
-  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, nullptr, &exit, stream);
 }
 
@@ -494,46 +502,38 @@ size_t mmd8_linear_to_codes_workspace_bytes(int M, int K, int N, int block) {
 }
 
 int mmd8_mixed_int8_linear_to_codes(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                                    const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                    uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau,
                                     const mmd8_half* residual, int ldr, int block, uint8_t* codes, float* absmax,
                                     mmd8_half* H, void* workspace, size_t workspace_bytes,
                                     const mmd8_debug_taps* taps, void* stream) {
   if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
   const CodedExit exit = {residual, ldr, block, codes, absmax};
-  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, H, N, workspace,
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, H, N, workspace,
                     workspace_bytes, taps, nullptr, nullptr, &exit, stream);
 }
 
 int mmd8_mixed_int8_linear_lora(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
-                                const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau,
                                 const mmd8_half* lora_A, const mmd8_half* lora_B, int r, mmd8_half* lora_T,
                                 mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
                                 const mmd8_debug_taps* taps, void* stream) {
   if (check_lora_rank(r) != MMD8_OK) return MMD8_E_SHAPE;
   const Adapter lora = {lora_A, lora_B, r, lora_T};
-  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace,
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace,
                     workspace_bytes, taps, nullptr, &lora, nullptr, stream);
 }
 
 int mmd8_mixed_int8_linear_from_codes(const uint8_t* codes, const float* absmax, int block, int M, int K,
-                                      mmd8_half* X_decoded, const int8_t* Wq_packed, const float* col_absmax, int N,
+                                      mmd8_half* X_decoded, const int8_t* Wq_packed, uint32_t Wq_layout, const float* col_absmax, int N,
                                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace,
                                       size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
   if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
   if (M > 0 && (!codes || !absmax || !aligned(codes, 16) || !aligned(absmax, 4))) return MMD8_E_ARG;
   const CodedInput coded = {codes, absmax, block};
-  return run_linear(X_decoded, M, K, K, Wq_packed, col_absmax, N, bias, tau, Y, ldy, workspace, workspace_bytes, taps,
+  return run_linear(X_decoded, M, K, K, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace, workspace_bytes, taps,
                     &coded, nullptr, nullptr, stream);
 }
 
 uint32_t mmd8_threshold_fp16_pattern(float tau) { return threshold_pattern(tau); }
-
-// Tuning hook (not part of the documented interface): force a GEMM tile configuration; -1 = automatic.
-void mmd8_set_gemm_variant(int v) { g_gemm_variant = v; }
-void mmd8_set_panel_waves(int w) { set_panel_waves(w); }
-// ... and: 0 = always run the scan and pack kernels ahead of the decode GEMM (1 = leave them out for a few rows)
-void mmd8_set_panel_prep(int on) { g_panel_prep = on != 0; }
-// ... and: 0 = never use the one-kernel form for a few rows
-void mmd8_set_rows_kernel(int on) { g_rows_kernel = on != 0; }
 
 }  // extern "C"

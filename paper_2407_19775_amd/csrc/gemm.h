@@ -50,7 +50,7 @@ __device__ inline void reset_column_flags(uint8_t* flags, int Kpad) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = v4u{0, 0, 0, 0};
 }
 
-// variant selects a tile configuration (< 0: automatic); every variant computes the same result.
+// variant selects a tile configuration, 0..5 (anything else: automatic); every variant computes the same result.
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream);
 // sets the LDS attribute of every GEMM kernel on the current device (otherwise done by a kernel's first launch,
 // which must then not happen while a stream is being captured)

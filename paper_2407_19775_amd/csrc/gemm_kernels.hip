@@ -15,10 +15,9 @@
 // inside the instruction is irrelevant as long as both operands use the same piece for the same
 // lane group, which they do.
 //
-// Two kernels share these pieces:
-//   k_gemm_mixed     4 waves, small tiles, fragments double-buffered in registers (small problems)
-//   k_gemm_pingpong  8 waves, 256 x 256 tile: the two waves of a SIMD alternate between a memory
-//                    phase and an MFMA phase, so the matrix pipe always has a wave feeding it
+// One kernel, k_gemm_mixed, instantiated for several tile configurations (256 x 256 with eight waves for
+// large problems, smaller tiles for small ones); fragments are double-buffered in registers.
+#include <atomic>
 #include <type_traits>
 
 #include "codec_device.h"
@@ -611,250 +610,71 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
 }
 
 // ------------------------------------------------------------------------------------------------
-// Ping-pong kernel: 8 waves, two per SIMD (waves w and w + 4 share SIMD w % 4).  The time between
-// two workgroup barriers is one phase.  In a memory phase a wave reads all fragments of a slab
-// from LDS into registers and requests a slab from global memory; in an MFMA phase it issues the
-// 16 MFMAs of that slab at raised priority.  The second group of four waves runs one phase behind
-// the first, so on every SIMD one wave is always in its MFMA phase while the other fetches.
-//
-//   phase T:          2s            2s+1           2s+2
-//   waves 0-3:      MEM(s)       MFMA(s)        MEM(s+1)
-//   waves 4-7:      MFMA(s-1)    MEM(s)         MFMA(s)
-//
-// Slab s must be visible in LDS before phase 2s: every wave waits for its share of slab s+1 at
-// the end of phase 2s+1 (group 0: end of MFMA(s); group 1: end of MEM(s)) and the barrier makes
-// it visible.  Slab s + kAhead is requested during MEM(s) into the buffer of slab s - 1, whose
-// last reader (group 1, phase 2s-1) finished before the barrier that ended that phase.
-//
-// The first kOutlierSlab critical columns ride along as one more slab of fp16 operands
-// (X[m, O_j] and f16(Wt[n, O_j] c[n]/127), prepared by the pack kernel): same LDS layout, same
-// fragment reads, fp16 MFMAs onto the already dequantized accumulators.  The row scales of the
-// tile are brought into LDS by one extra request at the very start.
-// ------------------------------------------------------------------------------------------------
-template <class Cfg, bool kTap, bool kFull, bool kCoded>
-__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_pingpong(const GemmArgs a) {
-  extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
-  constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages, AHEAD = Cfg::kAhead;
-  constexpr int DPS = Cfg::DMA_PER_SLAB;
-  static_assert(Cfg::kWaves == 8, "two groups of four waves");
-
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int grp = wave >> 2;
-  reset_column_flags(a.flag_reset, a.Kpad);
-  int tm, tn;
-  if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
-  const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
-  const int n_slabs = a.Kpad / BK;
-  const int n_out = *a.n_out;
-  const bool has_slab_o = n_out > 0;
-  const int total_slabs = n_slabs + (has_slab_o ? 1 : 0);
-
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-  float* s_r = reinterpret_cast<float*>(smem + Cfg::RING_BYTES);
-  // the row scales first: the oldest request of wave 0, so every later wait covers it
-  if (wave == 0) dma16(a.r + p.m0 + lane * 4, lds0 + Cfg::RING_BYTES);
-
-  float cs[TJ], bn[TJ];
-  load_column_terms<Cfg>(a, p, cs, bn);
-
-  const int8_t* srcA[Cfg::A_DMA];
-  const int8_t* srcB[Cfg::B_DMA];
-  const int8_t* srcXo[Cfg::A_DMA];
-  const int8_t* srcWo[Cfg::B_DMA];
-#pragma unroll
-  for (int j = 0; j < Cfg::A_DMA; ++j) {
-    srcA[j] = dma_source(a.Xq, p.m0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcXo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, a.f_slabs, j, Cfg::kWaves, wave, lane);
-  }
-#pragma unroll
-  for (int j = 0; j < Cfg::B_DMA; ++j) {
-    srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
-    srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane);
-  }
-  auto issue_slab = [&](int slab, int stage) {
-    const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
-    const bool o = slab >= n_slabs;                                // the fp16 slab of critical columns
-#pragma unroll
-    for (int j = 0; j < Cfg::A_DMA; ++j)
-      dma16(o ? srcXo[j] : srcA[j] + (size_t)slab * kBlockBytes, base + j * Cfg::kWaves * (kWave * 16));
-#pragma unroll
-    for (int j = 0; j < Cfg::B_DMA; ++j)
-      dma16(o ? srcWo[j] : srcB[j] + (size_t)slab * kBlockBytes, base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
-  };
-
-  int a_off[NKS], b_off[NKS];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    // group of 32 rows: 2 KB = [k-step][lane] 16-byte pieces
-    a_off[ks] = (p.wm * Cfg::WM / 32) * 2048 + ks * 1024 + p.lane * 16;
-    b_off[ks] = Cfg::A_BYTES + (p.wn * Cfg::WN / 32) * 2048 + ks * 1024 + p.lane * 16;
-  }
-  v4i fa[NKS][TI], fb[NKS][TJ];
-  auto read_slab = [&](int stage) {
-    const int8_t* base = smem + stage * Cfg::STAGE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-#pragma unroll
-      for (int i = 0; i < TI; ++i) fa[ks][i] = *reinterpret_cast<const v4i*>(base + a_off[ks] + i * 32 * BK);
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) fb[ks][j] = *reinterpret_cast<const v4i*>(base + b_off[ks] + j * 32 * BK);
-    }
-  };
-
-  v16i acc[TI][TJ];
-#pragma unroll
-  for (int i = 0; i < TI; ++i)
-#pragma unroll
-    for (int j = 0; j < TJ; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
-
-  // kIssue: slab s + kAhead exists and is requested in this iteration.  kFp16: slab s is the slab
-  // of critical columns.
-  int stage = 0;
-  auto iteration = [&](int s, auto issue_tag, auto fp16_tag) {
-    constexpr bool kIssue = decltype(issue_tag)::value, kFp16 = decltype(fp16_tag)::value;
-    constexpr int kVm = kIssue ? (AHEAD - 1) * DPS : 0;            // younger than slab s+1: slabs s+2 .. s+kAhead
-    const int stage_req = (stage == 0) ? STAGES - 1 : stage - 1;   // (s + kAhead) mod kStages
-    // ---- memory phase (the accumulators are dequantized before the fp16 fragments occupy registers)
-    if constexpr (kFp16) dequantize_in_place<Cfg>(p, acc, s_r, cs);
-    read_slab(stage);
-    if (kIssue) issue_slab(s + AHEAD, stage_req);
-    if (grp == 1)
-      wait_slab_and_sync<kVm>();
-    else
-      wait_lds_and_sync();
-    // ---- MFMA phase
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (kFp16) {
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-#pragma unroll
-          for (int j = 0; j < TJ; ++j)
-            acc[i][j] = __builtin_bit_cast(
-                v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fa[ks][i]),
-                                                             __builtin_bit_cast(v8h, fb[ks][j]),
-                                                             __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
-    } else {
-      __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-#pragma unroll
-          for (int j = 0; j < TJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_s_setprio(0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (grp == 0)
-      wait_slab_and_sync<kVm>();
-    else
-      sync_only();
-    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
-  };
-  using yes = std::true_type;
-  using no = std::false_type;
-
-  static_assert(AHEAD == 3, "prologue written for three slabs ahead");
-  int issued = 0;
-  for (; issued < AHEAD && issued < total_slabs; ++issued) issue_slab(issued, issued);
-  if (issued == 1)
-    wait_slab_and_sync<0>();
-  else if (issued == 2)
-    wait_slab_and_sync<DPS>();
-  else
-    wait_slab_and_sync<2 * DPS>();
-  if (grp == 1) sync_only();                                       // group 1 runs one phase behind
-  int s = 0;
-  for (; s + AHEAD < total_slabs && s < n_slabs; ++s) iteration(s, yes{}, no{});
-  for (; s < n_slabs; ++s) iteration(s, no{}, no{});
-  if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
-  if (has_slab_o) {
-    iteration(s, no{}, yes{});
-  } else {
-    dequantize_in_place<Cfg>(p, acc, s_r, cs);
-  }
-  if (grp == 0) sync_only();                                       // as many barriers as group 1
-
-  if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
-  if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
-  if constexpr (kCoded)
-    store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
-  else
-    store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
-}
-
-// ------------------------------------------------------------------------------------------------
 // The kernels need more LDS than a kernel gets by default; the attribute is set once per instantiation and device,
 // by prepare_gemm_kernels() (called when a workspace is set up) or else by the first launch.
-template <class Cfg, bool kTap, bool kFull, bool kPingPong, bool kCoded>
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
 static hipError_t ensure_lds_attribute() {
-  static bool attr_set[64] = {};                                   // per device: the attribute belongs to the device's code object
+  // per device: the attribute belongs to the device's code object.  Two threads may both find it unset and set
+  // it twice, which is harmless.
+  static std::atomic<bool> attr_set[64] = {};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (attr_set[dev]) return hipSuccess;
-  const void* fn;
-  if constexpr (kPingPong)
-    fn = reinterpret_cast<const void*>(&k_gemm_pingpong<Cfg, kTap, kFull, kCoded>);
-  else
-    fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull, kCoded>);
+  const void* fn = reinterpret_cast<const void*>(&k_gemm_mixed<Cfg, kTap, kFull, kCoded>);
   const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
   if (e == hipSuccess) attr_set[dev] = true;
   return e;
 }
 
-template <class Cfg, bool kTap, bool kFull, bool kPingPong, bool kCoded>
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
-  if (hipError_t e = ensure_lds_attribute<Cfg, kTap, kFull, kPingPong, kCoded>(); e != hipSuccess) return e;
+  if (hipError_t e = ensure_lds_attribute<Cfg, kTap, kFull, kCoded>(); e != hipSuccess) return e;
   const int grid = ceil_div(a.tiles_m * a.tiles_n, 8) * 8;
-  if constexpr (kPingPong)
-    hipLaunchKernelGGL((k_gemm_pingpong<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
-  else
-    hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL((k_gemm_mixed<Cfg, kTap, kFull, kCoded>), dim3(grid), dim3(Cfg::kThreads), Cfg::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
-template <class Cfg, bool kPingPong>
+template <class Cfg>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t stream) {
   a.tiles_m = ceil_div(a.M, Cfg::BM);
   a.tiles_n = ceil_div(a.N, Cfg::BN);
   const bool full = (a.M % Cfg::BM == 0) && (a.N % Cfg::BN == 0);
   if (a.codes || a.residual || a.gelu) {
     if (a.codes && Cfg::BN % (1 << a.code_log_block) != 0) return hipErrorInvalidValue;   // a block would leave the tile
-    if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, true>(a, stream);
-    return full ? launch_one<Cfg, false, true, kPingPong, true>(a, stream)
-                : launch_one<Cfg, false, false, kPingPong, true>(a, stream);
+    if (a.tap_acc) return launch_one<Cfg, true, false, true>(a, stream);
+    return full ? launch_one<Cfg, false, true, true>(a, stream)
+                : launch_one<Cfg, false, false, true>(a, stream);
   }
-  if (a.tap_acc) return launch_one<Cfg, true, false, kPingPong, false>(a, stream);
-  return full ? launch_one<Cfg, false, true, kPingPong, false>(a, stream)
-              : launch_one<Cfg, false, false, kPingPong, false>(a, stream);
+  if (a.tap_acc) return launch_one<Cfg, true, false, false>(a, stream);
+  return full ? launch_one<Cfg, false, true, false>(a, stream)
+              : launch_one<Cfg, false, false, false>(a, stream);
 }
 
 // every instantiation launch_cfg can reach
-template <class Cfg, bool kPingPong>
+// The tile configurations, by the number a caller can force one with (gemm.h):
+using Cfg0 = GemmCfg<128, 128, 2, 2, 3, 3>;   // 49 KB of LDS: three workgroups per CU
+using Cfg1 = GemmCfg<256, 128, 2, 2, 3, 2>;
+using Cfg2 = GemmCfg<128, 256, 2, 2, 3, 2>;
+using Cfg3 = GemmCfg<256, 256, 2, 4, 3, 2>;
+using Cfg4 = GemmCfg<256, 256, 2, 4, 4, 2>;   // the large tile: whole rounds of one tile per CU
+using Cfg5 = GemmCfg<128, 256, 2, 4, 4, 2>;   // remainders and less than one round of large tiles
+template <class Cfg>
 static hipError_t prepare_cfg() {
-  hipError_t e = ensure_lds_attribute<Cfg, true, false, kPingPong, false>();
-  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, kPingPong, false>();
-  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, kPingPong, false>();
-  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, true, false, kPingPong, true>();
-  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, kPingPong, true>();
-  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, kPingPong, true>();
+  hipError_t e = ensure_lds_attribute<Cfg, true, false, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, false>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, true, false, true>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, true, true>();
+  if (e == hipSuccess) e = ensure_lds_attribute<Cfg, false, false, true>();
   return e;
 }
 hipError_t prepare_gemm_kernels() {
-  hipError_t e = prepare_cfg<GemmCfg<128, 128, 2, 2, 3, 3>, false>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, true>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>();
-  if (e == hipSuccess) e = prepare_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>();
+  hipError_t e = prepare_cfg<Cfg0>();
+  if (e == hipSuccess) e = prepare_cfg<Cfg1>();
+  if (e == hipSuccess) e = prepare_cfg<Cfg2>();
+  if (e == hipSuccess) e = prepare_cfg<Cfg3>();
+  if (e == hipSuccess) e = prepare_cfg<Cfg4>();
+  if (e == hipSuccess) e = prepare_cfg<Cfg5>();
   return e;
 }
 
@@ -862,14 +682,12 @@ static hipError_t launch_variant(const GemmArgs& a, int variant, hipStream_t str
   // coded output with blocks wider than the 128-column tiles: the 256-column tile of the same height class
   if (a.codes && a.code_log_block > 7 && (variant == 0 || variant == 1)) variant = 2;
   switch (variant) {
-    case 1: return launch_cfg<GemmCfg<256, 128, 2, 2, 3, 2>, false>(a, stream);
-    case 2: return launch_cfg<GemmCfg<128, 256, 2, 2, 3, 2>, false>(a, stream);
-    case 3: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, true>(a, stream);
-    case 4: return launch_cfg<GemmCfg<256, 256, 4, 2, 4, 2>, true>(a, stream);
-    case 5: return launch_cfg<GemmCfg<256, 256, 2, 4, 3, 2>, false>(a, stream);
-    case 6: return launch_cfg<GemmCfg<256, 256, 2, 4, 4, 2>, false>(a, stream);
-    case 7: return launch_cfg<GemmCfg<128, 256, 2, 4, 4, 2>, false>(a, stream);
-    default: return launch_cfg<GemmCfg<128, 128, 2, 2, 3, 3>, false>(a, stream);   // 49 KB of LDS: three workgroups per CU
+    case 1: return launch_cfg<Cfg1>(a, stream);
+    case 2: return launch_cfg<Cfg2>(a, stream);
+    case 3: return launch_cfg<Cfg3>(a, stream);
+    case 4: return launch_cfg<Cfg4>(a, stream);
+    case 5: return launch_cfg<Cfg5>(a, stream);
+    default: return launch_cfg<Cfg0>(a, stream);
   }
 }
 
@@ -891,7 +709,7 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
 }
 
 hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream) {
-  if (variant >= 0) return launch_variant(a, variant, stream);
+  if (variant >= 0 && variant <= 5) return launch_variant(a, variant, stream);
   // Automatic.  The 256 x 256 tile with the four-slab ring is the most efficient per CU, but it runs
   // in rounds of one tile per CU.  Whole rounds go to it; a remainder that would leave a good part of
   // the chip idle is launched separately with 128 x 256 tiles (same ring depth, twice as many
@@ -906,13 +724,13 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     const int n_tiles_main = (int)((tiles_256 - rest) / tiles_m);      // whole columns of tiles in the whole rounds
     const int n_tiles_rest = tiles_n - n_tiles_main;
     if (rest > 0 && 2 * rest <= cus && n_tiles_main > 0 && n_tiles_rest > 0) {
-      hipError_t e = launch_variant(column_range(a, 0, n_tiles_main * 256), 6, stream);
+      hipError_t e = launch_variant(column_range(a, 0, n_tiles_main * 256), 4, stream);
       if (e != hipSuccess) return e;
-      return launch_variant(column_range(a, n_tiles_main * 256, a.N - n_tiles_main * 256), 7, stream);
+      return launch_variant(column_range(a, n_tiles_main * 256, a.N - n_tiles_main * 256), 5, stream);
     }
-    return launch_variant(a, 6, stream);
+    return launch_variant(a, 4, stream);
   }
-  if (a.M > 64 && 2 * tiles_128x256 >= cus) return launch_variant(a, 7, stream);   // less than one round of large tiles
+  if (a.M > 64 && 2 * tiles_128x256 >= cus) return launch_variant(a, 5, stream);   // less than one round of large tiles
   if (a.M > 64 && tiles_128x256 >= 64) return launch_variant(a, 2, stream);
   return launch_variant(a, 0, stream);
 }

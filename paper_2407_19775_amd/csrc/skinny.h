@@ -24,7 +24,6 @@ struct SkinnyPlan {
 };
 // how the K range is split between workgroups for this shape (depends on the device's CU count)
 SkinnyPlan plan_skinny(int M, int K, int N);
-void set_panel_waves(int waves);   // tuning hook: force 4 or 8 waves per panel workgroup (0 = automatic)
 
 struct SkinnyArgs {
   const int8_t* Xq;       // activation codes, blocked layout, rows 0..63 of panel 0

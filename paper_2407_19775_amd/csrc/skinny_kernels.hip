@@ -25,6 +25,8 @@
 // 16-bit part (the same decision for the whole workgroup).
 #include <type_traits>
 
+#include <atomic>
+
 #include "codec_device.h"
 #include "common.h"
 #include "operand_layout.h"
@@ -426,7 +428,6 @@ __global__ void k_fill_i32(int32_t* __restrict__ p, size_t n) {
 }
 
 // Decode plan: `waves` neighbouring 32-column groups per workgroup.
-static int g_panel_waves, g_panel_splits;
 static SkinnyPlan plan_panel(int M, int K, int N, int waves) {
   SkinnyPlan p;
   p.waves = waves;
@@ -435,22 +436,16 @@ static SkinnyPlan plan_panel(int M, int K, int N, int waves) {
   // as many workgroups as the chip holds at once (two of four waves or one of eight per CU), every
   // workgroup with at least 8 slabs, no second round
   const int slots = device_cu_count() * (waves == 4 ? 2 : 1);
-  const int want = g_panel_splits > 0 ? min(g_panel_splits, p.n_slabs) : max(1, min(p.n_slabs / 8, slots / p.tiles_n));
+  const int want = max(1, min(p.n_slabs / 8, slots / p.tiles_n));
   p.slabs_per_split = ceil_div(p.n_slabs, want);
   p.splits = ceil_div(p.n_slabs, p.slabs_per_split);
   p.partial_bytes = p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
   return p;
 }
-// tuning hook: 0 = automatic
-void set_panel_waves(int w) {                        // waves + 100 * (forced number of K splits)
-  g_panel_splits = w / 100;
-  w %= 100;
-  g_panel_waves = (w == 4 || w == 8) ? w : 0;
-}
 SkinnyPlan plan_skinny(int M, int K, int N) {
   const SkinnyPlan p4 = plan_panel(M, K, N, 4), p8 = plan_panel(M, K, N, 8);
   // measured on the Llama-7B linears: eight waves per panel beat four (half the LDS fills per weight byte)
-  SkinnyPlan p = (g_panel_waves == 4) ? p4 : p8;
+  SkinnyPlan p = p8;
   p.partial_bytes = max(p4.partial_bytes, p8.partial_bytes);     // the workspace serves either
   return p;
 }
@@ -750,7 +745,7 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
 
 // more than the default 64 KB of LDS: an attribute per kernel and device
 hipError_t prepare_rows_kernels() {
-  static bool attr_set[64] = {};
+  static std::atomic<bool> attr_set[64] = {};                      // setting an attribute twice is harmless
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (attr_set[dev]) return hipSuccess;

@@ -1,6 +1,6 @@
 """Up to eight rows: the decode GEMM kernel prepares its own operands (row scales, codes, critical columns) and
 the scan and pack kernels are left out.  The result must equal, bit for bit, the one obtained with those kernels
-(forced through the tuning hook, or by asking for their taps), the int32 accumulators must equal the oracle's, and
+(forced through the call's tuning word, or by asking for their taps), the int32 accumulators must equal the oracle's, and
 the output must meet the oracle's to the fp16 bar; with every companion of the layer (bias, adapter, activation,
 coded input, coded output).  One or two rows (while their operands fit in LDS) go through a single kernel that shares K out between the waves of a
 workgroup: same integers, and an output that may differ from the split-K kernels' in the last fp16 bit (another
@@ -17,13 +17,32 @@ from gpu_util import assert_y_close, to_gpu, to_np
 pytestmark = pytest.mark.gpu
 
 
+class Tune:
+    """The kernel choice handed to every call of this module (mmd8_debug_taps.tuning): per call, no library state."""
+    value = 0
+
+
+def lin(*args, **kw):
+    return binding.mixed_int8_linear(*args, tuning=Tune.value, **kw)
+
+
+def lin_to_codes(*args, **kw):
+    return binding.mixed_int8_linear_to_codes(*args, tuning=Tune.value, **kw)
+
+
+def rows_kernel(on):
+    Tune.value = (Tune.value & ~binding.TUNE_NO_ROWS_KERNEL) | (0 if on else binding.TUNE_NO_ROWS_KERNEL)
+
+
+def own_prep(on):
+    Tune.value = (Tune.value & ~binding.TUNE_SEPARATE_PREP) | (0 if on else binding.TUNE_SEPARATE_PREP)
+
+
 @pytest.fixture(autouse=True)
 def own_prep_on():
-    binding.lib().mmd8_set_panel_prep(1)
-    binding.lib().mmd8_set_rows_kernel(1)
+    Tune.value = 0
     yield
-    binding.lib().mmd8_set_panel_prep(1)
-    binding.lib().mmd8_set_rows_kernel(1)
+    Tune.value = 0
 
 
 def fp16_steps(a, b):
@@ -59,19 +78,19 @@ def test_own_preparation_equals_the_separate_kernels(K, N):
             Xbuf = torch.zeros((M, K + 8), dtype=torch.float16, device="cuda")
             Xg = Xbuf[:, :K]
             Xg.copy_(to_gpu(X))
-            binding.lib().mmd8_set_rows_kernel(0)
-            Y_taps, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)     # scan + pack (their taps asked for)
-            binding.lib().mmd8_set_panel_prep(0)
-            Y_off = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)                       # scan + pack (hook)
-            binding.lib().mmd8_set_panel_prep(1)
-            Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))   # own preparation in the panel kernel
-            binding.lib().mmd8_set_rows_kernel(1)
+            rows_kernel(0)
+            Y_taps, taps = lin(Xg, pw, tau, bias=bg, taps=True)     # scan + pack (their taps asked for)
+            own_prep(0)
+            Y_off = lin(Xg, pw, tau, bias=bg)                       # scan + pack (hook)
+            own_prep(1)
+            Y, t_acc = lin(Xg, pw, tau, bias=bg, taps=("acc",))   # own preparation in the panel kernel
+            rows_kernel(1)
             torch.cuda.synchronize()
             assert torch.equal(Y, Y_off) and torch.equal(Y, Y_taps), (M, K, N, tau)
             assert torch.equal(t_acc["acc"], taps["acc"]), (M, K, N, tau)
             if M <= 2 and 3 * M * ((K + 63) // 64 * 64) <= 66 * 1024:                     # the single kernel
-                Y, t_acc = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=("acc",))
-                Y_all, t_all = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True)   # scan + pack for their taps only
+                Y, t_acc = lin(Xg, pw, tau, bias=bg, taps=("acc",))
+                Y_all, t_all = lin(Xg, pw, tau, bias=bg, taps=True)   # scan + pack for their taps only
                 torch.cuda.synchronize()
                 assert torch.equal(t_acc["acc"], taps["acc"]), (M, K, N, tau)
                 assert torch.equal(Y, Y_all), (M, K, N, tau)
@@ -97,19 +116,19 @@ def test_companions_of_the_layer(M):
     cg, ag = to_gpu(codes_o), to_gpu(absmax_o)
 
     def run_all():
-        out = [binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, lora=(A, B)),
-               binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, gelu=True)]
+        out = [lin(Xg, pw, wl.TAU, bias=bg, lora=(A, B)),
+               lin(Xg, pw, wl.TAU, bias=bg, gelu=True)]
         Xd = torch.empty((M, K), dtype=torch.float16, device="cuda")
-        out.append(binding.mixed_int8_linear(Xd, pw, wl.TAU, bias=bg, coded=(cg, ag, 256)))
+        out.append(lin(Xd, pw, wl.TAU, bias=bg, coded=(cg, ag, 256)))
         out.append(Xd)
-        out.extend(binding.mixed_int8_linear_to_codes(Xg, pw, wl.TAU, 1024, bias=bg, residual=R))
+        out.extend(lin_to_codes(Xg, pw, wl.TAU, 1024, bias=bg, residual=R))
         torch.cuda.synchronize()
         return out
 
     on = run_all()
-    binding.lib().mmd8_set_panel_prep(0)
+    own_prep(0)
     off = run_all()
-    binding.lib().mmd8_set_panel_prep(1)
+    own_prep(1)
     for i, (a, b_) in enumerate(zip(on, off)):
         if a.dtype == torch.float16 and i == 1 and M <= 2:
             # GELU of a pre-activation that moved by one fp16 step: many steps of the much smaller output
@@ -122,10 +141,10 @@ def test_companions_of_the_layer(M):
             assert torch.equal(a, b_), i
     # the coded output (last two entries) is encoded by the kernel that sums the partial outputs on both ways
     assert torch.equal(on[-2], off[-2]) and torch.equal(on[-1], off[-1])
-    Rplain = binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, residual=R)
-    binding.lib().mmd8_set_rows_kernel(0)
-    Rpanel = binding.mixed_int8_linear(Xg, pw, wl.TAU, bias=bg, residual=R)
-    binding.lib().mmd8_set_rows_kernel(1)
+    Rplain = lin(Xg, pw, wl.TAU, bias=bg, residual=R)
+    rows_kernel(0)
+    Rpanel = lin(Xg, pw, wl.TAU, bias=bg, residual=R)
+    rows_kernel(1)
     torch.cuda.synchronize()
     assert_y_close(to_np(Rplain), to_np(Rpanel), rel=2e-3)
 
@@ -139,8 +158,8 @@ def test_same_workspace_alternates_between_both_ways():
     X64 = to_gpu(wl.to_fp16(np.random.default_rng(1).standard_t(3.0, size=(64, K)).astype(np.float32)))
     ys = []
     for i in range(3):
-        ys.append(binding.mixed_int8_linear(Xg, pw, wl.TAU, workspace=ws))
-        y64 = binding.mixed_int8_linear(X64, pw, wl.TAU, workspace=ws)           # scan + pack, leaves the flags zero again
+        ys.append(lin(Xg, pw, wl.TAU, workspace=ws))
+        y64 = lin(X64, pw, wl.TAU, workspace=ws)           # scan + pack, leaves the flags zero again
         if i == 0:
             y64_first = y64
         else:

@@ -29,7 +29,7 @@ def make_case(M, K, N, seed, heavy=False, bias=True, residual=True):
     return X, W, b, R
 
 
-def run_and_check(X, W, b, R, block, tau=wl.TAU, want_h=True, taps=False, pad_r=0):
+def run_and_check(X, W, b, R, block, tau=wl.TAU, want_h=True, taps=False, pad_r=0, tuning=0):
     M, K = X.shape
     N = W.shape[1]
     pw = binding.prequantize_weight(to_gpu(W))
@@ -47,8 +47,8 @@ def run_and_check(X, W, b, R, block, tau=wl.TAU, want_h=True, taps=False, pad_r=
     codes = torch.full((n + 16,), 0xAB, dtype=torch.uint8, device="cuda")
     absmax = torch.full((nb + 4,), -1.0, dtype=torch.float32, device="cuda")
     out = binding.mixed_int8_linear_to_codes(Xg, pw, tau, block, bias=bg, residual=Rg, codes=codes, absmax=absmax,
-                                             H=Hg, taps=taps)
-    Y_plain = binding.mixed_int8_linear(Xg, pw, tau, bias=bg)
+                                             H=Hg, taps=taps, tuning=tuning)
+    Y_plain = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, tuning=tuning)
     torch.cuda.synchronize()
     o = be.mixed_int8_linear_to_codes(X, Wq_o, c_o, tau, block, bias=b, residual=R)
     codes_g, absmax_g = to_np(codes), to_np(absmax)
@@ -122,13 +122,9 @@ def test_taps_and_thresholds():
 
 def test_every_tile_configuration_encodes_alike():
     X, W, b, R = make_case(300, 272, 768, 1)
-    try:
-        for variant in range(8):
-            binding.lib().mmd8_set_gemm_variant(variant)
-            for block in (64, 256):
-                run_and_check(X, W, b, R, block, want_h=bool(variant % 2))
-    finally:
-        binding.lib().mmd8_set_gemm_variant(-1)
+    for variant in range(6):
+        for block in (64, 256):
+            run_and_check(X, W, b, R, block, want_h=bool(variant % 2), tuning=binding.tune_gemm_tiles(variant))
 
 
 def test_zero_rows_and_blocks_take_the_zero_code():

@@ -16,15 +16,15 @@ from gpu_util import assert_y_close, to_gpu, to_np
 pytestmark = pytest.mark.gpu
 
 
-def check_lora(X, W, A, B, tau, bias=None, rows=None):
+def check_lora(X, W, A, B, tau, bias=None, rows=None, tuning=0):
     pw = binding.prequantize_weight(to_gpu(W))
     Wq_o, c_o = ml.prequantize_weight(W)
     M, r = X.shape[0], A.shape[0]
     Xg, Ag, Bg = to_gpu(X), to_gpu(A), to_gpu(B)
     bg = to_gpu(bias) if bias is not None else None
     T = torch.full((M, r), float("nan"), dtype=torch.float16, device="cuda")
-    Y, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True, lora=(Ag, Bg, T))
-    Y2 = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, lora=(Ag, Bg))          # untapped, no T output
+    Y, taps = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, taps=True, lora=(Ag, Bg, T), tuning=tuning)
+    Y2 = binding.mixed_int8_linear(Xg, pw, tau, bias=bg, lora=(Ag, Bg), tuning=tuning)   # untapped, no T output
     torch.cuda.synchronize()
     o = lora.mixed_int8_linear_lora(X, Wq_o, c_o, tau, A, B, bias, rows=rows)
     sel = slice(None) if rows is None else np.asarray(rows)
@@ -91,17 +91,13 @@ def test_prefill_full_size(shape):
     check_lora(X, W, A, B, wl.TAU)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
 def test_every_gemm_tile_configuration(variant):
-    L = binding.lib()
-    L.mmd8_set_gemm_variant(variant)
-    try:
-        X, W, A, B = rand_case(variant, 300, 1040, 520, 64, outlier_cols=(3, 777))
-        check_lora(X, W, A, B, 6.0)
-        X, W, A, B = rand_case(variant + 50, 512, 1024, 512, 32)     # full tiles: the unchecked store path
-        check_lora(X, W, A, B, 6.0)
-    finally:
-        L.mmd8_set_gemm_variant(-1)
+    tune = binding.tune_gemm_tiles(variant)
+    X, W, A, B = rand_case(variant, 300, 1040, 520, 64, outlier_cols=(3, 777))
+    check_lora(X, W, A, B, 6.0, tuning=tune)
+    X, W, A, B = rand_case(variant + 50, 512, 1024, 512, 32)     # full tiles: the unchecked store path
+    check_lora(X, W, A, B, 6.0, tuning=tune)
 
 
 def test_one_workspace_with_and_without_the_adapter():

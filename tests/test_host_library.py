@@ -32,6 +32,42 @@ def test_every_declared_symbol_is_exported():
         assert name in names
 
 
+def test_every_exported_symbol_is_declared():
+    """The other direction: the library exports no mmd8_* function that the header does not declare."""
+    import shutil
+    import subprocess
+    if shutil.which("nm") is None:
+        pytest.skip("no nm")
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = sorted({line.split()[-1] for line in out.splitlines() if re.search(r"\s[TW]\s+mmd8_", line)})
+    assert exported, "no mmd8_* symbols found"
+    assert exported == declared_functions()
+
+
+def test_packed_weights_of_another_layout_are_refused():
+    """A blob written under another layout tag is not multiplied: MMD8_E_VERSION before anything is launched."""
+    L = binding.lib()
+    fake, y = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    tag = L.mmd8_packed_weight_layout()
+    ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
+    for bad in (0, tag - 1, tag + 1, tag ^ 0x00010000):
+        assert L.mmd8_mixed_int8_linear(fake, 8, 128, 128, fake, bad, fake, 64, None, 6.0, y, 64, fake, ws, None, None) == -5
+        assert L.mmd8_mixed_int8_linear_gelu(fake, 8, 128, 128, fake, bad, fake, 64, None, 6.0, y, 64, fake, ws, None, None) == -5
+        assert L.mmd8_mixed_int8_linear_residual(fake, 8, 128, 128, fake, bad, fake, 64, None, 6.0, fake, 64, y, 64, fake, ws,
+                                                 None, None) == -5
+        assert L.mmd8_mixed_int8_linear_to_codes(fake, 8, 128, 128, fake, bad, fake, 64, None, 6.0, None, 64, 64, y, y, None,
+                                                 fake, L.mmd8_linear_to_codes_workspace_bytes(8, 128, 64, 64), None, None) == -5
+        assert L.mmd8_mixed_int8_linear_lora(fake, 8, 128, 128, fake, bad, fake, 64, None, 6.0, fake, fake, 16, None, y, 64, fake,
+                                             L.mmd8_linear_lora_workspace_bytes(8, 128, 64, 16), None, None) == -5
+        assert L.mmd8_mixed_int8_linear_from_codes(fake, fake, 64, 8, 128, y, fake, bad, fake, 64, None, 6.0,
+                                                   ctypes.c_void_p(0x4000), 64, fake, ws, None, None) == -5
+        assert L.mmd8_unpack_weight(fake, bad, 128, 64, y, None) == -5
+        assert L.mmd8_mixed_int8_linear(None, 0, 128, 128, None, bad, None, 64, None, 6.0, None, 64, None, 0, None, None) == -5
+    assert b"layout" in L.mmd8_status_string(-5)
+    pw = binding.PackedWeight(None, None, 128, 64, layout=tag + 1)       # the binding hands the stored tag back
+    assert pw.layout == tag + 1 and binding.PackedWeight(None, None, 128, 64).layout == tag
+
+
 def test_host_tables_equal_the_oracle_bit_for_bit():
     T = binding.code_table().numpy()
     Mid = binding.code_midpoints().numpy()
@@ -88,12 +124,13 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert L.mmd8_prequantize_weight(fake, 128, 64, 32, fake, fake, None) == -1    # ldw < N
     assert L.mmd8_prequantize_weight(fake, 128, 64, 64, None, fake, None) == -1
     ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
+    tag = L.mmd8_packed_weight_layout()
     args = dict(X=fake, M=8, K=128, ldx=128, W=fake, c=fake, N=64, bias=None, tau=6.0, Y=ctypes.c_void_p(0x2000),
                 ldy=64, ws=fake, wsb=ws)
 
     def call(**kw):
         a = dict(args, **kw)
-        return L.mmd8_mixed_int8_linear(a["X"], a["M"], a["K"], a["ldx"], a["W"], a["c"], a["N"], a["bias"],
+        return L.mmd8_mixed_int8_linear(a["X"], a["M"], a["K"], a["ldx"], a["W"], tag, a["c"], a["N"], a["bias"],
                                         a["tau"], a["Y"], a["ldy"], a["ws"], a["wsb"], None, None)
 
     assert call(K=100) == -2
@@ -102,6 +139,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert call(ldx=64) == -1
     assert call(ldy=60) == -1
     assert call(Y=fake) == -1                                                      # aliasing X
+    assert call(Y=ctypes.c_void_p(0x1000 + 16)) == -1                              # overlapping X (8 x 128 fp16 = 2 KB)
+    assert call(Y=ctypes.c_void_p(0x1000 + 2032)) == -1                            # its last 16 bytes
+    assert call(Y=ctypes.c_void_p(0x1000 + 2048), wsb=ws - 1) == -3                # right behind X: passes that check
     assert call(wsb=ws - 1) == -3
     assert call(X=None) == -1
     assert call(M=-1) == -1
@@ -120,8 +160,8 @@ def test_adapter_arguments_are_rejected_before_any_launch():
     ws = L.mmd8_linear_lora_workspace_bytes(8, 128, 64, 16)
 
     def call(A=fake, B=fake, r=16, T=None, wsb=ws, K=128):
-        return L.mmd8_mixed_int8_linear_lora(fake, 8, K, 128, fake, fake, 64, None, 6.0, A, B, r, T, y, 64, fake, wsb,
-                                             None, None)
+        return L.mmd8_mixed_int8_linear_lora(fake, 8, K, 128, fake, L.mmd8_packed_weight_layout(), fake, 64, None, 6.0, A, B, r,
+                                             T, y, 64, fake, wsb, None, None)
 
     assert call(r=4) == -2 and call(r=20) == -2 and call(r=128) == -2
     assert call(A=None) == -1 and call(B=None) == -1
@@ -148,8 +188,8 @@ def test_coded_output_arguments_are_rejected_before_any_launch():
     ws = wsb(8, 128, 64, 64)
 
     def call(res=None, ldr=64, block=64, codes=out, absmax=out, H=None, wsb_=ws, K=128):
-        return L.mmd8_mixed_int8_linear_to_codes(fake, 8, K, 128, fake, fake, 64, None, 6.0, res, ldr, block, codes, absmax, H,
-                                                 fake, wsb_, None, None)
+        return L.mmd8_mixed_int8_linear_to_codes(fake, 8, K, 128, fake, L.mmd8_packed_weight_layout(), fake, 64, None, 6.0, res,
+                                                 ldr, block, codes, absmax, H, fake, wsb_, None, None)
 
     assert call(block=48) == -2 and call(block=8192) == -2 and call(K=100) == -2
     assert call(codes=None) == -1 and call(absmax=None) == -1 and call(codes=odd) == -1
@@ -165,7 +205,8 @@ def test_residual_arguments_are_rejected_before_any_launch():
     ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
 
     def call(res=fake, ldr=64, Y=y, K=128):
-        return L.mmd8_mixed_int8_linear_residual(fake, 8, K, 128, fake, fake, 64, None, 6.0, res, ldr, Y, 64, fake, ws, None, None)
+        return L.mmd8_mixed_int8_linear_residual(fake, 8, K, 128, fake, L.mmd8_packed_weight_layout(), fake, 64, None, 6.0, res, ldr,
+                                                 Y, 64, fake, ws, None, None)
 
     assert call(res=None) == -1 and call(res=odd) == -1 and call(ldr=56) == -1 and call(ldr=68) == -1
     assert call(Y=None) == -1 and call(K=100) == -2
@@ -185,3 +226,29 @@ def test_public_headers_are_plain_c():
         r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
                             "-I", os.path.join(ROOT, "include"), src], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_gelu_coefficients_in_the_kernel_header_reproduce_erfc():
+    """The GPU's GELU is x Phi(x) with Phi(-|x|) = t exp(-z^2 + g(t)) / 2, t = 1 / (1 + z / 2), z = |x| / sqrt 2, g a
+    degree-8 polynomial whose coefficients are written out in csrc/common.h.  Re-evaluated here in float64 from
+    the header's own text and compared with math.erfc over the whole range in which the result is a nonzero fp16
+    number: the constants are pinned to the function, not to the script that once fitted them."""
+    import math
+    text = open(os.path.join(ROOT, "paper_2407_19775_amd", "csrc", "common.h")).read()
+    body = text[text.index("gelu_to_half_bits(float x)"):]
+    body = body[:body.index("return float_to_half_bits")]
+    lead = float(re.search(r"float g = ([-+0-9.e]+)f;", body).group(1))
+    rest = [float(v) for v in re.findall(r"g = __builtin_fmaf\(g, t, ([-+0-9.e]+)f\);", body)]
+    assert len(rest) == 8
+    worst = 0.0
+    for i in range(0, 5501):
+        x = i * 1e-3
+        z = x / math.sqrt(2.0)
+        t = 1.0 / (1.0 + 0.5 * z)
+        g = lead
+        for c in rest:
+            g = g * t + c
+        phi = 0.5 * t * math.exp(-z * z + g)
+        exact = 0.5 * math.erfc(z)
+        worst = max(worst, abs(phi - exact) / exact)
+    assert worst < 1e-5, worst
