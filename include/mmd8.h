@@ -152,6 +152,22 @@ int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
                            void* workspace /*DEVICE*/, size_t workspace_bytes,
                            const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
+/* mmd8_mixed_int8_linear for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and errors, without the
+ * workspace: the library's own device array of MMD8_STATIC_WORKSPACE_BYTES serves as one (every GPU the library
+ * runs on holds it until the process ends; that is enough for up to 64 rows of every Llama-7B- and
+ * 70B-shaped linear).  A problem with mmd8_linear_workspace_bytes(M, K, N) above that size returns
+ * MMD8_E_WORKSPACE and launches nothing.  The call allocates and frees nothing and synchronises nothing; the
+ * first call on a device looks up the array's address and sets kernel attributes (make it before a capture
+ * starts).  All calls on one GPU share the one array: calls that overlap in time (two streams, two threads)
+ * race; order them. */
+#define MMD8_STATIC_WORKSPACE_BYTES (32u << 20)
+int mmd8_mixed_int8_linear_static(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                  const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
+                                  const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                  mmd8_half* Y /*DEVICE*/, int ldy,
+                                  const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
 /* The same layer applied to activations that arrive in blockwise-coded form (the hidden state a
  * shard receives from its predecessor: "Compression techniques", item 1 feeding item 2):
  *     X = dequantize_blockwise(codes, absmax, block)        as [M, K], contiguous (ldx = K)

@@ -20,7 +20,7 @@ EXPORTS = (
     "mmd8_unpack_weight", "mmd8_linear_workspace_bytes", "mmd8_linear_workspace_init", "mmd8_mixed_int8_linear",
     "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
     "mmd8_mixed_int8_linear_lora", "mmd8_linear_to_codes_workspace_bytes", "mmd8_mixed_int8_linear_to_codes",
-    "mmd8_mixed_int8_linear_gelu", "mmd8_mixed_int8_linear_residual",
+    "mmd8_mixed_int8_linear_gelu", "mmd8_mixed_int8_linear_residual", "mmd8_mixed_int8_linear_static",
 )
 
 
@@ -66,6 +66,8 @@ def lib():
         L.mmd8_linear_workspace_init.argtypes = [vp, sz, vp]
         L.mmd8_mixed_int8_linear.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32, vp, sz,
                                              ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_mixed_int8_linear_static.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32,
+                                                    ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, u32, vp, i32, vp, f32, vp, i32, vp, sz,
                                                         ctypes.POINTER(DebugTaps), vp]
         L.mmd8_linear_lora_workspace_bytes.restype = sz
@@ -326,3 +328,26 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
         workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
     return (out, tensors) if taps else out
 
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def mixed_int8_linear_static(X: torch.Tensor, pw: PackedWeight, tau: float, out: torch.Tensor, bias: torch.Tensor = None,
+                             taps: bool = False):
+    """mixed_int8_linear without a workspace argument (the library's own device array serves as one): for callers
+    that cannot allocate.  `out` must be given; nothing is allocated here unless taps are asked for."""
+    _dev(X, torch.float16, "X")
+    _dev(out, torch.float16, "out")
+    M, K = X.shape
+    if K != pw.K or X.stride(1) != 1:
+        raise Mmd8Error("X must be [M, %d] with unit stride along K" % pw.K)
+    N = pw.N
+    if out.shape != (M, N) or out.stride(1) != 1:
+        raise Mmd8Error("out must be [M, N] with unit stride along N")
+    tensors = _taps(M, K, N, X.device) if taps else None
+    tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()}) if taps else None
+    _check(lib().mmd8_mixed_int8_linear_static(
+        X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
+        bias.data_ptr() if bias is not None else None, float(tau), out.data_ptr(), out.stride(0) if M > 0 else N,
+        ctypes.byref(tp) if tp is not None else None, _stream()))
+    return (out, tensors) if taps else out

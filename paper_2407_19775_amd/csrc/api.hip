@@ -480,6 +480,57 @@ int mmd8_mixed_int8_linear(const mmd8_half* X, int M, int K, int ldx, const int8
                     workspace_bytes, taps, nullptr, nullptr, nullptr, stream);
 }
 
+// ---- The layer for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops):
+// the workspace is a file-scope device array instead of an argument.  Host code never uses the array's name as an
+// address: the device address is asked for once per device (hipGetSymbolAddress, with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[MMD8_STATIC_WORKSPACE_BYTES];
+namespace {
+struct StaticWorkspace {
+  void* ptr;       // device address of `scratch` on this device; null until the first call on it
+  bool head_zero;  // the head (counters, column flags) holds zeros: true between calls that succeeded
+};
+StaticWorkspace g_static_ws[64];
+std::mutex g_static_mu;
+}  // namespace
+
+int mmd8_mixed_int8_linear_static(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, uint32_t Wq_layout,
+                                  const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
+                                  const mmd8_debug_taps* taps, void* stream) {
+  if (M < 0) return MMD8_E_ARG;
+  if (int s = check_linear_shape(K, N)) return s;
+  if (carve(nullptr, M, K, N).bytes > (size_t)MMD8_STATIC_WORKSPACE_BYTES) return MMD8_E_WORKSPACE;   // too large for the array
+  if (Wq_layout != kPackedLayoutTag) return MMD8_E_VERSION;
+  if (M == 0) return isnan(tau) ? MMD8_E_ARG : MMD8_OK;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MMD8_E_HIP;
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticWorkspace& w = g_static_ws[dev];
+    if (!w.ptr) {   // first call on this device: every GPU holds its own copy of the array at its own address
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MMD8_E_HIP;
+      if (prepare_gemm_kernels() != hipSuccess || prepare_rows_kernels() != hipSuccess) return MMD8_E_HIP;
+      w.ptr = p;
+      w.head_zero = false;
+    }
+    if (!w.head_zero) {
+      // a fill kernel, not a memset: the call may be recorded into a graph
+      if (launch_fill_u32(static_cast<uint32_t*>(w.ptr), 0u, (int)(kHeadBytes / 4), static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MMD8_E_HIP;
+      w.head_zero = true;
+    }
+    ws = w.ptr;
+  }
+  const int s = run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, ws,
+                           MMD8_STATIC_WORKSPACE_BYTES, taps, nullptr, nullptr, nullptr, stream);
+  if (s == MMD8_E_HIP) {   // some kernels of the call may have run: the head is cleared again before the next call
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    g_static_ws[dev].head_zero = false;
+  }
+  return s;
+}
+
 int mmd8_mixed_int8_linear_gelu(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,
                                 uint32_t Wq_layout, const float* col_absmax, int N, const mmd8_half* bias, float tau, mmd8_half* Y, int ldy,
                                 void* workspace, size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {

@@ -252,3 +252,19 @@ def test_gelu_coefficients_in_the_kernel_header_reproduce_erfc():
         exact = 0.5 * math.erfc(z)
         worst = max(worst, abs(phi - exact) / exact)
     assert worst < 1e-5, worst
+
+
+def test_the_entry_point_without_a_workspace_refuses_sizes_beyond_its_array():
+    L = binding.lib()
+    fake, y = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x40000000)
+    tag = L.mmd8_packed_weight_layout()
+
+    def call(M, K, N, layout=tag, tau=6.0):
+        return L.mmd8_mixed_int8_linear_static(fake, M, K, K, fake, layout, fake, N, None, tau, y, N, None, None)
+
+    assert L.mmd8_linear_workspace_bytes(2048, 28672, 8192) > binding.STATIC_WORKSPACE_BYTES
+    assert call(2048, 28672, 8192) == -3                          # before any HIP call: no GPU needed to be told so
+    assert call(4096, 8192, 8192) == -3
+    assert call(8, 100, 64) == -2 and call(-1, 128, 64) == -1
+    assert call(8, 128, 64, layout=tag + 1) == -5
+    assert call(0, 128, 64) == 0 and call(0, 128, 64, tau=float("nan")) == -1
