@@ -108,8 +108,10 @@ typedef struct {
   int32_t* outlier_idx;   /* [K]    ascending indices of the critical dimensions; entries
                                     past n_outliers are unspecified                         */
   /* Optional hipEvent_t handles (HOST, created by the caller) recorded on `stream`: when the
-     call starts, just before the GEMM kernel and just after it.  For per-stage timing.      */
+     call starts, after the first kernel of the activation preparation (the one pass over X, or
+     the scan), just before the GEMM kernel and just after it.  For per-stage timing.           */
   void* event_begin;
+  void* event_prep_mid;
   void* event_gemm_begin;
   void* event_gemm_end;
   /* Kernel choice of this one call, for tests and tuning: 0 = the library's own choice, else an OR of the
@@ -167,6 +169,35 @@ int mmd8_mixed_int8_linear_static(const mmd8_half* X /*DEVICE*/, int M, int K, i
                                   const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
                                   mmd8_half* Y /*DEVICE*/, int ldy,
                                   const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
+
+/* The layer under the other readings of "Compression techniques", item 2 ("a small fraction of critical weights at
+ * 16-bit precision"; the paper gives no formula for the scale of the 8-bit part nor for where the 16-bit weights
+ * come from).  Two switches, independent of each other:
+ *   row_scale   MMD8_ROW_SCALE_SUB_THRESHOLD: r[m] = max{|X[m,k]| : |X[m,k]| < tau}, as in mmd8_mixed_int8_linear;
+ *               MMD8_ROW_SCALE_NON_CRITICAL:  r[m] = max{|X[m,k]| : flag[k] == 0}, the largest magnitude among the
+ *               columns that stay in the 8-bit part (needs the flags of every row first: one more pass over X).
+ *   W_master    NULL: the 16-bit weights of the critical dimensions are re-created from the codes,
+ *               f16(Wq[k,n] * (c[n] / 127.0f)), as in mmd8_mixed_int8_linear (1 byte per weight resident);
+ *               else DEVICE [K][ldw] fp16, the original weight matrix W (the one mmd8_prequantize_weight read):
+ *               its rows W[k,:] multiply the critical columns as they are (3 bytes per weight resident; tau = 0
+ *               then gives the fp16 product X W itself).  16-byte aligned, ldw >= N, ldw % 8 == 0.
+ * Everything else (flags, codes given the scale, the integer product, the dequantization, one rounding) is as in
+ * mmd8_mixed_int8_linear, and so are the other arguments, the workspace and the errors (MMD8_E_ARG for a NULL
+ * `readings`, an unknown row_scale or a bad W_master / ldw).  These readings always run the separate scan and pack
+ * kernels, and with W_master the tiled GEMM for any number of rows. */
+enum { MMD8_ROW_SCALE_SUB_THRESHOLD = 0, MMD8_ROW_SCALE_NON_CRITICAL = 1 };
+typedef struct {
+  int row_scale;              /* MMD8_ROW_SCALE_*                                   */
+  const mmd8_half* W_master;  /* DEVICE [K][ldw] fp16 or NULL                       */
+  int ldw;
+} mmd8_readings;
+int mmd8_mixed_int8_linear_readings(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
+                                    const int8_t* Wq_packed /*DEVICE*/, uint32_t Wq_layout, const float* col_absmax /*DEVICE [N]*/, int N,
+                                    const mmd8_half* bias /*DEVICE [N] or NULL*/, float tau,
+                                    const mmd8_readings* readings /*HOST struct*/,
+                                    mmd8_half* Y /*DEVICE*/, int ldy,
+                                    void* workspace /*DEVICE*/, size_t workspace_bytes,
+                                    const mmd8_debug_taps* taps /*HOST struct or NULL*/, void* stream);
 
 /* The same layer applied to activations that arrive in blockwise-coded form (the hidden state a
  * shard receives from its predecessor: "Compression techniques", item 1 feeding item 2):

@@ -21,14 +21,21 @@ EXPORTS = (
     "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
     "mmd8_mixed_int8_linear_lora", "mmd8_linear_to_codes_workspace_bytes", "mmd8_mixed_int8_linear_to_codes",
     "mmd8_mixed_int8_linear_gelu", "mmd8_mixed_int8_linear_residual", "mmd8_mixed_int8_linear_static",
+    "mmd8_mixed_int8_linear_readings",
 )
 
 
 class DebugTaps(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in
                 ("outlier_mask", "row_absmax", "xq", "acc", "n_outliers", "outlier_idx",
-                 "event_begin", "event_gemm_begin", "event_gemm_end")] + [("tuning", ctypes.c_uint32)]
+                 "event_begin", "event_prep_mid", "event_gemm_begin", "event_gemm_end")] + [("tuning", ctypes.c_uint32)]
 
+
+class Readings(ctypes.Structure):
+    _fields_ = [("row_scale", ctypes.c_int), ("W_master", ctypes.c_void_p), ("ldw", ctypes.c_int)]
+
+
+ROW_SCALE_SUB_THRESHOLD, ROW_SCALE_NON_CRITICAL = 0, 1
 
 # kernel choices of one call (mmd8_debug_taps.tuning, include/mmd8.h)
 TUNE_SEPARATE_PREP = 0x10
@@ -68,6 +75,8 @@ def lib():
                                              ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_static.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, vp, i32,
                                                     ctypes.POINTER(DebugTaps), vp]
+        L.mmd8_mixed_int8_linear_readings.argtypes = [vp, i32, i32, i32, vp, u32, vp, i32, vp, f32, ctypes.POINTER(Readings),
+                                                      vp, i32, vp, sz, ctypes.POINTER(DebugTaps), vp]
         L.mmd8_mixed_int8_linear_from_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp, u32, vp, i32, vp, f32, vp, i32, vp, sz,
                                                         ctypes.POINTER(DebugTaps), vp]
         L.mmd8_linear_lora_workspace_bytes.restype = sz
@@ -231,8 +240,9 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
         workspace = linear_workspace(M, K, N, X.device, exit_block=block)
     tensors = _taps(M, K, N, X.device) if taps else None
     tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()}) if taps else None
-    if events is not None and not taps:         # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
-        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
+    if events is not None and not taps:         # (begin, gemm_begin, gemm_end[, prep_mid]) hipEvent_t handles as ints
+        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2],
+                       event_prep_mid=events[3] if len(events) > 3 else None)
     if tuning:
         tp = tp if tp is not None else DebugTaps()
         tp.tuning = int(tuning)
@@ -249,14 +259,16 @@ def mixed_int8_linear_to_codes(X: torch.Tensor, pw: PackedWeight, tau: float, bl
 def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch.Tensor = None,
                       out: torch.Tensor = None, workspace: torch.Tensor = None, taps: bool = False,
                       events=None, coded=None, lora=None, gelu: bool = False, residual: torch.Tensor = None,
-                      tuning: int = 0):
+                      tuning: int = 0, readings=None):
     """Y = X W through the mixed decomposition (gelu=True: followed by the exact GELU, in the same kernels).
     residual: fp16 [M, N] added to the output as an fp16 addition, in the same kernels (may be `out` itself).
     taps: True for every intermediate, or a tuple of tap names.  With taps=True also returns a dict of the
     intermediates (outlier_mask, row_absmax, xq, acc, n_outliers, outlier_idx).
     coded=(codes, absmax, block): the activations arrive blockwise-coded; X is then the contiguous
     [M, K] fp16 buffer that receives the decoded values.
-    lora=(A [r, K], B [N, r]) or (A, B, T_out [M, r]), fp16: adds the low-rank term of W' = W + B A."""
+    lora=(A [r, K], B [N, r]) or (A, B, T_out [M, r]), fp16: adds the low-rank term of W' = W + B A.
+    readings=(row_scale, W_master): the layer under the other readings (ROW_SCALE_* above; W_master: None or the
+    original fp16 weights [K, N], whose rows then multiply the critical columns)."""
     _dev(X, torch.float16, "X")
     M, K = X.shape
     if K != pw.K or X.stride(1) != 1:
@@ -266,6 +278,8 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     N = pw.N
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if readings is not None and (coded is not None or lora is not None):
+        raise Mmd8Error("the alternative readings cannot be combined with coded activations or an adapter in one call")
     if coded is not None and lora is not None:
         raise Mmd8Error("coded activations and an adapter cannot be combined in one call")
     if gelu and (coded is not None or lora is not None):
@@ -279,8 +293,9 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
     if workspace is None:
         workspace = linear_workspace(M, K, N, X.device, lora[0].shape[0] if lora is not None else 0)
     tp, tensors = None, None
-    if events is not None:                      # (begin, gemm_begin, gemm_end) hipEvent_t handles as ints
-        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2])
+    if events is not None:                      # (begin, gemm_begin, gemm_end[, prep_mid]) hipEvent_t handles as ints
+        tp = DebugTaps(event_begin=events[0], event_gemm_begin=events[1], event_gemm_end=events[2],
+                       event_prep_mid=events[3] if len(events) > 3 else None)
     if taps:
         tensors = _taps(M, K, N, X.device, None if taps is True else tuple(taps))
         tp = DebugTaps(**{k: v.data_ptr() for k, v in tensors.items()})
@@ -313,6 +328,22 @@ def mixed_int8_linear(X: torch.Tensor, pw: PackedWeight, tau: float, bias: torch
             bias.data_ptr() if bias is not None else None, float(tau), A.data_ptr(), B.data_ptr(), int(r),
             T_out.data_ptr() if T_out is not None else None, out.data_ptr(), out.stride(0) if M > 0 else N,
             workspace.data_ptr(), workspace.numel(), ctypes.byref(tp) if tp is not None else None, _stream()))
+        return (out, tensors) if taps else out
+    if readings is not None:
+        if gelu or residual is not None:
+            raise Mmd8Error("the alternative readings cannot be combined with an activation or a residual in one call")
+        row_scale, Wm = readings
+        rd = Readings(int(row_scale), None, 0)
+        if Wm is not None:
+            _dev(Wm, torch.float16, "W_master")
+            if Wm.shape != (K, N) or Wm.stride(1) != 1:
+                raise Mmd8Error("W_master must be [K, N] with unit stride along N")
+            rd = Readings(int(row_scale), Wm.data_ptr(), Wm.stride(0))
+        _check(lib().mmd8_mixed_int8_linear_readings(
+            X.data_ptr(), M, K, X.stride(0) if M > 0 else K, pw.blob.data_ptr(), pw.layout, pw.col_absmax.data_ptr(), N,
+            bias.data_ptr() if bias is not None else None, float(tau), ctypes.byref(rd), out.data_ptr(),
+            out.stride(0) if M > 0 else N, workspace.data_ptr(), workspace.numel(),
+            ctypes.byref(tp) if tp is not None else None, _stream()))
         return (out, tensors) if taps else out
     if residual is not None:
         _check(lib().mmd8_mixed_int8_linear_residual(

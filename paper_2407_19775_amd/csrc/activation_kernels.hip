@@ -45,6 +45,10 @@ __global__ void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int n) {
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 __device__ inline us2 as_us2(uint32_t v) { return __builtin_bit_cast(us2, v); }
 __device__ inline uint32_t as_u32(us2 v) { return __builtin_bit_cast(uint32_t, v); }
+// 16 column flags (bytes 0 / 1) starting at column k0
+__device__ inline v4u flags16(const uint8_t* __restrict__ flag, int k0) {
+  return *reinterpret_cast<const v4u*>(flag + k0) & 0x01010101u;
+}
 
 template <int kScanRows>
 __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ X, int M, int K, int ldx,
@@ -111,6 +115,35 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
   }
 }
 
+// ------------------------------------------------------------------ row scale over the non-critical columns
+// The alternative reading of the row scale: r[m] = max |X[m,k]| over the columns whose flag is 0.  It needs the
+// flags of every row, so it is a pass of its own between the scan and the pack kernel: one wave per row, the
+// row's 16-column pieces strided over the lanes, flags read 16 bytes at a time.
+__global__ __launch_bounds__(kThreads) void k_row_absmax_noncritical(const uint16_t* __restrict__ X, int M, int K, int ldx,
+                                                                     const uint8_t* __restrict__ flag,
+                                                                     float* __restrict__ r_out) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int m = blockIdx.x * (kThreads / kWave) + wave;
+  if (m >= M) return;
+  uint32_t mx = 0;
+  for (int k0 = lane * 16; k0 < K; k0 += kWave * 16) {               // K % 16 == 0: whole pieces
+    const v4u f = flags16(flag, k0);
+    const v4u a = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0);
+    const v4u b = *reinterpret_cast<const v4u*>(X + (size_t)m * ldx + k0 + 8);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      // flag bytes 2 w' and 2 w' + 1 of the piece belong to the two halves of word w' (a: columns 0..7, b: 8..15)
+      const uint32_t fa = f[w >> 1] >> (16 * (w & 1)), fb = f[2 + (w >> 1)] >> (16 * (w & 1));
+      const uint32_t keep_a = ((fa & 1u) ? 0u : 0x7fffu) | ((fa & 0x100u) ? 0u : 0x7fff0000u);
+      const uint32_t keep_b = ((fb & 1u) ? 0u : 0x7fffu) | ((fb & 0x100u) ? 0u : 0x7fff0000u);
+      const uint32_t va = a[w] & keep_a, vb = b[w] & keep_b;
+      mx = max(mx, max(max(va & 0xffffu, va >> 16), max(vb & 0xffffu, vb >> 16)));
+    }
+  }
+  mx = wave_max_u32(mx);
+  if (lane == 0) r_out[m] = half_lo_to_float(mx);                    // fp16 magnitudes order like their patterns
+}
+
 // ------------------------------------------------------------------ pack
 // Xq in the blocked operand layout (operand_layout.h): codes of the non-critical columns, zeros
 // in the critical columns and in the K padding.  A wave converts 32 rows x one 64-byte slab per
@@ -121,10 +154,6 @@ __global__ __launch_bounds__(kThreads) void k_scan(const uint16_t* __restrict__ 
 constexpr int kPackRowSteps = 2;
 constexpr int kPackRows = 32 * kPackRowSteps;          // rows per workgroup
 constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (one per wave)
-// 16 column flags (bytes 0 / 1) starting at column k0
-__device__ inline v4u flags16(const uint8_t* __restrict__ flag, int k0) {
-  return *reinterpret_cast<const v4u*>(flag + k0) & 0x01010101u;
-}
 
 // The ascending list of critical columns and their count, computed by one whole workgroup from
 // the flags (every workgroup that needs the list recomputes it: a few KB of flags from L2 are
@@ -218,14 +247,23 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
-    const float step = o.c[n] / 127.0f;
-    int8_t q[8];
+    if (o.W_master) {
+      // the original 16-bit rows of the critical dimensions, as they are
+      uint16_t w[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) q[t] = o.Wt[packed_offset(n, max(kcol[t], 0), n_slabs)];
+      for (int t = 0; t < 8; ++t) w[t] = o.W_master[(size_t)max(kcol[t], 0) * o.ldw + n];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const uint32_t h = rounded_float_to_half_bits((float)q[t] * step);
-      out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
+      for (int t = 0; t < 8; ++t) out[t >> 1] |= (kcol[t] >= 0 ? (uint32_t)w[t] : 0u) << (16 * (t & 1));
+    } else {
+      const float step = o.c[n] / 127.0f;
+      int8_t q[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) q[t] = o.Wt[packed_offset(n, max(kcol[t], 0), n_slabs)];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const uint32_t h = rounded_float_to_half_bits((float)q[t] * step);
+        out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
+      }
     }
     *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, o.f_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
@@ -553,6 +591,12 @@ hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, in
   return hipGetLastError();
 }
 
+hipError_t launch_row_absmax_noncritical(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, float* r,
+                                         hipStream_t stream) {
+  hipLaunchKernelGGL(k_row_absmax_noncritical, dim3(ceil_div(M, kThreads / kWave)), dim3(kThreads), 0, stream, X, M, K, ldx, flag, r);
+  return hipGetLastError();
+}
+
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
                        int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes;
@@ -571,7 +615,8 @@ bool prep_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 8; }
 bool prep_from_codes_fits(int K) { return packed_k(K) / 16 <= 16 * 16 * 4; }
 
 hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
-                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream) {
+                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, void* event_mid,
+                       hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes, n_pieces = Kpad / 16;
   const dim3 grid(ceil_div(M, 4));
   const CodedInput ci = coded ? *coded : CodedInput{};
@@ -595,6 +640,7 @@ hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad
 #undef MMD8_PREP
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (event_mid && (e = hipEventRecord(static_cast<hipEvent_t>(event_mid), stream)) != hipSuccess) return e;
   const int slab_blocks = max(1, ceil_div((M + o.N) * (kOutlierSlab / 8), kThreads));
   const int clear_blocks = ceil_div(M, kThreads);
   hipLaunchKernelGGL(k_outlier_columns, dim3(slab_blocks + clear_blocks), dim3(kThreads), 0, stream, X, M, K, ldx, flag, Xq,

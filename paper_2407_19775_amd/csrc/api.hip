@@ -239,6 +239,12 @@ struct CodedExit {   // a residual added to the output and / or the output leavi
   float* absmax;               // [ceil(M N / block)]
 };
 
+struct Readings {   // alternative readings of the method (mmd8_readings), checked
+  bool non_critical_scale;
+  const mmd8_half* W_master;   // [K][ldw] or null
+  int ldw;
+};
+
 struct Adapter {   // low-rank factors of W' = W + B A
   const mmd8_half* A;   // [r][K]
   const mmd8_half* B;   // [N][r]
@@ -254,7 +260,7 @@ struct Adapter {   // low-rank factors of W' = W + B A
 static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, uint32_t Wq_layout, const float* col_absmax, int N,
                       const mmd8_half* bias, float tau, mmd8_half* Y, int ldy, void* workspace, size_t workspace_bytes,
                       const mmd8_debug_taps* taps, const CodedInput* coded, const Adapter* lora, const CodedExit* exit,
-                      void* stream, bool gelu = false) {
+                      void* stream, bool gelu = false, const Readings* readings = nullptr) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
   if (isnan(tau)) return MMD8_E_ARG;
@@ -292,22 +298,26 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
-                           Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs};
+                           Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs,
+                           readings ? readings->W_master : nullptr, readings ? readings->ldw : 0};
   // Up to 128 rows go through the decode kernels, 64 rows at a time (the weights are streamed twice for more
   // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
   // with heavy-tailed activations (hundreds of critical columns) it is ten times faster.
-  const bool skinny = M <= kSkinnyChunkedMaxM;
+  // (the decode kernels multiply the critical columns with the weight codes themselves: original 16-bit rows go
+  // through the tiled GEMM whatever the number of rows)
+  const bool skinny = M <= kSkinnyChunkedMaxM && !(readings && readings->W_master);
   // A few rows (at most kPanelPrepMaxM): the decode GEMM kernel prepares its own operands (scales, codes, critical
   // columns) from X, and the scan and pack kernels are left out.  Not when their outputs are asked for through the taps.
   const bool wants_prep_taps = t.outlier_mask || t.row_absmax || t.xq || t.n_outliers || t.outlier_idx;
   // One or two rows (while their operands fit in LDS): the whole layer is one kernel (k_gemm_rows).  When the taps of the
   // preparation are asked for, the scan and pack kernels run ahead of it for their sake only.
-  const bool may_own_prep = !(t.tuning & MMD8_TUNE_SEPARATE_PREP);
+  // (alternative readings: always the separate scan and pack kernels, which is where they differ)
+  const bool may_own_prep = !(t.tuning & MMD8_TUNE_SEPARATE_PREP) && !readings;
   const bool rows_path = may_own_prep && !(t.tuning & MMD8_TUNE_NO_ROWS_KERNEL) && rows_kernel_fits(M, Kpad);
   const bool own_prep = skinny && !rows_path && !wants_prep_taps && may_own_prep && panel_prep_fits(M, plan_skinny(M, K, N));
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
-  const bool one_pass = !skinny && prep_fits(K);
+  const bool one_pass = !skinny && prep_fits(K) && !readings;
   const bool fused_decode = coded && one_pass && prep_from_codes_fits(K) && (size_t)M * K < ((size_t)1 << 31);
   if (coded && !fused_decode &&
       launch_dequantize_blockwise(coded->codes, coded->absmax, (size_t)M * K, coded->block, X, st) != hipSuccess)
@@ -315,10 +325,15 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (one_pass) {
     // one pass over X: scales, flags and codes together, then the critical columns are cleared
     if (launch_prep(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, ws.xq, t.xq, po, fused_decode ? coded : nullptr,
-                    st) != hipSuccess)
+                    t.event_prep_mid, st) != hipSuccess)
       return MMD8_E_HIP;
   } else if (!own_prep && (!rows_path || wants_prep_taps)) {
     if (launch_scan(X, M, K, ldx, threshold_pattern(tau), Kpad, ws.flag, ws.r, st) != hipSuccess) return MMD8_E_HIP;
+    if (!record(t.event_prep_mid)) return MMD8_E_HIP;
+    // the row scale over the non-critical columns only: needs the flags of every row, hence a pass of its own
+    if (readings && readings->non_critical_scale &&
+        launch_row_absmax_noncritical(X, M, K, ldx, ws.flag, ws.r, st) != hipSuccess)
+      return MMD8_E_HIP;
     // (the decode kernels' operands are packed 64 rows at a time, below)
     if (!skinny && launch_pack(X, M, K, ldx, ws.flag, ws.r, ws.xq, Kpad, t.xq, nullptr, po, st) != hipSuccess)
       return MMD8_E_HIP;
@@ -453,6 +468,10 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.tiles_m = g.tiles_n = 0;
     g.flag_reset = ws.flag;
     g.gelu = gelu ? 1 : 0;
+    if (readings) {
+      g.W_master = readings->W_master;
+      g.ldw_master = readings->ldw;
+    }
     if (exit) {
       g.residual = exit->residual;
       g.ldr = exit->ldr;
@@ -529,6 +548,20 @@ int mmd8_mixed_int8_linear_static(const mmd8_half* X, int M, int K, int ldx, con
     g_static_ws[dev].head_zero = false;
   }
   return s;
+}
+
+int mmd8_mixed_int8_linear_readings(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed, uint32_t Wq_layout,
+                                    const float* col_absmax, int N, const mmd8_half* bias, float tau,
+                                    const mmd8_readings* readings, mmd8_half* Y, int ldy, void* workspace,
+                                    size_t workspace_bytes, const mmd8_debug_taps* taps, void* stream) {
+  if (!readings) return MMD8_E_ARG;
+  if (readings->row_scale != MMD8_ROW_SCALE_SUB_THRESHOLD && readings->row_scale != MMD8_ROW_SCALE_NON_CRITICAL)
+    return MMD8_E_ARG;
+  if (readings->W_master && (readings->ldw < N || (readings->ldw % 8) != 0 || !aligned(readings->W_master, 16)))
+    return MMD8_E_ARG;
+  const Readings rd = {readings->row_scale == MMD8_ROW_SCALE_NON_CRITICAL, readings->W_master, readings->ldw};
+  return run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, workspace,
+                    workspace_bytes, taps, nullptr, nullptr, nullptr, stream, false, &rd);
 }
 
 int mmd8_mixed_int8_linear_gelu(const mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_packed,

@@ -39,6 +39,10 @@ struct GemmArgs {
   int tap_ld;
   int tiles_m, tiles_n;
   uint8_t* flag_reset;   // [Kpad] column flags of the scan: zeroed again by workgroup 0
+  // Alternative reading: the 16-bit weights of the critical dimensions are the rows of the original fp16 matrix
+  // W[k * ldw_master + n] (null: they are re-created from the codes).  Wo was then gathered from it as well.
+  const uint16_t* W_master;
+  int ldw_master;
 };
 
 // Workgroup 0 of the kernel that ends a call puts the scan's column flags back to zero (the next

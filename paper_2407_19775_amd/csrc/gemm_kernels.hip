@@ -184,6 +184,18 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
     }
 #pragma unroll 1
     for (int ib = 0; ib < NW; ib += BW) {
+      if (a.W_master) {                                              // the original 16-bit rows, as they are
+        uint16_t wv[BW];
+#pragma unroll
+        for (int i = 0; i < BW; ++i)
+          wv[i] = a.W_master[(size_t)k * a.ldw_master + min(p.n0 + r0 + (ib + i) * RSTEP, a.N - 1)];
+#pragma unroll
+        for (int i = 0; i < BW; ++i) {
+          const int row = r0 + (ib + i) * RSTEP;
+          sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? wv[i] : (uint16_t)0;
+        }
+        continue;
+      }
       int8_t wq[BW];
       float wc[BW];
 #pragma unroll
@@ -704,6 +716,7 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
   b.codes = a.codes ? a.codes + n0 : nullptr;
   b.code_absmax = a.codes ? a.code_absmax + (n0 >> a.code_log_block) : nullptr;   // n0 is a multiple of 256
   b.tap_acc = a.tap_acc ? a.tap_acc + n0 : nullptr;
+  b.W_master = a.W_master ? a.W_master + n0 : nullptr;
   b.N = n;
   return b;
 }

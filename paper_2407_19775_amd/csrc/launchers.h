@@ -33,6 +33,10 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
   uint16_t* Xo;
   uint16_t* Wo;
   int f_slabs;           // fp16 slabs per panel in Xo / Wo (the critical columns are slab 0)
+  // Alternative reading of where the 16-bit weights of the critical dimensions come from: null (re-created from
+  // the codes, f16(Wt c / 127)), or the original fp16 weights W[k * ldw + n], whose rows are then used as they are.
+  const uint16_t* W_master;
+  int ldw;
 };
 struct CodedInput {     // activations in their blockwise-coded form
   const uint8_t* codes;
@@ -42,6 +46,10 @@ struct CodedInput {     // activations in their blockwise-coded form
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t stream);
 hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
                        hipStream_t stream);
+// Alternative reading of the row scale: r[m] = max |X[m,k]| over the columns that are not critical (flag 0); needs
+// the flags of all rows, i.e. runs after launch_scan.  Overwrites the scan's r.
+hipError_t launch_row_absmax_noncritical(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, float* r,
+                                         hipStream_t stream);
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
                        int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream);
 // One-pass preparation for inputs taller than the decode kernels take; prep_fits is false when K is too
@@ -50,6 +58,7 @@ bool prep_fits(int K);
 bool prep_from_codes_fits(int K);   // likewise for launch_prep with coded activations (a smaller bound)
 // coded: null, or the blockwise-coded form of the activations (X is then written, not read).
 hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad, uint8_t* flag, float* r,
-                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, hipStream_t stream);
+                       int8_t* Xq, int8_t* tap_xq, const PackOutliers& o, const CodedInput* coded, void* event_mid,
+                       hipStream_t stream);   // event_mid: null, or a hipEvent_t recorded between the two kernels
 
 }  // namespace mmd8
