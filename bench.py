@@ -362,8 +362,27 @@ def main():
                             "dequantize_pct_hbm": round(100 * nbytes / td / 1e6 / HBM_PEAK_GBS, 1),
                             "quantize_us": round(tq * 1e3, 1), "dequantize_us": round(td * 1e3, 1),
                             "hot_quantize_gbs": round(nbytes / tq_hot / 1e6, 1), "hot_dequantize_gbs": round(nbytes / td_hot / 1e6, 1)}
-    del xs, cs, am
+    # the other storage of the block scales (fp16 numbers, 2 bytes per block), smallest block: what it saves
+    am16 = [torch.empty(big // 256, dtype=torch.float16, device=dev) for _ in range(nb)]
+
+    def q_big16():
+        i = turn[0] = (turn[0] + 1) % nb
+        binding.quantize_blockwise(xs[i], 256, codes=cs[i], absmax=am16[i], fp16_scales=True)
+
+    def d_big16():
+        i = turn[0] = (turn[0] + 1) % nb
+        binding.dequantize_blockwise(cs[i], am16[i], 256, out=xs[i])
+
+    for i in range(nb):
+        binding.quantize_blockwise(xs[i], 256, codes=cs[i], absmax=am16[i], fp16_scales=True)
+    tq16, td16 = timed(q_big16, 12), timed(d_big16, 12)
+    fp16_scales = {"block": 256, "quantize_us": round(tq16 * 1e3, 1), "dequantize_us": round(td16 * 1e3, 1),
+                   "bytes_per_element": 3.0 + 2.0 / 256, "coded_fraction": (1 + 2.0 / 256) / 2,
+                   "fp32_scales_quantize_us": by_block["256"]["quantize_us"],
+                   "fp32_scales_dequantize_us": by_block["256"]["dequantize_us"]}
+    del xs, cs, am, am16
     out.setdefault("codec", {}).update({
+        "fp16_block_scales": fp16_scales,
         "elements": big, "by_block": by_block,
         "note": "shard-boundary hidden state [8192,8192] (Student-t(3), 4 feature dimensions x50, host recipe), three buffer "
                 "sets taking turns (every call streams from HBM: the cold figures); hot_*: one buffer set over and over; "
@@ -427,6 +446,23 @@ def main():
                 binding.mixed_int8_linear(Xh[shp.K], weights[0][j], wl.TAU, out=Yh[shp.name], workspace=wsh)
 
         heavy["layer_M%d_student_t" % Mh] = {"us_per_layer": round(timed(heavy_pass, 5) * 1e3, 1)}
+
+    # ---- the other readings of the layer (row scale over the non-critical columns only; original fp16 rows for the
+    # critical dimensions): what each costs on the 7B-shaped QKV linear at 2048 tokens, whole calls
+    qkv = shapes[0]
+    W_master = torch.from_numpy(wl.prefill_weight(2, 20, qkv, 0.02)).to(dev)      # the matrix weights[0][0] was packed from
+    readings = {}
+    for name, rd in (("library", None), ("separate_scan_and_pack", (binding.ROW_SCALE_SUB_THRESHOLD, None)),
+                     ("non_critical_row_scale", (binding.ROW_SCALE_NON_CRITICAL, None)),
+                     ("fp16_master_rows", (binding.ROW_SCALE_SUB_THRESHOLD, W_master)),
+                     ("both", (binding.ROW_SCALE_NON_CRITICAL, W_master))):
+        t = timed(lambda: binding.mixed_int8_linear(Xs[qkv.K], weights[0][0], wl.TAU, out=Ys[qkv.name], workspace=workspace,
+                                                    readings=rd), 20)
+        readings[name] = {"call_us": round(t * 1e3, 1)}
+    readings["note"] = ("QKV 4096->12288, 2048 tokens; the alternative readings run the scan and pack kernels separately "
+                        "(5 bytes per element instead of 3), the non-critical scale one more pass over X; the master rows "
+                        "cost 2 more resident bytes per weight, not time")
+    del W_master
 
     # ---- the prefill linears with a rank-16 adapter (W' = W + B A, fp16 factors): "prep" now includes the
     # down-projection T = X A^T, the GEMM multiplies one more fp16 slab (T, B) per tile
@@ -551,7 +587,8 @@ def main():
                         "binding (about 7 us of host time per call), not by the kernel (3-6 us)"}
     del kv_x, kv_c, kv_a, kv_read_views
 
-    out.update({"decode": decode, "heavy_tailed_prefill": heavy, "adapter": adapter, "boundary_exit": boundary_exit,
+    out.update({"decode": decode, "heavy_tailed_prefill": heavy, "readings": readings, "adapter": adapter,
+                "boundary_exit": boundary_exit,
                 "vit_l_block": vit, "kv_cache": kv_cache, "weight_prequant": prequant})
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()

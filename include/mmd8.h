@@ -68,6 +68,15 @@ int mmd8_quantize_blockwise(const mmd8_half* x /*DEVICE [n]*/, size_t n, int blo
                             void* stream);
 int mmd8_dequantize_blockwise(const uint8_t* codes /*DEVICE [n]*/, const float* absmax /*DEVICE*/,
                               size_t n, int block, mmd8_half* out /*DEVICE [n]*/, void* stream);
+/* The other reading of how a block's scale is stored ("Compression techniques", item 1 names the technique, not
+ * the width of the scale): every absmax is the magnitude of an fp16 element, so 2 bytes hold it exactly.  Same
+ * codes, same decoded values, absmax as fp16 bit patterns: (1 + 2 / block) / 2 of the fp16 tensor's bytes instead of
+ * (1 + 4 / block) / 2.  absmax: DEVICE [ceil(n/block)] fp16, 2-byte aligned; everything else as above. */
+int mmd8_quantize_blockwise_h(const mmd8_half* x /*DEVICE [n]*/, size_t n, int block,
+                              uint8_t* codes /*DEVICE [n]*/, mmd8_half* absmax /*DEVICE [ceil(n/block)]*/,
+                              void* stream);
+int mmd8_dequantize_blockwise_h(const uint8_t* codes /*DEVICE [n]*/, const mmd8_half* absmax /*DEVICE*/,
+                                size_t n, int block, mmd8_half* out /*DEVICE [n]*/, void* stream);
 /* HOST pointers to the 256 code values (ascending) and the 255 midpoints. */
 const float* mmd8_code_table(void);
 const float* mmd8_code_midpoints(void);

@@ -14,6 +14,10 @@ quantized block by block to 8 bits, halving the bytes on the wire.  Steps, in or
 All arithmetic is IEEE binary32, round to nearest even, no fused operations.  The full blocks
 are handled as the rows of an ``[n // B, B]`` array and a short last block on its own; each row
 goes through exactly the steps above.
+
+Another reading of step 2 stores ``a[b]`` as the fp16 number it is (2 bytes per block instead of 4): with
+``fp16_scales=True`` the encoder returns the scales as fp16 and the decoder takes them as such; every other
+value is unchanged because the conversion is exact in both directions.
 """
 import numpy as np
 
@@ -55,8 +59,8 @@ def _encode_rows(rows: np.ndarray, a: np.ndarray, mid: np.ndarray) -> np.ndarray
     return np.searchsorted(mid, v.reshape(-1), side="left").astype(np.uint8)
 
 
-def quantize_blockwise(x: np.ndarray, block: int):
-    """x: fp16, any shape -> (codes uint8 [n], absmax float32 [ceil(n/block)])."""
+def quantize_blockwise(x: np.ndarray, block: int, fp16_scales: bool = False):
+    """x: fp16, any shape -> (codes uint8 [n], absmax float32 [ceil(n/block)]; float16 with fp16_scales)."""
     flat = np.ascontiguousarray(x).reshape(-1)
     assert flat.dtype == np.float16 and block >= 1
     mid = dynamic_code.midpoints()
@@ -66,11 +70,17 @@ def quantize_blockwise(x: np.ndarray, block: int):
     parts = [_encode_rows(full, a[:nfull], mid)]
     if tail is not None:
         parts.append(_encode_rows(tail, a[nfull:], mid))
+    if fp16_scales:
+        a16 = a.astype(np.float16)
+        assert np.array_equal(a16.astype(np.float32), a)                       # the magnitude of an fp16 element
+        return np.concatenate(parts), a16
     return np.concatenate(parts), a
 
 
 def dequantize_blockwise(codes: np.ndarray, absmax: np.ndarray, block: int) -> np.ndarray:
-    """codes uint8 [n], absmax float32 [ceil(n/block)] -> fp16 [n]."""
+    """codes uint8 [n], absmax float32 (or float16: the other storage of the scales) [ceil(n/block)] -> fp16 [n]."""
+    if absmax.dtype == np.float16:
+        absmax = absmax.astype(np.float32)                                     # exact
     t = dynamic_code.code_table()
     codes = np.ascontiguousarray(codes).reshape(-1)
     n = codes.size
@@ -88,7 +98,7 @@ def dequantize_blockwise(codes: np.ndarray, absmax: np.ndarray, block: int) -> n
     return np.concatenate(outs) if outs else np.zeros(0, np.float16)
 
 
-def compressed_fraction(n: int, block: int) -> float:
-    """Bytes after / bytes before for an fp16 tensor of n elements (codes + fp32 absmax)."""
+def compressed_fraction(n: int, block: int, scale_bytes: int = 4) -> float:
+    """Bytes after / bytes before for an fp16 tensor of n elements (codes + absmax of scale_bytes each)."""
     nblk = (n + block - 1) // block
-    return (n + 4 * nblk) / (2 * n)
+    return (n + scale_bytes * nblk) / (2 * n)

@@ -1,9 +1,9 @@
-"""Alternative readings of the row scale of the int8 layer (oracle; test infrastructure; CPU only).
+"""Alternative readings of the int8 layer (oracle; test infrastructure; CPU only).
 
 "Compression techniques", item 2, keeps "a small fraction of critical weights at 16-bit precision" and says no
 more about how the 8-bit part is scaled.  The library scales a row by the largest magnitude below the threshold
 (mixed_linear.row_absmax).  Two other readings are written out here so that what the choice costs can be
-measured (study_row_scale.py); neither is built on the GPU.
+measured and the library's switchable variants of them can be checked.
 
   sub_threshold   r[m] = max{ |X[m,k]| : |X[m,k]| < tau }                  the library's reading
   non_critical    r[m] = max{ |X[m,k]| : column k not critical }           needs the flags of all rows first

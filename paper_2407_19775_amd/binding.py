@@ -21,7 +21,7 @@ EXPORTS = (
     "mmd8_threshold_fp16_pattern", "mmd8_mixed_int8_linear_from_codes", "mmd8_linear_lora_workspace_bytes",
     "mmd8_mixed_int8_linear_lora", "mmd8_linear_to_codes_workspace_bytes", "mmd8_mixed_int8_linear_to_codes",
     "mmd8_mixed_int8_linear_gelu", "mmd8_mixed_int8_linear_residual", "mmd8_mixed_int8_linear_static",
-    "mmd8_mixed_int8_linear_readings",
+    "mmd8_mixed_int8_linear_readings", "mmd8_quantize_blockwise_h", "mmd8_dequantize_blockwise_h",
 )
 
 
@@ -61,6 +61,8 @@ def lib():
         L.mmd8_status_string.argtypes = [i32]
         L.mmd8_quantize_blockwise.argtypes = [vp, sz, i32, vp, vp, vp]
         L.mmd8_dequantize_blockwise.argtypes = [vp, vp, sz, i32, vp, vp]
+        L.mmd8_quantize_blockwise_h.argtypes = [vp, sz, i32, vp, vp, vp]
+        L.mmd8_dequantize_blockwise_h.argtypes = [vp, vp, sz, i32, vp, vp]
         L.mmd8_code_table.restype = ctypes.POINTER(ctypes.c_float)
         L.mmd8_code_midpoints.restype = ctypes.POINTER(ctypes.c_float)
         L.mmd8_packed_weight_layout.restype = ctypes.c_uint32
@@ -120,8 +122,10 @@ def code_midpoints() -> torch.Tensor:
 
 
 # ------------------------------------------------------------------ blockwise codec
-def quantize_blockwise(x: torch.Tensor, block: int, codes: torch.Tensor = None, absmax: torch.Tensor = None):
-    """x: fp16 GPU tensor (contiguous, any shape) -> (codes uint8 [n], absmax float32 [ceil(n/block)])."""
+def quantize_blockwise(x: torch.Tensor, block: int, codes: torch.Tensor = None, absmax: torch.Tensor = None,
+                       fp16_scales: bool = False):
+    """x: fp16 GPU tensor (contiguous, any shape) -> (codes uint8 [n], absmax float32 [ceil(n/block)]).
+    fp16_scales: the block scales as fp16 numbers (2 bytes per block) instead of fp32."""
     _dev(x, torch.float16, "x")
     if not x.is_contiguous():
         raise Mmd8Error("x must be contiguous")
@@ -129,19 +133,26 @@ def quantize_blockwise(x: torch.Tensor, block: int, codes: torch.Tensor = None, 
     nblk = (n + block - 1) // block if block > 0 else 0
     if codes is None:
         codes = torch.empty(n, dtype=torch.uint8, device=x.device)
+    sdt = torch.float16 if fp16_scales else torch.float32
     if absmax is None:
-        absmax = torch.empty(nblk, dtype=torch.float32, device=x.device)
-    _check(lib().mmd8_quantize_blockwise(x.data_ptr(), n, block, codes.data_ptr(), absmax.data_ptr(), _stream()))
+        absmax = torch.empty(nblk, dtype=sdt, device=x.device)
+    _dev(absmax, sdt, "absmax")
+    fn = lib().mmd8_quantize_blockwise_h if fp16_scales else lib().mmd8_quantize_blockwise
+    _check(fn(x.data_ptr(), n, block, codes.data_ptr(), absmax.data_ptr(), _stream()))
     return codes, absmax
 
 
 def dequantize_blockwise(codes: torch.Tensor, absmax: torch.Tensor, block: int, out: torch.Tensor = None):
     _dev(codes, torch.uint8, "codes")
-    _dev(absmax, torch.float32, "absmax")
+    if absmax.dtype == torch.float16:           # block scales stored as fp16 numbers
+        fn = lib().mmd8_dequantize_blockwise_h
+    else:
+        _dev(absmax, torch.float32, "absmax")
+        fn = lib().mmd8_dequantize_blockwise
     n = codes.numel()
     if out is None:
         out = torch.empty(n, dtype=torch.float16, device=codes.device)
-    _check(lib().mmd8_dequantize_blockwise(codes.data_ptr(), absmax.data_ptr(), n, block, out.data_ptr(), _stream()))
+    _check(fn(codes.data_ptr(), absmax.data_ptr(), n, block, out.data_ptr(), _stream()))
     return out
 
 

@@ -182,6 +182,25 @@ int mmd8_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t 
              : MMD8_E_HIP;
 }
 
+int mmd8_quantize_blockwise_h(const mmd8_half* x, size_t n, int block, uint8_t* codes, mmd8_half* absmax, void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  if (n == 0) return MMD8_OK;
+  if (!x || !codes || !absmax || !aligned(x, 16) || !aligned(codes, 8) || !aligned(absmax, 2)) return MMD8_E_ARG;
+  return launch_quantize_blockwise_h(x, n, block, codes, absmax, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
+int mmd8_dequantize_blockwise_h(const uint8_t* codes, const mmd8_half* absmax, size_t n, int block, mmd8_half* out,
+                                void* stream) {
+  if (check_block(block) != MMD8_OK) return MMD8_E_SHAPE;
+  if (n == 0) return MMD8_OK;
+  if (!codes || !absmax || !out || !aligned(out, 16) || !aligned(codes, 8) || !aligned(absmax, 2)) return MMD8_E_ARG;
+  return launch_dequantize_blockwise_h(codes, absmax, n, block, out, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MMD8_OK
+             : MMD8_E_HIP;
+}
+
 uint32_t mmd8_packed_weight_layout(void) { return kPackedLayoutTag; }
 
 size_t mmd8_packed_weight_bytes(int K, int N) {

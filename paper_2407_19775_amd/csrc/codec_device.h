@@ -9,6 +9,13 @@
 
 namespace mmd8 {
 
+// A block scale is the magnitude of an fp16 element.  It is stored either as fp32 (4 bytes per block, the
+// default) or as the fp16 number it is (2 bytes per block): both are exact, the codes are the same.
+__device__ inline void store_scale(float* p, size_t i, uint32_t fp16_pattern) { p[i] = half_lo_to_float(fp16_pattern); }
+__device__ inline void store_scale(uint16_t* p, size_t i, uint32_t fp16_pattern) { p[i] = (uint16_t)fp16_pattern; }
+__device__ inline float load_scale(const float* p, size_t i) { return p[i]; }
+__device__ inline float load_scale(const uint16_t* p, size_t i) { return half_lo_to_float(p[i]); }
+
 constexpr int kCodecThreads = 256;
 constexpr int kCodecChunk = 8;                          // fp16 elements per 16-byte load
 constexpr int kCodecSpanMax = 4096;                     // elements per span: 2 chunks per thread
@@ -32,9 +39,9 @@ __device__ inline uint32_t encode_one(float v, const CodeCell* __restrict__ cell
 // of kCodecThreads threads walks spans of blocks_per_span whole blocks (at most kCodecSpanMax elements).
 // src.chunk(e0, valid) returns the eight fp16 values that start at element e0 (a multiple of 8), of which
 // `valid` (1..8) lie inside the tensor; the others must come back as zeros.
-template <class Source>
+template <class Source, class Scale = float>
 __device__ inline void encode_spans(const Source& src, size_t n, int block, uint8_t* __restrict__ codes,
-                                    float* __restrict__ absmax, int blocks_per_span, size_t n_spans,
+                                    Scale* __restrict__ absmax, int blocks_per_span, size_t n_spans,
                                     const DynamicCode& code) {
   constexpr int kThreads = kCodecThreads, kChunk = kCodecChunk, kChunksPerThread = kCodecChunksPerThread;
   __shared__ CodeCell s_cells[DynamicCode::kCells];
@@ -84,7 +91,7 @@ __device__ inline void encode_spans(const Source& src, size_t n, int block, uint
       if (lane == 0) {
         s_block_max[b] = m;
         const size_t gb = span * (size_t)blocks_per_span + b;
-        if (gb * (size_t)block < n) absmax[gb] = half_lo_to_float(m);
+        if (gb * (size_t)block < n) store_scale(absmax, gb, m);
       }
     }
     __syncthreads();

@@ -35,9 +35,10 @@ struct GlobalHalves {
 };
 
 // Generic kernel: any block size that is a multiple of 64, any n (ragged end included).
+template <class Scale>
 __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
     const uint16_t* __restrict__ x, size_t n, int block, uint8_t* __restrict__ codes,
-    float* __restrict__ absmax, int blocks_per_span, size_t n_spans) {
+    Scale* __restrict__ absmax, int blocks_per_span, size_t n_spans) {
   encode_spans(GlobalHalves{x}, n, block, codes, absmax, blocks_per_span, n_spans, kCodeDev);
 }
 
@@ -54,10 +55,10 @@ __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
 // different stages, and the memory system sees a few long sequential streams.  (Measured on the
 // [8192, 8192] hidden state: 1, 2, 4, 8 spans per workgroup give 4.3, 4.8, 4.6, 4.1 TB/s.)
 constexpr int kSpansPerGroup = 2;
-template <int kLogBlock>
+template <int kLogBlock, class Scale>
 __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __restrict__ x, size_t n_spans,
                                                             uint8_t* __restrict__ codes,
-                                                            float* __restrict__ absmax) {
+                                                            Scale* __restrict__ absmax) {
   static_assert(kLogBlock >= 6 && kLogBlock <= 12, "64 .. 4096");
   __shared__ v2u s_cells[DynamicCode::kCells];
   __shared__ uint32_t s_wave_max[2][kThreads / kWave];
@@ -92,8 +93,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
       m0 = group_max<kLanesPerBlock>(m0);
       m1 = group_max<kLanesPerBlock>(m1);
       if (real && (lane & (kLanesPerBlock - 1)) == 0) {
-        absmax[(e_wave + lane * kChunk) >> kLogBlock] = half_lo_to_float(m0);
-        absmax[(e_wave + 512 + lane * kChunk) >> kLogBlock] = half_lo_to_float(m1);
+        store_scale(absmax, (e_wave + lane * kChunk) >> kLogBlock, m0);
+        store_scale(absmax, (e_wave + 512 + lane * kChunk) >> kLogBlock, m1);
       }
     } else {
       m0 = group_max<kWave>(max(m0, m1));
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
       m1 = m0;
       const bool writer = (kLogBlock == 10) ? lane == 0 : (kLogBlock == 11) ? (lane == 0 && (wave & 1) == 0)
                                                                             : threadIdx.x == 0;
-      if (real && writer) absmax[e_wave >> kLogBlock] = half_lo_to_float(m0);
+      if (real && writer) store_scale(absmax, e_wave >> kLogBlock, m0);
     }
     const float a0 = half_lo_to_float(m0), a1 = half_lo_to_float(m1);
     const float inv0 = (a0 == 0.0f) ? 0.0f : 1.0f / a0;            // IEEE division
@@ -144,8 +145,9 @@ __device__ inline v4u decode_group(const v2u& c, float a, const float* s_T) {
 // Whole groups only.  A thread decodes kDeqPerThread groups that lie an eighth of the tensor apart,
 // all loads first (same launch shape as the encoder).
 constexpr int kDeqPerThread = 8;
+template <class Scale>
 __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
-    const uint8_t* __restrict__ codes, const float* __restrict__ absmax, int block,
+    const uint8_t* __restrict__ codes, const Scale* __restrict__ absmax, int block,
     int log_block /* -1 if block is not a power of two */, uint16_t* __restrict__ out, size_t n_groups) {
   __shared__ float s_T[256];
   const size_t stride = (size_t)gridDim.x * kThreads;
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
     const size_t g = g0 + j * stride;
     const size_t e0 = (g < n_groups ? g : n_groups - 1) * kDeqGroup;   // a missing group re-reads the last one
     c[j] = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(codes + e0));
-    a[j] = absmax[(log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block)];
+    a[j] = load_scale(absmax, (log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block));
   }
   s_T[threadIdx.x] = kCodeDev.T[threadIdx.x];
   __syncthreads();
@@ -170,10 +172,11 @@ __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
 }
 
 // The last, short group of a tensor whose length is not a multiple of 8: one thread.
-__global__ void k_dequantize_tail(const uint8_t* __restrict__ codes, const float* __restrict__ absmax, size_t e0, int valid,
+template <class Scale>
+__global__ void k_dequantize_tail(const uint8_t* __restrict__ codes, const Scale* __restrict__ absmax, size_t e0, int valid,
                                   int block, uint16_t* __restrict__ out) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  const float a = absmax[e0 / (size_t)block];
+  const float a = load_scale(absmax, e0 / (size_t)block);
   for (int t = 0; t < valid; ++t)
     out[e0 + t] = (uint16_t)rounded_float_to_half_bits(kCodeDev.T[codes[e0 + t]] * a);
 }
@@ -185,20 +188,22 @@ static int log2_exact(int v) {
   return -1;
 }
 
-static hipError_t launch_quantize_generic(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
+template <class Scale>
+static hipError_t launch_quantize_generic(const uint16_t* x, size_t n, int block, uint8_t* codes, Scale* absmax,
                                           hipStream_t stream) {
   const int blocks_per_span = kSpanMax / block;                  // >= 1
   const size_t span_elems = (size_t)blocks_per_span * block;
   const size_t n_spans = (n + span_elems - 1) / span_elems;
   const size_t max_grid = (size_t)device_cu_count() * 8;
   const dim3 grid((unsigned)(n_spans < max_grid ? n_spans : max_grid));
-  hipLaunchKernelGGL(k_quantize_blockwise, grid, dim3(kThreads), 0, stream, x, n, block, codes, absmax,
+  hipLaunchKernelGGL(k_quantize_blockwise<Scale>, grid, dim3(kThreads), 0, stream, x, n, block, codes, absmax,
                      blocks_per_span, n_spans);
   return hipGetLastError();
 }
 
-hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
-                                     hipStream_t stream) {
+template <class Scale>
+static hipError_t launch_quantize_any(const uint16_t* x, size_t n, int block, uint8_t* codes, Scale* absmax,
+                                      hipStream_t stream) {
   const int log_block = log2_exact(block);
   if (log_block < 0) return launch_quantize_generic(x, n, block, codes, absmax, stream);
   // whole 4096-element spans on the fast path, the ragged end (whole blocks plus a short one)
@@ -206,7 +211,7 @@ hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uin
   const size_t n_spans = n / kSpanMax;
   if (n_spans > 0) {
     const dim3 grid((unsigned)((n_spans + kSpansPerGroup - 1) / kSpansPerGroup));
-#define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L>), grid, dim3(kThreads), 0, stream, x, n_spans, codes, absmax)
+#define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L, Scale>), grid, dim3(kThreads), 0, stream, x, n_spans, codes, absmax)
     switch (log_block) {
       case 6: MMD8_Q(6); break;
       case 7: MMD8_Q(7); break;
@@ -226,23 +231,42 @@ hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uin
   return hipSuccess;
 }
 
-hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block,
-                                       uint16_t* out, hipStream_t stream) {
+hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uint8_t* codes, float* absmax,
+                                     hipStream_t stream) {
+  return launch_quantize_any(x, n, block, codes, absmax, stream);
+}
+hipError_t launch_quantize_blockwise_h(const uint16_t* x, size_t n, int block, uint8_t* codes, uint16_t* absmax,
+                                       hipStream_t stream) {
+  return launch_quantize_any(x, n, block, codes, absmax, stream);
+}
+
+template <class Scale>
+static hipError_t launch_dequantize_any(const uint8_t* codes, const Scale* absmax, size_t n, int block,
+                                        uint16_t* out, hipStream_t stream) {
   const size_t n_groups = n / kDeqGroup;                         // whole groups
   if (n_groups > 0) {
     const size_t per_wg = (size_t)kThreads * kDeqPerThread;
     const dim3 grid((unsigned)((n_groups + per_wg - 1) / per_wg));
-    hipLaunchKernelGGL(k_dequantize_blockwise, grid, dim3(kThreads), 0, stream, codes, absmax, block, log2_exact(block), out,
-                       n_groups);
+    hipLaunchKernelGGL(k_dequantize_blockwise<Scale>, grid, dim3(kThreads), 0, stream, codes, absmax, block, log2_exact(block),
+                       out, n_groups);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const int rest = (int)(n - n_groups * kDeqGroup);
   if (rest > 0) {
-    hipLaunchKernelGGL(k_dequantize_tail, dim3(1), dim3(64), 0, stream, codes, absmax, n_groups * kDeqGroup, rest, block, out);
+    hipLaunchKernelGGL(k_dequantize_tail<Scale>, dim3(1), dim3(64), 0, stream, codes, absmax, n_groups * kDeqGroup, rest, block,
+                       out);
     return hipGetLastError();
   }
   return hipSuccess;
+}
+hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block,
+                                       uint16_t* out, hipStream_t stream) {
+  return launch_dequantize_any(codes, absmax, n, block, out, stream);
+}
+hipError_t launch_dequantize_blockwise_h(const uint8_t* codes, const uint16_t* absmax, size_t n, int block,
+                                         uint16_t* out, hipStream_t stream) {
+  return launch_dequantize_any(codes, absmax, n, block, out, stream);
 }
 
 }  // namespace mmd8

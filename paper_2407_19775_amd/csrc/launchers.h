@@ -13,6 +13,12 @@ hipError_t launch_quantize_blockwise(const uint16_t* x, size_t n, int block, uin
 hipError_t launch_dequantize_blockwise(const uint8_t* codes, const float* absmax, size_t n, int block, uint16_t* out,
                                        hipStream_t stream);
 
+// the same with the block scales stored as the fp16 numbers they are (2 bytes per block)
+hipError_t launch_quantize_blockwise_h(const uint16_t* x, size_t n, int block, uint8_t* codes, uint16_t* absmax,
+                                       hipStream_t stream);
+hipError_t launch_dequantize_blockwise_h(const uint8_t* codes, const uint16_t* absmax, size_t n, int block, uint16_t* out,
+                                         hipStream_t stream);
+
 // ---- weight_kernels.hip
 hipError_t launch_col_absmax(const uint16_t* W, int K, int N, int ldw, float* c, hipStream_t stream);
 hipError_t launch_weight_quant_pack(const uint16_t* W, int K, int N, int ldw, const float* c, int8_t* Wt,

@@ -95,3 +95,29 @@ def test_config4_full_size(block):
     x, dims = wl.boundary_hidden_state()
     assert dims.size == 4
     check(x, block)
+
+
+@pytest.mark.parametrize("n,block", [(8192 * 64, 256), (70000, 4096), (5000, 64), (4096 * 3 + 40, 1024), (130, 128), (7, 64),
+                                     (262144, 2048), (100000, 192)])
+def test_block_scales_stored_as_fp16(n, block):
+    """The other storage of the block scales: same codes, same decoded values, scales as fp16 bit patterns; against
+    the oracle and against the library's fp32 form."""
+    rng = np.random.default_rng([n, block])
+    x = (rng.standard_t(3.0, size=n) * rng.uniform(0.01, 300.0)).astype(np.float16)
+    x[rng.integers(0, n, 3)] = 0
+    xg = torch.from_numpy(x).cuda()
+    nb = (n + block - 1) // block
+    codes = torch.full((n + 16,), 0xAB, dtype=torch.uint8, device="cuda")
+    scales = torch.full((nb + 8,), -1.0, dtype=torch.float16, device="cuda")
+    binding.quantize_blockwise(xg, block, codes=codes[:n], absmax=scales[:nb], fp16_scales=True)
+    c32, a32 = binding.quantize_blockwise(xg, block)
+    dec = binding.dequantize_blockwise(codes[:n], scales[:nb], block)
+    dec32 = binding.dequantize_blockwise(c32, a32, block)
+    torch.cuda.synchronize()
+    oc, oa = bc.quantize_blockwise(x, block, fp16_scales=True)
+    assert np.array_equal(codes[:n].cpu().numpy(), oc)
+    assert np.array_equal(scales[:nb].cpu().numpy().view(np.uint16), oa.view(np.uint16))
+    assert bool((codes[n:] == 0xAB).all()) and bool((scales[nb:] == -1.0).all()), "wrote past the outputs"
+    assert torch.equal(codes[:n], c32) and torch.equal(scales[:nb].float(), a32)
+    assert np.array_equal(dec.cpu().numpy().view(np.uint16), bc.dequantize_blockwise(oc, oa, block).view(np.uint16))
+    assert torch.equal(dec, dec32)

@@ -268,3 +268,32 @@ def test_the_entry_point_without_a_workspace_refuses_sizes_beyond_its_array():
     assert call(8, 100, 64) == -2 and call(-1, 128, 64) == -1
     assert call(8, 128, 64, layout=tag + 1) == -5
     assert call(0, 128, 64) == 0 and call(0, 128, 64, tau=float("nan")) == -1
+
+
+def test_variant_entry_points_check_their_arguments():
+    L = binding.lib()
+    fake, y = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x40000000)
+    odd1 = ctypes.c_void_p(0x1001)
+    # block scales stored as fp16: 2-byte alignment is enough, odd addresses are not
+    assert L.mmd8_quantize_blockwise_h(fake, 1024, 100, fake, fake, None) == -2
+    assert L.mmd8_quantize_blockwise_h(fake, 1024, 256, fake, odd1, None) == -1
+    assert L.mmd8_quantize_blockwise_h(None, 0, 256, None, None, None) == 0
+    assert L.mmd8_dequantize_blockwise_h(fake, odd1, 1024, 256, fake, None) == -1
+    assert L.mmd8_dequantize_blockwise_h(fake, None, 1024, 256, fake, None) == -1
+    assert L.mmd8_dequantize_blockwise_h(None, None, 0, 64, None, None) == 0
+    # the other readings of the layer
+    tag = L.mmd8_packed_weight_layout()
+    ws = L.mmd8_linear_workspace_bytes(8, 128, 64)
+
+    def call(rd, layout=tag, wsb=ws):
+        return L.mmd8_mixed_int8_linear_readings(fake, 8, 128, 128, fake, layout, fake, 64, None, 6.0, rd, y, 64, fake, wsb,
+                                                 None, None)
+
+    R = binding.Readings
+    assert call(None) == -1
+    assert call(ctypes.byref(R(2, None, 0))) == -1 and call(ctypes.byref(R(-1, None, 0))) == -1
+    assert call(ctypes.byref(R(0, 0x2000, 60))) == -1          # ldw < N
+    assert call(ctypes.byref(R(0, 0x2000, 68))) == -1          # ldw % 8
+    assert call(ctypes.byref(R(1, 0x2008, 64))) == -1          # misaligned
+    assert call(ctypes.byref(R(1, 0x2000, 64)), layout=tag + 1) == -5
+    assert call(ctypes.byref(R(1, 0x2000, 64)), wsb=ws - 1) == -3

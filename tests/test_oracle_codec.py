@@ -194,3 +194,25 @@ def test_block_scales_are_fp16_numbers():
     x = (rng.standard_t(3.0, size=5000) * 7.0).astype(np.float16)
     _, a = bc.quantize_blockwise(x, 64)
     assert np.array_equal(a, a.astype(np.float16).astype(np.float32))
+
+
+def test_fp16_scales_change_nothing_but_the_bytes():
+    """The other storage of the block scales (2 bytes each): the scales are the same numbers, the codes are the
+    same, decoding from them gives the same values, and the hand-worked example of the golden file still holds."""
+    rng = np.random.default_rng(12)
+    for n, block in [(5000, 64), (4096, 256), (70000, 4096), (130, 128)]:
+        x = (rng.standard_t(3.0, size=n) * rng.uniform(0.01, 300.0)).astype(np.float16)
+        x[rng.integers(0, n, 5)] = 0
+        c32, a32 = bc.quantize_blockwise(x, block)
+        c16, a16 = bc.quantize_blockwise(x, block, fp16_scales=True)
+        assert a16.dtype == np.float16 and a16.nbytes * 2 == a32.nbytes
+        assert np.array_equal(c16, c32) and np.array_equal(a16.astype(np.float32), a32)
+        # the scale is the largest magnitude of the block, read straight off the fp16 data
+        full = np.abs(x[: n // block * block].reshape(-1, block)).max(axis=1)
+        assert np.array_equal(a16[: n // block], full)
+        assert np.array_equal(bc.dequantize_blockwise(c16, a16, block), bc.dequantize_blockwise(c32, a32, block))
+    g = np.array([1, -0.5, 0.25, 0, -3, 0.003, 1.5, 3], dtype=np.float16)        # the worked example of the codec, blocks of 4
+    codes, a = bc.quantize_blockwise(g, 4, fp16_scales=True)
+    assert codes.tolist() == [255, 35, 201, 127, 0, 142, 219, 255] and a.tolist() == [1.0, 3.0]
+    assert bc.compressed_fraction(1 << 20, 256, scale_bytes=2) == (1 + 2 / 256) / 2
+    assert bc.compressed_fraction(1 << 20, 4096, scale_bytes=2) == (1 + 2 / 4096) / 2
