@@ -43,83 +43,86 @@ __global__ __launch_bounds__(kThreads) void k_quantize_blockwise(
 }
 
 // ------------------------------------------------------------------------------------------------
-// Fast path: block sizes that are powers of two.  A workgroup walks spans of 4096 elements; each
-// of its four waves owns a 1024-element quarter (two 16-byte loads per lane, 1 KB per wave
-// instruction).  Blocks of up to 1024 elements live inside one wave, so their absmax is a
-// cross-lane reduction (DPP / swizzle, no LDS memory, no barrier); 2048 and 4096 exchange four
-// wave maxima through LDS with one barrier per span.  (The per-element encoding is in codec_device.h.)
+// Fast path: block sizes that are powers of two.  The unit of work is what one wave encodes on its own: 1024
+// elements (two 16-byte loads per lane, 1 KB per wave instruction) holding whole blocks of up to 1024, or one
+// whole block of 2048 / 4096 elements (four / eight loads per lane).  A block never leaves its wave, so every
+// absmax is a cross-lane reduction (DPP / swizzle): no LDS memory, no barrier.  (The per-element encoding is in
+// codec_device.h.)
+//
+// Launch shape: a fixed number of workgroups per compute unit (kEncodeGroupsPerCu, fewer for small tensors); a
+// wave walks its units with the loads of the next one already in flight while the current one is encoded and
+// stored, so reads and writes overlap inside every wave instead of the launch being one burst of reads
+// followed by one burst of writes.  (Measured on the [8192, 8192] hidden state, blocks of 256: two 4096-element
+// spans per short workgroup with all loads first 41.5 us; this form with 4 / 6 / 8 / 12 / 16 workgroups per
+// compute unit 39.2 / 38.4 / 37.5 / 39.8 / 38.7 us; plain instead of nontemporal accesses 41.0 us.)
 // ------------------------------------------------------------------------------------------------
+constexpr int kEncodeGroupsPerCu = 8;
+constexpr int kWavesPerGroup = kThreads / kWave;
+template <int kLogBlock>
+constexpr int encode_unit() { return (1 << kLogBlock) > 1024 ? (1 << kLogBlock) : 1024; }
 
-// A workgroup encodes kSpansPerGroup spans that lie half the tensor apart, all of their loads issued
-// before anything else: every workgroup is short, the chip always holds many workgroups at
-// different stages, and the memory system sees a few long sequential streams.  (Measured on the
-// [8192, 8192] hidden state: 1, 2, 4, 8 spans per workgroup give 4.3, 4.8, 4.6, 4.1 TB/s.)
-constexpr int kSpansPerGroup = 2;
 template <int kLogBlock, class Scale>
-__global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __restrict__ x, size_t n_spans,
+__global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __restrict__ x, size_t n_units,
                                                             uint8_t* __restrict__ codes,
                                                             Scale* __restrict__ absmax) {
   static_assert(kLogBlock >= 6 && kLogBlock <= 12, "64 .. 4096");
   __shared__ v2u s_cells[DynamicCode::kCells];
-  __shared__ uint32_t s_wave_max[2][kThreads / kWave];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   constexpr int kBlock = 1 << kLogBlock;
-  constexpr int kLanesPerBlock = kBlock / kChunk;                  // lanes of one load that share a block
+  constexpr int kUnit = encode_unit<kLogBlock>();
+  constexpr int kLoads = kUnit / (kWave * kChunk);                 // 16-byte loads per lane and unit: 2, 4 or 8
+  constexpr int kLanesPerBlock = kBlock / kChunk;                  // lanes of one load that share a block (small blocks)
 
-  // span j of this workgroup; a missing one re-reads the last span and stores nothing
-  v4u raw[kSpansPerGroup][2];
-  size_t span_of[kSpansPerGroup];
+  auto load_unit = [&](size_t u, v4u (&r)[kLoads]) {
+    const uint16_t* base = x + u * kUnit + lane * kChunk;
 #pragma unroll
-  for (int j = 0; j < kSpansPerGroup; ++j) {
-    span_of[j] = blockIdx.x + (size_t)j * gridDim.x;
-    const size_t sp = span_of[j] < n_spans ? span_of[j] : n_spans - 1;
-    const uint16_t* base = x + sp * kSpanMax + wave * 1024 + lane * kChunk;
-    raw[j][0] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base));
-    raw[j][1] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base + 512));
-  }
+    for (int c = 0; c < kLoads; ++c) r[c] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(base + c * (kWave * kChunk)));
+  };
+  const size_t stride = (size_t)gridDim.x * kWavesPerGroup;
+  size_t u = (size_t)blockIdx.x * kWavesPerGroup + wave;
+  v4u raw[kLoads], ahead[kLoads];
+  if (u < n_units) load_unit(u, raw);
   for (int i = threadIdx.x; i < DynamicCode::kCells; i += kThreads) {
     const CodeCell c = kCodeDev.cell[i];
     s_cells[i] = v2u{c.threshold == kNoThreshold ? kNoThreshold : c.threshold * 2u, c.base};
   }
-  __syncthreads();
+  __syncthreads();                                                 // the only barrier: every wave passes it once
   const uint32_t cells_biased = (uint32_t)(uintptr_t)s_cells - (uint32_t)DynamicCode::kCellLo * 8u;
 
+  for (; u < n_units; u += stride) {
+    const size_t u_next = u + stride;
+    load_unit(u_next < n_units ? u_next : u, ahead);               // (the last trip re-reads its own unit: no branch)
+    const size_t e0 = u * kUnit;                                   // first element of the unit
+    uint32_t m[kLoads];
 #pragma unroll
-  for (int j = 0; j < kSpansPerGroup; ++j) {
-    const bool real = span_of[j] < n_spans;                        // the same for every thread
-    uint32_t m0 = chunk_absmax_pattern(raw[j][0]), m1 = chunk_absmax_pattern(raw[j][1]);
-    const size_t e_wave = span_of[j] * kSpanMax + wave * 1024;     // first element of this wave's quarter
+    for (int c = 0; c < kLoads; ++c) m[c] = chunk_absmax_pattern(raw[c]);
     if constexpr (kLogBlock <= 9) {
-      m0 = group_max<kLanesPerBlock>(m0);
-      m1 = group_max<kLanesPerBlock>(m1);
-      if (real && (lane & (kLanesPerBlock - 1)) == 0) {
-        store_scale(absmax, (e_wave + lane * kChunk) >> kLogBlock, m0);
-        store_scale(absmax, (e_wave + 512 + lane * kChunk) >> kLogBlock, m1);
+#pragma unroll
+      for (int c = 0; c < kLoads; ++c) {
+        m[c] = group_max<kLanesPerBlock>(m[c]);
+        if ((lane & (kLanesPerBlock - 1)) == 0) store_scale(absmax, (e0 + c * (kWave * kChunk) + lane * kChunk) >> kLogBlock, m[c]);
       }
     } else {
-      m0 = group_max<kWave>(max(m0, m1));
-      if constexpr (kLogBlock >= 11) {
-        // blocks of 2 or 4 waves: exchange through LDS (slot alternates, so one barrier per span)
-        if (lane == 0) s_wave_max[j & 1][wave] = m0;
-        __syncthreads();
-        if constexpr (kLogBlock == 11)
-          m0 = max(s_wave_max[j & 1][wave & ~1], s_wave_max[j & 1][wave | 1]);
-        else
-          m0 = max(max(s_wave_max[j & 1][0], s_wave_max[j & 1][1]), max(s_wave_max[j & 1][2], s_wave_max[j & 1][3]));
+      uint32_t mm = m[0];
+#pragma unroll
+      for (int c = 1; c < kLoads; ++c) mm = max(mm, m[c]);
+      mm = group_max<kWave>(mm);                                   // the unit is one block
+      if (lane == 0) store_scale(absmax, e0 >> kLogBlock, mm);
+#pragma unroll
+      for (int c = 0; c < kLoads; ++c) m[c] = mm;
+    }
+    uint8_t* out = codes + e0 + lane * kChunk;
+    float inv = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kLoads; ++c) {
+      if (kLogBlock <= 9 || c == 0) {
+        const float a = half_lo_to_float(m[c]);
+        inv = (a == 0.0f) ? 0.0f : 1.0f / a;                       // IEEE division
       }
-      m1 = m0;
-      const bool writer = (kLogBlock == 10) ? lane == 0 : (kLogBlock == 11) ? (lane == 0 && (wave & 1) == 0)
-                                                                            : threadIdx.x == 0;
-      if (real && writer) store_scale(absmax, e_wave >> kLogBlock, m0);
+      __builtin_nontemporal_store(encode_chunk(raw[c], inv, cells_biased), reinterpret_cast<v2u*>(out + c * (kWave * kChunk)));
     }
-    const float a0 = half_lo_to_float(m0), a1 = half_lo_to_float(m1);
-    const float inv0 = (a0 == 0.0f) ? 0.0f : 1.0f / a0;            // IEEE division
-    const float inv1 = (kLogBlock >= 10) ? inv0 : ((a1 == 0.0f) ? 0.0f : 1.0f / a1);
-    if (real) {
-      uint8_t* out = codes + e_wave + lane * kChunk;
-      __builtin_nontemporal_store(encode_chunk(raw[j][0], inv0, cells_biased), reinterpret_cast<v2u*>(out));
-      __builtin_nontemporal_store(encode_chunk(raw[j][1], inv1, cells_biased), reinterpret_cast<v2u*>(out + 512));
-    }
+#pragma unroll
+    for (int c = 0; c < kLoads; ++c) raw[c] = ahead[c];
   }
 }
 
@@ -145,10 +148,12 @@ __device__ inline v4u decode_group(const v2u& c, float a, const float* s_T) {
 // Whole groups only.  A thread decodes kDeqPerThread groups that lie an eighth of the tensor apart,
 // all loads first (same launch shape as the encoder).
 constexpr int kDeqPerThread = 8;
-template <class Scale>
+// kPow2: the block size is 1 << log_block (otherwise log_block is unused: the block index is a 64-bit division,
+// which must not sit in front of the loads of the common case).
+template <class Scale, bool kPow2>
 __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
     const uint8_t* __restrict__ codes, const Scale* __restrict__ absmax, int block,
-    int log_block /* -1 if block is not a power of two */, uint16_t* __restrict__ out, size_t n_groups) {
+    int log_block, uint16_t* __restrict__ out, size_t n_groups) {
   __shared__ float s_T[256];
   const size_t stride = (size_t)gridDim.x * kThreads;
   const size_t g0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void k_dequantize_blockwise(
     const size_t g = g0 + j * stride;
     const size_t e0 = (g < n_groups ? g : n_groups - 1) * kDeqGroup;   // a missing group re-reads the last one
     c[j] = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(codes + e0));
-    a[j] = load_scale(absmax, (log_block >= 0) ? (e0 >> log_block) : (e0 / (size_t)block));
+    a[j] = load_scale(absmax, kPow2 ? (e0 >> log_block) : (e0 / (size_t)block));
   }
   s_T[threadIdx.x] = kCodeDev.T[threadIdx.x];
   __syncthreads();
@@ -206,12 +211,17 @@ static hipError_t launch_quantize_any(const uint16_t* x, size_t n, int block, ui
                                       hipStream_t stream) {
   const int log_block = log2_exact(block);
   if (log_block < 0) return launch_quantize_generic(x, n, block, codes, absmax, stream);
-  // whole 4096-element spans on the fast path, the ragged end (whole blocks plus a short one)
-  // through the generic kernel
-  const size_t n_spans = n / kSpanMax;
-  if (n_spans > 0) {
-    const dim3 grid((unsigned)((n_spans + kSpansPerGroup - 1) / kSpansPerGroup));
-#define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L, Scale>), grid, dim3(kThreads), 0, stream, x, n_spans, codes, absmax)
+  // whole units on the fast path (1024 elements, or one block of 2048 / 4096), the ragged end (whole blocks plus a
+  // short one) through the generic kernel
+  const size_t unit = block > 1024 ? (size_t)block : 1024;
+  const size_t n_units = n / unit;
+  if (n_units > 0) {
+    // (a 4096-element unit keeps 16 loads per lane in flight and needs more registers: fewer workgroups per compute
+    // unit, so that all of them are resident together)
+    const size_t per_cu = log_block >= 12 ? kEncodeGroupsPerCu / 2 : kEncodeGroupsPerCu;
+    const size_t want = (n_units + kWavesPerGroup - 1) / kWavesPerGroup, max_groups = (size_t)device_cu_count() * per_cu;
+    const dim3 grid((unsigned)(want < max_groups ? want : max_groups));
+#define MMD8_Q(L) hipLaunchKernelGGL((k_quantize_pow2<L, Scale>), grid, dim3(kThreads), 0, stream, x, n_units, codes, absmax)
     switch (log_block) {
       case 6: MMD8_Q(6); break;
       case 7: MMD8_Q(7); break;
@@ -225,7 +235,7 @@ static hipError_t launch_quantize_any(const uint16_t* x, size_t n, int block, ui
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const size_t done = n_spans * kSpanMax;
+  const size_t done = n_units * unit;
   if (done < n)
     return launch_quantize_generic(x + done, n - done, block, codes + done, absmax + done / block, stream);
   return hipSuccess;
@@ -247,8 +257,13 @@ static hipError_t launch_dequantize_any(const uint8_t* codes, const Scale* absma
   if (n_groups > 0) {
     const size_t per_wg = (size_t)kThreads * kDeqPerThread;
     const dim3 grid((unsigned)((n_groups + per_wg - 1) / per_wg));
-    hipLaunchKernelGGL(k_dequantize_blockwise<Scale>, grid, dim3(kThreads), 0, stream, codes, absmax, block, log2_exact(block),
-                       out, n_groups);
+    const int log_block = log2_exact(block);
+    if (log_block >= 0)
+      hipLaunchKernelGGL((k_dequantize_blockwise<Scale, true>), grid, dim3(kThreads), 0, stream, codes, absmax, block, log_block,
+                         out, n_groups);
+    else
+      hipLaunchKernelGGL((k_dequantize_blockwise<Scale, false>), grid, dim3(kThreads), 0, stream, codes, absmax, block, 0, out,
+                         n_groups);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -82,15 +82,32 @@ __device__ inline void wait_slab_and_sync() {
 __device__ inline void wait_lds_and_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); }
 __device__ inline void sync_only() { asm volatile("s_barrier" : : : "memory"); }
 
-// tile assignment: consecutive workgroup ids land on different XCDs (8 of them), so each XCD gets
-// a contiguous run of tiles that walk M fastest: the run shares a few Wt row panels in its L2
+// Tile assignment.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2), so XCD x
+// gets the ids x, x + 8, ...: a contiguous run of the tile order below, 32 tiles (one per CU) at a time.  The order
+// walks blocks of 8 tile rows x 4 tile columns (bands of 4 columns; inside a band blocks of 8 rows; inside a
+// block rows fastest), so the 32 tiles an XCD works on at once share 8 activation panels and 4 weight panels:
+// 12 panel streams through its L2 instead of the 18 of a plain rows-fastest order with 16 tile rows (measured on
+// the 70B-shaped linears at 4096 tokens: 1.4-2.1 % faster; identical for up to 8 tile rows).
 __device__ inline bool tile_of_block(const GemmArgs& a, int bid, int& tm, int& tn) {
+  constexpr int kBlockRows = 8, kBandCols = 4;
   const int n_tiles = a.tiles_m * a.tiles_n;
   const int per_xcd = ceil_div(n_tiles, 8);
   const int logical = (bid % 8) * per_xcd + bid / 8;
   if (logical >= n_tiles) return false;
-  tm = logical % a.tiles_m;
-  tn = logical / a.tiles_m;
+  const int band_tiles = a.tiles_m * kBandCols;                    // (every band but the last is full)
+  const int band = logical / band_tiles;
+  const int w = min(kBandCols, a.tiles_n - band * kBandCols);      // width of this band
+  const int q = logical - band * band_tiles;                       // index inside the band
+  const int full_blocks = a.tiles_m / kBlockRows, rest_rows = a.tiles_m - full_blocks * kBlockRows;
+  if (q < full_blocks * kBlockRows * w) {
+    const int r = q % (kBlockRows * w);
+    tm = (q / (kBlockRows * w)) * kBlockRows + r % kBlockRows;
+    tn = band * kBandCols + r / kBlockRows;
+  } else {                                                         // the last, shorter block of rows
+    const int r = q - full_blocks * kBlockRows * w;
+    tm = full_blocks * kBlockRows + r % rest_rows;
+    tn = band * kBandCols + r / rest_rows;
+  }
   return true;
 }
 
