@@ -161,7 +161,7 @@ constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (
 // land in LDS; the workgroup with `publish` also writes the list, the count, the byte mask and
 // the taps to global memory.  Each thread owns a contiguous run of 16-column units.
 __device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag, int K, int Kpad, const PackOutliers& o,
-                                                bool publish, int* s_idx /*[kOutlierSlab]*/, int* s_n_out,
+                                                bool publish, int* s_idx /*[kOutlierSlab * kCriticalSlabs]*/, int* s_n_out,
                                                 int* s_wave_total /*[kThreads / kWave]*/) {
   constexpr int kMaxUnits = MMD8_MAX_K / 16 / kThreads;            // 16
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -202,7 +202,7 @@ __device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag
           const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
           if (publish && o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
           if (set) {
-            if (pos < kOutlierSlab) s_idx[pos] = k;
+            if (pos < kOutlierSlab * o.crit_slabs) s_idx[pos] = k;
             if (publish) {
               o.idx[pos] = k;
               if (o.tap_idx) o.tap_idx[pos] = k;
@@ -223,15 +223,26 @@ __device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag
   __syncthreads();
 }
 
-// Rows of the critical-column slab, 8 columns (16 bytes) per thread: Xo[m][j] = X[m, O_j] for
-// the first kOutlierSlab critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
-// j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Both
-// are stored like one slab of a packed operand.
+// Rows of the critical-column slabs, 8 columns (16 bytes) per thread and slab: Xo[m][j] = X[m, O_j] for
+// the first kOutlierSlab * crit_slabs critical columns and Wo[n][j] = f16(Wt[n, O_j] c[n] / 127); zero for
+// j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Each group of 32
+// columns is stored like one slab of a packed operand; slab 0 is always written (zeros without critical
+// columns), slab s > 0 only when more than 32 s columns are critical (the GEMM reads no other).
+__device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
+                                               const PackOutliers& o, int row, int ch, int slab, const int* s_idx,
+                                               int n_out);
 __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                            const PackOutliers& o, int item, const int* s_idx, int n_out_all) {
-  const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8), j0 = ch * 8;
+  const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8);
   if (row >= M + o.N) return;
-  const int n_out = min(n_out_all, kOutlierSlab);
+  const int n_out = min(n_out_all, kOutlierSlab * o.crit_slabs);
+  const int used = max(1, ceil_div(n_out, kOutlierSlab));
+  for (int slab = 0; slab < used; ++slab) gather_outlier_slab_one(X, M, ldx, n_slabs, o, row, ch, slab, s_idx, n_out);
+}
+__device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
+                                               const PackOutliers& o, int row, int ch, int slab, const int* s_idx,
+                                               int n_out) {
+  const int j0 = slab * kOutlierSlab + ch * 8;
   // all eight loads of a thread are issued together: a missing column re-reads column 0 and is masked
   int kcol[8];
 #pragma unroll
@@ -243,7 +254,7 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
     for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + max(kcol[t], 0)];
 #pragma unroll
     for (int t = 0; t < 8; ++t) out[t >> 1] |= (kcol[t] >= 0 ? (uint32_t)v[t] : 0u) << (16 * (t & 1));
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, 0, ch, o.f_slabs)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, slab, ch, o.f_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
@@ -265,7 +276,7 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
         out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
       }
     }
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, 0, ch, o.f_slabs)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, slab, ch, o.f_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   }
 }
@@ -277,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
                                                    uint16_t* __restrict__ Xf, const PackOutliers o) {
   if ((int)blockIdx.y >= pack_blocks_y) {
     // the extra blocks list the critical columns and prepare their slab; the first one publishes
-    __shared__ int s_idx[kOutlierSlab];
+    __shared__ int s_idx[kOutlierSlab * kCriticalSlabs];
     __shared__ int s_n_out;
     __shared__ int s_wave_total[kThreads / kWave];
     const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
@@ -530,7 +541,7 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
                                                               const PackOutliers o) {
   const int Kpad = n_slabs * kSlabBytes;
   if ((int)blockIdx.x < slab_blocks) {
-    __shared__ int s_idx[kOutlierSlab];
+    __shared__ int s_idx[kOutlierSlab * kCriticalSlabs];
     __shared__ int s_n_out;
     __shared__ int s_wave_total[kThreads / kWave];
     compact_critical_columns(flag, K, Kpad, o, blockIdx.x == 0, s_idx, &s_n_out, s_wave_total);

@@ -70,7 +70,8 @@ struct Workspace {
   float* r;            // [Mpad + 256]
   uint16_t* xo;        // [Mpad][kOutlierSlab] per fp16 slab, blocked like the codes
   uint16_t* wo;        // [Npad][kOutlierSlab] per fp16 slab
-  int f_slabs;         // fp16 slabs: the critical columns, then the low-rank operands of an adapter of rank r
+  int f_slabs;         // fp16 slabs: crit_slabs for the critical columns, then the low-rank operands of an adapter of rank r
+  int crit_slabs;      // 32 critical columns each: kCriticalSlabs where the tiled GEMM is the usual path, else 1
   uint16_t* lora_t;    // adapter only: [M][kLoraMaxRank] fp16
   float* lora_part;    // adapter only: partial sums of the down-projection when K is split between workgroups
   int8_t* xq;          // Mpad x Kpad codes, blocked layout
@@ -96,7 +97,10 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_bloc
   w.mask = take(Kpad);
   w.idx = reinterpret_cast<int32_t*>(take(Kpad * 4));
   w.r = reinterpret_cast<float*>(take((Mpad + 256) * 4));
-  w.f_slabs = 1 + lora_slabs(r);
+  // (up to 128 rows the decode kernels do the work and these slabs are not used, except by calls that force the
+  // tiled GEMM: one slab, further critical columns through its gather loop)
+  w.crit_slabs = M > kSkinnyChunkedMaxM ? kCriticalSlabs : 1;
+  w.f_slabs = w.crit_slabs + lora_slabs(r);
   w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2 * w.f_slabs));
   w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2 * w.f_slabs));
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
@@ -317,7 +321,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   };
   if (!record(t.event_begin)) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
-                           Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs,
+                           Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs, ws.crit_slabs,
                            readings ? readings->W_master : nullptr, readings ? readings->ldw : 0};
   // Up to 128 rows go through the decode kernels, 64 rows at a time (the weights are streamed twice for more
   // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
@@ -377,6 +381,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     l.Xo = skinny ? nullptr : ws.xo;
     l.Wo = skinny ? nullptr : ws.wo;
     l.f_slabs = ws.f_slabs;
+    l.crit_slabs = ws.crit_slabs;
     if (launch_lora_down(l, plan_lora(M, K), ws.lora_part, st) != hipSuccess) return MMD8_E_HIP;
   }
 
@@ -480,6 +485,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.Xo = ws.xo;
     g.Wo = ws.wo;
     g.f_slabs = ws.f_slabs;
+    g.crit_slabs = ws.crit_slabs;
     g.Y = Y;
     g.ldy = ldy;
     g.tap_acc = t.acc;

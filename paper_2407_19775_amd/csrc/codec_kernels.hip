@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pow2(const uint16_t* __re
 
   for (; u < n_units; u += stride) {
     const size_t u_next = u + stride;
-    load_unit(u_next < n_units ? u_next : u, ahead);               // (the last trip re-reads its own unit: no branch)
+    if (u_next < n_units) load_unit(u_next, ahead);                // (uniform over the wave; nothing is fetched twice)
     const size_t e0 = u * kUnit;                                   // first element of the unit
     uint32_t m[kLoads];
 #pragma unroll

@@ -4,9 +4,12 @@
 
 namespace mmd8 {
 
-// Critical columns handled on the fast path: they travel as one extra 64-byte K-slab of fp16
-// operands (32 columns).  Columns beyond that go through the gather loop of the epilogue.
+// Critical columns handled on the fast path: they travel as extra 64-byte K-slabs of fp16 operands, 32 columns
+// each, prepared once per call by the pack kernels: the first slab rides through the GEMM's slab ring behind
+// the codes, up to kCriticalSlabs - 1 more follow it one by one.  Columns beyond 32 kCriticalSlabs go through
+// the gather loop of the epilogue (every tile gathers them again: much slower).
 constexpr int kOutlierSlab = 32;
+constexpr int kCriticalSlabs = 8;
 
 struct GemmArgs {
   const int8_t* Xq;      // activation codes, blocked layout (operand_layout.h), Mpad x Kpad
@@ -21,8 +24,9 @@ struct GemmArgs {
   const int32_t* n_out;  // their count
   const uint16_t* Xo;    // one slab of fp16 per row, blocked like the codes: X[m, O_j], zero for j >= n_out
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
-  int f_slabs;           // fp16 slabs per panel in Xo / Wo: 1, or 1 + those of a low-rank adapter (at most 3), whose
-                         // operands follow the critical columns and are multiplied in the same way
+  int f_slabs;           // fp16 slabs per panel in Xo / Wo: crit_slabs for the critical columns, then those of a low-rank
+                         // adapter (at most 2), whose operands are multiplied in the same way
+  int crit_slabs;        // slabs set aside for critical columns (1 .. kCriticalSlabs); ceil(min(n_out, 32 crit_slabs) / 32) are in use
   uint16_t* Y;           // may be null when `codes` is given (only the coded form of the output is wanted)
   int ldy;
   // The output leaving in coded form (the shard's last linear): H = Y, or f16(Y + residual) when a residual is

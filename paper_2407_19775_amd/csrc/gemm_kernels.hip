@@ -246,52 +246,6 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
   }
 }
 
-// The fp16 slabs behind the one of the critical columns (the operands of a low-rank adapter: T on the
-// activation side, B on the weight side), one after the other through the first slab buffer: request,
-// wait, multiply.  Not overlapped with anything: two or three extra slabs next to the K / 64 of the codes.
-template <class Cfg>
-__device__ __forceinline__ void low_rank_slabs(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
-                                      int8_t* smem) {
-  constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
-  // everything here is derived after this point (nothing of it is kept in registers through the main loop)
-  int lane = p.lane, wm = p.wm, wn = p.wn;
-  asm volatile("" : "+v"(lane), "+s"(wm), "+s"(wn));
-  const int wave = wm * Cfg::WAVES_N + wn;
-  const uint32_t base = (uint32_t)(uintptr_t)smem + wave * (kWave * 16);
-  __syncthreads();                                               // every wave is done with the slab buffers
-  for (int f = 1; f < a.f_slabs; ++f) {
-#pragma unroll
-    for (int j = 0; j < Cfg::A_DMA; ++j)
-      dma16(dma_source(reinterpret_cast<const int8_t*>(a.Xo), p.m0, a.f_slabs, j, Cfg::kWaves, wave, lane) +
-                (size_t)f * kBlockBytes,
-            base + j * Cfg::kWaves * (kWave * 16));
-#pragma unroll
-    for (int j = 0; j < Cfg::B_DMA; ++j)
-      dma16(dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane) +
-                (size_t)f * kBlockBytes,
-            base + Cfg::A_BYTES + j * Cfg::kWaves * (kWave * 16));
-    wait_slab_and_sync<0>();
-#pragma unroll
-    for (int ks = 0; ks < Cfg::NKS; ++ks) {
-      // group of 32 rows: 2 KB = [k-step][lane] 16-byte pieces, as in the main loop
-      const int8_t* fa = smem + (wm * Cfg::WM / 32) * 2048 + ks * 1024 + lane * 16;
-      const int8_t* fb = smem + Cfg::A_BYTES + (wn * Cfg::WN / 32) * 2048 + ks * 1024 + lane * 16;
-      v8h xa[TI], xb[TJ];
-#pragma unroll
-      for (int i = 0; i < TI; ++i) xa[i] = *reinterpret_cast<const v8h*>(fa + i * 32 * BK);
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) xb[j] = *reinterpret_cast<const v8h*>(fb + j * 32 * BK);
-#pragma unroll
-      for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          acc[i][j] = __builtin_bit_cast(
-              v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[i], xb[j], __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
-    }
-    __syncthreads();                                             // the buffer is read before the next slab lands in it
-  }
-}
-
 // bias, rounding to fp16, and stores, through LDS (the slab buffers are free by now).  Neighbouring lanes hold
 // neighbouring columns of the same rows; an even/odd lane pair swaps halves so that each lane has two adjacent
 // columns (4 bytes): the even lane of row e, the odd lane of row e + 1.  A wave parks 64 (or 32) rows of its
@@ -476,9 +430,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   if (!tile_of_block(a, blockIdx.x, tm, tn)) return;
   const WavePos<Cfg> p(tm * Cfg::BM, tn * Cfg::BN, wave, lane);
   const int n_slabs = a.Kpad / BK;
-  const int n_out = *a.n_out;
-  const bool has_slab_o = n_out > 0;                                // the critical columns ride as one more slab
-  const int total_slabs = n_slabs + (has_slab_o ? 1 : 0);
+  const int n_out = __builtin_amdgcn_readfirstlane(*a.n_out);
+  // Behind the slabs of codes, through the same ring: the fp16 slabs of the critical columns that are in use (32
+  // columns each, at most crit_slabs of them; further columns are gathered after the loop) and those of a low-rank
+  // adapter (T on the activation side, B on the weight side), which start at slab crit_slabs of Xo / Wo.
+  const int crit_used = min(a.crit_slabs, ceil_div(n_out, kOutlierSlab));
+  const int total_slabs = n_slabs + crit_used + (a.f_slabs - a.crit_slabs);
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
   // [(j kWaves + wave) ROWS_PER_DMA, +ROWS_PER_DMA) of the operand tile: 1 KB, contiguous in
@@ -498,19 +455,28 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
     srcB[j] = dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane);
     srcWo[j] = dma_source(reinterpret_cast<const int8_t*>(a.Wo), p.n0, a.f_slabs, j, Cfg::kWaves, wave, lane);
   }
-  // request d (0 .. DMA_PER_SLAB-1) of a slab: the A rows first, then the B rows
-  auto issue_dma = [&](int slab, int stage, int d) {
+  // request d (0 .. DMA_PER_SLAB-1) of the slab at position `pos` of the ring's sequence: the A rows first, then the
+  // B rows.  kFp16 says which kind of slab that position holds (known where the request is written down, so that
+  // the loop over the codes carries no choice between the two)
+  auto issue_dma = [&](int pos, int stage, int d, auto fp16_tag) {
+    constexpr bool kF = decltype(fp16_tag)::value;
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
-    const bool o = slab >= n_slabs;                                 // the fp16 slab of critical columns
+    const int f = pos - n_slabs;                                    // among the fp16 slabs in use: its place in Xo / Wo
+    const size_t off = (size_t)(!kF ? pos : f < crit_used ? f : f - crit_used + a.crit_slabs) * kBlockBytes;
     if (d < Cfg::A_DMA)
-      dma16(o ? srcXo[d] : srcA[d] + (size_t)slab * kBlockBytes, base + d * Cfg::kWaves * (kWave * 16));
+      dma16((kF ? srcXo[d] : srcA[d]) + off, base + d * Cfg::kWaves * (kWave * 16));
     else
-      dma16(o ? srcWo[d - Cfg::A_DMA] : srcB[d - Cfg::A_DMA] + (size_t)slab * kBlockBytes,
+      dma16((kF ? srcWo[d - Cfg::A_DMA] : srcB[d - Cfg::A_DMA]) + off,
             base + Cfg::A_BYTES + (d - Cfg::A_DMA) * Cfg::kWaves * (kWave * 16));
   };
-  auto issue_slab = [&](int slab, int stage) {
+  auto issue_slab = [&](int pos, int stage) {
 #pragma unroll
-    for (int d = 0; d < Cfg::DMA_PER_SLAB; ++d) issue_dma(slab, stage, d);
+    for (int d = 0; d < Cfg::DMA_PER_SLAB; ++d) {
+      if (pos < n_slabs)
+        issue_dma(pos, stage, d, std::false_type{});
+      else
+        issue_dma(pos, stage, d, std::true_type{});
+    }
   };
 
   // ---- per-lane LDS read offsets: row (lane % 32) of an MFMA tile, piece (2 ks + lane / 32)
@@ -544,7 +510,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   // wave waits until only the requests younger than slab s + 1 are outstanding.
   // A wave issues in order, and a request that finds the memory queue full blocks the MFMAs
   // behind it, so the requests of a slab are spread evenly between the MFMAs of the iteration.
-  // kIssue: slab s + kAhead exists and is requested in this iteration; kNext: slab s + 1 exists.
+  // issue_tag: slab s + kAhead exists and is requested in this iteration (1: it is a slab of codes, 2: an fp16 slab;
+  // 0: no request); kNext: slab s + 1 exists.
   constexpr int AHEAD = Cfg::kAhead;
   constexpr int MFMAS = TI * TJ;                                   // per k-step
   // request d of a slab goes out after MFMA number d SLOTS / DMA_PER_SLAB of the iteration
@@ -555,14 +522,14 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   float cs[TJ], bn[TJ];
   load_column_terms<Cfg>(a, p, cs, bn);
   int stage = 0;
-  // kFp16: slab s is the slab of critical columns (fp16 operands, fp32 accumulation onto the
-  // accumulators, which are dequantized first)
+  // kFp16: slab s is one of the fp16 slabs (fp16 operands, fp32 accumulation onto the accumulators, which
+  // were dequantized before the first of them)
   auto iteration = [&](int s, auto issue_tag, auto next_tag, auto fp16_tag) {
-    constexpr bool kIssue = decltype(issue_tag)::value, kNext = decltype(next_tag)::value;
+    constexpr int kIssueKind = decltype(issue_tag)::value;
+    constexpr bool kIssue = kIssueKind != 0, kNext = decltype(next_tag)::value;
     constexpr bool kFp16 = decltype(fp16_tag)::value;
     const int stage1 = (stage + 1 == STAGES) ? 0 : stage + 1;
     const int stage_req = (stage == 0) ? STAGES - 1 : stage - 1;   // (s + kAhead) mod kStages
-    if constexpr (kFp16) dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
@@ -598,7 +565,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
           const bool here = d < DPS_ && (d * SLOTS + DPS_ - 1) / DPS_ == slot;
           if (kIssue && here) {
             __builtin_amdgcn_sched_barrier(0);
-            issue_dma(s + AHEAD, stage_req, d);
+            issue_dma(s + AHEAD, stage_req, d, std::bool_constant<kIssueKind == 2>{});
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -620,18 +587,21 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
     wait_slab_and_sync<2 * Cfg::DMA_PER_SLAB>();
   read_frags(0, 0, 0);
   int s = 0;
-  for (; s + AHEAD < total_slabs && s < n_slabs; ++s) iteration(s, yes{}, yes{}, no{});
-  for (; s + 1 < total_slabs && s < n_slabs; ++s) iteration(s, no{}, yes{}, no{});
-  if (s < n_slabs) iteration(s, no{}, no{}, no{});                  // the last slab when nothing follows it
+  using none = std::integral_constant<int, 0>;
+  using codes = std::integral_constant<int, 1>;
+  using halves = std::integral_constant<int, 2>;
+  for (; s + AHEAD < n_slabs; ++s) iteration(s, codes{}, yes{}, no{});                      // nearly all of the time
+  for (; s < n_slabs && s + AHEAD < total_slabs; ++s) iteration(s, halves{}, yes{}, no{});  // the first fp16 slabs requested
+  for (; s < n_slabs && s + 1 < total_slabs; ++s) iteration(s, none{}, yes{}, no{});
+  if (s < n_slabs) iteration(s++, none{}, no{}, no{});              // the last slab when nothing follows it
   if constexpr (kTap) tap_accumulators<Cfg>(a, p, acc);
-  if (has_slab_o)
-    iteration(n_slabs, no{}, no{}, yes{});
-  else
-    dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
+  dequantize_in_place<Cfg>(p, acc, a.r + p.m0, cs);
+  for (; s + AHEAD < total_slabs; ++s) iteration(s, halves{}, yes{}, yes{});
+  for (; s + 1 < total_slabs; ++s) iteration(s, none{}, yes{}, yes{});
+  if (s < total_slabs) iteration(s, none{}, no{}, yes{});
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
   // free for the gather staging, which starts with a barrier of its own before writing them
-  if (n_out > kOutlierSlab) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab, n_out);
-  if (a.f_slabs > 1) low_rank_slabs<Cfg>(a, p, acc, smem);
+  if (n_out > kOutlierSlab * a.crit_slabs) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab * a.crit_slabs, n_out);
   if constexpr (kCoded)
     store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
   else

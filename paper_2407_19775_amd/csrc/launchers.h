@@ -38,7 +38,8 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
   int N;
   uint16_t* Xo;
   uint16_t* Wo;
-  int f_slabs;           // fp16 slabs per panel in Xo / Wo (the critical columns are slab 0)
+  int f_slabs;           // fp16 slabs per panel in Xo / Wo
+  int crit_slabs;        // ... of which the first crit_slabs are for critical columns, 32 each (the rest: an adapter's)
   // Alternative reading of where the 16-bit weights of the critical dimensions come from: null (re-created from
   // the codes, f16(Wt c / 127)), or the original fp16 weights W[k * ldw + n], whose rows are then used as they are.
   const uint16_t* W_master;

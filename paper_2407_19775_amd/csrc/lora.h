@@ -19,7 +19,8 @@ struct LoraArgs {
   uint16_t* T_user;      // [M][r] or null
   uint16_t* Xo;          // fp16 slabs of the GEMM's activation side (slab 0: critical columns), or null
   uint16_t* Wo;          // likewise, weight side
-  int f_slabs;           // slabs per panel in Xo / Wo: 1 + lora_slabs(r)
+  int f_slabs;           // slabs per panel in Xo / Wo: crit_slabs + lora_slabs(r)
+  int crit_slabs;        // slabs of the critical columns in front of the adapter's
 };
 // how K is split between workgroups for this shape (depends on the device's CU count)
 struct LoraPlan {

@@ -35,7 +35,7 @@ __device__ inline void store_low_rank_activation(const LoraArgs& a, int m, int c
   *reinterpret_cast<v4u*>(a.T + (size_t)m * kLoraMaxRank + j0) = v;
   if (a.T_user && j0 < a.r) *reinterpret_cast<v4u*>(a.T_user + (size_t)m * a.r + j0) = v;
   if (a.Xo)
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(a.Xo) + packed_chunk_offset(m, 1 + ch / 4, ch % 4, a.f_slabs)) = v;
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(a.Xo) + packed_chunk_offset(m, a.crit_slabs + ch / 4, ch % 4, a.f_slabs)) = v;
 }
 
 template <int kTiles>   // 16-wide tiles of the rank: ceil(r / 16)
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kLoraThreads) void k_lora_down(const LoraArgs a, in
     const int ch = item / a.N, n = item % a.N;
     v4u v = {0, 0, 0, 0};
     if (8 * ch < a.r) v = *reinterpret_cast<const v4u*>(a.B + (size_t)n * a.r + 8 * ch);
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(a.Wo) + packed_chunk_offset(n, 1 + ch / 4, ch % 4, a.f_slabs)) = v;
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(a.Wo) + packed_chunk_offset(n, a.crit_slabs + ch / 4, ch % 4, a.f_slabs)) = v;
     return;
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;

@@ -223,6 +223,43 @@ def test_every_gemm_tile_configuration(variant):
     check_linear(X, wl.gaussian_weight(4096, 512, 0.02, rng), 6.0, tuning=tune)
 
 
+def exactly_n_critical(rng, M, K, n_crit):
+    """Activations in (-5, 5) except `n_crit` columns (chosen at random, first and last column among them when
+    n_crit >= 2) that hold one entry above tau = 6 each, in different rows, and ordinary values otherwise."""
+    x = np.clip(rng.standard_normal((M, K)), -5.0, 5.0).astype(np.float32)
+    cols = rng.choice(np.arange(1, K - 1), max(0, n_crit - 2), replace=False) if n_crit >= 2 else \
+        rng.choice(K, n_crit, replace=False)
+    cols = np.sort(np.concatenate([cols, [0, K - 1]])) if n_crit >= 2 else cols
+    for j, k in enumerate(cols):
+        x[(7 * j) % M, k] = (-1.0) ** j * (8.0 + j % 50)
+    return wl.to_fp16(x), cols
+
+
+@pytest.mark.parametrize("variant", [4, 0, 2])
+@pytest.mark.parametrize("n_crit", [0, 1, 31, 32, 33, 64, 65, 100, 255, 256, 257, 300])
+def test_counts_of_critical_columns_around_the_slab_limits(n_crit, variant):
+    """The tiled GEMM takes critical columns 32 at a time as fp16 slabs, up to 256 of them, and gathers the rest:
+    counts on both sides of every border between those paths, over several row panels and a ragged tail."""
+    M, K, N = 600, 1040, 520
+    rng = np.random.default_rng([n_crit, variant])
+    X, cols = exactly_n_critical(rng, M, K, n_crit)
+    flag = ml.outlier_mask(X, 6.0)
+    assert np.array_equal(np.flatnonzero(flag), cols)
+    bias = wl.gaussian_bias(N, 0.1, rng) if n_crit % 2 else None
+    check_linear(X, wl.gaussian_weight(K, N, 0.05, rng), 6.0, bias=bias, tuning=binding.tune_gemm_tiles(variant))
+
+
+def test_moderate_share_of_critical_columns_full_size():
+    """A 7B-shaped projection at 2048 tokens with 3 % of its dimensions critical (123 columns: four slabs)."""
+    shape = wl.LLAMA_7B_LINEARS[0]
+    rng = np.random.default_rng(31)
+    X, _ = wl.gaussian_with_outlier_dims(2048, shape.K, 0.03, 8.0, 40.0, rng)
+    n = int(ml.outlier_mask(X, wl.TAU).sum())
+    assert 64 < n <= 256, n
+    rows = np.concatenate([np.arange(0, 300), np.arange(2048 - 130, 2048)])
+    check_linear(X, wl.prefill_weight(2, 77, shape, 0.02), wl.TAU, rows=rows)
+
+
 @pytest.mark.parametrize("shape", wl.VIT_L_LINEARS, ids=lambda s: s.name)
 def test_vit_shaped_linears_with_bias(shape):
     """ViT-L-shaped linears (width 1024, 4 images of 197 tokens: a ragged M) with a bias vector."""
