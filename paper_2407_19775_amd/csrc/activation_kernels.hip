@@ -383,6 +383,16 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
 // item 1: codes + per-block absmax, contiguous [M][K]).  The kernel decodes them first, exactly as
 // the decoder does (f16(T[code] * absmax), fp32 product, then round), writes the fp16 values to X
 // (which is then an output: the decoded hidden state, ldx = K) and carries on with them.
+//
+// Workgroups go to the eight XCDs in turn (workgroup b to XCD b % 8), each with an L2 of its own, and the 16-byte
+// pieces of 32 neighbouring rows are 512 contiguous bytes of the blocked codes: the eight row quads of such a
+// group are given to one XCD (workgroups b, b + 8, ..., b + 56, dispatched one after the other), so that its L2
+// sees whole 128-byte lines instead of halves that two XCDs write separately.
+__device__ inline int row_quad_of_block(int b, int n_blocks) {
+  if (b >= (n_blocks & ~63)) return b;                      // a last partial chunk of 64 keeps its order
+  return (b & ~63) | ((b & 7) << 3) | ((b >> 3) & 7);
+}
+
 template <int kWaves, int kPasses, bool kFromCodes>
 __global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ X, int M, int K, int ldx, uint32_t th,
                                                          int n_slabs, uint8_t* __restrict__ flag,
@@ -392,7 +402,7 @@ __global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ 
   __shared__ float s_T[kFromCodes ? 256 : 1];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int j = lane & 3, i = lane >> 2;
-  const int m = blockIdx.x * 4 + j;
+  const int m = row_quad_of_block(blockIdx.x, gridDim.x) * 4 + j;
   const bool row_ok = m < M;
   const int Kpad = n_slabs * kSlabBytes;
   const int n_pieces = Kpad / 16, k_pieces = K / 16;
