@@ -88,7 +88,7 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
   __shared__ __attribute__((aligned(16))) int8_t s_x[4][Cfg::STAGE_BYTES];
   __shared__ uint8_t s_any[Cfg::kMaxSlabs];
   __shared__ __attribute__((aligned(16))) uint16_t s_row[kPrep ? kPanelPrepMaxRowSlabs * kSlabBytes : 8];   // [M][cnt x 64]
-  __shared__ uint8_t s_crit[kPrep ? kPanelPrepMaxSlabs * kSlabBytes : 8];                                    // [cnt x 64]
+  __shared__ __attribute__((aligned(16))) uint8_t s_crit[kPrep ? kPanelPrepMaxSlabs * kSlabBytes : 16];                                    // [cnt x 64]
   __shared__ uint32_t s_part[kPanelPrepMaxM][WAVES];
   __shared__ float s_r[kPanelPrepMaxM], s_scale[kPanelPrepMaxM];
   const int lane = threadIdx.x & (kWave - 1);
@@ -142,7 +142,6 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
       *reinterpret_cast<uint16_t*>(&s_x[stage][Cfg::XQ_BYTES + (2 * ks + (col >> 3)) * 1024 + (32 * g + m) * 16 +
                                                (col & 7) * 2]) = crit ? (uint16_t)x : (uint16_t)0;
     }
-    if (crit) s_any[j] = 1;
   };
   auto park_x = [&](int stage, const v4i (&xr)[Cfg::kFetch], int j) {   // j: the slab these pieces belong to
     if constexpr (kPrep) {
@@ -206,24 +205,31 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
   };
 
   // Software pipeline (past the end the requests repeat the last slab: L2 hits, uniform loop body).
-  // In iteration j: request the activation pieces and the weights of slab j + 3; read the fragments
+  // In iteration j: request the activation pieces of slab j + 5 and the weights of slab j + 3; read the fragments
   // of slab j + 1 from LDS (they overlap the MFMAs of slab j, whose fragments were read an iteration
-  // ago); park the pieces of slab j + 2 (requested an iteration ago) in the buffer that slab j - 1
+  // ago); park the pieces of slab j + 2 (requested three iterations ago) in the buffer that slab j - 1
   // used (a ring of four, so that every index is static in a loop unrolled four times); barrier.
   const int last = cnt - 1;
   W2 f[4];
-  v4i xr[2][Cfg::kFetch];
+  // Activation pieces on their way from L2 to LDS: slab s >= 1 travels in xr[s % 4] (slab 0 in x0), requested three
+  // iterations before it is parked (the pieces were written by another kernel, possibly through another XCD's
+  // L2; four registers per set).
+  v4i x0[Cfg::kFetch], xr[4][Cfg::kFetch];
   Frags fr[2];
-  fetch_x(0, xr[0]);
+  // (requests in the order the loop issues them, so that what the compiler counts as in flight on entry to the
+  // loop is what it counts when coming round)
+  fetch_x(0, x0);
   fetch_x(min(1, last), xr[1]);
+  fetch_x(min(2, last), xr[2]);
   fetch_w(0, f[0]);
+  fetch_x(min(3, last), xr[3]);
   fetch_w(min(1, last), f[1]);
+  fetch_x(min(4, last), xr[0]);
   fetch_w(min(2, last), f[2]);
   if constexpr (kPrep) {
     // (the weight requests above are in flight meanwhile)
     for (int i = threadIdx.x; i < 4 * Cfg::STAGE_BYTES / 16; i += Cfg::kThreads)
       reinterpret_cast<v4u*>(&s_x[0][0])[i] = v4u{0, 0, 0, 0};
-    for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) s_any[t] = 0;
     const us2 th2 = __builtin_bit_cast(us2, a.th | (a.th << 16));
     // rows innermost, so that the loads of all rows are in flight together
     us2 best[kPanelPrepMaxM];
@@ -279,28 +285,47 @@ __global__ __launch_bounds__(Cfg::kThreads, 2) void k_gemm_panel(const SkinnyArg
       s_scale[threadIdx.x] = (r == 0.0f) ? 0.0f : 127.0f / r;       // IEEE division
     }
     __syncthreads();
-  }
-  park_x(0, xr[0], 0);
-  park_x(1, xr[1], min(1, last));
-  fetch_x(min(2, last), xr[1]);                                    // parked in iteration 0
-  __syncthreads();
-  bool any_next = s_any[0];
-  read_frags(0, any_next, fr[0]);
-  for (int j0 = 0; j0 < cnt; j0 += 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + u;
-      if (j >= cnt) break;
-      const bool any_cur = any_next;
-      any_next = s_any[min(j + 1, last)];
-      fetch_x(min(j + 3, last), xr[u & 1]);
-      fetch_w(min(j + 3, last), f[(u + 3) & 3]);
-      read_frags((u + 1) & 3, any_next, fr[(u + 1) & 1]);
-      multiply(any_cur, fr[u & 1], f[u & 3]);
-      park_x((u + 2) & 3, xr[(u + 1) & 1], min(j + 2, last));
-      __syncthreads();
+    for (int t = threadIdx.x; t < cnt; t += Cfg::kThreads) {         // "slab t holds a critical column"
+      const v4u* fl = reinterpret_cast<const v4u*>(&s_crit[t * kSlabBytes]);
+      const v4u m = fl[0] | fl[1] | fl[2] | fl[3];
+      s_any[t] = (m[0] | m[1] | m[2] | m[3]) != 0;
     }
   }
+  park_x(0, x0, 0);
+  park_x(1, xr[1], min(1, last));
+  __syncthreads();
+  // The flags of the next 64 slabs as one scalar mask (bit i: slab base + i, the last slab repeated past the end),
+  // refilled every 64 iterations: no LDS read and no vector compare between a slab's fragments and its MFMAs.
+  uint64_t any_mask = __builtin_amdgcn_ballot_w64(s_any[min(lane, last)] != 0);
+  bool any_next = any_mask & 1u;
+  read_frags(0, any_next, fr[0]);
+  auto iteration = [&](int j, auto u_tag) {
+    constexpr int u = decltype(u_tag)::value;                        // j % 4
+    const bool any_cur = any_next;
+    if constexpr (u == 3) {                                          // 64 is a multiple of four: only here can j + 1 start a window
+      if (((j + 1) & 63) == 0) any_mask = __builtin_amdgcn_ballot_w64(s_any[min(j + 1 + lane, last)] != 0);
+    }
+    any_next = (any_mask >> ((j + 1) & 63)) & 1u;
+    fetch_x(min(j + 5, last), xr[(u + 1) & 3]);
+    fetch_w(min(j + 3, last), f[(u + 3) & 3]);
+    read_frags((u + 1) & 3, any_next, fr[(u + 1) & 1]);
+    multiply(any_cur, fr[u & 1], f[u & 3]);
+    park_x((u + 2) & 3, xr[(u + 2) & 3], min(j + 2, last));
+    __syncthreads();
+  };
+  // Whole groups of four iterations run without a way out in between: with an exit after every iteration the
+  // compiler's count of the requests still in flight is merged over all those paths, and it then waits for
+  // weights requested one iteration earlier instead of three (every iteration took a whole memory latency).
+  int j0 = 0;
+  for (; j0 + 4 <= cnt; j0 += 4) {
+    iteration(j0, std::integral_constant<int, 0>{});
+    iteration(j0 + 1, std::integral_constant<int, 1>{});
+    iteration(j0 + 2, std::integral_constant<int, 2>{});
+    iteration(j0 + 3, std::integral_constant<int, 3>{});
+  }
+  if (j0 < cnt) iteration(j0, std::integral_constant<int, 0>{});
+  if (j0 + 1 < cnt) iteration(j0 + 1, std::integral_constant<int, 1>{});
+  if (j0 + 2 < cnt) iteration(j0 + 2, std::integral_constant<int, 2>{});
 
   // ---- outputs.  C layout of the 32x32 MFMA: lane = column n (lane % 32), register e = row
   // 8 (e / 4) + 4 (lane / 32) + (e % 4).
@@ -655,53 +680,70 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   const int row = row_live ? lr : 0;                                  // lanes beyond M read row 0 and feed zeros
   const int8_t* my_code = s_code + (size_t)row * Kpad + lg * 16;
   const uint16_t* my_xf = s_xf + (size_t)row * Kpad + lg * 16;
-  for (int i0 = 0; i0 < mine; i0 += kAhead) {
+  // "slab holds a critical column" for this wave's next 64 slabs as one scalar mask (a flag read from LDS when it
+  // is needed would stand between the slab's arrival and its MFMAs)
+  uint64_t any_mask = 0;
+  // this wave's i-th slab: multiply what was requested kAhead slabs ago, then request slab i + kAhead into the
+  // registers just used
+  auto step = [&](int i, auto u_tag) {
+    constexpr int u = decltype(u_tag)::value;                        // i % kAhead
+    const W2& w = f[u];
+    const int slab = wave + WAVES * i;
+    if constexpr (u == 0) {                                          // 64 is a multiple of kAhead: only here can i start a window
+      if ((i & 63) == 0) any_mask = __builtin_amdgcn_ballot_w64(s_any[wave + WAVES * min(i + lane, max(mine - 1, 0))] != 0);
+    }
+    const bool any = (any_mask >> (i & 63)) & 1u;                    // the same for the whole wave
+    if constexpr (kCols == 32) {
+      // lane group lg of k-step ks holds columns 32 ks + 16 lg .. + 16 of the slab
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) {
-      const int i = i0 + u;
-      if (i >= mine) break;
-      const W2 w = f[u];
-      fetch_w(i + kAhead, f[u]);
-      const int slab = wave + WAVES * i;
-      const bool any = s_any[slab] != 0;                              // the same for the whole wave
-      if constexpr (kCols == 32) {
-        // lane group lg of k-step ks holds columns 32 ks + 16 lg .. + 16 of the slab
+      for (int ks = 0; ks < 2; ++ks) {
+        v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes + ks * 32);
+        if (!row_live) xa = v4i{0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa, w.w[ks], acc, 0, 0, 0);
+      }
+      if (any) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-          v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes + ks * 32);
-          if (!row_live) xa = v4i{0, 0, 0, 0};
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa, w.w[ks], acc, 0, 0, 0);
-        }
-        if (any) {
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks) {
-            const v4u wu = __builtin_bit_cast(v4u, w.w[ks]) ^ 0x80808080u;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-              v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + ks * 32 + t * 8);
-              if (!row_live) xr = v4u{0, 0, 0, 0};
-              accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
-            }
-          }
-        }
-      } else {
-        // lane group lg (0..3) holds columns 16 lg .. + 16 of the slab; the two fp16 instructions take the two
-        // halves of every lane group's piece (any split of the 64 columns does, as long as both operands agree)
-        v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes);
-        if (!row_live) xa = v4i{0, 0, 0, 0};
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w.w[0], acc, 0, 0, 0);
-        if (any) {
-          const v4u wu = __builtin_bit_cast(v4u, w.w[0]) ^ 0x80808080u;
+          const v4u wu = __builtin_bit_cast(v4u, w.w[ks]) ^ 0x80808080u;
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + t * 8);
+            v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + ks * 32 + t * 8);
             if (!row_live) xr = v4u{0, 0, 0, 0};
-            accf = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
+            accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
           }
         }
       }
+    } else {
+      // lane group lg (0..3) holds columns 16 lg .. + 16 of the slab; the two fp16 instructions take the two
+      // halves of every lane group's piece (any split of the 64 columns does, as long as both operands agree)
+      v4i xa = *reinterpret_cast<const v4i*>(my_code + slab * kSlabBytes);
+      if (!row_live) xa = v4i{0, 0, 0, 0};
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w.w[0], acc, 0, 0, 0);
+      if (any) {
+        const v4u wu = __builtin_bit_cast(v4u, w.w[0]) ^ 0x80808080u;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          v4u xr = *reinterpret_cast<const v4u*>(my_xf + slab * kSlabBytes + t * 8);
+          if (!row_live) xr = v4u{0, 0, 0, 0};
+          accf = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, xr), codes_to_half8(wu, t), accf, 0, 0, 0);
+        }
+      }
     }
+    fetch_w(i + kAhead, f[u]);
+  };
+  // Whole groups of kAhead slabs run without a way out in between (with an exit after every slab the compiler
+  // waited for every request in flight at the end of each group, emptying the queue of weights four slabs deep).
+  static_assert(kAhead == 4, "the groups below are written out");
+  int i0 = 0;
+  for (; i0 + kAhead <= mine; i0 += kAhead) {
+    step(i0, std::integral_constant<int, 0>{});
+    step(i0 + 1, std::integral_constant<int, 1>{});
+    step(i0 + 2, std::integral_constant<int, 2>{});
+    step(i0 + 3, std::integral_constant<int, 3>{});
   }
+  if (i0 < mine) step(i0, std::integral_constant<int, 0>{});
+  if (i0 + 1 < mine) step(i0 + 1, std::integral_constant<int, 1>{});
+  if (i0 + 2 < mine) step(i0 + 2, std::integral_constant<int, 2>{});
 
   // ---- the eight partial results.  C layout of both MFMA shapes: lane = column (lane % kCols); row m < 4 is
   // register m of the first kCols lanes
