@@ -24,11 +24,14 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per GEMM launch of the 7B-shaped step (mean over the five launches of a decoder layer) from rocprofv3
-# FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size (profiles/gemm_llama7b_prefill_hbm_traffic.txt).
-# Valid for the GEMM source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 200.0e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "99b6dffbde06008ff7fea89490783a3113f389fdbbe2116e245f541079ff32a1"
+# HBM bytes per GEMM launch (mean over the five launches of a decoder layer) from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for kernels of known traffic in the same runs
+# (profiles/gemm_llama70b_prefill_counters.txt, profiles/gemm_llama7b_prefill_counters.txt): the timed step
+# (70B-shaped layer, 4096 tokens) and the 7B-shaped step.  Valid for the GEMM source they were measured on:
+# reported as null once that file has changed.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 183.6e6
+GEMM_TRAFFIC_SOURCE_SHA256 = "ecc0389df8f8f8865d71870c5893c326f365893729717b624650215204a6ba7c"
 
 
 def parse():
@@ -74,20 +77,20 @@ class HipEvents:
         return ms.value
 
 
-def gemm_traffic():
+def gemm_traffic(value=None):
     import hashlib
     src = os.path.join(ROOT, "paper_2407_19775_amd", "csrc", "gemm_kernels.hip")
     try:
         same = hashlib.sha256(open(src, "rb").read()).hexdigest() == GEMM_TRAFFIC_SOURCE_SHA256
     except OSError:
         same = False
-    return GEMM_TRAFFIC_BYTES_PER_LAUNCH if same else None
+    return (GEMM_TRAFFIC_BYTES_PER_LAUNCH if value is None else value) if same else None
 
 
 def cpu_baseline(sample, hidden, block):
-    """The CPU oracle, as it stands, on a bounded sample of the step: three of the layer's four linears at full
-    size (all 4096 tokens) plus one codec round trip of the [4096, 8192] hidden state with the step's block size.
-    sample: list of (name, X, W) host arrays."""
+    """The CPU oracle, as it stands, on one step's worth of work: the layer's four linears at full size (all 4096
+    tokens) plus one codec round trip of the [4096, 8192] hidden state with the step's block size (10-15 s on 16
+    cores).  sample: list of (name, X, W) host arrays."""
     from oracle import blockwise_codec as bc
     from oracle import mixed_linear as ml
     from paper_2407_19775_amd import workloads as wl
@@ -192,8 +195,8 @@ def main():
             W = torch.from_numpy(Wh).to(dev)
             w5.append(binding.prequantize_weight(W))
             del W
-            if shp.name != "gate_up" and not args.no_cpu_baseline:
-                cpu_sample.append((shp.name, X5h[shp.K], Wh))          # the oracle's sample: three of the four linears
+            if not args.no_cpu_baseline:
+                cpu_sample.append((shp.name, X5h[shp.K], Wh))          # the oracle's sample: the step's own tensors
             del Wh
         hidden_host = X5h[8192]
         Y5 = {s.name: torch.empty((M5, s.N), dtype=torch.float16, device=dev) for s in shapes5}
@@ -242,9 +245,9 @@ def main():
                                    "entry and encoded on exit, block %d" % block,
                        "tokens": M5, "layers": 1, "codec_block": block},
             "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
-            "roofline": {"bound": "mfma", "kernel": "k_gemm_mixed (int8 MFMA GEMM + fused epilogue), the step's four launches",
+            "roofline": {"bound": "mfma", "kernel": "k_gemm_mixed (int8 MFMA GEMM + fused epilogue), the step's five launches (four linears; the 8192->10240 one takes two)",
                          "achieved": round(gemm_tops5, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                         "frac": round(gemm_tops5 / INT8_PEAK_TOPS, 4), "traffic": None},
+                         "frac": round(gemm_tops5 / INT8_PEAK_TOPS, 4), "traffic": gemm_traffic()},
             "per_linear": per5,
             "codec": {"step_tensor": {"quantize_gbs": round(cb5 / q5 / 1e6, 1), "dequantize_gbs": round(cb5 / d5 / 1e6, 1),
                                       "elements": nel5, "block": block,
@@ -318,7 +321,7 @@ def main():
             "ms_per_step": round(ms7, 4), "steps": args.steps, "value_tops": round(ops7 / (ms7 * 1e-3) / 1e12, 2),
             "pct_int8_peak": round(100.0 * ops7 / (ms7 * 1e-3) / 1e12 / INT8_PEAK_TOPS, 2),
             "gemm_tops": round(gemm_tops7, 2), "gemm_frac_of_int8_peak": round(gemm_tops7 / INT8_PEAK_TOPS, 4),
-            "gemm_traffic_bytes_per_launch": gemm_traffic(), "per_linear": per7}
+            "gemm_traffic_bytes_per_launch": gemm_traffic(GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B), "per_linear": per7}
     dev_events = he.quad()
     genv = torch.Generator(device=dev)               # device-drawn tensors of the smaller sections
     genv.manual_seed(7)
