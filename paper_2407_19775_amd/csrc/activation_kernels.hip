@@ -160,10 +160,11 @@ constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (
 // cheaper than a serial step between two kernels).  The first kOutlierSlab indices and the count
 // land in LDS; the workgroup with `publish` also writes the list, the count, the byte mask and
 // the taps to global memory.  Each thread owns a contiguous run of 16-column units.
-__device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag, int K, int Kpad, const PackOutliers& o,
-                                                bool publish, int* s_idx /*[kOutlierSlab * kCriticalSlabs]*/, int* s_n_out,
-                                                int* s_wave_total /*[kThreads / kWave]*/) {
-  constexpr int kMaxUnits = MMD8_MAX_K / 16 / kThreads;            // 16
+template <int kMaxUnits>   // units a thread may own: ceil(Kpad / 16 / kThreads) at most
+__device__ __forceinline__ void compact_critical_columns_n(const uint8_t* __restrict__ flag, int K, int Kpad,
+                                                           const PackOutliers& o, bool publish,
+                                                           int* s_idx /*[kOutlierSlab * kCriticalSlabs]*/, int* s_n_out,
+                                                           int* s_wave_total /*[kThreads / kWave]*/) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int units = Kpad / 16;
   const int per = ceil_div(units, kThreads);
@@ -221,6 +222,17 @@ __device__ inline void compact_critical_columns(const uint8_t* __restrict__ flag
     }
   }
   __syncthreads();
+}
+
+// (a thread's loads are all issued whether it owns that many units or not, so the count is a template argument)
+__device__ __forceinline__ void compact_critical_columns(const uint8_t* __restrict__ flag, int K, int Kpad,
+                                                         const PackOutliers& o, bool publish, int* s_idx, int* s_n_out,
+                                                         int* s_wave_total) {
+  static_assert(MMD8_MAX_K / 16 / kThreads == 16, "largest number of units per thread");
+  const int per = ceil_div(Kpad / 16, kThreads);
+  if (per <= 2) compact_critical_columns_n<2>(flag, K, Kpad, o, publish, s_idx, s_n_out, s_wave_total);
+  else if (per <= 8) compact_critical_columns_n<8>(flag, K, Kpad, o, publish, s_idx, s_n_out, s_wave_total);
+  else compact_critical_columns_n<16>(flag, K, Kpad, o, publish, s_idx, s_n_out, s_wave_total);
 }
 
 // Rows of the critical-column slabs, 8 columns (16 bytes) per thread and slab: Xo[m][j] = X[m, O_j] for
