@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
 HBM_PEAK_GBS = 8000.0
+# What the matrix pipes alone sustain on this kind of data within the package power limit: a register-only
+# v_mfma_i32_32x32x32_i8 loop on Gaussian int8 codes, eight waves per CU (profiles/mfma_i8_power_ceiling.txt).
+INT8_POWER_LIMITED_TOPS = 3468.0
 # HBM bytes per GEMM launch (mean over the five launches of a decoder layer) from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for kernels of known traffic in the same runs
 # (profiles/gemm_llama70b_prefill_counters.txt, profiles/gemm_llama7b_prefill_counters.txt): the timed step
@@ -247,7 +250,12 @@ def main():
             "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
             "roofline": {"bound": "mfma", "kernel": "k_gemm_mixed (int8 MFMA GEMM + fused epilogue), the step's five launches (four linears; the 8192->10240 one takes two)",
                          "achieved": round(gemm_tops5, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                         "frac": round(gemm_tops5 / INT8_PEAK_TOPS, 4), "traffic": gemm_traffic()},
+                         "frac": round(gemm_tops5 / INT8_PEAK_TOPS, 4), "traffic": gemm_traffic(),
+                         "power_limited_ceiling": {"value": INT8_POWER_LIMITED_TOPS, "unit": "TOP/s",
+                                                   "frac": round(gemm_tops5 / INT8_POWER_LIMITED_TOPS, 4),
+                                                   "what": "register-only MFMA loop on Gaussian int8 codes under the "
+                                                           "package power limit (no data movement); context next to "
+                                                           "the nominal peak, which is what frac is quoted against"}},
             "per_linear": per5,
             "codec": {"step_tensor": {"quantize_gbs": round(cb5 / q5 / 1e6, 1), "dequantize_gbs": round(cb5 / d5 / 1e6, 1),
                                       "elements": nel5, "block": block,
