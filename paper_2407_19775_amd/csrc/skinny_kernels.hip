@@ -24,6 +24,7 @@
 // term), far inside the tolerance of the fp16 output.  A slab without a critical column skips the
 // 16-bit part (the same decision for the whole workgroup).
 #include <type_traits>
+#include <utility>
 
 #include <atomic>
 
@@ -546,10 +547,11 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
 // another order) when 32 would leave compute units without a workgroup (N up to 8192 on 256 of them).  (Two groups
 // per workgroup, for shapes with more groups than the chip holds workgroups at once, was slower: the registers then
 // allow a prefetch of only two slabs, and the 4096 -> 22016 linear took 29.9 us instead of 21.6.)
+constexpr int kRowsAhead = 4;   // weight slabs a wave has requested ahead of the one it multiplies (2 KB each); 8: slower (registers: 4 instead of 7 waves per SIMD; a 7B layer at one token 64 us instead of 56)
 template <bool kTap, int kCols>
 __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   static_assert(kCols == 32 || kCols == 16, "one group of 32 weight rows, or half of one");
-  constexpr int WAVES = 8, kThreads = WAVES * kWave, kAhead = 4;
+  constexpr int WAVES = 8, kThreads = WAVES * kWave, kAhead = kRowsAhead;
   constexpr int kPieces = kCols == 32 ? 2 : 1;                       // 16-byte weight pieces per lane and slab
   extern __shared__ __attribute__((aligned(16))) int8_t s_ops[];     // [M][Kpad] codes, then [M][Kpad] fp16
   __shared__ uint8_t s_any[MMD8_MAX_K / kSlabBytes];
@@ -685,7 +687,7 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   uint64_t any_mask = 0;
   // this wave's i-th slab: multiply what was requested kAhead slabs ago, then request slab i + kAhead into the
   // registers just used
-  auto step = [&](int i, auto u_tag) {
+  auto step = [&](int i, auto u_tag) __attribute__((always_inline)) {
     constexpr int u = decltype(u_tag)::value;                        // i % kAhead
     const W2& w = f[u];
     const int slab = wave + WAVES * i;
@@ -733,17 +735,16 @@ __global__ __launch_bounds__(512, 4) void k_gemm_rows(const SkinnyArgs a) {
   };
   // Whole groups of kAhead slabs run without a way out in between (with an exit after every slab the compiler
   // waited for every request in flight at the end of each group, emptying the queue of weights four slabs deep).
-  static_assert(kAhead == 4, "the groups below are written out");
+  static_assert(64 % kAhead == 0, "a window of slab flags starts at the head of a group");
+  auto group = [&]<int... kU>(int i0, std::integer_sequence<int, kU...>) __attribute__((always_inline)) {
+    (step(i0 + kU, std::integral_constant<int, kU>{}), ...);
+  };
+  auto tail = [&]<int... kU>(int i0, std::integer_sequence<int, kU...>) __attribute__((always_inline)) {
+    (void)((i0 + kU < mine ? (step(i0 + kU, std::integral_constant<int, kU>{}), true) : false) && ...);
+  };
   int i0 = 0;
-  for (; i0 + kAhead <= mine; i0 += kAhead) {
-    step(i0, std::integral_constant<int, 0>{});
-    step(i0 + 1, std::integral_constant<int, 1>{});
-    step(i0 + 2, std::integral_constant<int, 2>{});
-    step(i0 + 3, std::integral_constant<int, 3>{});
-  }
-  if (i0 < mine) step(i0, std::integral_constant<int, 0>{});
-  if (i0 + 1 < mine) step(i0 + 1, std::integral_constant<int, 1>{});
-  if (i0 + 2 < mine) step(i0 + 2, std::integral_constant<int, 2>{});
+  for (; i0 + kAhead <= mine; i0 += kAhead) group(i0, std::make_integer_sequence<int, kAhead>{});
+  tail(i0, std::make_integer_sequence<int, kAhead - 1>{});
 
   // ---- the eight partial results.  C layout of both MFMA shapes: lane = column (lane % kCols); row m < 4 is
   // register m of the first kCols lanes
