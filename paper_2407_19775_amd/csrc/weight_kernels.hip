@@ -65,9 +65,14 @@ __device__ inline uint32_t weight_code(float w, float scale) {
 __global__ __launch_bounds__(256) void k_weight_quant_pack(const uint16_t* __restrict__ W, int K, int N, int ldw,
                                                            const float* __restrict__ c,
                                                            int8_t* __restrict__ Wt, int n_slabs) {
-  __shared__ uint8_t s_tile[kTileN][kTileK + 16];
+  // the transposed tile: row n holds its 128 codes as eight 16-byte chunks, chunk q stored at place q ^ (n / 8).
+  // A thread has the codes of 8 columns n for 4 neighbouring k: one dword per column.  The 8 column groups of a
+  // wave are 8 rows apart, which is a whole number of bank cycles for any 16-byte aligned row length, so
+  // without the exchange of chunks they would all write to the same banks.
+  constexpr int kRowBytes = kTileK + 16;
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kTileN][kRowBytes];
   const int kt0 = blockIdx.x * kTileK, nt0 = blockIdx.y * kTileN;
-  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;          // 8 column groups x 32 row lanes
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;          // 8 column groups x 32 groups of 4 rows (k)
   const int n0 = nt0 + cg * 8;
   float scale[8];
 #pragma unroll
@@ -75,24 +80,35 @@ __global__ __launch_bounds__(256) void k_weight_quant_pack(const uint16_t* __res
     const float cn = (n0 + t < N) ? c[n0 + t] : 0.0f;
     scale[t] = (cn == 0.0f) ? 0.0f : 127.0f / cn;                  // IEEE division
   }
+  v4u raw[4];
 #pragma unroll
-  for (int pass = 0; pass < kTileK / 32; ++pass) {
-    const int kl = pass * 32 + rl, k = kt0 + kl;
-    v4u raw = v4u{0, 0, 0, 0};
-    if (k < K && n0 < N) raw = *reinterpret_cast<const v4u*>(W + (size_t)k * ldw + n0);
+  for (int i = 0; i < 4; ++i) {
+    const int k = kt0 + 4 * rl + i;
+    // unconditional loads (all four in flight together); rows and columns outside W re-read its first element
+    // and are masked
+    const bool ok = k < K && n0 < N;
+    raw[i] = *reinterpret_cast<const v4u*>(W + (ok ? (size_t)k * ldw + n0 : (size_t)0));
+    if (!ok) raw[i] = v4u{0, 0, 0, 0};
+  }
+  uint32_t col[8] = {0, 0, 0, 0, 0, 0, 0, 0};                       // column t: the codes of k .. k + 3, lowest byte first
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      s_tile[cg * 8 + 2 * w][kl] = (uint8_t)weight_code(half_lo_to_float(raw[w]), scale[2 * w]);
-      s_tile[cg * 8 + 2 * w + 1][kl] = (uint8_t)weight_code(half_hi_to_float(raw[w]), scale[2 * w + 1]);
+      col[2 * w] |= weight_code(half_lo_to_float(raw[i][w]), scale[2 * w]) << (8 * i);
+      col[2 * w + 1] |= weight_code(half_hi_to_float(raw[i][w]), scale[2 * w + 1]) << (8 * i);
     }
-  }
+  // dword rl of the row = chunk rl / 4, dword rl % 4 inside it
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+    *reinterpret_cast<uint32_t*>(&s_tile[cg * 8 + t][(((rl >> 2) ^ cg) << 4) + ((rl & 3) << 2)]) = col[t];
   __syncthreads();
   // one 64-byte slab of the 64 rows per pass: 4 KB contiguous in the packed layout
   static_assert(kTileK / kSlabBytes == 2 && kTileN * (kSlabBytes / 16) == 256, "write-out mapping");
 #pragma unroll
   for (int pass = 0; pass < kTileK / kSlabBytes; ++pass) {
     const int nl = threadIdx.x >> 2, ch = threadIdx.x & 3;
-    const v4u v = *reinterpret_cast<const v4u*>(&s_tile[nl][pass * kSlabBytes + ch * 16]);
+    const v4u v = *reinterpret_cast<const v4u*>(&s_tile[nl][((pass * 4 + ch) ^ (nl >> 3)) << 4]);
     *reinterpret_cast<v4u*>(Wt + packed_chunk_offset(nt0 + nl, kt0 / kSlabBytes + pass, ch, n_slabs)) = v;
   }
 }
