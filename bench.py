@@ -213,18 +213,21 @@ def main():
         absmax_out5 = torch.empty((M5 * last5.N + block - 1) // block, dtype=torch.float32, device=dev)
         torch.cuda.synchronize()
 
+        def linear5(i, ev=None):
+            shp = shapes5[i]
+            if i == len(shapes5) - 1:
+                # the last linear adds the residual stream (the decoded incoming hidden state) and encodes
+                binding.mixed_int8_linear_to_codes(X5[shp.K], w5[i], wl.TAU, block, residual=hidden5, codes=codes_out5,
+                                                   absmax=absmax_out5, workspace=ws5_exit, events=ev, tuning=tune)
+            else:
+                # the first linear takes the coded hidden state and decodes it
+                binding.mixed_int8_linear(hidden5 if i == 0 else X5[shp.K], w5[i], wl.TAU, out=Y5[shp.name],
+                                          workspace=ws5, events=ev, tuning=tune,
+                                          coded=(codes_in5, absmax_in5, block) if i == 0 else None)
+
         def step5(events=None):
-            for i, shp in enumerate(shapes5):
-                ev = events[i] if events else None
-                if i == len(shapes5) - 1:
-                    # the last linear adds the residual stream (the decoded incoming hidden state) and encodes
-                    binding.mixed_int8_linear_to_codes(X5[shp.K], w5[i], wl.TAU, block, residual=hidden5, codes=codes_out5,
-                                                       absmax=absmax_out5, workspace=ws5_exit, events=ev, tuning=tune)
-                else:
-                    # the first linear takes the coded hidden state and decodes it
-                    binding.mixed_int8_linear(hidden5 if i == 0 else X5[shp.K], w5[i], wl.TAU, out=Y5[shp.name],
-                                              workspace=ws5, events=ev, tuning=tune,
-                                              coded=(codes_in5, absmax_in5, block) if i == 0 else None)
+            for i in range(len(shapes5)):
+                linear5(i, events[i] if events else None)
 
         ms_per_step = timed_wall(step5, args.steps, args.warmup, torch)
         ops5 = wl.linear_ops(M5, shapes5)
@@ -233,6 +236,14 @@ def main():
         prep5, prep15, gemm5 = events_pass(step5, evs5, max(3, min(10, args.steps)), he, torch)
         gemm_tops5 = sum(2.0 * M5 * s.K * s.N for s in shapes5) / (sum(gemm5) * 1e-3) / 1e12
         per5 = {s.name: linear_row(M5, s, gemm5[i], prep5[i], prep15[i]) for i, s in enumerate(shapes5)}
+        for i, s in enumerate(shapes5):
+            # the whole call, back to back, no events recorded inside it (each record costs a few microseconds
+            # between the kernels, which the prep_us / gemm_us split above includes)
+            t_call = timed(lambda: linear5(i), 10)
+            per5[s.name]["call_us"] = round(t_call * 1e3, 1)
+            per5[s.name]["call_tops"] = round(2.0 * M5 * s.K * s.N / t_call / 1e9, 1)
+            # what the preparation costs inside a call, where no event stands between the kernels
+            per5[s.name]["call_minus_gemm_us"] = round(t_call * 1e3 - gemm5[i] * 1e3, 1)
         nel5 = M5 * 8192
         cb5 = 3.0 * nel5 + 4.0 * nel5 / block
         q5 = timed(lambda: binding.quantize_blockwise(Y5["o"], block, codes=codes_out5, absmax=absmax_out5))
@@ -322,6 +333,18 @@ def main():
         for j, shp in enumerate(shapes):
             mean = lambda v: float(np.mean([v[l * len(shapes) + j] for l in range(args.layers)]))
             per7[shp.name] = linear_row(M, shp, mean(gemm_ms), mean(prep_ms), mean(prep1_ms))
+            # the whole (plain) call, back to back, the four layers' weights in turn, no events recorded inside it
+            turn7 = [0]
+
+            def call7():
+                turn7[0] = (turn7[0] + 1) % args.layers
+                binding.mixed_int8_linear(Xs[shp.K], weights[turn7[0]][j], wl.TAU, out=Ys[shp.name], workspace=workspace,
+                                          tuning=tune)
+
+            t_call = timed(call7, 12)
+            per7[shp.name]["call_us"] = round(t_call * 1e3, 1)
+            per7[shp.name]["call_tops"] = round(2.0 * M * shp.K * shp.N / t_call / 1e9, 1)
+            per7[shp.name]["call_minus_gemm_us"] = round(t_call * 1e3 - mean(gemm_ms) * 1e3, 1)
         out["llama7b_prefill"] = {
             "workload": "Llama-7B-shaped shard prefill: %d decoder layers x (QKV 4096->12288, O 4096->4096, gate/up 4096->22016, "
                         "down 11008->4096), 2048 tokens, tau 6.0, 0.1%% outlier dims; hidden state [2048,4096] decoded on entry "
