@@ -249,6 +249,20 @@ def test_counts_of_critical_columns_around_the_slab_limits(n_crit, variant):
     check_linear(X, wl.gaussian_weight(K, N, 0.05, rng), 6.0, bias=bias, tuning=binding.tune_gemm_tiles(variant))
 
 
+@pytest.mark.parametrize("variant", [4, 3, 0])
+@pytest.mark.parametrize("K", [16, 64, 128, 192, 320])
+@pytest.mark.parametrize("tau", [6.0, 0.0])
+def test_short_rows_in_the_tiled_gemm(K, tau, variant):
+    """Two to five slabs of codes: fewer than the ring holds ahead, so the first requests already reach into the fp16
+    slabs (tau = 0: every column critical, up to ten fp16 slabs behind two to five slabs of codes)."""
+    M, N = 300, 264
+    rng = np.random.default_rng([K, variant])
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, K // 2] *= 20.0
+    check_linear(wl.to_fp16(x), wl.gaussian_weight(K, N, 0.05, rng), tau, bias=wl.gaussian_bias(N, 0.1, rng),
+                 tuning=binding.tune_gemm_tiles(variant))
+
+
 def test_moderate_share_of_critical_columns_full_size():
     """A 7B-shaped projection at 2048 tokens with 3 % of its dimensions critical (123 columns: four slabs)."""
     shape = wl.LLAMA_7B_LINEARS[0]
