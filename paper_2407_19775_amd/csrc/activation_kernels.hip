@@ -634,7 +634,7 @@ hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* 
                        int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream) {
   const int n_slabs = Kpad / kSlabBytes;
   const int gx = ceil_div(n_slabs, kPackSlabs), pack_y = ceil_div(M, kPackRows);
-  // the slab of critical columns is for the tiled GEMM kernels; the decode kernel reads Xf instead
+  // the slabs of critical columns are for the tiled GEMM kernels; the decode kernel reads Xf instead
   // (one extra block still lists the critical columns)
   const int slab_items = Xf ? 0 : (M + o.N) * (kOutlierSlab / 8);
   const int slab_y = max(1, ceil_div(ceil_div(slab_items, kThreads), gx));

@@ -22,7 +22,7 @@ struct GemmArgs {
   int ldx;
   const int32_t* idx;    // ascending critical columns
   const int32_t* n_out;  // their count
-  const uint16_t* Xo;    // one slab of fp16 per row, blocked like the codes: X[m, O_j], zero for j >= n_out
+  const uint16_t* Xo;    // f_slabs slabs of fp16 per row, each blocked like a slab of codes: X[m, O_j], zero for j >= n_out
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   int f_slabs;           // fp16 slabs per panel in Xo / Wo: crit_slabs for the critical columns, then those of a low-rank
                          // adapter (at most 2), whose operands are multiplied in the same way

@@ -4,8 +4,8 @@
 
 namespace mmd8 {
 
-// Rank limit: the low-rank operands travel through the GEMM as fp16 slabs of 32 columns behind
-// the slab of critical columns, and the GEMM's request window covers three slabs past the codes.
+// The low-rank operands travel through the GEMM's slab ring as fp16 slabs of 32 columns behind the slabs of the
+// critical columns; the rank limit bounds the workspace (two slabs per row of both operands).
 constexpr int kLoraMaxRank = MMD8_MAX_LORA_RANK;
 __host__ __device__ constexpr inline int lora_slabs(int r) { return ceil_div(r, 32); }
 
@@ -17,7 +17,7 @@ struct LoraArgs {
   int r, N;
   uint16_t* T;           // [M][kLoraMaxRank] fp16, columns >= r zero: T = f16(X A^T)
   uint16_t* T_user;      // [M][r] or null
-  uint16_t* Xo;          // fp16 slabs of the GEMM's activation side (slab 0: critical columns), or null
+  uint16_t* Xo;          // fp16 slabs of the GEMM's activation side (slabs 0 .. crit_slabs - 1: critical columns), or null
   uint16_t* Wo;          // likewise, weight side
   int f_slabs;           // slabs per panel in Xo / Wo: crit_slabs + lora_slabs(r)
   int crit_slabs;        // slabs of the critical columns in front of the adapter's

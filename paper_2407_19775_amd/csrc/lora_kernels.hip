@@ -2,7 +2,7 @@
 // fine-tuning via adapters"): Y = (int8 layer)(X) + T B^T with T = f16(X A^T).
 //
 // k_lora_down computes T on the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulation, one
-// rounding to fp16) and lays T and B out as extra fp16 slabs behind the slab of critical columns,
+// rounding to fp16) and lays T and B out as extra fp16 slabs behind the slabs of the critical columns,
 // so that the GEMM kernel adds T B^T exactly as it adds the critical columns: more fp16 MFMAs onto
 // the dequantized accumulators.  For decode shapes T is kept as a plain matrix and the product
 // with B is added by the kernel that sums the split-K partial outputs.
