@@ -478,7 +478,7 @@ def main():
     if want("heavy"):
         # ---- more than 128 rows of heavy-tailed input (hundreds of critical columns): the tiled GEMM's 16-bit part
         heavy = {}
-        for Mh in (256,):
+        for Mh in (128, 256):                  # 128: the last size that still takes the decode kernels (two passes)
             Xh = {K: torch.from_numpy(wl.decode_activation(900 + Mh, Mh, K)).to(dev) for K in sorted({s.K for s in shapes})}
             Yh = {s.name: torch.empty((Mh, s.N), dtype=torch.float16, device=dev) for s in shapes}
             big_h = max(shapes, key=lambda s: binding.lib().mmd8_linear_workspace_bytes(Mh, s.K, s.N))
