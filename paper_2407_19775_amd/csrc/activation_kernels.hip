@@ -247,6 +247,7 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
                                            const PackOutliers& o, int item, const int* s_idx, int n_out_all) {
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8);
   if (row >= M + o.N) return;
+  if (dense_critical_path(n_out_all, o.crit_slabs, n_slabs, o.W_master != nullptr)) return;   // the GEMM reads no slab then
   const int n_out = min(n_out_all, kOutlierSlab * o.crit_slabs);
   const int used = max(1, ceil_div(n_out, kOutlierSlab));
   for (int slab = 0; slab < used; ++slab) gather_outlier_slab_one(X, M, ldx, n_slabs, o, row, ch, slab, s_idx, n_out);
@@ -554,7 +555,7 @@ __global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ 
 
 // After k_prep: the first `slab_blocks` workgroups list the critical columns (the first one
 // publishes the list, the count and the byte mask) and build the fp16 slab of the first
-// kOutlierSlab of them; in the remaining workgroups every wave owns 64 rows (lane = row) and
+// kOutlierSlab of them; each of the remaining workgroups owns 64 rows (lane = row) and 4096 columns and
 // clears the codes of the critical columns in those rows with byte stores of zero.  Driven by the
 // flags themselves, so any number of critical columns is handled the same way.
 __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __restrict__ X, int M, int K, int ldx,
@@ -570,14 +571,17 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
     gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
     return;
   }
+  // A clearing workgroup owns 64 rows (lane = row) and 256 units of 16 columns, 64 units per wave: lane l of a
+  // wave looks at unit u0 + l.  (With input whose columns are nearly all critical the clearing is the longest
+  // part of the preparation unless many waves share a row.)
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int m = (((int)blockIdx.x - slab_blocks) * (kThreads / kWave) + wave) * kWave + lane;
   const int units = Kpad / 16;
-  // lane l looks at unit u0 + l; the flags of the next 64 units are fetched while these are handled
-  v4u f = lane < units ? flags16(flag, 16 * lane) : v4u{0, 0, 0, 0};
-  for (int u0 = 0; u0 < units; u0 += kWave) {
-    const int u_next = u0 + kWave + lane;
-    const v4u f_next = u_next < units ? flags16(flag, 16 * u_next) : v4u{0, 0, 0, 0};
+  const int unit_groups = ceil_div(units, kThreads);
+  const int cb = (int)blockIdx.x - slab_blocks;
+  const int m = (cb / unit_groups) * kWave + lane;
+  const int u0 = (cb % unit_groups) * kThreads + wave * kWave;
+  {
+    const v4u f = u0 + lane < units ? flags16(flag, 16 * (u0 + lane)) : v4u{0, 0, 0, 0};
     uint64_t todo = __builtin_amdgcn_ballot_w64((f[0] | f[1] | f[2] | f[3]) != 0);
     while (todo) {
       const int t = __builtin_ctzll(todo);
@@ -601,7 +605,6 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
         }
       }
     }
-    f = f_next;
   }
 }
 
@@ -675,7 +678,7 @@ hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad
   if (e != hipSuccess) return e;
   if (event_mid && (e = hipEventRecord(static_cast<hipEvent_t>(event_mid), stream)) != hipSuccess) return e;
   const int slab_blocks = max(1, ceil_div((M + o.N) * (kOutlierSlab / 8), kThreads));
-  const int clear_blocks = ceil_div(M, kThreads);
+  const int clear_blocks = ceil_div(M, kWave) * ceil_div(n_slabs * (kSlabBytes / 16), kThreads);   // 64 rows x 4096 columns each
   hipLaunchKernelGGL(k_outlier_columns, dim3(slab_blocks + clear_blocks), dim3(kThreads), 0, stream, X, M, K, ldx, flag, Xq,
                      n_slabs, tap_xq, slab_blocks, o);
   return hipGetLastError();

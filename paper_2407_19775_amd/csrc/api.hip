@@ -482,6 +482,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.ldx = ldx;
     g.idx = ws.idx;
     g.n_out = ws.n_out;
+    g.mask = ws.mask;
     g.Xo = ws.xo;
     g.Wo = ws.wo;
     g.f_slabs = ws.f_slabs;

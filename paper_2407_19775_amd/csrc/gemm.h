@@ -5,11 +5,19 @@
 namespace mmd8 {
 
 // Critical columns handled on the fast path: they travel as extra 64-byte K-slabs of fp16 operands, 32 columns
-// each, prepared once per call by the pack kernels: the first slab rides through the GEMM's slab ring behind
-// the codes, up to kCriticalSlabs - 1 more follow it one by one.  Columns beyond 32 kCriticalSlabs go through
-// the gather loop of the epilogue (every tile gathers them again: much slower).
+// each, prepared once per call by the pack kernels; they ride through the GEMM's slab ring behind the codes.
+// Columns beyond 32 kCriticalSlabs (inputs where a large share of the dimensions is critical) are multiplied 64
+// at a time after the ring has drained: fp16 activations straight from X, weight codes converted in registers.
 constexpr int kOutlierSlab = 32;
 constexpr int kCriticalSlabs = 8;
+// Whether a call takes the dense path for its critical columns: more of them than the slabs hold, and at least eight
+// per 64-column slab of K on average (below that, gathering the columns beyond the slabs one by one is cheaper than
+// a pass over every slab: about 0.5 us per column against 3.7 us per slab on a 2048 x 4096 x 12288 call).  Then no fp16 slab is prepared or read at all.  The same decision in the kernel that
+// prepares the slabs and in the GEMM, from the count that both read; never with original 16-bit weight rows (the
+// dense path multiplies the weight codes).
+__host__ __device__ constexpr inline bool dense_critical_path(int n_out, int crit_slabs, int n_slabs, bool master_rows) {
+  return !master_rows && n_out > kOutlierSlab * crit_slabs && n_out >= 8 * n_slabs;
+}
 
 struct GemmArgs {
   const int8_t* Xq;      // activation codes, blocked layout (operand_layout.h), Mpad x Kpad
@@ -22,6 +30,7 @@ struct GemmArgs {
   int ldx;
   const int32_t* idx;    // ascending critical columns
   const int32_t* n_out;  // their count
+  const uint8_t* mask;   // [Kpad] 1 = critical column (the copy of the flags that the compaction publishes)
   const uint16_t* Xo;    // f_slabs slabs of fp16 per row, each blocked like a slab of codes: X[m, O_j], zero for j >= n_out
   const uint16_t* Wo;    // likewise: f16(Wt[n, O_j] c[n] / 127), zero for j >= n_out
   int f_slabs;           // fp16 slabs per panel in Xo / Wo: crit_slabs for the critical columns, then those of a low-rank

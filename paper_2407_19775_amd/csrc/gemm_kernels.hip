@@ -246,6 +246,131 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
   }
 }
 
+// All critical columns of an input where hundreds or thousands of feature dimensions are critical
+// (dense_critical_path: none of them travelled as an fp16 slab then): slab after slab of 64 columns.
+//   A side: the tile's rows of X itself (fp16, 128 contiguous bytes per row and slab), columns that are not
+//           critical set to zero, parked in LDS as rows of 144 bytes;
+//   B side: the slab of weight codes, fetched like in the main loop, the codes turned into fp16 integers in
+//           registers (codes_to_half8) as the decode kernels do.
+// The accumulators hold Y so far in fp32; sum_k X[m,k] q[n,k] lacks the column's step c[n] / 127, so they are
+// divided by it on entry and multiplied by it on exit (columns with c[n] = 0 have only zero codes: factor 1).
+// Against the slabs prepared by the pack kernel the weights are not rounded to fp16 after scaling: at most 2^-11
+// relative per term, as in the decode kernels.  Requests for the next slab (its rows of X into registers, its
+// codes into the other LDS buffer) are out while the current one is multiplied.
+template <class Cfg>
+__device__ __forceinline__ void dense_critical_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
+                                                       int8_t* smem, const float (&cs)[Cfg::TJ]) {
+  constexpr int TI = Cfg::TI, TJ = Cfg::TJ;
+  constexpr int TPR = Cfg::kThreads / Cfg::BM;                      // threads per row of the activation tile
+  static_assert(Cfg::kThreads % Cfg::BM == 0 && TPR >= 1 && TPR <= 8, "whole threads per row");
+  constexpr int CPT = BK / TPR, NL = CPT / 8;                        // columns per thread, 16-byte loads per thread
+  constexpr int kRowBytes = 2 * BK + 16;                             // 144: rows 8 apart share banks, not rows next to each other
+  constexpr int A_LDS = (Cfg::BM * kRowBytes + 1023) / 1024 * 1024;
+  static_assert(A_LDS + 2 * Cfg::B_BYTES <= Cfg::RING_BYTES, "the parked rows and two weight slabs fit where the ring was");
+  int8_t* sA = smem;
+  int8_t* sB = smem + A_LDS;
+  const int lane = p.lane, wm = p.wm, wn = p.wn;
+  const int wave = wm * Cfg::WAVES_N + wn;
+  const int n_slabs = a.Kpad / BK;
+  const int row = threadIdx.x / TPR, part = threadIdx.x % TPR;
+  const uint16_t* xrow = a.X + (size_t)min(p.m0 + row, a.M - 1) * a.ldx + part * CPT;
+
+  float back[TJ];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) {
+    const float step = cs[j] * 127.0f;                               // c[n] / 127
+    back[j] = step != 0.0f ? step : 1.0f;
+    const float inv = step != 0.0f ? 1.0f / step : 1.0f;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      v16f y = __builtin_bit_cast(v16f, acc[i][j]);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] *= inv;
+      acc[i][j] = __builtin_bit_cast(v16i, y);
+    }
+  }
+
+  auto load_a = [&](int s, v4u (&ra)[NL]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      // pieces beyond the row's end (the padding of K) re-read the row's first piece; none of their columns is critical
+      const int col = s * BK + part * CPT + 8 * q;
+      ra[q] = *reinterpret_cast<const v4u*>(xrow + (col < a.ldx ? col - part * CPT : -part * CPT));
+    }
+  };
+  const uint32_t ldsB = (uint32_t)(uintptr_t)sB + wave * (kWave * 16);
+  auto issue_b = [&](int s, int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < Cfg::B_DMA; ++j)
+      dma16(dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane) + (size_t)s * kBlockBytes,
+            ldsB + buf * Cfg::B_BYTES + j * Cfg::kWaves * (kWave * 16));
+  };
+
+  wait_lds_and_sync();                                               // every wave is done with the slab ring
+  uint64_t bits = __builtin_amdgcn_ballot_w64(a.mask[lane] != 0);    // bit c: column 64 s + c is critical
+  v4u ra[NL];
+  load_a(0, ra);
+  issue_b(0, 0);
+  for (int s = 0, buf = 0; s < n_slabs; ++s, buf ^= 1) {
+    // park the rows of slab s, critical columns only
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const uint32_t b8 = (uint32_t)(bits >> (part * CPT + 8 * q)) & 0xffu;
+      v4u v = ra[q];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        v[w] &= (((b8 >> (2 * w)) & 1u) ? 0x0000ffffu : 0u) | (((b8 >> (2 * w + 1)) & 1u) ? 0xffff0000u : 0u);
+      *reinterpret_cast<v4u*>(sA + row * kRowBytes + (part * CPT + 8 * q) * 2) = v;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");              // the codes of slab s have landed too
+    const uint64_t bits_now = bits;
+    uint8_t next_flag = 0;
+    if (s + 1 < n_slabs) {
+      next_flag = a.mask[(s + 1) * BK + lane];
+      load_a(s + 1, ra);
+      issue_b(s + 1, buf ^ 1);
+    }
+    wait_lds_and_sync();
+    if (bits_now != 0) {
+      const int8_t* fbase = sB + buf * Cfg::B_BYTES + (wn * Cfg::WN / 32) * 2048 + lane * 16;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        v4u wu[TJ];
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+          wu[j] = *reinterpret_cast<const v4u*>(fbase + j * 32 * BK + ks * 1024) ^ 0x80808080u;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          v8h xa[TI];
+#pragma unroll
+          for (int i = 0; i < TI; ++i)
+            xa[i] = *reinterpret_cast<const v8h*>(sA + (wm * Cfg::WM + i * 32 + (lane & 31)) * kRowBytes +
+                                                  (32 * ks + 16 * (lane >> 5) + 8 * t) * 2);
+#pragma unroll
+          for (int j = 0; j < TJ; ++j) {
+            const v8h wh = codes_to_half8(wu[j], t);
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+              acc[i][j] = __builtin_bit_cast(
+                  v16i, __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[i], wh, __builtin_bit_cast(v16f, acc[i][j]), 0, 0, 0));
+          }
+        }
+      }
+    }
+    wait_lds_and_sync();                                             // both buffers are read before they are written again
+    bits = __builtin_amdgcn_ballot_w64(next_flag != 0);
+  }
+#pragma unroll
+  for (int j = 0; j < TJ; ++j)
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      v16f y = __builtin_bit_cast(v16f, acc[i][j]);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] *= back[j];
+      acc[i][j] = __builtin_bit_cast(v16i, y);
+    }
+}
+
 // bias, rounding to fp16, and stores, through LDS (the slab buffers are free by now).  Neighbouring lanes hold
 // neighbouring columns of the same rows; an even/odd lane pair swaps halves so that each lane has two adjacent
 // columns (4 bytes): the even lane of row e, the odd lane of row e + 1.  A wave parks 64 (or 32) rows of its
@@ -418,8 +543,10 @@ __device__ __forceinline__ void load_column_terms(const GemmArgs& a, const WaveP
 // kCoded: the output goes through an activation, takes a residual and / or leaves in blockwise-coded form
 // (store_tile_coded).
 // ------------------------------------------------------------------------------------------------
-template <class Cfg, bool kTap, bool kFull, bool kCoded>
-__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
+// kDense: the critical columns are handled by dense_critical_columns after the loop instead of through fp16 slabs
+// and the gather (the kernel decides; the two cases are compiled apart, see k_gemm_mixed).
+template <class Cfg, bool kTap, bool kFull, bool kCoded, bool kDense>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& a) {
   extern __shared__ __attribute__((aligned(1024))) int8_t smem[];
   constexpr int TI = Cfg::TI, TJ = Cfg::TJ, NKS = Cfg::NKS, STAGES = Cfg::kStages;
 
@@ -434,7 +561,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   // Behind the slabs of codes, through the same ring: the fp16 slabs of the critical columns that are in use (32
   // columns each, at most crit_slabs of them; further columns are gathered after the loop) and those of a low-rank
   // adapter (T on the activation side, B on the weight side), which start at slab crit_slabs of Xo / Wo.
-  const int crit_used = min(a.crit_slabs, ceil_div(n_out, kOutlierSlab));
+  const int crit_used = kDense ? 0 : min(a.crit_slabs, ceil_div(n_out, kOutlierSlab));
   const int total_slabs = n_slabs + crit_used + (a.f_slabs - a.crit_slabs);
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
@@ -601,11 +728,40 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixe
   if (s < total_slabs) iteration(s, none{}, no{}, yes{});
   // every wave passed the last barrier after its last LDS read of the ring: the slab buffers are
   // free for the gather staging, which starts with a barrier of its own before writing them
-  if (n_out > kOutlierSlab * a.crit_slabs) gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab * a.crit_slabs, n_out);
+  if constexpr (kDense)
+    dense_critical_columns<Cfg>(a, p, acc, smem, cs);
+  else if (n_out > kOutlierSlab * a.crit_slabs)
+    gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab * a.crit_slabs, n_out);
   if constexpr (kCoded)
     store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
   else
     store_tile<Cfg, kFull>(a, p, acc, bn, smem, wave);
+}
+
+// The tile routine for input with very many critical columns, as a function of its own: the kernels sit at the edge
+// of their register budget, and with this rarely taken path compiled into the same body every one of them spilled
+// registers (up to 320; the gather of single columns next to it ran twice as long).  Its only argument is the
+// address of the kernel's own arguments where the launch put them (a function does not receive that address by
+// itself, and arguments arrive in vector registers: made uniform again here, so that the arguments are read into
+// scalar registers as in the kernel).
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
+__device__ __noinline__ void gemm_tile_dense(uint32_t args_lo, uint32_t args_hi) {
+  using constant_bytes = const __attribute__((address_space(4))) char*;
+  const uint64_t address = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)args_lo) |
+                           (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)args_hi) << 32;
+  const GemmArgs a = *(const GemmArgs*)(constant_bytes)address;
+  gemm_tile<Cfg, kTap, kFull, kCoded, true>(a);
+}
+
+template <class Cfg, bool kTap, bool kFull, bool kCoded>
+__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
+  const int n_out = __builtin_amdgcn_readfirstlane(*a.n_out);
+  if (dense_critical_path(n_out, a.crit_slabs, a.Kpad / BK, a.W_master != nullptr)) {
+    const uint64_t address = (uint64_t)(const char*)__builtin_amdgcn_kernarg_segment_ptr();   // `a` is the first argument
+    gemm_tile_dense<Cfg, kTap, kFull, kCoded>((uint32_t)address, (uint32_t)(address >> 32));
+    return;
+  }
+  gemm_tile<Cfg, kTap, kFull, kCoded, false>(a);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -35,24 +35,6 @@
 
 namespace mmd8 {
 
-// eight weight codes (bytes [8 t, 8 t + 8) of the lane's 16, already XORed with 0x80: u = q + 128)
-// -> the integers q as fp16.  The fp16 number 1024 + u has the bit pattern 0x6400 | u.
-__device__ inline v8h codes_to_half8(const v4u& wu, int t) {
-  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-  v4u out;
-#pragma unroll
-  for (int d = 0; d < 2; ++d) {
-    const uint32_t word = wu[2 * t + d];
-    // bytes of {0x64646464 : word}: selectors 0-3 = word bytes, 4-7 = 0x64
-    const uint32_t lo = __builtin_amdgcn_perm(0x64646464u, word, 0x04010400u);   // [b0, 0x64, b1, 0x64] little end first
-    const uint32_t hi = __builtin_amdgcn_perm(0x64646464u, word, 0x04030402u);   // [b2, 0x64, b3, 0x64]
-    const h2 bias = {(_Float16)1152.0f, (_Float16)1152.0f};
-    out[2 * d] = __builtin_bit_cast(uint32_t, (h2)(__builtin_bit_cast(h2, lo) - bias));
-    out[2 * d + 1] = __builtin_bit_cast(uint32_t, (h2)(__builtin_bit_cast(h2, hi) - bias));
-  }
-  return __builtin_bit_cast(v8h, out);
-}
-
 // ------------------------------------------------------------------------------------------------
 // If every wave fetched its own copy of the activation fragments from L2, that would be up to 6
 // times the bytes of the weights it streams (64 rows).  So the kWaves waves of a workgroup own

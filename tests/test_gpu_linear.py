@@ -263,6 +263,19 @@ def test_short_rows_in_the_tiled_gemm(K, tau, variant):
                  tuning=binding.tune_gemm_tiles(variant))
 
 
+@pytest.mark.parametrize("variant", [4, 3, 0])
+@pytest.mark.parametrize("M,K,N", [(129, 2096, 304), (600, 1040, 520), (1030, 4096, 264)])
+def test_most_columns_critical_over_many_rows(M, K, N, variant):
+    """Heavy-tailed rows (Student-t, 3 degrees of freedom) over more rows than the decode kernels take: most
+    columns are critical, far more than the fp16 slabs hold, with and without the master-weight reading."""
+    rng = np.random.default_rng([M, K, variant])
+    X = wl.to_fp16(rng.standard_t(3.0, size=(M, K)).astype(np.float32))
+    n = int(ml.outlier_mask(X, wl.TAU).sum())
+    assert n > 256 and n >= K // 8, n
+    W = wl.gaussian_weight(K, N, 0.05, rng)
+    check_linear(X, W, wl.TAU, bias=wl.gaussian_bias(N, 0.1, rng), tuning=binding.tune_gemm_tiles(variant))
+
+
 def test_moderate_share_of_critical_columns_full_size():
     """A 7B-shaped projection at 2048 tokens with 3 % of its dimensions critical (123 columns: four slabs)."""
     shape = wl.LLAMA_7B_LINEARS[0]
