@@ -555,13 +555,13 @@ __global__ __launch_bounds__(kWaves * kWave) void k_prep(uint16_t* __restrict__ 
 
 // After k_prep: the first `slab_blocks` workgroups list the critical columns (the first one
 // publishes the list, the count and the byte mask) and build the fp16 slab of the first
-// kOutlierSlab of them; each of the remaining workgroups owns 64 rows (lane = row) and 4096 columns and
-// clears the codes of the critical columns in those rows with byte stores of zero.  Driven by the
+// kOutlierSlab of them; each of the remaining workgroups owns 64 rows (lane = row) and 4096 columns or a multiple
+// and clears the codes of the critical columns in those rows with byte stores of zero.  Driven by the
 // flags themselves, so any number of critical columns is handled the same way.
 __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __restrict__ X, int M, int K, int ldx,
                                                               const uint8_t* __restrict__ flag, int8_t* __restrict__ Xq,
                                                               int n_slabs, int8_t* __restrict__ tap_xq, int slab_blocks,
-                                                              const PackOutliers o) {
+                                                              int clear_units, const PackOutliers o) {
   const int Kpad = n_slabs * kSlabBytes;
   if ((int)blockIdx.x < slab_blocks) {
     __shared__ int s_idx[kOutlierSlab * kCriticalSlabs];
@@ -571,16 +571,16 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
     gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
     return;
   }
-  // A clearing workgroup owns 64 rows (lane = row) and 256 units of 16 columns, 64 units per wave: lane l of a
-  // wave looks at unit u0 + l.  (With input whose columns are nearly all critical the clearing is the longest
-  // part of the preparation unless many waves share a row.)
+  // A clearing workgroup owns 64 rows (lane = row) and clear_units units of 16 columns (a multiple of 256), which
+  // its waves take 64 at a time: lane l of a wave looks at unit u0 + l.  (With input whose columns are nearly all
+  // critical the clearing is the longest part of the preparation unless many waves share a row.)
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int units = Kpad / 16;
-  const int unit_groups = ceil_div(units, kThreads);
+  const int unit_groups = ceil_div(units, clear_units);
   const int cb = (int)blockIdx.x - slab_blocks;
   const int m = (cb / unit_groups) * kWave + lane;
-  const int u0 = (cb % unit_groups) * kThreads + wave * kWave;
-  {
+  const int u_end = min(units, (cb % unit_groups + 1) * clear_units);
+  for (int u0 = (cb % unit_groups) * clear_units + wave * kWave; u0 < u_end; u0 += kThreads) {
     const v4u f = u0 + lane < units ? flags16(flag, 16 * (u0 + lane)) : v4u{0, 0, 0, 0};
     uint64_t todo = __builtin_amdgcn_ballot_w64((f[0] | f[1] | f[2] | f[3]) != 0);
     while (todo) {
@@ -678,9 +678,14 @@ hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad
   if (e != hipSuccess) return e;
   if (event_mid && (e = hipEventRecord(static_cast<hipEvent_t>(event_mid), stream)) != hipSuccess) return e;
   const int slab_blocks = max(1, ceil_div((M + o.N) * (kOutlierSlab / 8), kThreads));
-  const int clear_blocks = ceil_div(M, kWave) * ceil_div(n_slabs * (kSlabBytes / 16), kThreads);   // 64 rows x 4096 columns each
+  // clearing workgroups: 64 rows x 4096 columns each, more columns each once that would be more than one per CU
+  // (with few critical columns, the usual case, a workgroup has next to nothing to do and their number is the cost)
+  const int row_groups = ceil_div(M, kWave), units = n_slabs * (kSlabBytes / 16);
+  const int merge = max(1, ceil_div(row_groups * ceil_div(units, kThreads), device_cu_count()));
+  const int clear_units = kThreads * merge;
+  const int clear_blocks = row_groups * ceil_div(units, clear_units);
   hipLaunchKernelGGL(k_outlier_columns, dim3(slab_blocks + clear_blocks), dim3(kThreads), 0, stream, X, M, K, ldx, flag, Xq,
-                     n_slabs, tap_xq, slab_blocks, o);
+                     n_slabs, tap_xq, slab_blocks, clear_units, o);
   return hipGetLastError();
 }
 
