@@ -634,13 +634,16 @@ hipError_t launch_row_absmax_noncritical(const uint16_t* X, int M, int K, int ld
 }
 
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
-                       int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream) {
+                       int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream, bool list_columns) {
   const int n_slabs = Kpad / kSlabBytes;
   const int gx = ceil_div(n_slabs, kPackSlabs), pack_y = ceil_div(M, kPackRows);
   // the slabs of critical columns are for the tiled GEMM kernels; the decode kernel reads Xf instead
   // (one extra block still lists the critical columns)
   const int slab_items = Xf ? 0 : (M + o.N) * (kOutlierSlab / 8);
-  const int slab_y = max(1, ceil_div(ceil_div(slab_items, kThreads), gx));
+  // (the list is a chain of dependent steps over all of K in one workgroup: the longest part of this kernel at
+  // decode sizes; the decode kernels can read the flags themselves)
+  if (!list_columns && !Xf) return hipErrorInvalidValue;
+  const int slab_y = list_columns ? max(1, ceil_div(ceil_div(slab_items, kThreads), gx)) : 0;
   const dim3 grid(gx, pack_y + slab_y);
   hipLaunchKernelGGL(k_pack, grid, dim3(kThreads), 0, stream, X, M, K, ldx, flag, r, Xq, n_slabs, tap_xq, pack_y, Xf, o);
   return hipGetLastError();

@@ -341,6 +341,15 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   // coded activations are decoded by the one-pass preparation kernel itself where that kernel runs
   // (element offsets are held in 32 bits there); otherwise by the decoder, ahead of the usual kernels
   const bool one_pass = !skinny && prep_fits(K) && !readings;
+  // Decode kernels after the scan and pack kernels, nobody asking for the list of critical columns: the pack kernel
+  // leaves the list out (its longest part at these sizes) and the decode kernel reads the column flags themselves as
+  // its mask.  Every workgroup reads them, so they are put back to zero by the kernel after it, the one that sums
+  // the splits: only calls that have one.
+  bool lean_pack = false;
+  if (skinny && !rows_path && !own_prep && !wants_prep_taps) {
+    const SkinnyPlan plan = plan_skinny(M < kSkinnyMaxM ? M : kSkinnyMaxM, K, N);
+    lean_pack = plan.splits > 1 || lora || gelu || (exit && (exit->residual || exit_fused));
+  }
   const bool fused_decode = coded && one_pass && prep_from_codes_fits(K) && (size_t)M * K < ((size_t)1 << 31);
   if (coded && !fused_decode &&
       launch_dequantize_blockwise(coded->codes, coded->absmax, (size_t)M * K, coded->block, X, st) != hipSuccess)
@@ -424,7 +433,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       // codes and the fp16 copy of these rows, masked with the flags of all M rows; the list of critical columns is
       // published again with every pass (the same list)
       if (!own_prep && launch_pack(X + (size_t)row0 * ldx, Mc, K, ldx, ws.flag, ws.r + row0, ws.xq, Kpad,
-                                   t.xq ? t.xq + (size_t)row0 * K : nullptr, ws.xf, po, st) != hipSuccess)
+                                   t.xq ? t.xq + (size_t)row0 * K : nullptr, ws.xf, po, st, !lean_pack) != hipSuccess)
         return MMD8_E_HIP;
       if (row0 == 0 && !record(t.event_gemm_begin)) return MMD8_E_HIP;
       SkinnyArgs g = {};
@@ -453,6 +462,11 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
       g.partial = ws.partial;
       g.tap_acc = t.acc ? t.acc + (size_t)row0 * N : nullptr;
       g.flag_reset = (!own_prep && row0 + kSkinnyMaxM >= M) ? ws.flag : nullptr;   // the last pass zeroes the column flags again
+      if (lean_pack) {
+        g.mask = ws.flag;
+        g.flag_reset_late = g.flag_reset;
+        g.flag_reset = nullptr;
+      }
       if (own_prep) {
         g.X = X;
         g.ldx = ldx;

@@ -58,7 +58,8 @@ hipError_t launch_scan(const uint16_t* X, int M, int K, int ldx, uint32_t th, in
 hipError_t launch_row_absmax_noncritical(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, float* r,
                                          hipStream_t stream);
 hipError_t launch_pack(const uint16_t* X, int M, int K, int ldx, const uint8_t* flag, const float* r, int8_t* Xq,
-                       int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream);
+                       int Kpad, int8_t* tap_xq, uint16_t* Xf, const PackOutliers& o, hipStream_t stream,
+                       bool list_columns = true);   // false (with Xf): codes and fp16 copy only, nothing of `o` is written
 // One-pass preparation for inputs taller than the decode kernels take; prep_fits is false when K is too
 // large for a row to be held in the registers of one workgroup (the caller then uses scan + pack).
 bool prep_fits(int K);

@@ -39,6 +39,7 @@ struct SkinnyArgs {
   float* partial;         // workspace for split K
   int32_t* tap_acc;       // [M][N] or null
   uint8_t* flag_reset;    // [Kpad] column flags of the scan: zeroed again by workgroup 0
+  uint8_t* flag_reset_late;   // likewise, by the kernel that sums the splits: for calls whose `mask` is the flags themselves
   const uint16_t* lora_T; // low-rank term T B^T added to the output: T [M][lora_ldt] fp16, B [N][lora_r] fp16
   const uint16_t* lora_B;
   int lora_ldt, lora_r;   // lora_r == 0: none

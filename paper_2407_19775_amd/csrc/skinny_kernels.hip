@@ -345,7 +345,8 @@ __global__ __launch_bounds__(256) void k_skinny_finalize(const float* __restrict
                                                          const uint16_t* __restrict__ T, int ldt,
                                                          const uint16_t* __restrict__ B, int r,
                                                          const uint16_t* residual /* may alias Y */, int ldr, int gelu,
-                                                         uint16_t* Y, int ldy) {
+                                                         uint16_t* Y, int ldy, uint8_t* flag_reset, int Kpad) {
+  reset_column_flags(flag_reset, Kpad);
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)M * N) return;
   const int m = (int)(i / N), n = (int)(i % N);
@@ -426,7 +427,9 @@ struct FinalizedHalves {
 __global__ __launch_bounds__(kCodecThreads) void k_skinny_finalize_coded(const FinalizedHalves src, int block,
                                                                          uint8_t* __restrict__ codes,
                                                                          float* __restrict__ absmax,
-                                                                         int blocks_per_span, size_t n_spans) {
+                                                                         int blocks_per_span, size_t n_spans,
+                                                                         uint8_t* flag_reset, int Kpad) {
+  reset_column_flags(flag_reset, Kpad);
   encode_spans(src, src.MN, block, codes, absmax, blocks_per_span, n_spans, kExitCode);
 }
 
@@ -495,6 +498,7 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
   const bool split = plan.splits > 1 || a.lora_r > 0 || a.residual || a.codes || a.gelu, tap = a.tap_acc != nullptr;
   const size_t n = (size_t)a.M * a.N;
   if (split && tap) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.tap_acc, n);
+  if (a.flag_reset_late && !split) return hipErrorInvalidValue;    // no kernel after the panel kernel to clear them
   hipError_t e = launch_panel(a, plan, stream);
   if (e != hipSuccess) return e;
   if (split && a.codes) {
@@ -503,11 +507,12 @@ hipError_t launch_gemm_skinny(SkinnyArgs a, const SkinnyPlan& plan, hipStream_t 
     const size_t span = (size_t)blocks_per_span * a.code_block, n_spans = (n + span - 1) / span;
     const FinalizedHalves src = {a.partial, plan.splits, a.N, n, a.bias, a.residual, a.ldr, a.Y};
     hipLaunchKernelGGL(k_skinny_finalize_coded, dim3((unsigned)n_spans), dim3(kCodecThreads), 0, stream, src, a.code_block,
-                       a.codes, a.code_absmax, blocks_per_span, n_spans);
+                       a.codes, a.code_absmax, blocks_per_span, n_spans, a.flag_reset_late, a.Kpad);
     e = hipGetLastError();
   } else if (split) {
     hipLaunchKernelGGL(k_skinny_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial, plan.splits,
-                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.residual, a.ldr, a.gelu, a.Y, a.ldy);
+                       a.M, a.N, a.bias, a.lora_T, a.lora_ldt, a.lora_B, a.lora_r, a.residual, a.ldr, a.gelu, a.Y, a.ldy,
+                       a.flag_reset_late, a.Kpad);
     e = hipGetLastError();
   }
   return e;
