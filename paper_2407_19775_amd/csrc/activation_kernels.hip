@@ -589,14 +589,23 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
       const int unit = u0 + t;
       // the flagged columns of this unit, one bit each (the same for every lane)
       uint32_t cols = 0;
+      v4u keep;                                                       // 0xff per column that stays
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const uint32_t fw = (uint32_t)__builtin_amdgcn_readlane((int)f[w], t);
         cols |= ((fw & 1u) | ((fw >> 7) & 2u) | ((fw >> 14) & 4u) | ((fw >> 21) & 8u)) << (4 * w);
+        keep[w] = (0x01010101u - fw) * 0xffu;                         // flag bytes are 0 or 1: no carries
       }
       if (m < M) {
         int8_t* p = Xq + packed_chunk_offset(m, unit >> 2, unit & 3, n_slabs);
         int8_t* tp = tap_xq ? tap_xq + (size_t)m * K + unit * 16 : nullptr;
+        if (__builtin_popcount(cols) >= 4) {
+          // many of the unit's 16 columns (heavy-tailed input): the row's 16 bytes are read, masked and written back
+          // (they are this lane's alone) instead of a byte store per column
+          *reinterpret_cast<v4u*>(p) = *reinterpret_cast<const v4u*>(p) & keep;
+          if (tp) *reinterpret_cast<v4u*>(tp) = *reinterpret_cast<const v4u*>(tp) & keep;
+          continue;
+        }
         while (cols) {
           const int c = __builtin_ctz(cols);
           cols &= cols - 1;

@@ -255,8 +255,7 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
 // The accumulators hold Y so far in fp32; sum_k X[m,k] q[n,k] lacks the column's step c[n] / 127, so they are
 // divided by it on entry and multiplied by it on exit (columns with c[n] = 0 have only zero codes: factor 1).
 // Against the slabs prepared by the pack kernel the weights are not rounded to fp16 after scaling: at most 2^-11
-// relative per term, as in the decode kernels.  Requests for the next slab (its rows of X into registers, its
-// codes into the other LDS buffer) are out while the current one is multiplied.
+// relative per term, as in the decode kernels.  Requests run several slabs ahead of the MFMAs (see kDepth).
 template <class Cfg>
 __device__ __forceinline__ void dense_critical_columns(const GemmArgs& a, const WavePos<Cfg>& p, v16i (&acc)[Cfg::TI][Cfg::TJ],
                                                        int8_t* smem, const float (&cs)[Cfg::TJ]) {
@@ -266,7 +265,17 @@ __device__ __forceinline__ void dense_critical_columns(const GemmArgs& a, const 
   constexpr int CPT = BK / TPR, NL = CPT / 8;                        // columns per thread, 16-byte loads per thread
   constexpr int kRowBytes = 2 * BK + 16;                             // 144: rows 8 apart share banks, not rows next to each other
   constexpr int A_LDS = (Cfg::BM * kRowBytes + 1023) / 1024 * 1024;
-  static_assert(A_LDS + 2 * Cfg::B_BYTES <= Cfg::RING_BYTES, "the parked rows and two weight slabs fit where the ring was");
+  // Slabs in flight.  A slab's requests (this thread's pieces of the rows of X and the slab's mask byte into
+  // registers, the weight codes into an LDS buffer) go out kDepth slabs ahead: a slab's MFMAs take a quarter of the
+  // time its data takes to arrive.  One weight buffer more than that, so that a request never targets the buffer
+  // being read.  Every slab position issues the same kPerSlab requests in the same order (positions past the end
+  // ask for the last slab again), so the number still in flight behind a slab's weight codes is known; the loads
+  // into registers are the compiler's to wait for, and it counts only those, so its waits come out stricter than
+  // needed (about two slabs ahead instead of kDepth - 1), never looser.
+  constexpr int kBuffers = (Cfg::RING_BYTES - A_LDS) / Cfg::B_BYTES < 5 ? (Cfg::RING_BYTES - A_LDS) / Cfg::B_BYTES : 5;
+  constexpr int kDepth = kBuffers - 1;
+  constexpr int kPerSlab = NL + 1 + Cfg::B_DMA;                      // requests per slab and lane
+  static_assert(kDepth >= 1 && (kDepth - 1) * kPerSlab <= 63, "at least two weight buffers; the count fits the wait instruction");
   int8_t* sA = smem;
   int8_t* sB = smem + A_LDS;
   const int lane = p.lane, wm = p.wm, wn = p.wn;
@@ -290,49 +299,48 @@ __device__ __forceinline__ void dense_critical_columns(const GemmArgs& a, const 
     }
   }
 
-  auto load_a = [&](int s, v4u (&ra)[NL]) __attribute__((always_inline)) {
+  v4u ra[kDepth][NL];
+  uint8_t fl[kDepth];
+  const uint32_t ldsB = (uint32_t)(uintptr_t)sB + wave * (kWave * 16);
+  // position `pos` of the sequence (slab pos, or the last slab again past the end) into register set u and weight
+  // buffer pos % kBuffers (a repeated request lands in a buffer that is not read any more)
+  auto request = [&](int pos, auto u_tag) __attribute__((always_inline)) {
+    constexpr int u = decltype(u_tag)::value;
+    const int s = min(pos, n_slabs - 1);
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       // pieces beyond the row's end (the padding of K) re-read the row's first piece; none of their columns is critical
       const int col = s * BK + part * CPT + 8 * q;
-      ra[q] = *reinterpret_cast<const v4u*>(xrow + (col < a.ldx ? col - part * CPT : -part * CPT));
+      ra[u][q] = *reinterpret_cast<const v4u*>(xrow + (col < a.ldx ? col - part * CPT : -part * CPT));
     }
-  };
-  const uint32_t ldsB = (uint32_t)(uintptr_t)sB + wave * (kWave * 16);
-  auto issue_b = [&](int s, int buf) __attribute__((always_inline)) {
+    fl[u] = a.mask[s * BK + lane];
+    const uint32_t dst = ldsB + (pos % kBuffers) * Cfg::B_BYTES;
 #pragma unroll
     for (int j = 0; j < Cfg::B_DMA; ++j)
       dma16(dma_source(a.Wt, p.n0, n_slabs, j, Cfg::kWaves, wave, lane) + (size_t)s * kBlockBytes,
-            ldsB + buf * Cfg::B_BYTES + j * Cfg::kWaves * (kWave * 16));
+            dst + j * Cfg::kWaves * (kWave * 16));
   };
-
-  wait_lds_and_sync();                                               // every wave is done with the slab ring
-  uint64_t bits = __builtin_amdgcn_ballot_w64(a.mask[lane] != 0);    // bit c: column 64 s + c is critical
-  v4u ra[NL];
-  load_a(0, ra);
-  issue_b(0, 0);
-  for (int s = 0, buf = 0; s < n_slabs; ++s, buf ^= 1) {
+  auto iteration = [&](int s, auto u_tag) __attribute__((always_inline)) {
+    constexpr int u = decltype(u_tag)::value;                        // s % kDepth
+    // the weight codes of slab s have landed once only the requests of the kDepth - 1 positions after it are out
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"((kDepth - 1) * kPerSlab) : "memory");
+    // bit c: column 64 s + c is critical (positions past the end: nothing to multiply)
+    const uint64_t bits = s < n_slabs ? __builtin_amdgcn_ballot_w64(fl[u] != 0) : 0;
     // park the rows of slab s, critical columns only
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const uint32_t b8 = (uint32_t)(bits >> (part * CPT + 8 * q)) & 0xffu;
-      v4u v = ra[q];
+      v4u v = ra[u][q];
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         v[w] &= (((b8 >> (2 * w)) & 1u) ? 0x0000ffffu : 0u) | (((b8 >> (2 * w + 1)) & 1u) ? 0xffff0000u : 0u);
       *reinterpret_cast<v4u*>(sA + row * kRowBytes + (part * CPT + 8 * q) * 2) = v;
     }
-    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");              // the codes of slab s have landed too
-    const uint64_t bits_now = bits;
-    uint8_t next_flag = 0;
-    if (s + 1 < n_slabs) {
-      next_flag = a.mask[(s + 1) * BK + lane];
-      load_a(s + 1, ra);
-      issue_b(s + 1, buf ^ 1);
-    }
     wait_lds_and_sync();
-    if (bits_now != 0) {
-      const int8_t* fbase = sB + buf * Cfg::B_BYTES + (wn * Cfg::WN / 32) * 2048 + lane * 16;
+    // (past the end the last slab is asked for again: the count of requests in flight stays what the waits assume)
+    request(s + kDepth, u_tag);
+    if (bits != 0) {
+      const int8_t* fbase = sB + (s % kBuffers) * Cfg::B_BYTES + (wn * Cfg::WN / 32) * 2048 + lane * 16;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         v4u wu[TJ];
@@ -357,9 +365,18 @@ __device__ __forceinline__ void dense_critical_columns(const GemmArgs& a, const 
         }
       }
     }
-    wait_lds_and_sync();                                             // both buffers are read before they are written again
-    bits = __builtin_amdgcn_ballot_w64(next_flag != 0);
-  }
+    wait_lds_and_sync();                                             // the parked rows and this weight buffer are read before they are written again
+  };
+
+  wait_lds_and_sync();                                               // every wave is done with the slab ring
+  [&]<int... U>(std::integer_sequence<int, U...>) __attribute__((always_inline)) {
+    (request(U, std::integral_constant<int, U>{}), ...);
+    // whole groups of kDepth positions, one code path and no way out inside a group
+    for (int s = 0; s < n_slabs; s += kDepth) (iteration(s + U, std::integral_constant<int, U>{}), ...);
+  }(std::make_integer_sequence<int, kDepth>{});
+  // the requests repeated past the end are still on their way into registers and LDS
+  asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+  wait_lds_and_sync();
 #pragma unroll
   for (int j = 0; j < TJ; ++j)
 #pragma unroll
