@@ -188,6 +188,17 @@ def test_config3_decode_shapes(M, shape):
     check_linear(X, W, wl.TAU)
 
 
+@pytest.mark.parametrize("M", [96, 128, 256])
+@pytest.mark.parametrize("shape", wl.LLAMA_7B_LINEARS, ids=lambda s: s.name)
+def test_heavy_tailed_rows_around_the_change_of_path(M, shape):
+    """The heavy-tailed launches the benchmark times on both sides of the change from the decode kernels to the
+    tiled GEMM (Student-t activations at 128 and 256 rows: nearly every feature dimension is critical), and 96 rows
+    (two passes of the decode kernels, the second a ragged one)."""
+    X = wl.decode_activation(900 + M, M, shape.K)
+    W = wl.prefill_weight(2, 20 + wl.LLAMA_7B_LINEARS.index(shape), shape, 0.02)
+    check_linear(X, W, wl.TAU)
+
+
 @pytest.mark.parametrize("shape", wl.LLAMA_7B_LINEARS, ids=lambda s: s.name)
 def test_config2_prefill_full_size(shape):
     """The launches the benchmark times (2048 tokens), compared in full."""
