@@ -33,7 +33,7 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # (70B-shaped layer, 4096 tokens) and the 7B-shaped step.  Valid for the GEMM source they were measured on:
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
-GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.7e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 183.4e6
 GEMM_TRAFFIC_SOURCE_SHA256 = "5e280f95ae31a5b31f203c49af5dbb38883b823f8da6f069c9547f8ad67ae959"
 
 
