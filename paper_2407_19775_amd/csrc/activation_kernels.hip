@@ -571,17 +571,19 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
     gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
     return;
   }
-  // A clearing workgroup owns 64 rows (lane = row) and clear_units units of 16 columns (a multiple of 256), which
-  // its waves take 64 at a time: lane l of a wave looks at unit u0 + l.  (With input whose columns are nearly all
-  // critical the clearing is the longest part of the preparation unless many waves share a row.)
+  // A clearing workgroup owns 64 rows (lane = row) and clear_units units of 16 columns (a multiple of 64), a quarter
+  // of them per wave, taken 64 at a time: lane l of a wave looks at unit u0 + l.  (With input whose columns are
+  // nearly all critical the clearing is the longest part of the preparation unless many waves share a row.)
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int units = Kpad / 16;
   const int unit_groups = ceil_div(units, clear_units);
   const int cb = (int)blockIdx.x - slab_blocks;
   const int m = (cb / unit_groups) * kWave + lane;
-  const int u_end = min(units, (cb % unit_groups + 1) * clear_units);
-  for (int u0 = (cb % unit_groups) * clear_units + wave * kWave; u0 < u_end; u0 += kThreads) {
-    const v4u f = u0 + lane < units ? flags16(flag, 16 * (u0 + lane)) : v4u{0, 0, 0, 0};
+  const int wave_units = clear_units / (kThreads / kWave);
+  const int u_begin = (cb % unit_groups) * clear_units + wave * wave_units;
+  const int u_end = min(units, u_begin + wave_units);
+  for (int u0 = u_begin; u0 < u_end; u0 += kWave) {
+    const v4u f = u0 + lane < u_end ? flags16(flag, 16 * (u0 + lane)) : v4u{0, 0, 0, 0};
     uint64_t todo = __builtin_amdgcn_ballot_w64((f[0] | f[1] | f[2] | f[3]) != 0);
     while (todo) {
       const int t = __builtin_ctzll(todo);
@@ -694,8 +696,11 @@ hipError_t launch_prep(uint16_t* X, int M, int K, int ldx, uint32_t th, int Kpad
   // CUs (with few critical columns, the usual case, a workgroup has next to nothing to do and their number is the
   // cost: 17.1 us with 256 of them against 12.7 us with 16 on a 4096 x 28672 input)
   const int row_groups = ceil_div(M, kWave), units = n_slabs * (kSlabBytes / 16);
-  const int merge = max(1, ceil_div(row_groups * ceil_div(units, kThreads), max(1, device_cu_count() / 4)));
-  const int clear_units = kThreads * merge;
+  const int groups_256 = row_groups * ceil_div(units, kThreads);
+  const int merge = max(1, ceil_div(groups_256, max(1, device_cu_count() / 4)));
+  // (a few hundred rows: a quarter of that per workgroup, 16 units per wave, so that heavy-tailed input, where every
+  // unit has columns to clear, does not leave the clearing to four workgroups)
+  const int clear_units = groups_256 <= 16 ? kThreads / 4 : kThreads * merge;
   const int clear_blocks = row_groups * ceil_div(units, clear_units);
   hipLaunchKernelGGL(k_outlier_columns, dim3(slab_blocks + clear_blocks), dim3(kThreads), 0, stream, X, M, K, ldx, flag, Xq,
                      n_slabs, tap_xq, slab_blocks, clear_units, o);
