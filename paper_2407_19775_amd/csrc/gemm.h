@@ -10,13 +10,14 @@ namespace mmd8 {
 // at a time after the ring has drained: fp16 activations straight from X, weight codes converted in registers.
 constexpr int kOutlierSlab = 32;
 constexpr int kCriticalSlabs = 8;
-// Whether a call takes the dense path for its critical columns: more of them than the slabs hold, and at least eight
+// Whether a call takes the dense path for its critical columns: more of them than the slabs hold, and at least twelve
 // per 64-column slab of K on average (below that, gathering the columns beyond the slabs one by one is cheaper than
-// a pass over every slab: about 0.5 us per column against 3.7 us per slab on a 2048 x 4096 x 12288 call).  Then no fp16 slab is prepared or read at all.  The same decision in the kernel that
+// a pass over every slab: 0.44 us per column against 3.7 us per slab on a 2048 x 4096 x 12288 call, which meet at
+// 800 columns of 4096).  Then no fp16 slab is prepared or read at all.  The same decision in the kernel that
 // prepares the slabs and in the GEMM, from the count that both read; never with original 16-bit weight rows (the
 // dense path multiplies the weight codes).
 __host__ __device__ constexpr inline bool dense_critical_path(int n_out, int crit_slabs, int n_slabs, bool master_rows) {
-  return !master_rows && n_out > kOutlierSlab * crit_slabs && n_out >= 8 * n_slabs;
+  return !master_rows && n_out > kOutlierSlab * crit_slabs && n_out >= 12 * n_slabs;
 }
 
 struct GemmArgs {
