@@ -77,9 +77,26 @@ def test_no_critical_column_and_many(tau, M):
 @pytest.mark.parametrize("n_crit,r", [(1, 64), (33, 16), (70, 40), (200, 8), (256, 64), (257, 24)])
 def test_critical_column_slabs_next_to_the_adapter(n_crit, r, variant):
     """1 to 8 fp16 slabs of critical columns in use (the unused ones are skipped), then the adapter's one or two
-    slabs behind them in the same ring; 257: the gather loop on top."""
+    slabs behind them in the same ring; 257 of 1040 columns: no slab of critical columns at all, they go through
+    the second, fp16 pass over K after the adapter's slabs."""
     M, K, N = 300, 1040, 520
     rng = np.random.default_rng([n_crit, r, variant])
+    x = np.clip(rng.standard_normal((M, K)), -5.0, 5.0).astype(np.float32)
+    cols = np.sort(rng.choice(K, n_crit, replace=False))
+    for j, k in enumerate(cols):
+        x[(11 * j) % M, k] = (-1.0) ** j * (7.0 + j % 40)
+    X = wl.to_fp16(x)
+    assert np.array_equal(np.flatnonzero(ml.outlier_mask(X, 6.0)), cols)
+    A = wl.to_fp16(rng.standard_normal((r, K)).astype(np.float32) * 0.05)
+    B = wl.to_fp16(rng.standard_normal((N, r)).astype(np.float32) * 0.05)
+    check_lora(X, wl.gaussian_weight(K, N, 0.02, rng), A, B, 6.0, tuning=binding.tune_gemm_tiles(variant))
+
+
+@pytest.mark.parametrize("variant", [4, 2])
+def test_gathered_critical_columns_next_to_the_adapter(variant):
+    """300 of 2096 columns critical: eight slabs, the adapter's slab, then 44 columns gathered in the epilogue."""
+    M, K, N, n_crit, r = 300, 2096, 264, 300, 16
+    rng = np.random.default_rng([n_crit, r, variant, 3])
     x = np.clip(rng.standard_normal((M, K)), -5.0, 5.0).astype(np.float32)
     cols = np.sort(rng.choice(K, n_crit, replace=False))
     for j, k in enumerate(cols):
