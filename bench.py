@@ -34,7 +34,7 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
 GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 183.4e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "5e280f95ae31a5b31f203c49af5dbb38883b823f8da6f069c9547f8ad67ae959"
+GEMM_TRAFFIC_SOURCE_SHA256 = "c12b5dd4d3a204d49cee2a6570f7a5a7dc8a102d4f23caa21652374bb7ca0207"
 
 
 def parse():

@@ -246,8 +246,9 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
   }
 }
 
-// All critical columns of an input where hundreds or thousands of feature dimensions are critical
-// (dense_critical_path: none of them travelled as an fp16 slab then): slab after slab of 64 columns.
+// The 16-bit product over the critical feature dimensions ("Compression techniques", item 2) for an input where
+// hundreds or thousands of them are critical (dense_critical_path: none of them travelled as an fp16 slab then):
+// slab after slab of 64 columns.
 //   A side: the tile's rows of X itself (fp16, 128 contiguous bytes per row and slab), columns that are not
 //           critical set to zero, parked in LDS as rows of 144 bytes;
 //   B side: the slab of weight codes, fetched like in the main loop, the codes turned into fp16 integers in
