@@ -155,6 +155,8 @@ constexpr int kPackRowSteps = 2;
 constexpr int kPackRows = 32 * kPackRowSteps;          // rows per workgroup
 constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (one per wave)
 
+constexpr int kListedColumns = kOutlierSlab * kCriticalSlabs + kGatherMax;   // critical columns a workgroup keeps in LDS
+
 // The ascending list of critical columns and their count, computed by one whole workgroup from
 // the flags (every workgroup that needs the list recomputes it: a few KB of flags from L2 are
 // cheaper than a serial step between two kernels).  The first kOutlierSlab indices and the count
@@ -163,7 +165,7 @@ constexpr int kPackSlabs = kThreads / kWave;            // slabs per workgroup (
 template <int kMaxUnits>   // units a thread may own: ceil(Kpad / 16 / kThreads) at most
 __device__ __forceinline__ void compact_critical_columns_n(const uint8_t* __restrict__ flag, int K, int Kpad,
                                                            const PackOutliers& o, bool publish,
-                                                           int* s_idx /*[kOutlierSlab * kCriticalSlabs]*/, int* s_n_out,
+                                                           int* s_idx /*[kListedColumns]*/, int* s_n_out,
                                                            int* s_wave_total /*[kThreads / kWave]*/) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int units = Kpad / 16;
@@ -203,7 +205,7 @@ __device__ __forceinline__ void compact_critical_columns_n(const uint8_t* __rest
           const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
           if (publish && o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
           if (set) {
-            if (pos < kOutlierSlab * o.crit_slabs) s_idx[pos] = k;
+            if (pos < kOutlierSlab * o.crit_slabs + (o.Xg ? o.ldg : 0)) s_idx[pos] = k;
             if (publish) {
               o.idx[pos] = k;
               if (o.tap_idx) o.tap_idx[pos] = k;
@@ -247,11 +249,58 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
                                            const PackOutliers& o, int item, const int* s_idx, int n_out_all) {
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8);
   if (row >= M + o.N) return;
-  if (dense_critical_path(n_out_all, o.crit_slabs, n_slabs, o.W_master != nullptr)) return;   // the GEMM reads no slab then
+  if (dense_critical_path(n_out_all, o.crit_slabs, o.dense_from, o.W_master != nullptr)) return;   // the GEMM reads no slab then
   const int n_out = min(n_out_all, kOutlierSlab * o.crit_slabs);
   const int used = max(1, ceil_div(n_out, kOutlierSlab));
   for (int slab = 0; slab < used; ++slab) gather_outlier_slab_one(X, M, ldx, n_slabs, o, row, ch, slab, s_idx, n_out);
 }
+// Xg[m][e] = X[m, O_(32 crit_slabs + e)] for the critical columns beyond the slabs (gemm.h), and Wg[n][e], their
+// 16-bit weights as the slabs hold them: eight columns of a row (16 bytes) per item, the items shared out over all
+// the threads that build the slabs.  Nothing to do in the usual case (no such column), and nothing when the GEMM
+// takes the dense pass.
+__device__ inline void gather_further_columns(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
+                                              const PackOutliers& o, int first, int stride, const int* s_idx,
+                                              int n_out_all) {
+  if (o.Xg == nullptr || dense_critical_path(n_out_all, o.crit_slabs, o.dense_from, o.W_master != nullptr)) return;
+  const int j_begin = kOutlierSlab * o.crit_slabs;
+  const int n_more = min(n_out_all - j_begin, o.ldg);
+  if (n_more <= 0) return;
+  const int chunks = ceil_div(n_more, 8);
+  const int rows = M + (o.Wg ? o.N : 0);
+  for (int item = first; item < rows * chunks; item += stride) {
+    const int row = item / chunks, e0 = 8 * (item % chunks);
+    int kcol[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) kcol[t] = s_idx[j_begin + min(e0 + t, n_more - 1)];
+    uint32_t out[4] = {0, 0, 0, 0};
+    if (row < M) {
+      uint16_t v[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + kcol[t]];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) out[t >> 1] |= (uint32_t)v[t] << (16 * (t & 1));
+      *reinterpret_cast<v4u*>(o.Xg + (size_t)row * o.ldg + e0) = v4u{out[0], out[1], out[2], out[3]};
+    } else {
+      const int n = row - M;
+      if (o.W_master) {
+        uint16_t v[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = o.W_master[(size_t)kcol[t] * o.ldw + n];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t >> 1] |= (uint32_t)v[t] << (16 * (t & 1));
+      } else {
+        const float step = o.c[n] / 127.0f;
+        int8_t q[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) q[t] = o.Wt[packed_offset(n, kcol[t], n_slabs)];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t >> 1] |= rounded_float_to_half_bits((float)q[t] * step) << (16 * (t & 1));
+      }
+      *reinterpret_cast<v4u*>(o.Wg + (size_t)n * o.ldg + e0) = v4u{out[0], out[1], out[2], out[3]};
+    }
+  }
+}
+
 __device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                                const PackOutliers& o, int row, int ch, int slab, const int* s_idx,
                                                int n_out) {
@@ -301,12 +350,16 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
                                                    uint16_t* __restrict__ Xf, const PackOutliers o) {
   if ((int)blockIdx.y >= pack_blocks_y) {
     // the extra blocks list the critical columns and prepare their slab; the first one publishes
-    __shared__ int s_idx[kOutlierSlab * kCriticalSlabs];
+    __shared__ int s_idx[kListedColumns];
     __shared__ int s_n_out;
     __shared__ int s_wave_total[kThreads / kWave];
     const int b = ((int)blockIdx.y - pack_blocks_y) * gridDim.x + blockIdx.x;
     compact_critical_columns(flag, K, n_slabs * kSlabBytes, o, b == 0, s_idx, &s_n_out, s_wave_total);
-    if (!Xf) gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x, s_idx, s_n_out);
+    if (!Xf) {
+      gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x, s_idx, s_n_out);
+      gather_further_columns(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x,
+                             ((int)gridDim.y - pack_blocks_y) * (int)gridDim.x * kThreads, s_idx, s_n_out);
+    }
     return;
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -564,11 +617,12 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
                                                               int clear_units, const PackOutliers o) {
   const int Kpad = n_slabs * kSlabBytes;
   if ((int)blockIdx.x < slab_blocks) {
-    __shared__ int s_idx[kOutlierSlab * kCriticalSlabs];
+    __shared__ int s_idx[kListedColumns];
     __shared__ int s_n_out;
     __shared__ int s_wave_total[kThreads / kWave];
     compact_critical_columns(flag, K, Kpad, o, blockIdx.x == 0, s_idx, &s_n_out, s_wave_total);
     gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
+    gather_further_columns(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, slab_blocks * kThreads, s_idx, s_n_out);
     return;
   }
   // A clearing workgroup owns 64 rows (lane = row) and clear_units units of 16 columns (a multiple of 64), a quarter

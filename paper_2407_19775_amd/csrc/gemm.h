@@ -10,14 +10,46 @@ namespace mmd8 {
 // at a time after the ring has drained: fp16 activations straight from X, weight codes converted in registers.
 constexpr int kOutlierSlab = 32;
 constexpr int kCriticalSlabs = 8;
-// Whether a call takes the dense path for its critical columns: more of them than the slabs hold, and at least twelve
-// per 64-column slab of K on average (below that, gathering the columns beyond the slabs one by one is cheaper than
-// a pass over every slab: 0.44 us per column against 3.7 us per slab on a 2048 x 4096 x 12288 call, which meet at
-// 800 columns of 4096).  Then no fp16 slab is prepared or read at all.  The same decision in the kernel that
-// prepares the slabs and in the GEMM, from the count that both read; never with original 16-bit weight rows (the
-// dense path multiplies the weight codes).
-__host__ __device__ constexpr inline bool dense_critical_path(int n_out, int crit_slabs, int n_slabs, bool master_rows) {
-  return !master_rows && n_out > kOutlierSlab * crit_slabs && n_out >= 12 * n_slabs;
+// Critical columns beyond the slabs are gathered column by column in the GEMM's epilogue.  Reading X[m, O_j] for
+// one j and 256 rows touches 256 lines (and the weight code Wt[n, O_j] for 256 n touches 64), and every tile would
+// do it again, so the kernel that lists the critical columns gathers them once into rows of their own,
+// Xg[m][e] = X[m, O_(32 crit_slabs + e)] and Wg[n][e] = their 16-bit weights, for as many columns as the gather is
+// cheaper for than the dense pass, at most kGatherMax; a very wide layer goes without Wg.
+//
+// The dense pass (dense_critical_columns in gemm_kernels.hip) takes over where it is cheaper: it costs 3.7 us per
+// 64-column slab of K on a 2048 x 4096 x 12288 call, a gathered column 0.2 us with both sides gathered, 0.37 us with
+// X only, 0.44 us straight from X and the codes; measured on that call, applied as ratios.  dense_from is the
+// count of critical columns from which a call takes the dense pass.
+constexpr int kGatherMax = 2048;
+constexpr size_t kGatherWeightBytesMax = (size_t)96 << 20;   // no Wg when Npad x capacity x 2 bytes exceed this
+struct CriticalPlan {
+  int ldg;          // columns of Xg / Wg (a multiple of 16), 0: none
+  bool weights;     // Wg exists
+  int dense_from;
+};
+inline CriticalPlan plan_critical_columns(int n_slabs, size_t Npad, bool gathered_rows) {
+  const double dense = 3.7 * n_slabs;
+  CriticalPlan p = {0, false, 0};
+  if (gathered_rows) {
+    const int want = ((int)(dense / 0.2) + 15) / 16 * 16;
+    p.ldg = want < kGatherMax ? want : kGatherMax;
+    p.weights = Npad * (size_t)p.ldg * 2 <= kGatherWeightBytesMax;
+    if (!p.weights) {
+      const int want_x = ((int)(dense / 0.37) + 15) / 16 * 16;
+      p.ldg = want_x < kGatherMax ? want_x : kGatherMax;
+    }
+  }
+  const double per_gathered = p.weights ? 0.2 : 0.37;
+  const double in_rows = p.ldg * per_gathered < dense ? p.ldg : dense / per_gathered;
+  const double beyond = (dense - in_rows * per_gathered) / 0.44;
+  p.dense_from = kOutlierSlab * kCriticalSlabs + (int)(in_rows + beyond);
+  return p;
+}
+// Whether a call takes the dense pass for its critical columns.  Then no fp16 slab is prepared or read at all.  The
+// same decision in the kernel that prepares the slabs and in the GEMM, from the count that both read; never with
+// original 16-bit weight rows (the dense pass multiplies the weight codes).
+__host__ __device__ constexpr inline bool dense_critical_path(int n_out, int crit_slabs, int dense_from, bool master_rows) {
+  return !master_rows && n_out > kOutlierSlab * crit_slabs && n_out >= dense_from;
 }
 
 struct GemmArgs {
@@ -57,6 +89,10 @@ struct GemmArgs {
   // W[k * ldw_master + n] (null: they are re-created from the codes).  Wo was then gathered from it as well.
   const uint16_t* W_master;
   int ldw_master;
+  const uint16_t* Xg;    // [M][ldg] fp16: X[m, O_(32 crit_slabs + e)], or null (see gather_capacity)
+  const uint16_t* Wg;    // [N][ldg] fp16: the 16-bit weights of the same columns, or null (very wide layers)
+  int ldg;
+  int dense_from;        // critical columns from which the call takes the dense pass (plan_critical_columns)
 };
 
 // Workgroup 0 of the kernel that ends a call puts the scan's column flags back to zero (the next

@@ -182,50 +182,66 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
   const int kk = threadIdx.x & 15, r0 = threadIdx.x >> 4;
   const int n_slabs = a.Kpad / BK;
   __syncthreads();                                               // every wave is done with the slab ring
+  // (the column index of a step is asked for one step ahead, and a step's loads of X and of the weights go out
+  // together: one memory latency per step instead of three)
+  int k_next = j_begin + kk < n_out ? a.idx[j_begin + kk] : 0;
   for (int j0 = j_begin; j0 < n_out; j0 += 16) {
     const bool col_ok = j0 + kk < n_out;
-    const int k = col_ok ? a.idx[j0 + kk] : 0;
+    const int k = k_next;
+    k_next = j0 + 16 + kk < n_out ? a.idx[j0 + 16 + kk] : 0;
     // eight rows at a time: enough loads in flight, few registers next to the accumulators
     constexpr int BX = NX < 8 ? NX : 8, BW = NW < 8 ? NW : 8;
     static_assert(NX % BX == 0 && NW % BW == 0, "whole batches");
+    constexpr int kBatches = NX / BX > NW / BW ? NX / BX : NW / BW;
+    // the 16 columns of this step as gathered once by the preparation (neighbouring columns of a row are neighbours
+    // in memory there), or straight from X where that buffer ends or does not exist
+    const bool gathered = a.Xg != nullptr && j0 - j_begin + 16 <= a.ldg;
+    const uint16_t* xcol = gathered ? a.Xg + (j0 - j_begin + kk) : a.X + k;
+    const int xld = gathered ? a.ldg : a.ldx;
 #pragma unroll 1
-    for (int ib = 0; ib < NX; ib += BX) {
-      uint16_t xv[BX];
-#pragma unroll
-      for (int i = 0; i < BX; ++i) xv[i] = a.X[(size_t)min(p.m0 + r0 + (ib + i) * RSTEP, a.M - 1) * a.ldx + k];
-#pragma unroll
-      for (int i = 0; i < BX; ++i) {
-        const int row = r0 + (ib + i) * RSTEP;
-        sXo[row * 16 + kk] = (col_ok && p.m0 + row < a.M) ? xv[i] : (uint16_t)0;
-      }
-    }
-#pragma unroll 1
-    for (int ib = 0; ib < NW; ib += BW) {
-      if (a.W_master) {                                              // the original 16-bit rows, as they are
-        uint16_t wv[BW];
-#pragma unroll
-        for (int i = 0; i < BW; ++i)
-          wv[i] = a.W_master[(size_t)k * a.ldw_master + min(p.n0 + r0 + (ib + i) * RSTEP, a.N - 1)];
-#pragma unroll
-        for (int i = 0; i < BW; ++i) {
-          const int row = r0 + (ib + i) * RSTEP;
-          sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? wv[i] : (uint16_t)0;
-        }
-        continue;
-      }
+    for (int b = 0; b < kBatches; ++b) {
+      const bool has_x = b < NX / BX, has_w = b < NW / BW;
+      uint16_t xv[BX], wv[BW];
       int8_t wq[BW];
       float wc[BW];
+      if (has_x) {
 #pragma unroll
-      for (int i = 0; i < BW; ++i) {
-        const int n = min(p.n0 + r0 + (ib + i) * RSTEP, a.N - 1);
-        wq[i] = a.Wt[packed_offset(n, k, n_slabs)];
-        wc[i] = a.c[n];
+        for (int i = 0; i < BX; ++i) xv[i] = xcol[(size_t)min(p.m0 + r0 + (b * BX + i) * RSTEP, a.M - 1) * xld];
       }
+      const bool w_gathered = gathered && a.Wg != nullptr;
+      if (has_w) {
+        if (w_gathered) {                                            // as the preparation gathered them, 16 bits each
 #pragma unroll
-      for (int i = 0; i < BW; ++i) {
-        const int row = r0 + (ib + i) * RSTEP;
-        const uint16_t v = (uint16_t)rounded_float_to_half_bits((float)wq[i] * (wc[i] / 127.0f));
-        sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? v : (uint16_t)0;
+          for (int i = 0; i < BW; ++i)
+            wv[i] = a.Wg[(size_t)min(p.n0 + r0 + (b * BW + i) * RSTEP, a.N - 1) * a.ldg + (j0 - j_begin + kk)];
+        } else if (a.W_master) {                                     // the original 16-bit rows, as they are
+#pragma unroll
+          for (int i = 0; i < BW; ++i)
+            wv[i] = a.W_master[(size_t)k * a.ldw_master + min(p.n0 + r0 + (b * BW + i) * RSTEP, a.N - 1)];
+        } else {
+#pragma unroll
+          for (int i = 0; i < BW; ++i) {
+            const int n = min(p.n0 + r0 + (b * BW + i) * RSTEP, a.N - 1);
+            wq[i] = a.Wt[packed_offset(n, k, n_slabs)];
+            wc[i] = a.c[n];
+          }
+        }
+      }
+      if (has_x) {
+#pragma unroll
+        for (int i = 0; i < BX; ++i) {
+          const int row = r0 + (b * BX + i) * RSTEP;
+          sXo[row * 16 + kk] = (col_ok && p.m0 + row < a.M) ? xv[i] : (uint16_t)0;
+        }
+      }
+      if (has_w) {
+#pragma unroll
+        for (int i = 0; i < BW; ++i) {
+          const int row = r0 + (b * BW + i) * RSTEP;
+          const uint16_t v = (w_gathered || a.W_master) ? wv[i]
+                                                        : (uint16_t)rounded_float_to_half_bits((float)wq[i] * (wc[i] / 127.0f));
+          sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? v : (uint16_t)0;
+        }
       }
     }
     __syncthreads();
@@ -774,7 +790,7 @@ __device__ __noinline__ void gemm_tile_dense(uint32_t args_lo, uint32_t args_hi)
 template <class Cfg, bool kTap, bool kFull, bool kCoded>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) void k_gemm_mixed(const GemmArgs a) {
   const int n_out = __builtin_amdgcn_readfirstlane(*a.n_out);
-  if (dense_critical_path(n_out, a.crit_slabs, a.Kpad / BK, a.W_master != nullptr)) {
+  if (dense_critical_path(n_out, a.crit_slabs, a.dense_from, a.W_master != nullptr)) {
     const uint64_t address = (uint64_t)(const char*)__builtin_amdgcn_kernarg_segment_ptr();   // `a` is the first argument
     gemm_tile_dense<Cfg, kTap, kFull, kCoded>((uint32_t)address, (uint32_t)(address >> 32));
     return;
@@ -870,6 +886,7 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
   const size_t panels = (size_t)n0 / kPanelRows;
   b.Wt = a.Wt + panels * (size_t)(a.Kpad / BK) * kBlockBytes;
   b.Wo = a.Wo + panels * a.f_slabs * (kBlockBytes / 2);            // uint16_t elements
+  b.Wg = a.Wg ? a.Wg + (size_t)n0 * a.ldg : nullptr;
   b.c = a.c + n0;
   b.bias = a.bias ? a.bias + n0 : nullptr;
   b.Y = a.Y ? a.Y + n0 : nullptr;

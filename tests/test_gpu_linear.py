@@ -249,8 +249,9 @@ def exactly_n_critical(rng, M, K, n_crit):
 @pytest.mark.parametrize("variant", [4, 0, 2])
 @pytest.mark.parametrize("n_crit", [0, 1, 31, 32, 33, 64, 65, 100, 255, 256, 257, 300])
 def test_counts_of_critical_columns_around_the_slab_limits(n_crit, variant):
-    """The tiled GEMM takes critical columns 32 at a time as fp16 slabs, up to 256 of them, and gathers the rest:
-    counts on both sides of every border between those paths, over several row panels and a ragged tail."""
+    """The tiled GEMM takes critical columns 32 at a time as fp16 slabs, up to 256 of them, and adds the rest from
+    rows the preparation gathered: counts on both sides of every border between those paths, over several row
+    panels and a ragged tail."""
     M, K, N = 600, 1040, 520
     rng = np.random.default_rng([n_crit, variant])
     X, cols = exactly_n_critical(rng, M, K, n_crit)
@@ -261,10 +262,10 @@ def test_counts_of_critical_columns_around_the_slab_limits(n_crit, variant):
 
 
 @pytest.mark.parametrize("variant", [4, 5, 0])
-@pytest.mark.parametrize("n_crit", [257, 300, 395, 396, 420])
+@pytest.mark.parametrize("n_crit", [257, 300, 600, 865, 866, 900])
 def test_counts_of_critical_columns_around_the_change_to_the_dense_pass(n_crit, variant):
-    """33 slabs of K: up to 395 critical columns the ones beyond 256 are gathered column by column in the GEMM's
-    epilogue, from 396 (twelve per slab) all of them go through the second, fp16 pass over K."""
+    """33 slabs of K: up to 865 critical columns the ones beyond 256 are gathered once by the preparation and added
+    16 at a time in the GEMM's epilogue, from 866 on all of them go through the second, fp16 pass over K."""
     M, K, N = 300, 2096, 264
     rng = np.random.default_rng([n_crit, variant, 7])
     X, cols = exactly_n_critical(rng, M, K, n_crit)
@@ -295,7 +296,7 @@ def test_most_columns_critical_over_many_rows(M, K, N, variant):
     rng = np.random.default_rng([M, K, variant])
     X = wl.to_fp16(rng.standard_t(3.0, size=(M, K)).astype(np.float32))
     n = int(ml.outlier_mask(X, wl.TAU).sum())
-    assert n > 256 and n >= 12 * ((K + 63) // 64), n          # the dense pass, not the gather
+    assert n > 256 and n >= 23 * ((K + 63) // 64), n          # the dense pass, not the gather
     W = wl.gaussian_weight(K, N, 0.05, rng)
     check_linear(X, W, wl.TAU, bias=wl.gaussian_bias(N, 0.1, rng), tuning=binding.tune_gemm_tiles(variant))
 
