@@ -33,8 +33,8 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # (70B-shaped layer, 4096 tokens) and the 7B-shaped step.  Valid for the GEMM source they were measured on:
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
-GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 183.4e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "c12b5dd4d3a204d49cee2a6570f7a5a7dc8a102d4f23caa21652374bb7ca0207"
+GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.7e6
+GEMM_TRAFFIC_SOURCE_SHA256 = "7bd3fd1fcce5118a52460d38c486f62dfd1e6af03d9b4de387dd39212a0aa58b"
 
 
 def parse():
