@@ -921,8 +921,12 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
     }
     return launch_variant(a, 4, stream);
   }
-  if (a.M > 64 && 2 * tiles_128x256 >= cus) return launch_variant(a, 5, stream);   // less than one round of large tiles
-  if (a.M > 64 && tiles_128x256 >= 64) return launch_variant(a, 2, stream);
+  // Less than one round of large tiles: 128 x 256 with eight waves and the four-slab ring, unless that leaves most
+  // of the chip without a workgroup and K is short, where 128 x 128 tiles (up to three per CU) do better.  Measured
+  // on the 7B linears at 160-1024 rows: 4096 -> 12288 at 256 rows 39 us against 47 with the four-wave 128 x 256
+  // tile chosen before, 11008 -> 4096 (32 workgroups, 172 slabs) 73 against 79 with 128 x 128; 4096 -> 4096 stays
+  // with 128 x 128 (33 against 35).
+  if (a.M > 64 && (tiles_128x256 >= 64 || a.Kpad / BK >= 128)) return launch_variant(a, 5, stream);
   return launch_variant(a, 0, stream);
 }
 
