@@ -34,7 +34,7 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
 GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.7e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "515eb6a735dabc6275c2a267b43ff02a6e8bae9171759170b74672d35baeb0c8"
+GEMM_TRAFFIC_SOURCE_SHA256 = "a8bdadc93a2debe2cb0b1c3bc0f59db6b316d4719727e6fc1baf24a603f614aa"
 
 
 def parse():

@@ -926,6 +926,9 @@ hipError_t launch_gemm_mixed(const GemmArgs& a, int variant, hipStream_t stream)
   // on the 7B linears at 160-1024 rows: 4096 -> 12288 at 256 rows 39 us against 47 with the four-wave 128 x 256
   // tile chosen before, 11008 -> 4096 (32 workgroups, 172 slabs) 73 against 79 with 128 x 128; 4096 -> 4096 stays
   // with 128 x 128 (33 against 35).
+  // (where the 128 x 256 tiles would need a second round and the 256 x 256 ones fit in one, the large tiles win:
+  // 4096 -> 12288 at 768 rows 61 against 71 us, 4096 -> 22016 at 512 rows 61 against 70)
+  if (a.M > 128 && tiles_128x256 > cus) return launch_variant(a, 4, stream);
   if (a.M > 64 && (tiles_128x256 >= 64 || a.Kpad / BK >= 128)) return launch_variant(a, 5, stream);
   return launch_variant(a, 0, stream);
 }
