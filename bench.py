@@ -490,11 +490,11 @@ def main():
 
             heavy["layer_M%d_student_t" % Mh] = {"us_per_layer": round(timed(heavy_pass, 5) * 1e3, 1)}
         # the share of critical feature dimensions swept at 2048 tokens (Gaussian bulk, each critical dimension scaled by
-        # U(8, 40)): up to 256 critical columns travel as fp16 slabs, more are gathered once by the preparation and added
-        # 16 at a time in the GEMM's epilogue, and from 1440 of these 4096 on (the last case) the GEMM kernel makes a
-        # second, fp16 pass over K instead
+        # U(8, 40)): critical columns travel as fp16 slabs of 32 through the GEMM's ring (the first 256 in slabs every
+        # call has, up to 2048 more in further slabs), and from 2596 of these 4096 on (the last case) the GEMM kernel
+        # makes a second, fp16 pass over K instead
         qkv = shapes[0]
-        for share in (0.001, 0.008, 0.03, 0.06, 0.10, 0.25, 0.40):
+        for share in (0.001, 0.008, 0.03, 0.06, 0.10, 0.25, 0.40, 0.70):
             Xm = torch.from_numpy(wl.gaussian_with_outlier_dims(M, qkv.K, share, 8.0, 40.0, wl.rng_for(2, 700))[0]).to(dev)
             t = timed(lambda: binding.mixed_int8_linear(Xm, weights[0][0], wl.TAU, out=Ys[qkv.name], workspace=workspace), 10)
             ps, gs = [], []

@@ -167,10 +167,11 @@ int mmd8_mixed_int8_linear(const mmd8_half* X /*DEVICE*/, int M, int K, int ldx,
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and errors, without the
  * workspace: the library's own device array of MMD8_STATIC_WORKSPACE_BYTES serves as one (every GPU the library
  * runs on holds it until the process ends; that is enough for up to 64 rows of every Llama-7B- and
- * 70B-shaped linear).  The array takes the layout of a workspace of mmd8_linear_workspace_bytes(M, K, N) bytes
- * less the rows in which calls of more than 128 rows gather the critical columns of inputs that have hundreds
- * of them (here they are gathered tile by tile instead); a problem that does not fit returns MMD8_E_WORKSPACE
- * and launches nothing.  The call allocates and frees nothing and synchronises nothing; the
+ * 70B-shaped linear).  The array takes the layout of a workspace of mmd8_linear_workspace_bytes(M, K, N) bytes,
+ * or, where that does not fit, the same less the slabs in which calls of more than 128 rows gather the critical
+ * columns beyond the first 256 (those are then gathered tile by tile, and an output may differ from the other
+ * entry point's in its last bit for inputs that have so many); a problem that does not fit either way returns
+ * MMD8_E_WORKSPACE and launches nothing.  The call allocates and frees nothing and synchronises nothing; the
  * first call on a device looks up the array's address and sets kernel attributes (make it before a capture
  * starts).  All calls on one GPU share the one array: calls that overlap in time (two streams, two threads)
  * race; order them. */

@@ -205,7 +205,7 @@ __device__ __forceinline__ void compact_critical_columns_n(const uint8_t* __rest
           const bool set = (f[i][t >> 2] >> (8 * (t & 3))) & 1u;
           if (publish && o.tap_mask && k < K) o.tap_mask[k] = set ? 1 : 0;
           if (set) {
-            if (pos < kOutlierSlab * o.crit_slabs + (o.Xg ? o.ldg : 0)) s_idx[pos] = k;
+            if (pos < kOutlierSlab * (o.crit_slabs + (o.Xg ? o.g_slabs : 0))) s_idx[pos] = k;
             if (publish) {
               o.idx[pos] = k;
               if (o.tap_idx) o.tap_idx[pos] = k;
@@ -242,9 +242,10 @@ __device__ __forceinline__ void compact_critical_columns(const uint8_t* __restri
 // j >= n_out.  The weights are dequantized with two roundings (fp32 product, then fp16).  Each group of 32
 // columns is stored like one slab of a packed operand; slab 0 is always written (zeros without critical
 // columns), slab s > 0 only when more than 32 s columns are critical (the GEMM reads no other).
+// (slab `slab` of the list goes to slab `dst_slab` of dstX / dstW, which hold dst_slabs slabs per panel)
 __device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                                const PackOutliers& o, int row, int ch, int slab, const int* s_idx,
-                                               int n_out);
+                                               int n_out, uint16_t* dstX, uint16_t* dstW, int dst_slabs, int dst_slab);
 __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                            const PackOutliers& o, int item, const int* s_idx, int n_out_all) {
   const int row = item / (kOutlierSlab / 8), ch = item % (kOutlierSlab / 8);
@@ -252,58 +253,28 @@ __device__ inline void gather_outlier_slab(const uint16_t* __restrict__ X, int M
   if (dense_critical_path(n_out_all, o.crit_slabs, o.dense_from, o.W_master != nullptr)) return;   // the GEMM reads no slab then
   const int n_out = min(n_out_all, kOutlierSlab * o.crit_slabs);
   const int used = max(1, ceil_div(n_out, kOutlierSlab));
-  for (int slab = 0; slab < used; ++slab) gather_outlier_slab_one(X, M, ldx, n_slabs, o, row, ch, slab, s_idx, n_out);
+  for (int slab = 0; slab < used; ++slab)
+    gather_outlier_slab_one(X, M, ldx, n_slabs, o, row, ch, slab, s_idx, n_out, o.Xo, o.Wo, o.f_slabs, slab);
 }
-// Xg[m][e] = X[m, O_(32 crit_slabs + e)] for the critical columns beyond the slabs (gemm.h), and Wg[n][e], their
-// 16-bit weights as the slabs hold them: eight columns of a row (16 bytes) per item, the items shared out over all
-// the threads that build the slabs.  Nothing to do in the usual case (no such column), and nothing when the GEMM
-// takes the dense pass.
-__device__ inline void gather_further_columns(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
-                                              const PackOutliers& o, int first, int stride, const int* s_idx,
-                                              int n_out_all) {
+// The critical columns beyond those slabs, as further slabs of the same layout in Xg / Wg (gemm.h): the slabs in use
+// shared out over all the threads that build slabs.  Nothing to do in the usual case (no such column), and nothing
+// when the GEMM takes the dense pass.
+__device__ inline void gather_further_slabs(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
+                                            const PackOutliers& o, int first, int stride, const int* s_idx, int n_out_all) {
   if (o.Xg == nullptr || dense_critical_path(n_out_all, o.crit_slabs, o.dense_from, o.W_master != nullptr)) return;
-  const int j_begin = kOutlierSlab * o.crit_slabs;
-  const int n_more = min(n_out_all - j_begin, o.ldg);
-  if (n_more <= 0) return;
-  const int chunks = ceil_div(n_more, 8);
-  const int rows = M + (o.Wg ? o.N : 0);
-  for (int item = first; item < rows * chunks; item += stride) {
-    const int row = item / chunks, e0 = 8 * (item % chunks);
-    int kcol[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) kcol[t] = s_idx[j_begin + min(e0 + t, n_more - 1)];
-    uint32_t out[4] = {0, 0, 0, 0};
-    if (row < M) {
-      uint16_t v[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + kcol[t]];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) out[t >> 1] |= (uint32_t)v[t] << (16 * (t & 1));
-      *reinterpret_cast<v4u*>(o.Xg + (size_t)row * o.ldg + e0) = v4u{out[0], out[1], out[2], out[3]};
-    } else {
-      const int n = row - M;
-      if (o.W_master) {
-        uint16_t v[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] = o.W_master[(size_t)kcol[t] * o.ldw + n];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t >> 1] |= (uint32_t)v[t] << (16 * (t & 1));
-      } else {
-        const float step = o.c[n] / 127.0f;
-        int8_t q[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) q[t] = o.Wt[packed_offset(n, kcol[t], n_slabs)];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t >> 1] |= rounded_float_to_half_bits((float)q[t] * step) << (16 * (t & 1));
-      }
-      *reinterpret_cast<v4u*>(o.Wg + (size_t)n * o.ldg + e0) = v4u{out[0], out[1], out[2], out[3]};
-    }
+  const int n_out = min(n_out_all, kOutlierSlab * (o.crit_slabs + o.g_slabs));
+  const int more = ceil_div(n_out, kOutlierSlab) - o.crit_slabs;
+  if (more <= 0) return;
+  const int per_slab = (M + o.N) * (kOutlierSlab / 8);
+  for (int item = first; item < more * per_slab; item += stride) {
+    const int g = item / per_slab, rest = item % per_slab;
+    gather_outlier_slab_one(X, M, ldx, n_slabs, o, rest / (kOutlierSlab / 8), rest % (kOutlierSlab / 8), o.crit_slabs + g, s_idx,
+                            n_out, o.Xg, o.Wg, o.g_slabs, g);
   }
 }
-
 __device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, int M, int ldx, int n_slabs,
                                                const PackOutliers& o, int row, int ch, int slab, const int* s_idx,
-                                               int n_out) {
+                                               int n_out, uint16_t* dstX, uint16_t* dstW, int dst_slabs, int dst_slab) {
   const int j0 = slab * kOutlierSlab + ch * 8;
   // all eight loads of a thread are issued together: a missing column re-reads column 0 and is masked
   int kcol[8];
@@ -316,7 +287,7 @@ __device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, i
     for (int t = 0; t < 8; ++t) v[t] = X[(size_t)row * ldx + max(kcol[t], 0)];
 #pragma unroll
     for (int t = 0; t < 8; ++t) out[t >> 1] |= (kcol[t] >= 0 ? (uint32_t)v[t] : 0u) << (16 * (t & 1));
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Xo) + packed_chunk_offset(row, slab, ch, o.f_slabs)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(dstX) + packed_chunk_offset(row, dst_slab, ch, dst_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   } else {
     const int n = row - M;
@@ -338,7 +309,7 @@ __device__ inline void gather_outlier_slab_one(const uint16_t* __restrict__ X, i
         out[t >> 1] |= (kcol[t] >= 0 ? h : 0u) << (16 * (t & 1));
       }
     }
-    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(o.Wo) + packed_chunk_offset(n, slab, ch, o.f_slabs)) =
+    *reinterpret_cast<v4u*>(reinterpret_cast<int8_t*>(dstW) + packed_chunk_offset(n, dst_slab, ch, dst_slabs)) =
         v4u{out[0], out[1], out[2], out[3]};
   }
 }
@@ -357,7 +328,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(const uint16_t* __restrict__ 
     compact_critical_columns(flag, K, n_slabs * kSlabBytes, o, b == 0, s_idx, &s_n_out, s_wave_total);
     if (!Xf) {
       gather_outlier_slab(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x, s_idx, s_n_out);
-      gather_further_columns(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x,
+      gather_further_slabs(X, M, ldx, n_slabs, o, b * kThreads + threadIdx.x,
                              ((int)gridDim.y - pack_blocks_y) * (int)gridDim.x * kThreads, s_idx, s_n_out);
     }
     return;
@@ -622,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void k_outlier_columns(const uint16_t* __
     __shared__ int s_wave_total[kThreads / kWave];
     compact_critical_columns(flag, K, Kpad, o, blockIdx.x == 0, s_idx, &s_n_out, s_wave_total);
     gather_outlier_slab(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, s_idx, s_n_out);
-    gather_further_columns(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, slab_blocks * kThreads, s_idx, s_n_out);
+    gather_further_slabs(X, M, ldx, n_slabs, o, blockIdx.x * kThreads + threadIdx.x, slab_blocks * kThreads, s_idx, s_n_out);
     return;
   }
   // A clearing workgroup owns 64 rows (lane = row) and clear_units units of 16 columns (a multiple of 64), a quarter

@@ -70,9 +70,9 @@ struct Workspace {
   float* r;            // [Mpad + 256]
   uint16_t* xo;        // [Mpad][kOutlierSlab] per fp16 slab, blocked like the codes
   uint16_t* wo;        // [Npad][kOutlierSlab] per fp16 slab
-  uint16_t* xg;        // [Mpad][ldg] fp16: the critical columns beyond the slabs, gathered (tiled GEMM only), or null
-  uint16_t* wg;        // [Npad][ldg] fp16: their 16-bit weights, or null
-  int ldg;
+  uint16_t* xg;        // further fp16 slabs of critical columns (tiled GEMM only): [Mpad][32] per slab, blocked like xo, or null
+  uint16_t* wg;        // likewise [Npad][32] per slab
+  int g_slabs;
   int dense_from;      // critical columns from which the tiled GEMM takes its dense pass
   int f_slabs;         // fp16 slabs: crit_slabs for the critical columns, then the low-rank operands of an adapter of rank r
   int crit_slabs;      // 32 critical columns each: kCriticalSlabs where the tiled GEMM is the usual path, else 1
@@ -86,7 +86,7 @@ struct Workspace {
 };
 // r: rank of an adapter (0: none).  exit_block: block size of a coded output (0: plain output).
 static bool exit_fuses(int M, int K, int N, int block);
-// gathered_rows: room for the critical columns beyond the slabs, gathered once (not in the fixed-size static workspace)
+// gathered_rows: room for further slabs of critical columns (not in the fixed-size static workspace)
 static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_block = 0, bool gathered_rows = true) {
   const size_t Kpad = packed_k(K), Mpad = packed_n(M), Npad = packed_n(N);
   Workspace w;
@@ -108,14 +108,13 @@ static Workspace carve(void* base, int M, int K, int N, int r = 0, int exit_bloc
   w.f_slabs = w.crit_slabs + lora_slabs(r);
   w.xo = reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2 * w.f_slabs));
   w.wo = reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2 * w.f_slabs));
-  // (the same count decides for the dense pass with and without the gathered rows, so that a call gives the same
-  // bits whichever workspace it runs in; a workspace without those rows gathers tile by tile up to that count)
+  // (the same count decides for the dense pass with and without the further slabs, so that a call gives the same
+  // bits whichever workspace it runs in; a workspace without them gathers tile by tile up to that count)
   const CriticalPlan cp = plan_critical_columns((int)(Kpad / kSlabBytes), Npad, w.crit_slabs == kCriticalSlabs);
-  const bool rows_here = gathered_rows && cp.ldg > 0;
-  w.ldg = rows_here ? cp.ldg : 0;
+  w.g_slabs = gathered_rows ? cp.g_slabs : 0;
   w.dense_from = cp.dense_from;
-  w.xg = rows_here ? reinterpret_cast<uint16_t*>(take(Mpad * w.ldg * 2)) : nullptr;
-  w.wg = rows_here && cp.weights ? reinterpret_cast<uint16_t*>(take(Npad * w.ldg * 2)) : nullptr;
+  w.xg = w.g_slabs > 0 ? reinterpret_cast<uint16_t*>(take(Mpad * kOutlierSlab * 2 * w.g_slabs)) : nullptr;
+  w.wg = w.g_slabs > 0 ? reinterpret_cast<uint16_t*>(take(Npad * kOutlierSlab * 2 * w.g_slabs)) : nullptr;
   if (!base) w.xg = w.wg = nullptr;
   w.xq = reinterpret_cast<int8_t*>(take(Mpad * Kpad));
   w.xf = nullptr;
@@ -336,7 +335,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
   if (!record(t.event_begin)) return MMD8_E_HIP;
   const PackOutliers po = {ws.idx, ws.n_out, ws.mask, t.outlier_mask, t.outlier_idx, t.n_outliers,
                            Wq_packed, col_absmax, N, ws.xo, ws.wo, ws.f_slabs, ws.crit_slabs,
-                           readings ? readings->W_master : nullptr, readings ? readings->ldw : 0, ws.xg, ws.wg, ws.ldg, ws.dense_from};
+                           readings ? readings->W_master : nullptr, readings ? readings->ldw : 0, ws.xg, ws.wg, ws.g_slabs, ws.dense_from};
   // Up to 128 rows go through the decode kernels, 64 rows at a time (the weights are streamed twice for more
   // than 64): for activations with few critical columns that costs what the tiled GEMM costs at this size, and
   // with heavy-tailed activations (hundreds of critical columns) it is ten times faster.
@@ -524,7 +523,7 @@ static int run_linear(mmd8_half* X, int M, int K, int ldx, const int8_t* Wq_pack
     g.gelu = gelu ? 1 : 0;
     g.Xg = ws.xg;
     g.Wg = ws.wg;
-    g.ldg = ws.ldg;
+    g.g_slabs = ws.g_slabs;
     g.dense_from = ws.dense_from;
     if (readings) {
       g.W_master = readings->W_master;
@@ -575,8 +574,11 @@ int mmd8_mixed_int8_linear_static(const mmd8_half* X, int M, int K, int ldx, con
                                   const mmd8_debug_taps* taps, void* stream) {
   if (M < 0) return MMD8_E_ARG;
   if (int s = check_linear_shape(K, N)) return s;
-  // (the array is small: no rows for gathered critical columns in it, the GEMM gathers them tile by tile)
-  if (carve(nullptr, M, K, N, 0, 0, false).bytes > (size_t)MMD8_STATIC_WORKSPACE_BYTES) return MMD8_E_WORKSPACE;   // too large for the array
+  // (the array is small: the further slabs of critical columns only where they fit, else the GEMM gathers those
+  // columns tile by tile)
+  const bool further_slabs = carve(nullptr, M, K, N, 0, 0, true).bytes <= (size_t)MMD8_STATIC_WORKSPACE_BYTES;
+  if (!further_slabs && carve(nullptr, M, K, N, 0, 0, false).bytes > (size_t)MMD8_STATIC_WORKSPACE_BYTES)
+    return MMD8_E_WORKSPACE;   // too large for the array
   if (Wq_layout != kPackedLayoutTag) return MMD8_E_VERSION;
   if (M == 0) return isnan(tau) ? MMD8_E_ARG : MMD8_OK;
   int dev = 0;
@@ -601,7 +603,7 @@ int mmd8_mixed_int8_linear_static(const mmd8_half* X, int M, int K, int ldx, con
     ws = w.ptr;
   }
   const int s = run_linear(const_cast<mmd8_half*>(X), M, K, ldx, Wq_packed, Wq_layout, col_absmax, N, bias, tau, Y, ldy, ws,
-                           MMD8_STATIC_WORKSPACE_BYTES, taps, nullptr, nullptr, nullptr, stream, false, nullptr, false);
+                           MMD8_STATIC_WORKSPACE_BYTES, taps, nullptr, nullptr, nullptr, stream, false, nullptr, further_slabs);
   if (s == MMD8_E_HIP) {   // some kernels of the call may have run: the head is cleared again before the next call
     std::lock_guard<std::mutex> lock(g_static_mu);
     g_static_ws[dev].head_zero = false;

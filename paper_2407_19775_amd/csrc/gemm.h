@@ -10,39 +10,34 @@ namespace mmd8 {
 // at a time after the ring has drained: fp16 activations straight from X, weight codes converted in registers.
 constexpr int kOutlierSlab = 32;
 constexpr int kCriticalSlabs = 8;
-// Critical columns beyond the slabs are gathered column by column in the GEMM's epilogue.  Reading X[m, O_j] for
-// one j and 256 rows touches 256 lines (and the weight code Wt[n, O_j] for 256 n touches 64), and every tile would
-// do it again, so the kernel that lists the critical columns gathers them once into rows of their own,
-// Xg[m][e] = X[m, O_(32 crit_slabs + e)] and Wg[n][e] = their 16-bit weights, for as many columns as the gather is
-// cheaper for than the dense pass, at most kGatherMax; a very wide layer goes without Wg.
-//
-// The dense pass (dense_critical_columns in gemm_kernels.hip) takes over where it is cheaper: it costs 3.7 us per
-// 64-column slab of K on a 2048 x 4096 x 12288 call, a gathered column 0.2 us with both sides gathered, 0.37 us with
-// X only, 0.44 us straight from X and the codes; measured on that call, applied as ratios.  dense_from is the
-// count of critical columns from which a call takes the dense pass.
+// Critical columns beyond those slabs.  Gathering them column by column in the GEMM's epilogue (gather_outlier_columns)
+// costs 0.44 us per column on a 2048 x 4096 x 12288 call: a 2-byte element of a column of X pulls a whole line,
+// a weight code a quarter of one, and every tile does it again.  So the kernel that lists the critical columns
+// gathers them once into further slabs of the same layout, Xg / Wg (g_slabs of them per panel, up to kGatherMax
+// columns, fewer where the weight side would exceed kGatherWeightBytesMax), and the GEMM takes those through its
+// ring behind the first crit_slabs: 1.5 us per slab of 32 columns on that call.  Only columns beyond both are
+// gathered in the epilogue, and from dense_from critical columns on the GEMM makes a second, fp16 pass over K
+// instead (dense_critical_columns in gemm_kernels.hip, 3.7 us per 64-column slab of K on that call): where that is
+// cheaper, the measured costs applied as ratios.
 constexpr int kGatherMax = 2048;
-constexpr size_t kGatherWeightBytesMax = (size_t)96 << 20;   // no Wg when Npad x capacity x 2 bytes exceed this
+constexpr size_t kGatherWeightBytesMax = (size_t)96 << 20;
 struct CriticalPlan {
-  int ldg;          // columns of Xg / Wg (a multiple of 16), 0: none
-  bool weights;     // Wg exists
-  int dense_from;
+  int g_slabs;      // further slabs of 32 critical columns in Xg / Wg, 0: none
+  int dense_from;   // critical columns from which a call takes the dense pass
 };
-inline CriticalPlan plan_critical_columns(int n_slabs, size_t Npad, bool gathered_rows) {
-  const double dense = 3.7 * n_slabs;
-  CriticalPlan p = {0, false, 0};
-  if (gathered_rows) {
-    const int want = ((int)(dense / 0.2) + 15) / 16 * 16;
-    p.ldg = want < kGatherMax ? want : kGatherMax;
-    p.weights = Npad * (size_t)p.ldg * 2 <= kGatherWeightBytesMax;
-    if (!p.weights) {
-      const int want_x = ((int)(dense / 0.37) + 15) / 16 * 16;
-      p.ldg = want_x < kGatherMax ? want_x : kGatherMax;
-    }
+inline CriticalPlan plan_critical_columns(int n_slabs, size_t Npad, bool further_slabs) {
+  const double dense = 3.7 * n_slabs, per_slab_column = 1.5 / kOutlierSlab, per_gathered_column = 0.44;
+  CriticalPlan p = {0, 0};
+  if (further_slabs) {
+    size_t cols = (size_t)n_slabs * 32;                              // half of the columns at most
+    if (cols > (size_t)kGatherMax) cols = kGatherMax;
+    const size_t fit = kGatherWeightBytesMax / (Npad * 2);
+    if (cols > fit) cols = fit;
+    p.g_slabs = (int)(cols / kOutlierSlab);
   }
-  const double per_gathered = p.weights ? 0.2 : 0.37;
-  const double in_rows = p.ldg * per_gathered < dense ? p.ldg : dense / per_gathered;
-  const double beyond = (dense - in_rows * per_gathered) / 0.44;
-  p.dense_from = kOutlierSlab * kCriticalSlabs + (int)(in_rows + beyond);
+  const int in_slabs = kOutlierSlab * (kCriticalSlabs + p.g_slabs);
+  const double left = dense - in_slabs * per_slab_column;
+  p.dense_from = in_slabs + (left > 0 ? (int)(left / per_gathered_column) : 0);
   return p;
 }
 // Whether a call takes the dense pass for its critical columns.  Then no fp16 slab is prepared or read at all.  The
@@ -89,9 +84,9 @@ struct GemmArgs {
   // W[k * ldw_master + n] (null: they are re-created from the codes).  Wo was then gathered from it as well.
   const uint16_t* W_master;
   int ldw_master;
-  const uint16_t* Xg;    // [M][ldg] fp16: X[m, O_(32 crit_slabs + e)], or null (see gather_capacity)
-  const uint16_t* Wg;    // [N][ldg] fp16: the 16-bit weights of the same columns, or null (very wide layers)
-  int ldg;
+  const uint16_t* Xg;    // further fp16 slabs of critical columns, laid out like Xo with g_slabs per panel, or null
+  const uint16_t* Wg;    // likewise for the weight side (both or neither)
+  int g_slabs;
   int dense_from;        // critical columns from which the call takes the dense pass (plan_critical_columns)
 };
 

@@ -193,11 +193,8 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
     constexpr int BX = NX < 8 ? NX : 8, BW = NW < 8 ? NW : 8;
     static_assert(NX % BX == 0 && NW % BW == 0, "whole batches");
     constexpr int kBatches = NX / BX > NW / BW ? NX / BX : NW / BW;
-    // the 16 columns of this step as gathered once by the preparation (neighbouring columns of a row are neighbours
-    // in memory there), or straight from X where that buffer ends or does not exist
-    const bool gathered = a.Xg != nullptr && j0 - j_begin + 16 <= a.ldg;
-    const uint16_t* xcol = gathered ? a.Xg + (j0 - j_begin + kk) : a.X + k;
-    const int xld = gathered ? a.ldg : a.ldx;
+    const uint16_t* xcol = a.X + k;
+    const int xld = a.ldx;
 #pragma unroll 1
     for (int b = 0; b < kBatches; ++b) {
       const bool has_x = b < NX / BX, has_w = b < NW / BW;
@@ -208,13 +205,8 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
 #pragma unroll
         for (int i = 0; i < BX; ++i) xv[i] = xcol[(size_t)min(p.m0 + r0 + (b * BX + i) * RSTEP, a.M - 1) * xld];
       }
-      const bool w_gathered = gathered && a.Wg != nullptr;
       if (has_w) {
-        if (w_gathered) {                                            // as the preparation gathered them, 16 bits each
-#pragma unroll
-          for (int i = 0; i < BW; ++i)
-            wv[i] = a.Wg[(size_t)min(p.n0 + r0 + (b * BW + i) * RSTEP, a.N - 1) * a.ldg + (j0 - j_begin + kk)];
-        } else if (a.W_master) {                                     // the original 16-bit rows, as they are
+        if (a.W_master) {                                     // the original 16-bit rows, as they are
 #pragma unroll
           for (int i = 0; i < BW; ++i)
             wv[i] = a.W_master[(size_t)k * a.ldw_master + min(p.n0 + r0 + (b * BW + i) * RSTEP, a.N - 1)];
@@ -238,8 +230,7 @@ __device__ __forceinline__ void gather_outlier_columns(const GemmArgs& a, const 
 #pragma unroll
         for (int i = 0; i < BW; ++i) {
           const int row = r0 + (b * BW + i) * RSTEP;
-          const uint16_t v = (w_gathered || a.W_master) ? wv[i]
-                                                        : (uint16_t)rounded_float_to_half_bits((float)wq[i] * (wc[i] / 127.0f));
+          const uint16_t v = a.W_master ? wv[i] : (uint16_t)rounded_float_to_half_bits((float)wq[i] * (wc[i] / 127.0f));
           sWo[row * 16 + kk] = (col_ok && p.n0 + row < a.N) ? v : (uint16_t)0;
         }
       }
@@ -593,10 +584,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a) {
   const int n_slabs = a.Kpad / BK;
   const int n_out = __builtin_amdgcn_readfirstlane(*a.n_out);
   // Behind the slabs of codes, through the same ring: the fp16 slabs of the critical columns that are in use (32
-  // columns each, at most crit_slabs of them; further columns are gathered after the loop) and those of a low-rank
-  // adapter (T on the activation side, B on the weight side), which start at slab crit_slabs of Xo / Wo.
-  const int crit_used = kDense ? 0 : min(a.crit_slabs, ceil_div(n_out, kOutlierSlab));
-  const int total_slabs = n_slabs + crit_used + (a.f_slabs - a.crit_slabs);
+  // columns each: at most crit_slabs of them in Xo / Wo, then at most g_slabs further ones in Xg / Wg; columns
+  // beyond those are gathered after the loop) and those of a low-rank adapter (T on the activation side, B on the
+  // weight side), which start at slab crit_slabs of Xo / Wo.
+  const int crit_all = kDense ? 0 : ceil_div(n_out, kOutlierSlab);
+  const int crit_used = min(a.crit_slabs, crit_all);
+  const int more_used = a.Xg ? min(a.g_slabs, crit_all - crit_used) : 0;
+  const int total_slabs = n_slabs + crit_used + more_used + (a.f_slabs - a.crit_slabs);
+  // from this tile's slabs in Xo / Wo to its further slabs in Xg / Wg: the same place in a panel, other panel sizes
+  const ptrdiff_t to_more_x = reinterpret_cast<const int8_t*>(a.Xg) - reinterpret_cast<const int8_t*>(a.Xo) +
+                              (ptrdiff_t)(p.m0 >> 8) * (a.g_slabs - a.f_slabs) * kBlockBytes;
+  const ptrdiff_t to_more_w = reinterpret_cast<const int8_t*>(a.Wg) - reinterpret_cast<const int8_t*>(a.Wo) +
+                              (ptrdiff_t)(p.n0 >> 8) * (a.g_slabs - a.f_slabs) * kBlockBytes;
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
   // [(j kWaves + wave) ROWS_PER_DMA, +ROWS_PER_DMA) of the operand tile: 1 KB, contiguous in
@@ -622,8 +621,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a) {
   auto issue_dma = [&](int pos, int stage, int d, auto fp16_tag) {
     constexpr bool kF = decltype(fp16_tag)::value;
     const uint32_t base = lds0 + stage * Cfg::STAGE_BYTES + wave * (kWave * 16);
-    const int f = pos - n_slabs;                                    // among the fp16 slabs in use: its place in Xo / Wo
-    const size_t off = (size_t)(!kF ? pos : f < crit_used ? f : f - crit_used + a.crit_slabs) * kBlockBytes;
+    const int f = pos - n_slabs;                                    // among the fp16 slabs in use
+    // its place: slab f of Xo / Wo, slab f - crit_used of Xg / Wg, or an adapter's slab behind the crit_slabs of Xo / Wo
+    ptrdiff_t off = (ptrdiff_t)(!kF ? pos : f < crit_used ? f : f - crit_used - more_used + a.crit_slabs) * kBlockBytes;
+    if (kF && f >= crit_used && f < crit_used + more_used)
+      off = (d < Cfg::A_DMA ? to_more_x : to_more_w) + (ptrdiff_t)(f - crit_used) * kBlockBytes;
     if (d < Cfg::A_DMA)
       dma16((kF ? srcXo[d] : srcA[d]) + off, base + d * Cfg::kWaves * (kWave * 16));
     else
@@ -764,8 +766,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a) {
   // free for the gather staging, which starts with a barrier of its own before writing them
   if constexpr (kDense)
     dense_critical_columns<Cfg>(a, p, acc, smem, cs);
-  else if (n_out > kOutlierSlab * a.crit_slabs)
-    gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab * a.crit_slabs, n_out);
+  else if (n_out > kOutlierSlab * (crit_used + more_used))
+    gather_outlier_columns<Cfg>(a, p, acc, smem, kOutlierSlab * (crit_used + more_used), n_out);
   if constexpr (kCoded)
     store_tile_coded<Cfg, kFull>(a, p, acc, bn, smem, wave);
   else
@@ -886,7 +888,7 @@ static GemmArgs column_range(const GemmArgs& a, int n0, int n) {
   const size_t panels = (size_t)n0 / kPanelRows;
   b.Wt = a.Wt + panels * (size_t)(a.Kpad / BK) * kBlockBytes;
   b.Wo = a.Wo + panels * a.f_slabs * (kBlockBytes / 2);            // uint16_t elements
-  b.Wg = a.Wg ? a.Wg + (size_t)n0 * a.ldg : nullptr;
+  b.Wg = a.Wg ? a.Wg + panels * a.g_slabs * (kBlockBytes / 2) : nullptr;
   b.c = a.c + n0;
   b.bias = a.bias ? a.bias + n0 : nullptr;
   b.Y = a.Y ? a.Y + n0 : nullptr;

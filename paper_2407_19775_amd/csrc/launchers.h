@@ -44,9 +44,9 @@ struct PackOutliers {   // the critical columns: compaction outputs and the oper
   // the codes, f16(Wt c / 127)), or the original fp16 weights W[k * ldw + n], whose rows are then used as they are.
   const uint16_t* W_master;
   int ldw;
-  uint16_t* Xg;          // [M][ldg] fp16 or null: the critical columns beyond the slabs, gathered (gemm.h)
-  uint16_t* Wg;          // [N][ldg] fp16 or null: their 16-bit weights
-  int ldg;
+  uint16_t* Xg;          // further slabs of critical columns (gemm.h), laid out like Xo with g_slabs per panel, or null
+  uint16_t* Wg;          // likewise for the weight side
+  int g_slabs;
   int dense_from;        // critical columns from which the GEMM takes the dense pass (no slab is prepared then)
 };
 struct CodedInput {     // activations in their blockwise-coded form

@@ -27,3 +27,14 @@ def assert_y_close(y_gpu: np.ndarray, y_ref: np.ndarray, rel: float = 1e-2):
     assert fro <= rel, ("Frobenius", fro)
     assert worst <= 1.0, ("elementwise", worst)
     return fro, worst
+
+
+def critical_column_plan(K: int, N: int):
+    """How many critical columns the tiled GEMM takes as fp16 slabs through its ring, and from how many on it makes
+    its dense pass instead (the host-side plan of csrc/gemm.h, restated for the tests that aim at either side)."""
+    n_slabs = (K + 127) // 128 * 2
+    npad = (N + 255) // 256 * 256
+    cols = min(n_slabs * 32, 2048, (96 << 20) // (npad * 2))
+    in_slabs = 32 * (8 + cols // 32)
+    left = 3.7 * n_slabs - in_slabs * (1.5 / 32)
+    return in_slabs, in_slabs + (int(left / 0.44) if left > 0 else 0)

@@ -9,7 +9,7 @@ import torch
 
 from oracle import mixed_linear as ml
 from paper_2407_19775_amd import binding, workloads as wl
-from gpu_util import assert_y_close, to_gpu, to_np
+from gpu_util import critical_column_plan, assert_y_close, to_gpu, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -262,11 +262,13 @@ def test_counts_of_critical_columns_around_the_slab_limits(n_crit, variant):
 
 
 @pytest.mark.parametrize("variant", [4, 5, 0])
-@pytest.mark.parametrize("n_crit", [257, 300, 600, 865, 866, 900])
+@pytest.mark.parametrize("n_crit", [257, 300, 1312, 1344, 1345, 1485, 1486, 1550])
 def test_counts_of_critical_columns_around_the_change_to_the_dense_pass(n_crit, variant):
-    """33 slabs of K: up to 865 critical columns the ones beyond 256 are gathered once by the preparation and added
-    16 at a time in the GEMM's epilogue, from 866 on all of them go through the second, fp16 pass over K."""
+    """34 slabs of K: up to 1344 critical columns travel as fp16 slabs (8, then up to 34 further ones), up to 1485
+    the ones beyond are gathered in the GEMM's epilogue, from 1486 on all of them go through the second, fp16 pass
+    over K."""
     M, K, N = 300, 2096, 264
+    assert critical_column_plan(K, N) == (1344, 1486)
     rng = np.random.default_rng([n_crit, variant, 7])
     X, cols = exactly_n_critical(rng, M, K, n_crit)
     assert np.array_equal(np.flatnonzero(ml.outlier_mask(X, 6.0)), cols)
@@ -289,14 +291,14 @@ def test_short_rows_in_the_tiled_gemm(K, tau, variant):
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
-@pytest.mark.parametrize("M,K,N", [(129, 2096, 304), (600, 1040, 520), (1030, 4096, 264)])
+@pytest.mark.parametrize("M,K,N", [(260, 2096, 304), (600, 1040, 520), (1030, 4096, 264)])
 def test_most_columns_critical_over_many_rows(M, K, N, variant):
     """Heavy-tailed rows (Student-t, 3 degrees of freedom) over more rows than the decode kernels take: most
     columns are critical, far more than the fp16 slabs hold, with and without the master-weight reading."""
     rng = np.random.default_rng([M, K, variant])
     X = wl.to_fp16(rng.standard_t(3.0, size=(M, K)).astype(np.float32))
     n = int(ml.outlier_mask(X, wl.TAU).sum())
-    assert n > 256 and n >= 23 * ((K + 63) // 64), n          # the dense pass, not the gather
+    assert n >= critical_column_plan(K, N)[1], n               # the dense pass
     W = wl.gaussian_weight(K, N, 0.05, rng)
     check_linear(X, W, wl.TAU, bias=wl.gaussian_bias(N, 0.1, rng), tuning=binding.tune_gemm_tiles(variant))
 

@@ -74,11 +74,10 @@ def test_no_critical_column_and_many(tau, M):
 
 
 @pytest.mark.parametrize("variant", [4, 0, 5])
-@pytest.mark.parametrize("n_crit,r", [(1, 64), (33, 16), (70, 40), (200, 8), (256, 64), (257, 24)])
+@pytest.mark.parametrize("n_crit,r", [(1, 64), (33, 16), (70, 40), (200, 8), (256, 64), (257, 24), (700, 16), (830, 40)])
 def test_critical_column_slabs_next_to_the_adapter(n_crit, r, variant):
     """1 to 8 fp16 slabs of critical columns in use (the unused ones are skipped), then the adapter's one or two
-    slabs behind them in the same ring; 257: one more column, added in the epilogue from the rows the preparation
-    gathered."""
+    slabs behind them in the same ring; 257: one more column, in a ninth slab from the further ones."""
     M, K, N = 300, 1040, 520
     rng = np.random.default_rng([n_crit, r, variant])
     x = np.clip(rng.standard_normal((M, K)), -5.0, 5.0).astype(np.float32)
@@ -94,9 +93,9 @@ def test_critical_column_slabs_next_to_the_adapter(n_crit, r, variant):
 
 @pytest.mark.parametrize("variant", [4, 2])
 def test_dense_pass_next_to_the_adapter(variant):
-    """900 of 2096 columns critical: no slab of critical columns, the adapter's slab, then the second, fp16 pass
+    """1600 of 2096 columns critical: no slab of critical columns, the adapter's slab, then the second, fp16 pass
     over K."""
-    M, K, N, n_crit, r = 300, 2096, 264, 900, 16
+    M, K, N, n_crit, r = 300, 2096, 264, 1600, 16
     rng = np.random.default_rng([n_crit, r, variant, 3])
     x = np.clip(rng.standard_normal((M, K)), -5.0, 5.0).astype(np.float32)
     cols = np.sort(rng.choice(K, n_crit, replace=False))
