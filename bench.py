@@ -33,8 +33,8 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # (70B-shaped layer, 4096 tokens) and the 7B-shaped step.  Valid for the GEMM source they were measured on:
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
-GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.7e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "a8bdadc93a2debe2cb0b1c3bc0f59db6b316d4719727e6fc1baf24a603f614aa"
+GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.6e6
+GEMM_TRAFFIC_SOURCE_SHA256 = "0f38bcae1de51ee699e4fd7a42d585cb1a0f17212ae2f5f054d1ef3d91f8a748"
 
 
 def parse():
