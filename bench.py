@@ -34,7 +34,7 @@ INT8_POWER_LIMITED_TOPS = 3468.0
 # reported as null once that file has changed.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1185.3e6
 GEMM_TRAFFIC_BYTES_PER_LAUNCH_7B = 182.6e6
-GEMM_TRAFFIC_SOURCE_SHA256 = "0f38bcae1de51ee699e4fd7a42d585cb1a0f17212ae2f5f054d1ef3d91f8a748"
+GEMM_TRAFFIC_SOURCE_SHA256 = "d31feb445e95096b1c0fff96f120c4d970f74e19a65f82518998941645101b22"
 
 
 def parse():

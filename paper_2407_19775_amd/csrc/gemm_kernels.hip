@@ -592,9 +592,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a) {
   const int more_used = a.Xg ? min(a.g_slabs, crit_all - crit_used) : 0;
   const int total_slabs = n_slabs + crit_used + more_used + (a.f_slabs - a.crit_slabs);
   // from this tile's slabs in Xo / Wo to its further slabs in Xg / Wg: the same place in a panel, other panel sizes
-  const ptrdiff_t to_more_x = reinterpret_cast<const int8_t*>(a.Xg) - reinterpret_cast<const int8_t*>(a.Xo) +
+  // (two allocations: the distance as a difference of addresses, not of pointers)
+  const ptrdiff_t to_more_x = (ptrdiff_t)(reinterpret_cast<uintptr_t>(a.Xg) - reinterpret_cast<uintptr_t>(a.Xo)) +
                               (ptrdiff_t)(p.m0 >> 8) * (a.g_slabs - a.f_slabs) * kBlockBytes;
-  const ptrdiff_t to_more_w = reinterpret_cast<const int8_t*>(a.Wg) - reinterpret_cast<const int8_t*>(a.Wo) +
+  const ptrdiff_t to_more_w = (ptrdiff_t)(reinterpret_cast<uintptr_t>(a.Wg) - reinterpret_cast<uintptr_t>(a.Wo)) +
                               (ptrdiff_t)(p.n0 >> 8) * (a.g_slabs - a.f_slabs) * kBlockBytes;
 
   // ---- DMA plan of this lane: instruction j of this wave fills LDS rows
